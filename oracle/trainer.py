@@ -1,0 +1,114 @@
+"""Oracle state machine: Algorithm 1 with K replicas on one host (test infrastructure).
+
+Holds the single copy of the tables h (+ Adagrad accumulators), the K dense replicas
+w^(i), the centre copy w^PS, the aggregated copy w^global and the momentum buffer v,
+all initialised as Algorithm 1 states (h <- h0, w^PS <- w0, w^(i) <- w0; Algorithms 3
+and 4 initialise w^global <- w0).  train_step is one pass of a worker thread's loop
+body for one batch; shadow_sync is one pass of the shadow threads' loop body.
+"""
+
+from __future__ import annotations
+
+import numpy as np
+
+from . import dlrm, sync
+
+
+class OracleTrainer:
+    def __init__(self, bot_dims, top_dims, row_base, h0, w0, num_replicas,
+                 lr_dense=0.01, lr_emb=0.01, adagrad_eps=1e-8, dtype=np.float64,
+                 bf16=False):
+        self.layout = dlrm.DenseLayout(tuple(bot_dims), tuple(top_dims))
+        self.row_base = np.asarray(row_base, dtype=np.int64)
+        self.T = len(self.row_base) - 1
+        self.d = h0.shape[1]
+        assert h0.shape[0] == self.row_base[-1]
+        assert self.layout.top_dims[0] == self.d + self.T * (self.T + 1) // 2
+        assert w0.shape == (self.layout.num_params,)
+        self.dtype = dtype
+        self.bf16 = bf16
+        self.h = h0.astype(dtype).copy()
+        self.G = np.zeros(h0.shape[0], dtype=dtype)
+        self.W = np.tile(w0.astype(dtype), (num_replicas, 1))
+        self.w_ps = w0.astype(dtype).copy()
+        self.w_global = w0.astype(dtype).copy()
+        self.v = np.zeros_like(self.w_ps)
+        self.lr_dense, self.lr_emb, self.eps = lr_dense, lr_emb, adagrad_eps
+        self.steps = np.zeros(num_replicas, dtype=np.int64)
+        self.rounds = 0
+        self.last = None
+
+    # ------------------------------------------------------------------ worker thread
+    def train_step(self, replica, x, y, indices, offsets, update=True):
+        """One worker iteration (Algorithm 1, worker loop; Section 3.1 "Trainer"):
+        forward, loss, backward, then "update h" and "update local param w^(i)".
+        Returns the mean log-loss of the batch BEFORE the update."""
+        B = x.shape[0]
+        L = self.layout
+        w = self.W[replica]
+        fw = dlrm.dlrm_forward(L, w, self.h, self.row_base, x, indices, offsets,
+                               bf16=self.bf16)
+        loss, g, de = dlrm.dlrm_backward(L, fw, y.astype(self.dtype))
+        keys = dlrm.global_rows(self.row_base, indices, offsets, B)
+        bag = dlrm.bag_of_position(offsets, B, self.T)
+        rows, g_rows, sk, perm, heads = dlrm.embedding_row_gradients(
+            de.reshape(B * self.T, self.d), keys, bag)
+        self.last = dict(e=fw["e"], f=fw["f"], logit=fw["logit"], z0=fw["z0"], g=g,
+                         de=de, sorted_keys=sk, sorted_pos=perm, seg_starts=heads,
+                         rows=rows, g_rows=g_rows, bag_of_pos=bag)
+        if update:
+            self.W[replica] = w - self.lr_dense * g
+            dlrm.rowwise_adagrad_update(self.h, self.G, rows, g_rows, self.lr_emb,
+                                        self.eps)
+            self.steps[replica] += 1
+        return loss
+
+    def eval_logloss(self, replica, x, y, indices, offsets):
+        fw = dlrm.dlrm_forward(self.layout, self.W[replica], self.h, self.row_base, x,
+                               indices, offsets, bf16=self.bf16)
+        return dlrm.bce_with_logits(fw["logit"], y.astype(self.dtype))[0]
+
+    # ------------------------------------------------------------------ shadow thread
+    def shadow_sync(self, algo, alpha, eta=1.0, mu=0.0):
+        """One round of Algorithm 2 ("easgd"), 3 ("ma") or 4 ("bmuf")."""
+        if algo == "easgd":
+            sync.easgd_round(self.W, self.w_ps, alpha)
+        elif algo == "easgd_literal":
+            sync.easgd_round_literal(self.W, self.w_ps, alpha)
+        elif algo == "ma":
+            sync.ma_round(self.W, self.w_global, alpha)
+        elif algo == "bmuf":
+            sync.bmuf_round(self.W, self.w_global, self.v, alpha, eta, mu)
+        else:
+            raise ValueError(algo)
+        self.rounds += 1
+
+    # ------------------------------------------------------------------ schedules
+    def run_deterministic(self, batches, gap, algo, alpha, eta=1.0, mu=0.0):
+        """One worker per replica, sync at fixed steps: for s = 0, 1, ...: replica
+        i = 0..K-1 trains batch s*K+i in turn (the tables are one shared copy, so
+        replica i+1 sees replica i's row updates), and after every `gap` such sweeps one
+        sync round runs.  Returns the list of per-batch losses."""
+        K = self.W.shape[0]
+        losses = []
+        for s in range(len(batches) // K):
+            for i in range(K):
+                losses.append(self.train_step(i, *batches[s * K + i]))
+            if (s + 1) % gap == 0:
+                self.shadow_sync(algo, alpha, eta, mu)
+        return losses
+
+    def avg_sync_gap(self):
+        """Average sync gap (Section 4.1): trainer iterations per sync, i.e. iterations
+        of one trainer divided by the number of syncs it took part in."""
+        return float(self.steps.mean()) / max(self.rounds, 1)
+
+
+def normalized_entropy(p_hat, y):
+    """NE (Section 4, "Evaluation Metrics"): mean cross-entropy of the predictions
+    divided by the entropy of the empirical click rate."""
+    p_hat = np.asarray(p_hat, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    ce = -(y * np.log(p_hat) + (1 - y) * np.log(1 - p_hat)).mean()
+    p = y.mean()
+    return ce / -(p * np.log(p) + (1 - p) * np.log(1 - p))
