@@ -1,0 +1,212 @@
+/*
+ * shadowsync.h — C ABI of the MI355X (gfx950) ShadowSync hot-path library.
+ *
+ * One trainer's click-through-rate training step (ShadowSync, arXiv 2003.03477,
+ * Section 3.1 "Trainer" and Section 3.2 "Optimization Strategies") and the background
+ * ("shadow") synchronisation of Algorithms 1-4 over K dense-parameter replicas that all
+ * live in the HBM of one GPU.  The calls follow Algorithm 1: initialise the tables h and
+ * the replicas w^(i) (and w^PS / w^global); a worker iteration = ss_train_step(replica,
+ * batch) = "update h; update w^(i)"; a shadow iteration = ss_shadow_sync(algo, ...) =
+ * "sync w^(i)"; after training read back h and w^(1) (Section 4, "Experimental Setup").
+ *
+ * Conventions
+ *  - Every function returns SS_OK (0) or a negative ss_status; text via ss_last_error().
+ *    No exception or C++ type crosses this boundary.
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
+ *  - The library allocates NO device memory: the caller passes one workspace of
+ *    ss_workspace_bytes() bytes (256-byte aligned) that must outlive the context, and
+ *    owns every batch buffer.  The library owns only the host-side ss_ctx.
+ *  - All device work is enqueued asynchronously on the hipStream_t passed as `stream`
+ *    (cast to void*; NULL = the default stream).  ss_read_* synchronise the device.
+ *  - Thread safety: ss_train_step may be called concurrently from different host threads
+ *    with different worker slots; two calls on one slot must be ordered by the caller
+ *    (same stream, or an event).  Concurrent steps race on h and on w^(replica) exactly as
+ *    the paper's lock-free worker threads do.  Shape errors are reported; the CONTENT of
+ *    indices/offsets is not validated on the hot path (rows must be < rows[t], offsets
+ *    non-decreasing with offsets[0] = 0 and offsets[T*B] = num_ids).
+ *
+ * Dense parameter vector (exposed by ss_read_dense / ss_init_dense): bottom-MLP layers then
+ * top-MLP layers, each W[out][in] row-major followed by b[out]; P floats, no padding.
+ */
+#ifndef SHADOWSYNC_H
+#define SHADOWSYNC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ss_ctx ss_ctx;
+
+typedef enum {
+  SS_OK = 0,
+  SS_EINVAL = -1,  /* bad shape, index or argument                                   */
+  SS_ENOMEM = -2,  /* workspace too small                                            */
+  SS_EDEVICE = -3, /* a HIP call failed; sticky for the context                      */
+  SS_ESTATE = -4   /* call not valid in the current state (e.g. shadow loop running) */
+} ss_status;
+
+/* Synchronisation rule of one shadow round. */
+typedef enum {
+  SS_EASGD = 0,         /* Algorithm 2, symmetric elastic exchange (conserves mass)   */
+  SS_MA = 1,            /* Algorithm 3                                               */
+  SS_BMUF = 2,          /* Algorithm 4 with optional block momentum                  */
+  SS_EASGD_LITERAL = 3  /* Algorithm 2 with its two lines executed one after another */
+} ss_algo;
+
+typedef enum { SS_FP32 = 0, SS_BF16 = 1 } ss_mlp_prec;
+
+typedef struct {
+  int32_t num_tables;        /* T, 1..64                                                  */
+  const int64_t* rows;       /* host [T] rows per table; sum < 2^32                      */
+  int32_t emb_dim;           /* d: 16, 32, 64 or 128                                     */
+  int32_t num_dense;         /* width of the dense-feature input                        */
+  int32_t n_bot;             /* entries in bot_dims (layers + 1)                        */
+  const int32_t* bot_dims;   /* host, e.g. {13,256,128,64}; last must equal emb_dim     */
+  int32_t n_top;             /* entries in top_dims                                     */
+  const int32_t* top_dims;   /* host, e.g. {100,512,256,1}; first must equal
+                                emb_dim + T(T+1)/2 and last must be 1                    */
+  int32_t num_replicas;      /* K >= 1 dense replicas w^(i)                              */
+  int32_t max_batch;         /* largest batch any step will pass                        */
+  int64_t max_ids;           /* largest num_ids any step will pass (< 2^31)             */
+  int32_t num_worker_slots;  /* concurrent ss_train_step callers (private scratch each) */
+  int32_t mlp_prec;          /* ss_mlp_prec: SS_BF16 rounds the inputs of every MLP GEMM
+                                to bfloat16 (fp32 accumulate, fp32 master weights)       */
+  float lr_dense;            /* SGD step on w^(i)                                        */
+  float lr_emb;              /* row-wise Adagrad step on h                               */
+  float adagrad_eps;
+  uint64_t seed;             /* seed of the counter-based table initialiser             */
+} ss_config;
+
+/* One mini-batch.  All pointers are DEVICE pointers owned by the caller and must stay
+ * valid until the step's stream work has completed.  Table-major CSR: bag (t, b) is
+ * indices[offsets[t*batch + b] .. offsets[t*batch + b + 1]).  An empty bag pools to 0. */
+typedef struct {
+  int32_t batch;           /* B <= max_batch                                            */
+  int64_t num_ids;         /* n = offsets[T*B] <= max_ids (host copy of that value)     */
+  const float* dense;      /* dev [B, num_dense] row-major                              */
+  const float* labels;     /* dev [B], 0 or 1                                           */
+  const int32_t* indices;  /* dev [n], row within its table                             */
+  const int32_t* offsets;  /* dev [T*B + 1]                                             */
+} ss_batch;
+
+/* Device bytes ss_init needs for this configuration (0 on an invalid configuration). */
+size_t ss_workspace_bytes(const ss_config* cfg);
+
+/* Algorithm 1, initialisation: lay out h (+ Adagrad state), the K replicas, w^PS,
+ * w^global, the momentum buffer and the per-slot scratch inside `dev_workspace`; zero the
+ * optimiser state.  Runs on the current HIP device; synchronous.  */
+int ss_init(const ss_config* cfg, void* dev_workspace, size_t bytes, ss_ctx** out);
+void ss_destroy(ss_ctx* ctx);
+const char* ss_last_error(const ss_ctx* ctx); /* NULL ctx: error of the last failed ss_init */
+
+/* h <- h0 for every table from the counter-based hash of (seed, table, row, column):
+ * value = (u24 - 2^23) * (0.05 * 2^-23), u24 = top 24 bits of
+ * mix64(mix64(seed ^ (1000+table)*0xD1B54A32D192ED03) + (row*d+col)*0x9E3779B97F4A7C15),
+ * mix64 = the splitmix64 output function.  Also zeroes the Adagrad accumulators. */
+int ss_init_tables_hash(ss_ctx* ctx, void* stream);
+
+/* h[table, first_row .. first_row+n_rows) <- host values [n_rows, d]; accumulators of
+ * those rows <- 0.  Synchronous. */
+int ss_write_rows(ss_ctx* ctx, int32_t table, int64_t first_row, int64_t n_rows,
+                  const float* host_rows);
+
+/* Algorithm 1: w^(i) <- w0 for all i, w^PS <- w0, w^global <- w0 (Algorithms 3, 4), v <- 0.
+ * host_w0 holds P floats.  Synchronous. */
+int ss_init_dense(ss_ctx* ctx, const float* host_w0);
+
+/* Number of dense parameters P of the configured model. */
+int64_t ss_num_params(const ss_ctx* ctx);
+
+/* One worker iteration for one batch on replica `replica` (Algorithm 1 worker loop;
+ * Section 3.1 "Trainer"): bottom MLP, sum-pooled look-ups, pairwise-dot interaction, top
+ * MLP, mean log-loss, backward, then w^(replica) -= lr_dense * grad (lock-free) and one
+ * row-wise Adagrad update per distinct touched row of h with the gradients of all its
+ * occurrences summed first (stable sort by row, segmented reduction).
+ * dev_loss_out (device, 1 float, may be NULL) receives the mean log-loss BEFORE the update. */
+int ss_train_step(ss_ctx* ctx, int32_t replica, int32_t worker_slot, const ss_batch* batch,
+                  void* stream, float* dev_loss_out);
+
+/* Forward pass only: mean log-loss of replica `replica` on the batch, nothing is updated
+ * (the quantity whose ratio to the label entropy is the paper's NE, Section 4). */
+int ss_eval_step(ss_ctx* ctx, int32_t replica, int32_t worker_slot, const ss_batch* batch,
+                 void* stream, float* dev_loss_out);
+
+/* One shadow round over all K replicas, i ascending, element-wise (Algorithms 2-4):
+ *  SS_EASGD: for each i: delta = alpha (w^(i) - w^PS); w^PS += delta; w^(i) -= delta
+ *  SS_MA:    w^global = mean_i w^(i); w^(i) = (1-alpha) w^(i) + alpha w^global
+ *  SS_BMUF:  m = mean_i w^(i); v = momentum v + eta (m - w^global); w^global += v;
+ *            w^(i) = (1-alpha) w^(i) + alpha w^global
+ * eta and momentum are ignored except by SS_BMUF.  One fused, memory-bound kernel. */
+int ss_shadow_sync(ss_ctx* ctx, int32_t algo, float alpha, float eta, float momentum,
+                   void* stream);
+
+/* The same round on caller-owned device vectors (no context needed): `dev_replicas` holds
+ * K vectors of P floats, vector i starting at dev_replicas + i*stride (stride >= P,
+ * multiple of 4; all pointers 16-byte aligned).  dev_w_ps is used by the EASGD rules,
+ * dev_w_global by MA/BMUF, dev_v by BMUF; unused ones may be NULL.  K <= 16. */
+int ss_sync_round(int32_t algo, int32_t K, int64_t P, int64_t stride, float* dev_replicas,
+                  float* dev_w_ps, float* dev_w_global, float* dev_v, float alpha, float eta,
+                  float momentum, void* stream);
+
+/* Algorithm 1's shadow thread: a host thread owned by the context that enqueues rounds on
+ * `stream` one after another ("looping the synchronization without any knowledge of the
+ * training process") until ss_shadow_stop.  The stream must not be used by the caller
+ * while the loop runs. */
+int ss_shadow_start(ss_ctx* ctx, int32_t algo, float alpha, float eta, float momentum,
+                    void* stream);
+int ss_shadow_stop(ss_ctx* ctx);
+
+/* Read-back (synchronises the device first).  which: 0..K-1 = w^(which), -1 = w^PS,
+ * -2 = w^global, -3 = v.  n must equal P. */
+int ss_read_dense(ss_ctx* ctx, int32_t which, float* host_out, int64_t n);
+int ss_write_dense(ss_ctx* ctx, int32_t which, const float* host_in, int64_t n);
+/* rows: host [n] row ids of `table`; host_rows_out [n, d] and host_adagrad_out [n] may
+ * each be NULL. */
+int ss_read_rows(ss_ctx* ctx, int32_t table, const int64_t* rows, int64_t n,
+                 float* host_rows_out, float* host_adagrad_out);
+
+/* Intermediates of the LAST step run on a worker slot, for element-wise checks
+ * (synchronises first).  Copies min(bytes, size) bytes; returns the full size in bytes
+ * through *size_out (may be NULL). */
+typedef enum {
+  SS_DBG_POOLED = 0,       /* float  [B, T, d]   pooled embeddings e                       */
+  SS_DBG_INTERACT = 1,     /* float  [B, F]      interaction output f                      */
+  SS_DBG_LOGITS = 2,       /* float  [B]                                                    */
+  SS_DBG_DENSE_GRAD = 3,   /* float  [P]         gradient of the mean loss w.r.t. w         */
+  SS_DBG_POOLED_GRAD = 4,  /* float  [B, T, d]   de                                         */
+  SS_DBG_SORTED_ROWS = 5,  /* uint32 [n]         global row (row_base[t]+row), ascending    */
+  SS_DBG_SORTED_POS = 6,   /* uint32 [n]         flat position of each sorted entry         */
+  SS_DBG_SEG_STARTS = 7,   /* uint32 [U]         sorted index where each distinct row starts */
+  SS_DBG_NUM_UNIQUE = 8,   /* uint32 [1]         U                                          */
+  SS_DBG_BAG_OF_POS = 9    /* int32  [n]         b*T + t of each flat position              */
+} ss_debug_item;
+int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out, size_t bytes,
+                  size_t* size_out);
+
+/* Counters (Section 4: EPS; Section 4.1: average sync gap = trainer iterations per sync).
+ * steps_per_replica: host [K]; any pointer may be NULL. */
+int ss_get_counters(ss_ctx* ctx, uint64_t* steps_per_replica, uint64_t* rounds,
+                    uint64_t* examples);
+
+/* Kernel timing with HIP events on the launching stream: bracket every launch of the named
+ * kernel class until ss_profile_read, which synchronises, returns the number of bracketed
+ * launches and their summed duration in ms, and disarms.  kernel ids: ss_kernel_id. */
+typedef enum {
+  SS_K_NONE = 0,
+  SS_K_GATHER = 1,      /* embedding gather + sum pooling                              */
+  SS_K_SORT = 2,        /* all radix-sort passes of one step, as one bracket           */
+  SS_K_ROW_UPDATE = 3,  /* segmented reduction + row-wise Adagrad                       */
+  SS_K_SYNC = 4,        /* one shadow round                                             */
+  SS_K_MLP = 5,         /* all MLP GEMM kernels of one step (fwd+bwd), one bracket each */
+  SS_K_INTERACT = 6
+} ss_kernel_id;
+int ss_profile_arm(ss_ctx* ctx, int32_t kernel_id);
+int ss_profile_read(ss_ctx* ctx, int64_t* launches, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHADOWSYNC_H */

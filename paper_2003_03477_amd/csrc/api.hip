@@ -1,0 +1,790 @@
+// C ABI of libshadowsync: context, workspace layout, and the host-side sequencing of one
+// worker iteration and one shadow round (Algorithm 1).  No device memory is allocated here:
+// everything is carved out of the caller's workspace.
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "../../include/shadowsync.h"
+#include "ss_internal.h"
+
+using namespace ss;
+
+namespace {
+
+constexpr int MAX_LAYERS = 16;
+constexpr size_t ALIGN = 256;
+
+struct Layer {
+  int in, out;
+  int64_t w_off, b_off;  // offsets inside the dense vector
+};
+
+struct Slot {
+  // forward
+  float* act_f32[MAX_LAYERS];      // fp32 path: output of layer l
+  uint16_t* act_bf16[MAX_LAYERS];  // bf16 path: output of hidden layers
+  float* z0;                       // output of the last bottom layer (fp32 in both paths)
+  float* e;                        // [B,T,d]
+  float* f;                        // [B,ldf]
+  uint16_t* f_bf16;                // [B,ldf16]
+  float* logits;                   // [B]
+  float* loss;                     // [1]
+  // backward
+  float* dlogit;                   // [B]
+  float* grads;                    // [P]
+  float* dbuf[2];                  // fp32 path ping-pong [B, maxw]
+  uint16_t* dbuf16[2];             // bf16 path ping-pong
+  float* df;                       // [B,ldf]
+  float* dz0;                      // [B,d]
+  float* de;                       // [B,T,d]
+  // embedding backward
+  uint32_t* keys;                  // [max_ids]
+  int32_t* bag_of_pos;             // [max_ids]
+  SortScratch sort;
+  SegScratch seg;
+  // results of the last step (for ss_read_debug)
+  uint32_t* sorted_keys = nullptr;
+  uint32_t* sorted_pos = nullptr;
+  uint32_t last_n = 0;
+  int last_B = 0;
+};
+
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base((char*)b) {}
+  template <typename T>
+  T* take(size_t count) {
+    off = (off + ALIGN - 1) / ALIGN * ALIGN;
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+}  // namespace
+
+struct ss_ctx {
+  // configuration
+  int T, d, num_dense, K, max_batch, num_slots, prec;
+  int64_t max_ids;
+  std::vector<int64_t> rows;
+  std::vector<Layer> layers;
+  int n_bot_layers, n_top_layers;
+  int64_t P, Pstride;
+  int F, ldf, ldf16, maxw;
+  int key_bits;
+  float lr_dense, lr_emb, eps;
+  uint64_t seed;
+  int device;
+  TableMeta meta;
+  uint64_t total_rows;
+  // device memory
+  float* h;
+  float* G;
+  float* W;  // K replicas, stride Pstride
+  float* w_ps;
+  float* w_global;
+  float* v;
+  std::vector<Slot> slots;
+  // state
+  std::string err;
+  std::atomic<int> sticky{0};
+  std::vector<std::atomic<uint64_t>> steps;
+  std::atomic<uint64_t> rounds{0}, examples{0};
+  // shadow loop
+  std::thread shadow;
+  std::atomic<bool> shadow_run{false};
+  // profiling
+  std::mutex prof_mu;
+  int prof_kernel = 0;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
+  size_t prof_used = 0;
+
+  explicit ss_ctx(int k) : steps(k) {
+    for (auto& a : steps) a.store(0);
+  }
+};
+
+static std::string g_init_err;
+
+static int fail(ss_ctx* ctx, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf; else g_init_err = buf;
+  return code;
+}
+
+static int check_hip(ss_ctx* ctx, hipError_t e, const char* what) {
+  if (e == hipSuccess) return SS_OK;
+  if (ctx) ctx->sticky = 1;
+  return fail(ctx, SS_EDEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(ctx, call)                                     \
+  do {                                                         \
+    int _rc = check_hip(ctx, (call), #call);                   \
+    if (_rc != SS_OK) return _rc;                              \
+  } while (0)
+
+// ------------------------------------------------------------------------------------------
+// Layout.  Returns total bytes; fills ctx pointers when base != nullptr.
+static int validate(const ss_config* c, std::string& why) {
+  char b[256];
+#define BAD(...) do { snprintf(b, sizeof b, __VA_ARGS__); why = b; return SS_EINVAL; } while (0)
+  if (!c) BAD("null config");
+  if (c->num_tables < 1 || c->num_tables > SS_MAX_TABLES) BAD("num_tables must be 1..%d", SS_MAX_TABLES);
+  if (!c->rows || !c->bot_dims || !c->top_dims) BAD("null rows/bot_dims/top_dims");
+  if (c->emb_dim != 16 && c->emb_dim != 32 && c->emb_dim != 64 && c->emb_dim != 128)
+    BAD("emb_dim must be 16, 32, 64 or 128");
+  if (c->n_bot < 2 || c->n_top < 2 || (c->n_bot - 1) + (c->n_top - 1) > MAX_LAYERS)
+    BAD("need 1..%d MLP layers in total", MAX_LAYERS);
+  if (c->num_dense < 1 || c->bot_dims[0] != c->num_dense) BAD("bot_dims[0] must equal num_dense");
+  if (c->bot_dims[c->n_bot - 1] != c->emb_dim) BAD("last bottom width must equal emb_dim");
+  const int T = c->num_tables;
+  if (c->top_dims[0] != c->emb_dim + T * (T + 1) / 2)
+    BAD("top_dims[0] must be emb_dim + T(T+1)/2 = %d", c->emb_dim + T * (T + 1) / 2);
+  if (c->top_dims[c->n_top - 1] != 1) BAD("last top width must be 1");
+  for (int i = 0; i < c->n_bot; ++i) if (c->bot_dims[i] < 1) BAD("bad bottom width");
+  for (int i = 0; i < c->n_top; ++i) if (c->top_dims[i] < 1) BAD("bad top width");
+  uint64_t tot = 0;
+  for (int t = 0; t < T; ++t) {
+    if (c->rows[t] < 1) BAD("table %d has no rows", t);
+    tot += (uint64_t)c->rows[t];
+  }
+  if (tot >= (1ull << 32)) BAD("total rows must be < 2^32");
+  if (c->num_replicas < 1 || c->num_replicas > 16) BAD("num_replicas must be 1..16");
+  if (c->max_batch < 1 || c->max_batch > (1 << 20)) BAD("bad max_batch");
+  if (c->max_ids < 1 || c->max_ids >= (1ll << 31)) BAD("max_ids must be 1..2^31-1");
+  if ((int64_t)c->max_batch * T >= (1ll << 31)) BAD("max_batch * num_tables too large");
+  if (c->num_worker_slots < 1 || c->num_worker_slots > 64) BAD("num_worker_slots must be 1..64");
+  if (c->mlp_prec != SS_FP32 && c->mlp_prec != SS_BF16) BAD("bad mlp_prec");
+  const size_t shm = (size_t)4 * ((T + 1) * (c->emb_dim + 4) + (((T + 1) * (T + 1) + 3) & ~3)) * 4;
+  if (shm > 64 * 1024) BAD("interaction tile (T+1) x d does not fit the LDS budget");
+#undef BAD
+  return SS_OK;
+}
+
+static size_t layout(ss_ctx* x, void* base) {
+  Carver cv(base);
+  const int B = x->max_batch;
+  const int64_t n = x->max_ids;
+  x->h = cv.take<float>(x->total_rows * (uint64_t)x->d);
+  x->G = cv.take<float>(x->total_rows);
+  x->W = cv.take<float>((size_t)x->K * x->Pstride);
+  x->w_ps = cv.take<float>(x->Pstride);
+  x->w_global = cv.take<float>(x->Pstride);
+  x->v = cv.take<float>(x->Pstride);
+  const int L = (int)x->layers.size();
+  const int sort_blocks = sort_max_blocks((uint32_t)n);
+  const int seg_blocks = ceil_div(n, 2048) + 1;
+  for (Slot& s : x->slots) {
+    for (int l = 0; l < L; ++l) {
+      s.act_f32[l] = nullptr;
+      s.act_bf16[l] = nullptr;
+      const bool is_z0 = (l == x->n_bot_layers - 1), is_logit = (l == L - 1);
+      if (is_z0 || is_logit) continue;
+      if (x->prec == SS_FP32) s.act_f32[l] = cv.take<float>((size_t)B * x->layers[l].out);
+      else s.act_bf16[l] = cv.take<uint16_t>((size_t)B * x->layers[l].out);
+    }
+    s.z0 = cv.take<float>((size_t)B * x->d);
+    s.e = cv.take<float>((size_t)B * x->T * x->d);
+    s.f = cv.take<float>((size_t)B * x->ldf);
+    s.f_bf16 = (x->prec == SS_BF16) ? cv.take<uint16_t>((size_t)B * x->ldf16) : nullptr;
+    s.logits = cv.take<float>(B);
+    s.loss = cv.take<float>(64);
+    s.dlogit = cv.take<float>(B);
+    s.grads = cv.take<float>(x->Pstride);
+    for (int i = 0; i < 2; ++i) {
+      s.dbuf[i] = nullptr;
+      s.dbuf16[i] = nullptr;
+      if (x->prec == SS_FP32) s.dbuf[i] = cv.take<float>((size_t)B * x->maxw);
+      else s.dbuf16[i] = cv.take<uint16_t>((size_t)B * x->maxw);
+    }
+    s.df = cv.take<float>((size_t)B * x->ldf);
+    s.dz0 = cv.take<float>((size_t)B * x->d);
+    s.de = cv.take<float>((size_t)B * x->T * x->d);
+    s.keys = cv.take<uint32_t>(n);
+    s.bag_of_pos = cv.take<int32_t>(n);
+    s.sort.keys_alt = cv.take<uint32_t>(n);
+    s.sort.vals = cv.take<uint32_t>(n);
+    s.sort.vals_alt = cv.take<uint32_t>(n);
+    s.sort.block_hist = cv.take<uint32_t>((size_t)256 * sort_blocks);
+    s.sort.digit_tot = cv.take<uint32_t>(256);
+    s.seg.block_counts = cv.take<uint32_t>(seg_blocks);
+    s.seg.seg_starts = cv.take<uint32_t>(n + 1);
+    s.seg.num_unique = cv.take<uint32_t>(64);
+    s.seg.long_list = cv.take<uint32_t>(n / 256 + 2);
+    s.seg.long_count = cv.take<uint32_t>(64);
+  }
+  return (cv.off + ALIGN - 1) / ALIGN * ALIGN;
+}
+
+static ss_ctx* make_ctx(const ss_config* c) {
+  ss_ctx* x = new ss_ctx(c->num_replicas);
+  x->T = c->num_tables; x->d = c->emb_dim; x->num_dense = c->num_dense;
+  x->K = c->num_replicas; x->max_batch = c->max_batch; x->max_ids = c->max_ids;
+  x->num_slots = c->num_worker_slots; x->prec = c->mlp_prec;
+  x->lr_dense = c->lr_dense; x->lr_emb = c->lr_emb; x->eps = c->adagrad_eps; x->seed = c->seed;
+  x->rows.assign(c->rows, c->rows + c->num_tables);
+  uint64_t base = 0;
+  memset(&x->meta, 0, sizeof x->meta);
+  for (int t = 0; t < x->T; ++t) { x->meta.row_base[t] = (uint32_t)base; base += (uint64_t)x->rows[t]; }
+  x->meta.row_base[x->T] = (uint32_t)base;
+  x->total_rows = base;
+  x->key_bits = 1;
+  while ((1ull << x->key_bits) < base) ++x->key_bits;
+  int64_t off = 0;
+  int maxw = 1;
+  auto add = [&](const int32_t* dims, int n) {
+    for (int i = 0; i + 1 < n; ++i) {
+      Layer l; l.in = dims[i]; l.out = dims[i + 1];
+      l.w_off = off; off += (int64_t)l.in * l.out;
+      l.b_off = off; off += l.out;
+      x->layers.push_back(l);
+      if (l.in > maxw) maxw = l.in;
+      if (l.out > maxw) maxw = l.out;
+    }
+  };
+  add(c->bot_dims, c->n_bot);
+  add(c->top_dims, c->n_top);
+  x->n_bot_layers = c->n_bot - 1; x->n_top_layers = c->n_top - 1;
+  x->P = off;
+  x->Pstride = (off + 255) / 256 * 256;
+  x->F = c->top_dims[0];
+  x->ldf = (x->F + 7) / 8 * 8;
+  x->ldf16 = (x->F + 7) / 8 * 8;
+  x->maxw = maxw;
+  x->slots.resize(x->num_slots);
+  return x;
+}
+
+// ------------------------------------------------------------------------------------------
+extern "C" {
+
+size_t ss_workspace_bytes(const ss_config* cfg) {
+  std::string why;
+  if (validate(cfg, why) != SS_OK) { g_init_err = why; return 0; }
+  ss_ctx* x = make_ctx(cfg);
+  size_t bytes = layout(x, nullptr);
+  delete x;
+  return bytes;
+}
+
+int ss_init(const ss_config* cfg, void* dev_workspace, size_t bytes, ss_ctx** out) {
+  if (!out) return fail(nullptr, SS_EINVAL, "null out pointer");
+  *out = nullptr;
+  std::string why;
+  if (validate(cfg, why) != SS_OK) return fail(nullptr, SS_EINVAL, "%s", why.c_str());
+  if (!dev_workspace || ((uintptr_t)dev_workspace % ALIGN) != 0)
+    return fail(nullptr, SS_EINVAL, "workspace must be non-null and %zu-byte aligned", ALIGN);
+  ss_ctx* x = make_ctx(cfg);
+  const size_t need = layout(x, dev_workspace);
+  if (bytes < need) {
+    delete x;
+    return fail(nullptr, SS_ENOMEM, "workspace too small: %zu bytes given, %zu needed", bytes, need);
+  }
+  hipError_t e = hipGetDevice(&x->device);
+  if (e != hipSuccess) {
+    delete x;
+    return fail(nullptr, SS_EDEVICE, "hipGetDevice: %s", hipGetErrorString(e));
+  }
+  // optimiser state and momentum start at zero (Algorithm 1 initialisation)
+  launch_fill_f32(x->G, x->total_rows, 0.f, nullptr);
+  launch_fill_f32(x->v, (uint64_t)x->Pstride, 0.f, nullptr);
+  launch_fill_f32(x->W, (uint64_t)x->K * x->Pstride, 0.f, nullptr);
+  launch_fill_f32(x->w_ps, (uint64_t)x->Pstride, 0.f, nullptr);
+  launch_fill_f32(x->w_global, (uint64_t)x->Pstride, 0.f, nullptr);
+  for (Slot& s : x->slots) launch_fill_f32(s.grads, (uint64_t)x->Pstride, 0.f, nullptr);
+  e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    delete x;
+    return fail(nullptr, SS_EDEVICE, "init kernels: %s", hipGetErrorString(e));
+  }
+  *out = x;
+  return SS_OK;
+}
+
+void ss_destroy(ss_ctx* ctx) {
+  if (!ctx) return;
+  ss_shadow_stop(ctx);
+  (void)hipDeviceSynchronize();
+  for (auto& p : ctx->prof_events) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+  delete ctx;
+}
+
+const char* ss_last_error(const ss_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_err.c_str(); }
+
+int64_t ss_num_params(const ss_ctx* ctx) { return ctx ? ctx->P : -1; }
+
+int ss_init_tables_hash(ss_ctx* ctx, void* stream) {
+  if (!ctx) return SS_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  for (int t = 0; t < ctx->T; ++t)
+    launch_table_hash_init(ctx->h + (size_t)ctx->meta.row_base[t] * ctx->d,
+                           (uint64_t)ctx->rows[t] * ctx->d, ctx->seed, t, s);
+  launch_fill_f32(ctx->G, ctx->total_rows, 0.f, s);
+  return check_hip(ctx, hipGetLastError(), "table init");
+}
+
+int ss_write_rows(ss_ctx* ctx, int32_t table, int64_t first_row, int64_t n_rows,
+                  const float* host_rows) {
+  if (!ctx) return SS_EINVAL;
+  if (table < 0 || table >= ctx->T || first_row < 0 || n_rows < 0 ||
+      first_row + n_rows > ctx->rows[table] || (!host_rows && n_rows))
+    return fail(ctx, SS_EINVAL, "ss_write_rows: bad table/row range");
+  if (n_rows == 0) return SS_OK;
+  const size_t r0 = (size_t)ctx->meta.row_base[table] + first_row;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemcpy(ctx->h + r0 * ctx->d, host_rows, (size_t)n_rows * ctx->d * sizeof(float),
+                         hipMemcpyHostToDevice));
+  launch_fill_f32(ctx->G + r0, (uint64_t)n_rows, 0.f, nullptr);
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  return SS_OK;
+}
+
+static float* dense_ptr(ss_ctx* ctx, int which) {
+  if (which >= 0 && which < ctx->K) return ctx->W + (size_t)which * ctx->Pstride;
+  if (which == -1) return ctx->w_ps;
+  if (which == -2) return ctx->w_global;
+  if (which == -3) return ctx->v;
+  return nullptr;
+}
+
+int ss_init_dense(ss_ctx* ctx, const float* host_w0) {
+  if (!ctx || !host_w0) return SS_EINVAL;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  for (int which = -2; which < ctx->K; ++which)
+    HIP_TRY(ctx, hipMemcpy(dense_ptr(ctx, which), host_w0, (size_t)ctx->P * sizeof(float),
+                           hipMemcpyHostToDevice));
+  launch_fill_f32(ctx->v, (uint64_t)ctx->Pstride, 0.f, nullptr);
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  return SS_OK;
+}
+
+int ss_read_dense(ss_ctx* ctx, int32_t which, float* host_out, int64_t n) {
+  if (!ctx || !host_out) return SS_EINVAL;
+  float* p = dense_ptr(ctx, which);
+  if (!p || n != ctx->P) return fail(ctx, SS_EINVAL, "ss_read_dense: bad selector or length");
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemcpy(host_out, p, (size_t)n * sizeof(float), hipMemcpyDeviceToHost));
+  return SS_OK;
+}
+
+int ss_write_dense(ss_ctx* ctx, int32_t which, const float* host_in, int64_t n) {
+  if (!ctx || !host_in) return SS_EINVAL;
+  float* p = dense_ptr(ctx, which);
+  if (!p || n != ctx->P) return fail(ctx, SS_EINVAL, "ss_write_dense: bad selector or length");
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemcpy(p, host_in, (size_t)n * sizeof(float), hipMemcpyHostToDevice));
+  return SS_OK;
+}
+
+int ss_read_rows(ss_ctx* ctx, int32_t table, const int64_t* rows, int64_t n, float* host_rows_out,
+                 float* host_adagrad_out) {
+  if (!ctx || (!rows && n)) return SS_EINVAL;
+  if (table < 0 || table >= ctx->T || n < 0) return fail(ctx, SS_EINVAL, "ss_read_rows: bad table");
+  for (int64_t i = 0; i < n; ++i)
+    if (rows[i] < 0 || rows[i] >= ctx->rows[table])
+      return fail(ctx, SS_EINVAL, "ss_read_rows: row %lld out of range", (long long)rows[i]);
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  const size_t base = ctx->meta.row_base[table];
+  // contiguous runs are copied in one piece
+  int64_t i = 0;
+  while (i < n) {
+    int64_t j = i + 1;
+    while (j < n && rows[j] == rows[j - 1] + 1) ++j;
+    const size_t r = base + (size_t)rows[i];
+    if (host_rows_out)
+      HIP_TRY(ctx, hipMemcpy(host_rows_out + (size_t)i * ctx->d, ctx->h + r * ctx->d,
+                             (size_t)(j - i) * ctx->d * sizeof(float), hipMemcpyDeviceToHost));
+    if (host_adagrad_out)
+      HIP_TRY(ctx, hipMemcpy(host_adagrad_out + i, ctx->G + r, (size_t)(j - i) * sizeof(float),
+                             hipMemcpyDeviceToHost));
+    i = j;
+  }
+  return SS_OK;
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------
+// Event brackets around one kernel class.
+namespace {
+struct ProfScope {
+  ss_ctx* x; hipStream_t s; hipEvent_t stop = nullptr;
+  ProfScope(ss_ctx* ctx, int id, hipStream_t st) : x(ctx), s(st) {
+    if (x->prof_kernel != id) return;
+    std::lock_guard<std::mutex> lk(x->prof_mu);
+    if (x->prof_kernel != id || x->prof_used >= x->prof_events.size()) return;
+    auto& p = x->prof_events[x->prof_used++];
+    (void)hipEventRecord(p.first, s);
+    stop = p.second;
+  }
+  ~ProfScope() { if (stop) (void)hipEventRecord(stop, s); }
+};
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// One worker iteration.
+static int check_batch(ss_ctx* x, int replica, int slot, const ss_batch* b) {
+  if (!b) return fail(x, SS_EINVAL, "null batch");
+  if (x->sticky) return SS_EDEVICE;
+  if (replica < 0 || replica >= x->K) return fail(x, SS_EINVAL, "replica %d out of range", replica);
+  if (slot < 0 || slot >= x->num_slots) return fail(x, SS_EINVAL, "worker slot %d out of range", slot);
+  if (b->batch < 1 || b->batch > x->max_batch)
+    return fail(x, SS_EINVAL, "batch %d outside 1..%d", b->batch, x->max_batch);
+  if (b->num_ids < 0 || b->num_ids > x->max_ids)
+    return fail(x, SS_EINVAL, "num_ids %lld outside 0..%lld", (long long)b->num_ids, (long long)x->max_ids);
+  if (!b->dense || !b->labels || !b->offsets || (!b->indices && b->num_ids))
+    return fail(x, SS_EINVAL, "null batch buffer");
+  return SS_OK;
+}
+
+static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipStream_t st) {
+  const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
+  const bool bf = x->prec == SS_BF16;
+  // ---- bottom MLP
+  {
+    ProfScope ps(x, SS_K_MLP, st);
+    const void* in = bt->dense; int ld_in = x->num_dense; bool in_f32 = true;
+    for (int l = 0; l < nb; ++l) {
+      const Layer& ly = x->layers[l];
+      const bool last = (l == nb - 1);
+      if (!bf) {
+        float* out = last ? s.z0 : s.act_f32[l];
+        launch_gemm_f32((const float*)in, ld_in, 1, w + ly.w_off, 1, ly.in, out, ly.out, B, ly.out,
+                        ly.in, EPI_BIAS | EPI_RELU, w + ly.b_off, nullptr, 0, st);
+        in = out; ld_in = ly.out;
+      } else {
+        GemmBf16Args a{};
+        a.A = in; a.a_is_f32 = in_f32; a.lda = ld_in; a.a_kcontig = 1;
+        a.B = w + ly.w_off; a.b_is_f32 = 1; a.ldb = ly.in; a.b_kcontig = 1;
+        a.M = B; a.N = ly.out; a.K = ly.in; a.ldc = ly.out;
+        a.epi = EPI_BIAS | EPI_RELU; a.bias = w + ly.b_off; a.split_k = 1;
+        if (last) a.C_f32 = s.z0; else a.C_bf16 = s.act_bf16[l];
+        launch_gemm_bf16(a, st);
+        in = last ? (const void*)s.z0 : (const void*)s.act_bf16[l];
+        ld_in = ly.out; in_f32 = last;
+      }
+    }
+  }
+  // ---- look-ups (pooled where the table lives) and interaction
+  {
+    ProfScope ps(x, SS_K_GATHER, st);
+    launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e, s.keys,
+                             s.bag_of_pos, st);
+  }
+  {
+    ProfScope ps(x, SS_K_INTERACT, st);
+    launch_interaction_fwd(s.z0, s.e, B, x->T, x->d, s.f, x->ldf, s.f_bf16, x->ldf16, st);
+  }
+  // ---- top MLP
+  {
+    ProfScope ps(x, SS_K_MLP, st);
+    const void* in = bf ? (const void*)s.f_bf16 : (const void*)s.f;
+    int ld_in = bf ? x->ldf16 : x->ldf;
+    for (int l = nb; l < L; ++l) {
+      const Layer& ly = x->layers[l];
+      const bool last = (l == L - 1);
+      const int epi = last ? EPI_BIAS : (EPI_BIAS | EPI_RELU);
+      if (!bf) {
+        float* out = last ? s.logits : s.act_f32[l];
+        launch_gemm_f32((const float*)in, ld_in, 1, w + ly.w_off, 1, ly.in, out, ly.out, B, ly.out,
+                        ly.in, epi, w + ly.b_off, nullptr, 0, st);
+        in = out; ld_in = ly.out;
+      } else {
+        GemmBf16Args a{};
+        a.A = in; a.a_is_f32 = 0; a.lda = ld_in; a.a_kcontig = 1;
+        a.B = w + ly.w_off; a.b_is_f32 = 1; a.ldb = ly.in; a.b_kcontig = 1;
+        a.M = B; a.N = ly.out; a.K = ly.in; a.ldc = ly.out;
+        a.epi = epi; a.bias = w + ly.b_off; a.split_k = 1;
+        if (last) a.C_f32 = s.logits; else a.C_bf16 = s.act_bf16[l];
+        launch_gemm_bf16(a, st);
+        in = s.act_bf16[l]; ld_in = ly.out;
+      }
+    }
+  }
+}
+
+static int choose_split(int M, int N, int K) {
+  const int tiles = ceil_div(M, 64) * ceil_div(N, 64);
+  if (tiles >= 128 || K < 512) return 1;
+  int split = ceil_div(256, tiles);
+  const int max_split = K / 128;
+  if (split > max_split) split = max_split;
+  return split < 1 ? 1 : split;
+}
+
+static void backward_dense(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipStream_t st) {
+  const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
+  const bool bf = x->prec == SS_BF16;
+  // input activation of layer l and its layout
+  auto layer_in = [&](int l, const void*& p, int& ld, bool& f32) {
+    if (l == 0) { p = bt->dense; ld = x->num_dense; f32 = true; }
+    else if (l == nb) { p = bf ? (const void*)s.f_bf16 : (const void*)s.f; ld = bf ? x->ldf16 : x->ldf; f32 = !bf; }
+    else { p = bf ? (const void*)s.act_bf16[l - 1] : (const void*)s.act_f32[l - 1]; ld = x->layers[l - 1].out; f32 = !bf; }
+  };
+  auto run_layers = [&](int l_hi, int l_lo, const void* d0, int ldd0, bool d0_f32) {
+    const void* dcur = d0; int ldd = ldd0; bool d_f32 = d0_f32; int pp = 0;
+    for (int l = l_hi; l >= l_lo; --l) {
+      const Layer& ly = x->layers[l];
+      const void* xin; int ldx; bool x_f32;
+      layer_in(l, xin, ldx, x_f32);
+      float* gW = s.grads + ly.w_off; float* gb = s.grads + ly.b_off;
+      const bool need_dx = (l != 0);
+      const bool to_df = (l == nb);            // gradient w.r.t. the interaction output
+      if (!bf) {
+        launch_gemm_f32((const float*)dcur, 1, ldd, (const float*)xin, ldx, 1, gW, ly.in, ly.out,
+                        ly.in, B, EPI_NONE, nullptr, nullptr, 0, st);
+        launch_col_sum_f32((const float*)dcur, ldd, B, ly.out, gb, st);
+        if (need_dx) {
+          float* out = to_df ? s.df : s.dbuf[pp];
+          const int ldo = to_df ? x->ldf : ly.in;
+          launch_gemm_f32((const float*)dcur, ldd, 1, w + ly.w_off, ly.in, 1, out, ldo, B, ly.in,
+                          ly.out, to_df ? EPI_NONE : EPI_MASK, nullptr,
+                          to_df ? nullptr : (const float*)xin, ldx, st);
+          dcur = out; ldd = ldo; pp ^= 1;
+        }
+      } else {
+        GemmBf16Args a{};
+        a.A = dcur; a.a_is_f32 = d_f32; a.lda = ldd; a.a_kcontig = 0;
+        a.B = xin; a.b_is_f32 = x_f32; a.ldb = ldx; a.b_kcontig = 0;
+        a.M = ly.out; a.N = ly.in; a.K = B; a.C_f32 = gW; a.ldc = ly.in; a.epi = EPI_NONE;
+        a.split_k = choose_split(ly.out, ly.in, B);
+        launch_gemm_bf16(a, st);
+        if (d_f32) launch_col_sum_f32((const float*)dcur, ldd, B, ly.out, gb, st);
+        else launch_col_sum_bf16((const uint16_t*)dcur, ldd, B, ly.out, gb, st);
+        if (need_dx) {
+          GemmBf16Args g{};
+          g.A = dcur; g.a_is_f32 = d_f32; g.lda = ldd; g.a_kcontig = 1;
+          g.B = w + ly.w_off; g.b_is_f32 = 1; g.ldb = ly.in; g.b_kcontig = 0;
+          g.M = B; g.N = ly.in; g.K = ly.out; g.split_k = 1;
+          if (to_df) { g.C_f32 = s.df; g.ldc = x->ldf; g.epi = EPI_NONE; }
+          else {
+            g.C_bf16 = s.dbuf16[pp]; g.ldc = ly.in; g.epi = EPI_MASK;
+            g.mask = (const uint16_t*)xin; g.ldmask = ldx;
+          }
+          launch_gemm_bf16(g, st);
+          if (to_df) { dcur = s.df; ldd = x->ldf; d_f32 = true; }
+          else { dcur = s.dbuf16[pp]; ldd = ly.in; d_f32 = false; pp ^= 1; }
+        }
+      }
+    }
+  };
+  {
+    ProfScope ps(x, SS_K_MLP, st);
+    if (bf) launch_fill_f32(s.grads, (uint64_t)x->P, 0.f, st);  // split-K accumulates atomically
+    run_layers(L - 1, nb, s.dlogit, 1, true);
+  }
+  {
+    ProfScope ps(x, SS_K_INTERACT, st);
+    launch_interaction_bwd(s.z0, s.e, s.df, x->ldf, B, x->T, x->d, s.dz0, s.de, st);
+  }
+  {
+    ProfScope ps(x, SS_K_MLP, st);
+    run_layers(nb - 1, 0, s.dz0, x->d, true);
+  }
+}
+
+static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, void* stream,
+                         float* dev_loss_out, bool train) {
+  if (!x) return SS_EINVAL;
+  int rc = check_batch(x, replica, slot, bt);
+  if (rc != SS_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  Slot& s = x->slots[slot];
+  float* w = x->W + (size_t)replica * x->Pstride;
+  const int B = bt->batch;
+  const uint32_t n = (uint32_t)bt->num_ids;
+  forward(x, s, w, bt, st);
+  float* loss = dev_loss_out ? dev_loss_out : s.loss;
+  launch_bce_loss(s.logits, bt->labels, B, loss, train ? s.dlogit : nullptr, st);
+  s.last_B = B;
+  s.last_n = n;
+  if (train) {
+    backward_dense(x, s, w, bt, st);
+    // "update local param w^(i)": lock-free SGD on the replica
+    launch_sgd(w, s.grads, x->P, x->lr_dense, st);
+    // "update h": stable sort by row, one Adagrad update per distinct row
+    {
+      ProfScope ps(x, SS_K_SORT, st);
+      launch_sort_pairs(s.keys, n, x->key_bits, s.sort, &s.sorted_keys, &s.sorted_pos, st);
+      launch_segment_starts(s.sorted_keys, n, s.seg, st);
+    }
+    {
+      ProfScope ps(x, SS_K_ROW_UPDATE, st);
+      launch_row_update(s.sorted_keys, s.sorted_pos, s.bag_of_pos, s.de, n, s.seg, x->d, x->h, x->G,
+                        x->lr_emb, x->eps, st);
+    }
+    x->steps[replica].fetch_add(1);
+    x->examples.fetch_add((uint64_t)B);
+  }
+  return check_hip(x, hipGetLastError(), train ? "ss_train_step" : "ss_eval_step");
+}
+
+extern "C" {
+
+int ss_train_step(ss_ctx* ctx, int32_t replica, int32_t worker_slot, const ss_batch* batch,
+                  void* stream, float* dev_loss_out) {
+  return train_or_eval(ctx, replica, worker_slot, batch, stream, dev_loss_out, true);
+}
+
+int ss_eval_step(ss_ctx* ctx, int32_t replica, int32_t worker_slot, const ss_batch* batch,
+                 void* stream, float* dev_loss_out) {
+  return train_or_eval(ctx, replica, worker_slot, batch, stream, dev_loss_out, false);
+}
+
+// ------------------------------------------------------------------------------------------
+int ss_sync_round(int32_t algo, int32_t K, int64_t P, int64_t stride, float* dev_replicas,
+                  float* dev_w_ps, float* dev_w_global, float* dev_v, float alpha, float eta,
+                  float momentum, void* stream) {
+  if (algo < SS_EASGD || algo > SS_EASGD_LITERAL || K < 1 || K > 16 || P < 1 || (P & 3) ||
+      stride < P || (stride & 3) || !dev_replicas)
+    return SS_EINVAL;
+  const bool easgd = (algo == SS_EASGD || algo == SS_EASGD_LITERAL);
+  if (easgd && !dev_w_ps) return SS_EINVAL;
+  if (!easgd && !dev_w_global) return SS_EINVAL;
+  if (algo == SS_BMUF && !dev_v) return SS_EINVAL;
+  uintptr_t al = (uintptr_t)dev_replicas | (uintptr_t)dev_w_ps | (uintptr_t)dev_w_global |
+                 (uintptr_t)dev_v;
+  if (al & 15) return SS_EINVAL;
+  launch_sync_round(algo, K, P, stride, dev_replicas, dev_w_ps, dev_w_global, dev_v, alpha, eta,
+                    momentum, (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? SS_OK : SS_EDEVICE;
+}
+
+static int sync_once(ss_ctx* x, int algo, float alpha, float eta, float mu, hipStream_t st) {
+  {
+    ProfScope ps(x, SS_K_SYNC, st);
+    // vectors are padded to Pstride (multiple of 256 floats); the pad is carried along
+    launch_sync_round(algo, x->K, x->Pstride, x->Pstride, x->W, x->w_ps, x->w_global, x->v, alpha,
+                      eta, mu, st);
+  }
+  x->rounds.fetch_add(1);
+  return check_hip(x, hipGetLastError(), "ss_shadow_sync");
+}
+
+int ss_shadow_sync(ss_ctx* ctx, int32_t algo, float alpha, float eta, float momentum, void* stream) {
+  if (!ctx) return SS_EINVAL;
+  if (ctx->sticky) return SS_EDEVICE;
+  if (algo < SS_EASGD || algo > SS_EASGD_LITERAL) return fail(ctx, SS_EINVAL, "unknown sync rule %d", algo);
+  if (ctx->shadow_run) return fail(ctx, SS_ESTATE, "shadow loop is running");
+  return sync_once(ctx, algo, alpha, eta, momentum, (hipStream_t)stream);
+}
+
+int ss_shadow_start(ss_ctx* ctx, int32_t algo, float alpha, float eta, float momentum, void* stream) {
+  if (!ctx) return SS_EINVAL;
+  if (algo < SS_EASGD || algo > SS_EASGD_LITERAL) return fail(ctx, SS_EINVAL, "unknown sync rule %d", algo);
+  if (ctx->shadow_run.exchange(true)) return fail(ctx, SS_ESTATE, "shadow loop already running");
+  hipStream_t st = (hipStream_t)stream;
+  ctx->shadow = std::thread([ctx, algo, alpha, eta, momentum, st]() {
+    if (hipSetDevice(ctx->device) != hipSuccess) { ctx->sticky = 1; return; }
+    // "simply looping the synchronization without any knowledge of the training process"
+    while (ctx->shadow_run.load()) {
+      if (sync_once(ctx, algo, alpha, eta, momentum, st) != SS_OK) break;
+      if (hipStreamSynchronize(st) != hipSuccess) { ctx->sticky = 1; break; }
+    }
+  });
+  return SS_OK;
+}
+
+int ss_shadow_stop(ss_ctx* ctx) {
+  if (!ctx) return SS_EINVAL;
+  if (!ctx->shadow_run.exchange(false)) {
+    if (ctx->shadow.joinable()) ctx->shadow.join();
+    return SS_OK;
+  }
+  if (ctx->shadow.joinable()) ctx->shadow.join();
+  return ctx->sticky ? SS_EDEVICE : SS_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out, size_t bytes,
+                  size_t* size_out) {
+  if (!ctx) return SS_EINVAL;
+  if (worker_slot < 0 || worker_slot >= ctx->num_slots) return fail(ctx, SS_EINVAL, "bad slot");
+  Slot& s = ctx->slots[worker_slot];
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  const size_t B = (size_t)s.last_B, n = s.last_n;
+  const void* src = nullptr; size_t size = 0; size_t pitch_src = 0, width = 0, rows = 0;
+  uint32_t U = 0;
+  if (item == SS_DBG_SEG_STARTS || item == SS_DBG_NUM_UNIQUE)
+    HIP_TRY(ctx, hipMemcpy(&U, s.seg.num_unique, 4, hipMemcpyDeviceToHost));
+  switch (item) {
+    case SS_DBG_POOLED: src = s.e; size = B * ctx->T * ctx->d * 4; break;
+    case SS_DBG_INTERACT: src = s.f; rows = B; width = (size_t)ctx->F * 4; pitch_src = (size_t)ctx->ldf * 4; size = rows * width; break;
+    case SS_DBG_LOGITS: src = s.logits; size = B * 4; break;
+    case SS_DBG_DENSE_GRAD: src = s.grads; size = (size_t)ctx->P * 4; break;
+    case SS_DBG_POOLED_GRAD: src = s.de; size = B * ctx->T * ctx->d * 4; break;
+    case SS_DBG_SORTED_ROWS: src = s.sorted_keys; size = n * 4; break;
+    case SS_DBG_SORTED_POS: src = s.sorted_pos; size = n * 4; break;
+    case SS_DBG_SEG_STARTS: src = s.seg.seg_starts; size = (size_t)U * 4; break;
+    case SS_DBG_NUM_UNIQUE: src = s.seg.num_unique; size = 4; break;
+    case SS_DBG_BAG_OF_POS: src = s.bag_of_pos; size = n * 4; break;
+    default: return fail(ctx, SS_EINVAL, "unknown debug item %d", item);
+  }
+  if (size_out) *size_out = size;
+  if (!host_out || bytes == 0 || size == 0) return SS_OK;
+  if (!src) return fail(ctx, SS_ESTATE, "no step has run on this slot yet");
+  if (rows) {
+    if (bytes < size) return fail(ctx, SS_EINVAL, "buffer too small for a strided item");
+    HIP_TRY(ctx, hipMemcpy2D(host_out, width, src, pitch_src, width, rows, hipMemcpyDeviceToHost));
+  } else {
+    HIP_TRY(ctx, hipMemcpy(host_out, src, bytes < size ? bytes : size, hipMemcpyDeviceToHost));
+  }
+  return SS_OK;
+}
+
+int ss_get_counters(ss_ctx* ctx, uint64_t* steps_per_replica, uint64_t* rounds, uint64_t* examples) {
+  if (!ctx) return SS_EINVAL;
+  if (steps_per_replica)
+    for (int i = 0; i < ctx->K; ++i) steps_per_replica[i] = ctx->steps[i].load();
+  if (rounds) *rounds = ctx->rounds.load();
+  if (examples) *examples = ctx->examples.load();
+  return SS_OK;
+}
+
+int ss_profile_arm(ss_ctx* ctx, int32_t kernel_id) {
+  if (!ctx) return SS_EINVAL;
+  if (kernel_id < SS_K_NONE || kernel_id > SS_K_INTERACT) return fail(ctx, SS_EINVAL, "bad kernel id");
+  std::lock_guard<std::mutex> lk(ctx->prof_mu);
+  if (ctx->prof_events.empty()) {
+    ctx->prof_events.resize(8192);
+    for (auto& p : ctx->prof_events) {
+      HIP_TRY(ctx, hipEventCreate(&p.first));
+      HIP_TRY(ctx, hipEventCreate(&p.second));
+    }
+  }
+  ctx->prof_used = 0;
+  ctx->prof_kernel = kernel_id;
+  return SS_OK;
+}
+
+int ss_profile_read(ss_ctx* ctx, int64_t* launches, double* total_ms) {
+  if (!ctx) return SS_EINVAL;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  std::lock_guard<std::mutex> lk(ctx->prof_mu);
+  double tot = 0;
+  for (size_t i = 0; i < ctx->prof_used; ++i) {
+    float ms = 0;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->prof_events[i].first, ctx->prof_events[i].second));
+    tot += ms;
+  }
+  if (launches) *launches = (int64_t)ctx->prof_used;
+  if (total_ms) *total_ms = tot;
+  ctx->prof_kernel = SS_K_NONE;
+  ctx->prof_used = 0;
+  return SS_OK;
+}
+
+}  // extern "C"

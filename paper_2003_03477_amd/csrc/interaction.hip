@@ -1,0 +1,156 @@
+// Pairwise-dot feature interaction, forward and backward (gfx950).
+// Per sample the T+1 vectors V = [z0; e_0; ...; e_{T-1}] (d floats each) are staged in LDS
+// by one wavefront; the forward emits z0 followed by <V_r, V_c> for the strictly lower
+// triangle in row-major order, the backward applies the product rule
+// dV_r = sum_{c != r} S[r][c] V_c with S the symmetric matrix of incoming pair gradients.
+// This is the "feature interaction" component between the bottom and top networks of the
+// model reviewed in Section 3.1; it is bandwidth-bound work (Section 4.3 notes these ops are
+// what saturates a trainer's memory bandwidth), so it stays on the vector ALUs in fp32.
+#include "ss_internal.h"
+
+namespace ss {
+
+constexpr int IPAD = 4;  // LDS row padding in floats (keeps float4 alignment)
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// r(r-1)/2 <= p < r(r+1)/2  ->  pair p is (r, c = p - r(r-1)/2), r >= 1
+__device__ __forceinline__ void pair_of(int p, int& r, int& c) {
+  int rr = (int)((1.0f + sqrtf(1.0f + 8.0f * (float)p)) * 0.5f);
+  while (rr * (rr - 1) / 2 > p) --rr;
+  while (rr * (rr + 1) / 2 <= p) ++rr;
+  r = rr;
+  c = p - rr * (rr - 1) / 2;
+}
+
+__device__ __forceinline__ void stage_V(float* Vs, const float* __restrict__ z0,
+                                        const float* __restrict__ e, int b, int T, int d,
+                                        int lane) {
+  const int ld = d + IPAD;
+  const int vec_per_row = d / 4;
+  const int total = (T + 1) * vec_per_row;
+  for (int i = lane; i < total; i += SS_WAVE) {
+    const int r = i / vec_per_row, k4 = i - r * vec_per_row;
+    const float* src = (r == 0) ? (z0 + (size_t)b * d) : (e + ((size_t)b * T + (r - 1)) * d);
+    *(float4*)(Vs + r * ld + 4 * k4) = *(const float4*)(src + 4 * k4);
+  }
+}
+
+__global__ __launch_bounds__(256) void interaction_fwd_kernel(
+    const float* __restrict__ z0, const float* __restrict__ e, int B, int T, int d,
+    float* __restrict__ f, int ldf, uint16_t* __restrict__ f_bf16, int ldf_bf16) {
+  extern __shared__ float smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ld = d + IPAD;
+  float* Vs = smem + (size_t)wave * (T + 1) * ld;
+  const int npairs = T * (T + 1) / 2;
+  const int F = d + npairs;
+  for (int b0 = blockIdx.x * 4; b0 < B; b0 += gridDim.x * 4) {
+    const int b = b0 + wave;
+    if (b < B) stage_V(Vs, z0, e, b, T, d, lane);
+    __syncthreads();
+    if (b < B) {
+      for (int k = lane; k < d; k += SS_WAVE) {
+        const float v = Vs[k];
+        if (f) f[(size_t)b * ldf + k] = v;
+        if (f_bf16) f_bf16[(size_t)b * ldf_bf16 + k] = f32_to_bf16(v);
+      }
+      for (int p = lane; p < npairs; p += SS_WAVE) {
+        int r, c;
+        pair_of(p, r, c);
+        const float4* vr = (const float4*)(Vs + r * ld);
+        const float4* vc = (const float4*)(Vs + c * ld);
+        float4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int k4 = 0; k4 < d / 4; ++k4) {
+          const float4 x = vr[k4], y = vc[k4];
+          acc.x += x.x * y.x; acc.y += x.y * y.y; acc.z += x.z * y.z; acc.w += x.w * y.w;
+        }
+        const float dot = (acc.x + acc.y) + (acc.z + acc.w);
+        if (f) f[(size_t)b * ldf + d + p] = dot;
+        if (f_bf16) f_bf16[(size_t)b * ldf_bf16 + d + p] = f32_to_bf16(dot);
+      }
+      if (f_bf16)
+        for (int k = F + lane; k < ldf_bf16; k += SS_WAVE) f_bf16[(size_t)b * ldf_bf16 + k] = 0;
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void interaction_bwd_kernel(
+    const float* __restrict__ z0, const float* __restrict__ e, const float* __restrict__ df,
+    int lddf, int B, int T, int d, float* __restrict__ dz0, float* __restrict__ de) {
+  extern __shared__ float smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ld = d + IPAD;
+  const int n1 = T + 1;
+  float* Vs = smem + (size_t)wave * (n1 * ld + ((n1 * n1 + 3) & ~3));  // float4-aligned regions
+  float* Ss = Vs + n1 * ld;
+  const int npairs = T * (T + 1) / 2;
+  const int vec_per_row = d / 4;
+  for (int b0 = blockIdx.x * 4; b0 < B; b0 += gridDim.x * 4) {
+    const int b = b0 + wave;
+    if (b < B) {
+      stage_V(Vs, z0, e, b, T, d, lane);
+      for (int i = lane; i < n1; i += SS_WAVE) Ss[i * n1 + i] = 0.f;
+      for (int p = lane; p < npairs; p += SS_WAVE) {
+        int r, c;
+        pair_of(p, r, c);
+        const float s = df[(size_t)b * lddf + d + p];
+        Ss[r * n1 + c] = s;
+        Ss[c * n1 + r] = s;
+      }
+    }
+    __syncthreads();
+    if (b < B) {
+      for (int i = lane; i < n1 * vec_per_row; i += SS_WAVE) {
+        const int r = i / vec_per_row, k4 = i - r * vec_per_row;
+        float4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < n1; ++c) {
+          const float s = Ss[r * n1 + c];
+          const float4 v = *(const float4*)(Vs + c * ld + 4 * k4);
+          acc.x += s * v.x; acc.y += s * v.y; acc.z += s * v.z; acc.w += s * v.w;
+        }
+        if (r == 0) {
+          const float4 pass = *(const float4*)(df + (size_t)b * lddf + 4 * k4);
+          const float4 z = *(const float4*)(Vs + 4 * k4);
+          float4 o;  // gradient w.r.t. the bottom MLP's last pre-activation: ReLU gate
+          o.x = z.x > 0.f ? acc.x + pass.x : 0.f;
+          o.y = z.y > 0.f ? acc.y + pass.y : 0.f;
+          o.z = z.z > 0.f ? acc.z + pass.z : 0.f;
+          o.w = z.w > 0.f ? acc.w + pass.w : 0.f;
+          *(float4*)(dz0 + (size_t)b * d + 4 * k4) = o;
+        } else {
+          *(float4*)(de + ((size_t)b * T + (r - 1)) * d + 4 * k4) = acc;
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+void launch_interaction_fwd(const float* z0, const float* e, int B, int T, int d, float* f,
+                            int ldf, uint16_t* f_bf16, int ldf_bf16, hipStream_t s) {
+  if (B == 0) return;
+  const size_t shm = (size_t)4 * (T + 1) * (d + IPAD) * sizeof(float);
+  int blocks = ceil_div(B, 4);
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(interaction_fwd_kernel, dim3(blocks), dim3(256), shm, s, z0, e, B, T, d, f,
+                     ldf, f_bf16, ldf_bf16);
+}
+
+void launch_interaction_bwd(const float* z0, const float* e, const float* df, int lddf, int B,
+                            int T, int d, float* dz0, float* de, hipStream_t s) {
+  if (B == 0) return;
+  const int n1 = T + 1;
+  const size_t shm = (size_t)4 * (n1 * (d + IPAD) + ((n1 * n1 + 3) & ~3)) * sizeof(float);
+  int blocks = ceil_div(B, 4);
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(interaction_bwd_kernel, dim3(blocks), dim3(256), shm, s, z0, e, df, lddf, B,
+                     T, d, dz0, de);
+}
+
+}  // namespace ss

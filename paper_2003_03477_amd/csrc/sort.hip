@@ -1,0 +1,191 @@
+// Stable LSD radix sort of (global row, flat position) pairs, 8 bits per pass (gfx950).
+// The embedding backward needs every distinct row's occurrences side by side and in
+// ascending flat position, so equal keys must keep their input order: each pass is
+// histogram -> per-digit scan over blocks -> stable scatter.
+//
+// A block owns a contiguous tile of 256*rounds elements; wave w of the block owns the w-th
+// quarter of the tile and walks it 64 elements at a time, so "earlier in the tile" is
+// (wave, round, lane) order.  Ranks among equal digits inside a wave come from 8 ballots
+// (one per digit bit); running per-wave digit counts live in LDS.
+#include "ss_internal.h"
+
+namespace ss {
+
+constexpr int RADIX_BITS = 8;
+constexpr int RADIX = 1 << RADIX_BITS;
+constexpr int SORT_THREADS = 256;
+constexpr int SORT_WAVES = SORT_THREADS / SS_WAVE;
+constexpr int MAX_ROUNDS = 16;
+
+int sort_num_blocks(uint32_t n, int* rounds_out) {
+  // aim at >= 512 blocks once there is enough work, tiles of at most 4096 elements
+  int rounds = (int)((n + 512u * SORT_THREADS - 1) / (512u * SORT_THREADS));
+  if (rounds < 1) rounds = 1;
+  if (rounds > MAX_ROUNDS) rounds = MAX_ROUNDS;
+  if (rounds_out) *rounds_out = rounds;
+  return ceil_div(n, (int64_t)SORT_THREADS * rounds);
+}
+
+int sort_max_blocks(uint32_t max_n) {
+  // below the round cap a sort never uses more than 512 blocks; above it, tiles of 4096
+  int b = ceil_div(max_n, (int64_t)SORT_THREADS * MAX_ROUNDS);
+  return (b > 512 ? b : 512) + 1;
+}
+
+__global__ __launch_bounds__(SORT_THREADS) void radix_hist_kernel(
+    const uint32_t* __restrict__ keys, uint32_t n, int shift, int rounds, int nblocks,
+    uint32_t* __restrict__ block_hist) {
+  __shared__ uint32_t hist[RADIX];
+  hist[threadIdx.x] = 0;
+  __syncthreads();
+  const uint32_t base = blockIdx.x * (uint32_t)(SORT_THREADS * rounds);
+  for (int r = 0; r < rounds; ++r) {
+    const uint32_t j = base + r * SORT_THREADS + threadIdx.x;
+    if (j < n) atomicAdd(&hist[(keys[j] >> shift) & (RADIX - 1)], 1u);
+  }
+  __syncthreads();
+  block_hist[(size_t)threadIdx.x * nblocks + blockIdx.x] = hist[threadIdx.x];  // digit-major
+}
+
+// One block per digit: exclusive scan of that digit's counts over the blocks (in place) and
+// the digit's total.
+__global__ __launch_bounds__(256) void radix_scan_kernel(uint32_t* __restrict__ block_hist,
+                                                         int nblocks,
+                                                         uint32_t* __restrict__ digit_tot) {
+  __shared__ uint32_t part[256];
+  uint32_t* row = block_hist + (size_t)blockIdx.x * nblocks;
+  const int tid = threadIdx.x;
+  const int per = (nblocks + 255) / 256;
+  const int lo = min(nblocks, tid * per), hi = min(nblocks, lo + per);
+  uint32_t s = 0;
+  for (int i = lo; i < hi; ++i) s += row[i];
+  part[tid] = s;
+  __syncthreads();
+  for (int off = 1; off < 256; off <<= 1) {
+    uint32_t v = (tid >= off) ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  uint32_t run = part[tid] - s;
+  for (int i = lo; i < hi; ++i) {
+    uint32_t c = row[i];
+    row[i] = run;
+    run += c;
+  }
+  if (tid == 255) digit_tot[blockIdx.x] = part[255];
+}
+
+__global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
+    const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in, uint32_t n,
+    int shift, int rounds, int nblocks, const uint32_t* __restrict__ block_hist,
+    const uint32_t* __restrict__ digit_tot, uint32_t* __restrict__ keys_out,
+    uint32_t* __restrict__ vals_out) {
+  // per-wave running digit counts; volatile: lanes of one wave hand values to each other
+  // through it between rounds without a barrier
+  __shared__ volatile uint32_t wrun[SORT_WAVES][RADIX];
+  __shared__ uint32_t dbase[RADIX];             // global start of this block's digit run
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // digit base = exclusive scan of the 256 totals + this block's offset inside the digit
+  {
+    uint32_t v = digit_tot[tid];
+    dbase[tid] = v;
+    __syncthreads();
+    for (int off = 1; off < RADIX; off <<= 1) {
+      uint32_t a = (tid >= off) ? dbase[tid - off] : 0;
+      __syncthreads();
+      dbase[tid] += a;
+      __syncthreads();
+    }
+    uint32_t excl = dbase[tid] - v;
+    __syncthreads();
+    dbase[tid] = excl + block_hist[(size_t)tid * nblocks + blockIdx.x];
+  }
+  for (int w = 0; w < SORT_WAVES; ++w) wrun[w][tid] = 0;
+  __syncthreads();
+
+  const uint32_t tile = (uint32_t)(SORT_THREADS * rounds);
+  const uint32_t wbase = blockIdx.x * tile + wave * (uint32_t)(SS_WAVE * rounds);
+  uint32_t key[MAX_ROUNDS], rank[MAX_ROUNDS];
+#pragma unroll
+  for (int r = 0; r < MAX_ROUNDS; ++r) {
+    if (r < rounds) {
+      const uint32_t j = wbase + r * SS_WAVE + lane;
+      const bool valid = j < n;
+      const uint32_t k = valid ? keys_in[j] : 0xFFFFFFFFu;
+      const uint32_t dg = (k >> shift) & (RADIX - 1);
+      uint64_t m = __ballot(valid);
+#pragma unroll
+      for (int b = 0; b < RADIX_BITS; ++b) {
+        const uint64_t bal = __ballot((dg >> b) & 1u);
+        m &= ((dg >> b) & 1u) ? bal : ~bal;
+      }
+      // m = valid lanes of this wave holding the same digit (includes this lane if valid)
+      const uint32_t before = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+      uint32_t prev = 0;
+      if (valid) prev = wrun[wave][dg];
+      // every lane has read the running count before the group's last lane bumps it: LDS
+      // operations of one wave complete in program order
+      if (valid && (m >> lane) == 1ull) wrun[wave][dg] = prev + (uint32_t)__popcll(m);
+      key[r] = k;
+      rank[r] = prev + before;
+    }
+  }
+  __syncthreads();
+  // exclusive prefix of the per-wave totals over the waves of this block, per digit
+  {
+    uint32_t run = 0;
+    for (int w = 0; w < SORT_WAVES; ++w) {
+      uint32_t c = wrun[w][tid];
+      wrun[w][tid] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < MAX_ROUNDS; ++r) {
+    if (r < rounds) {
+      const uint32_t j = wbase + r * SS_WAVE + lane;
+      if (j < n) {
+        const uint32_t dg = (key[r] >> shift) & (RADIX - 1);
+        const uint32_t dst = dbase[dg] + wrun[wave][dg] + rank[r];
+        keys_out[dst] = key[r];
+        vals_out[dst] = vals_in ? vals_in[j] : j;
+      }
+    }
+  }
+}
+
+void launch_sort_pairs(uint32_t* keys, uint32_t n, int key_bits, const SortScratch& sc,
+                       uint32_t** sorted_keys, uint32_t** sorted_vals, hipStream_t s) {
+  uint32_t* kin = keys;
+  uint32_t* kout = sc.keys_alt;
+  const uint32_t* vin = nullptr;  // first pass: the value is the element's own position
+  uint32_t* vout = sc.vals;
+  uint32_t* vother = sc.vals_alt;
+  int passes = (key_bits + RADIX_BITS - 1) / RADIX_BITS;
+  if (passes < 1) passes = 1;
+  int rounds = 1;
+  const int nblocks = sort_num_blocks(n, &rounds);
+  if (n == 0) {
+    *sorted_keys = kin;
+    *sorted_vals = sc.vals;
+    return;
+  }
+  for (int p = 0; p < passes; ++p) {
+    const int shift = p * RADIX_BITS;
+    hipLaunchKernelGGL(radix_hist_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, n, shift,
+                       rounds, nblocks, sc.block_hist);
+    hipLaunchKernelGGL(radix_scan_kernel, dim3(RADIX), dim3(256), 0, s, sc.block_hist, nblocks,
+                       sc.digit_tot);
+    hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, vin, n,
+                       shift, rounds, nblocks, sc.block_hist, sc.digit_tot, kout, vout);
+    uint32_t* t = kin; kin = kout; kout = t;
+    vin = vout;
+    uint32_t* tv = vout; vout = vother; vother = tv;
+  }
+  *sorted_keys = kin;
+  *sorted_vals = (uint32_t*)vin;
+}
+
+}  // namespace ss

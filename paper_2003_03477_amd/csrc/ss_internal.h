@@ -1,0 +1,105 @@
+// Internal declarations shared by the HIP translation units of libshadowsync (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define SS_MAX_TABLES 64
+#define SS_WAVE 64
+
+namespace ss {
+
+// First global row of every table; passed to kernels by value (kernarg memory).
+struct TableMeta {
+  uint32_t row_base[SS_MAX_TABLES + 1];
+};
+
+static inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// ---------------------------------------------------------------------------- init.hip
+void launch_table_hash_init(float* h, uint64_t n_elems, uint64_t seed, int table,
+                            hipStream_t s);
+void launch_fill_f32(float* p, uint64_t n, float v, hipStream_t s);
+void launch_fill_u32(uint32_t* p, uint64_t n, uint32_t v, hipStream_t s);
+
+// ---------------------------------------------------------------------------- embedding.hip
+// Sum-pooled gather: e[b,t,:] = sum_j h[row_base[t] + indices[j], :].  Also records, for the
+// backward pass, the sort key (global row) and the pooled-vector index b*T+t of every flat
+// position.
+void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int32_t* offsets,
+                              const TableMeta& meta, int B, int T, int d, float* e,
+                              uint32_t* keys, int32_t* bag_of_pos, hipStream_t s);
+
+struct SegScratch {
+  uint32_t* block_counts;  // [seg_blocks]
+  uint32_t* seg_starts;    // [max_ids + 1]
+  uint32_t* num_unique;    // [1]
+  uint32_t* long_list;     // [max_ids / LONG_SEG + 1] segment ids longer than the threshold
+  uint32_t* long_count;    // [1]
+};
+// Heads of runs of equal keys in a sorted key array -> compacted start offsets.
+void launch_segment_starts(const uint32_t* sorted_keys, uint32_t n, const SegScratch& sc,
+                           hipStream_t s);
+// Per distinct row: g = sum of de over its occurrences; row-wise Adagrad on h and G.
+void launch_row_update(const uint32_t* sorted_keys, const uint32_t* sorted_pos,
+                       const int32_t* bag_of_pos, const float* de, uint32_t n,
+                       const SegScratch& sc, int d, float* h, float* G, float lr, float eps,
+                       hipStream_t s);
+
+// ---------------------------------------------------------------------------- sort.hip
+struct SortScratch {
+  uint32_t* keys_alt;   // [max_ids]
+  uint32_t* vals;       // [max_ids]
+  uint32_t* vals_alt;   // [max_ids]
+  uint32_t* block_hist; // [256 * max_sort_blocks]
+  uint32_t* digit_tot;  // [256]
+};
+int sort_num_blocks(uint32_t n, int* rounds_out);
+int sort_max_blocks(uint32_t max_n);
+// Stable LSD radix sort of (key, position) pairs on key_bits bits.  keys is overwritten or
+// left as is depending on the pass count; the sorted arrays are returned through the out
+// pointers (each one of the two ping-pong buffers).
+void launch_sort_pairs(uint32_t* keys, uint32_t n, int key_bits, const SortScratch& sc,
+                       uint32_t** sorted_keys, uint32_t** sorted_vals, hipStream_t s);
+
+// ---------------------------------------------------------------------------- interaction.hip
+// f[b] = [z0[b], <V_r, V_c> for r>c], V = [z0[b]; e[b,0..T-1]].  Writes fp32 f (ldf floats per
+// row) and, if f_bf16 != nullptr, a bf16 copy with row stride ldf_bf16 (zero padded).
+void launch_interaction_fwd(const float* z0, const float* e, int B, int T, int d, float* f,
+                            int ldf, uint16_t* f_bf16, int ldf_bf16, hipStream_t s);
+// dz0 (masked by z0 > 0) and de from df.
+void launch_interaction_bwd(const float* z0, const float* e, const float* df, int lddf, int B,
+                            int T, int d, float* dz0, float* de, hipStream_t s);
+
+// ---------------------------------------------------------------------------- mlp_fp32.hip
+enum : int { EPI_NONE = 0, EPI_BIAS = 1, EPI_RELU = 2, EPI_MASK = 4 };
+// C[M,N] (ldc) = A*B with A(m,k) = A[m*sam + k*sak], B(k,n) = B[k*sbk + n*sbn];
+// + bias[n] (EPI_BIAS), ReLU (EPI_RELU), zero where mask[m*ldmask+n] <= 0 (EPI_MASK).
+void launch_gemm_f32(const float* A, int64_t sam, int64_t sak, const float* Bm, int64_t sbk,
+                     int64_t sbn, float* C, int ldc, int M, int N, int K, int epi,
+                     const float* bias, const float* mask, int ldmask, hipStream_t s);
+// db[n] = sum_m dY[m*ld + n]
+void launch_col_sum_f32(const float* dY, int ld, int M, int N, float* db, hipStream_t s);
+// loss = mean_b bce(logit_b, y_b) ; dlogit_b = (sigmoid(logit_b) - y_b) / B
+void launch_bce_loss(const float* logit, const float* y, int B, float* loss, float* dlogit,
+                     hipStream_t s);
+// w -= lr * g   (lock-free, plain loads and stores)
+void launch_sgd(float* w, const float* g, int64_t n, float lr, hipStream_t s);
+
+// ---------------------------------------------------------------------------- mlp_bf16.hip
+struct GemmBf16Args {
+  const void* A; int a_is_f32; int64_t lda; int a_kcontig;   // A(m,k)
+  const void* B; int b_is_f32; int64_t ldb; int b_kcontig;   // B(n,k)
+  int M, N, K;
+  float* C_f32; uint16_t* C_bf16; int ldc;                   // one of the two outputs
+  int epi; const float* bias; const uint16_t* mask; int ldmask;
+  int split_k;                                               // >1: atomicAdd into C_f32
+};
+void launch_gemm_bf16(const GemmBf16Args& a, hipStream_t s);
+void launch_col_sum_bf16(const uint16_t* dY, int ld, int M, int N, float* db, hipStream_t s);
+
+// ---------------------------------------------------------------------------- sync.hip
+int launch_sync_round(int algo, int K, int64_t P, int64_t stride, float* W, float* w_ps,
+                      float* w_global, float* v, float alpha, float eta, float mu,
+                      hipStream_t s);
+
+}  // namespace ss

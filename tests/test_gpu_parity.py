@@ -1,0 +1,171 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle on seeded inputs."""
+import numpy as np
+import pytest
+
+from paper_2003_03477_amd import binding, synth
+import gpu_harness as H
+from oracle import sync as osync
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    return torch
+
+
+# ----------------------------------------------------------------------------- sync rules
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 8])
+@pytest.mark.parametrize("algo", ["easgd", "easgd_literal", "ma", "bmuf"])
+def test_sync_round_matches_oracle(K, algo):
+    torch = _torch()
+    P, stride = 4 * 12345, 4 * 12345 + 256      # several blocks, a ragged last block, padded stride
+    rng = np.random.default_rng(100 + K)
+    W = (rng.standard_normal((K, stride)) * 0.02).astype(np.float32)
+    ps, wg, v = [(rng.standard_normal(P) * 0.02).astype(np.float32) for _ in range(3)]
+    dW, dps, dwg, dv = [torch.from_numpy(a.copy()).cuda() for a in (W, ps, wg, v)]
+    oW, ops, owg, ov = [a.astype(np.float64) for a in (W[:, :P], ps, wg, v)]
+    for r in range(3):
+        binding.ss_sync_round(algo, K, P, stride, dW, dps, dwg, dv, alpha=0.3, eta=0.7, momentum=0.9)
+        if algo == "easgd":
+            osync.easgd_round(oW, ops, 0.3)
+        elif algo == "easgd_literal":
+            osync.easgd_round_literal(oW, ops, 0.3)
+        elif algo == "ma":
+            osync.ma_round(oW, owg, 0.3)
+        else:
+            osync.bmuf_round(oW, owg, ov, 0.3, 0.7, 0.9)
+    torch.cuda.synchronize()
+    gW = dW.cpu().numpy()
+    H.close(gW[:, :P], oW, H.FP32_RTOL, "replicas")
+    assert np.array_equal(gW[:, P:], W[:, P:]), "padding between replicas was written"
+    H.close(dps.cpu().numpy(), ops, H.FP32_RTOL, "w_ps")
+    H.close(dwg.cpu().numpy(), owg, H.FP32_RTOL, "w_global")
+    H.close(dv.cpu().numpy(), ov, H.FP32_RTOL, "v", scale=0.02)
+
+
+def test_sync_invariants_on_device():
+    """Conservation under S-EASGD and replicas == mean under S-MA(alpha=1), measured on the
+    device results themselves (fp32 round-off only)."""
+    torch = _torch()
+    K, P = 8, 1 << 16
+    rng = np.random.default_rng(7)
+    W = torch.from_numpy((rng.standard_normal((K, P)) * 0.02).astype(np.float32)).cuda()
+    ps = torch.from_numpy((rng.standard_normal(P) * 0.02).astype(np.float32)).cuda()
+    total0 = W.double().sum(0) + ps.double()
+    for _ in range(5):
+        binding.ss_sync_round("easgd", K, P, P, W, ps, None, None, alpha=0.05)
+    total1 = W.double().sum(0) + ps.double()
+    assert float((total1 - total0).abs().max()) < 4 * 2 ** -24 * (K + 1) * 0.1
+    wg = torch.zeros(P, device="cuda")
+    mean0 = W.double().mean(0)
+    binding.ss_sync_round("ma", K, P, P, W, None, wg, None, alpha=1.0)
+    assert float((W.double() - mean0).abs().max()) < 1e-7
+    assert float((W - W[0]).abs().max()) == 0.0
+
+
+# ----------------------------------------------------------------------------- table init
+def test_hash_table_init_is_bit_identical():
+    wl = synth.tiny().scaled(rows=(1000, 37, 4096, 5))
+    gpu = binding.from_workload(wl)
+    gpu.ss_init_tables_hash()
+    for t, n in enumerate(wl.rows):
+        rows = np.arange(n)
+        vals, acc = gpu.ss_read_rows(t, rows)
+        assert np.array_equal(vals, synth.table_rows_h0(wl.seed, t, rows, wl.emb_dim))
+        assert not acc.any()
+
+
+# ----------------------------------------------------------------------------- end to end
+def test_tiny_config_deterministic_schedule():
+    """Tiny CTR model, fp32, K=2, S-MA(alpha=1) after every sweep, 20 sweeps."""
+    wl = synth.tiny()
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(40)]
+    gpu, orc = H.make_pair(wl, batches)
+    H.run_lockstep(gpu, orc, batches, wl.sync_gap, wl.algo, wl.alpha)
+    H.compare_state(gpu, orc, H.FP32_RTOL, "after 20 sweeps", wl.row_base)
+    steps, rounds, examples = gpu.ss_get_counters()
+    assert steps.tolist() == [20, 20] and rounds == 20 and examples == 40 * wl.batch
+
+
+@pytest.mark.parametrize("algo,alpha,eta,mu,gap", [("easgd", 0.1, 1.0, 0.0, 2),
+                                                   ("bmuf", 0.5, 1.0, 0.9, 1),
+                                                   ("easgd_literal", 0.2, 1.0, 0.0, 3)])
+def test_fp32_other_rules_and_ragged_shapes(algo, alpha, eta, mu, gap):
+    """d=64, 3 unequal tables, batch not a multiple of anything, several sort passes."""
+    wl = synth.tiny().scaled(batch=203, rows=(70001, 13, 2500), emb_dim=64, bag_lambda=6.0,
+                             bot_dims=(13, 40, 64), top_dims=(64 + 6, 33, 17, 1),
+                             num_replicas=3, algo=algo, alpha=alpha, eta=eta, mu=mu,
+                             sync_gap=gap, zipf_s=1.2)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(12)]
+    cp = synth.compact_problem(wl, batches)
+    # keep the original (sparse) row ids for the large table so the sort sees wide keys
+    gpu, orc = H.make_pair(wl, batches, h0=synth.full_tables_h0(wl))
+    H.run_lockstep(gpu, orc, batches, gap, algo, alpha, eta, mu)
+    H.compare_state(gpu, orc, H.FP32_RTOL, algo, wl.row_base)
+    assert len(cp.touched[0]) > 500
+
+
+def test_empty_bags_single_sample_and_hot_row():
+    """Edge cases: empty bags, batch of one, one row owning a very long segment."""
+    wl = synth.tiny().scaled(batch=64, rows=(50, 1000), emb_dim=16, bot_dims=(13, 16),
+                             top_dims=(16 + 3, 8, 1), num_replicas=1)
+    rng = np.random.default_rng(3)
+    B, T = 64, 2
+
+    def make(B, lens_fn, hot=None):
+        lengths = np.array([[lens_fn(t, b) for b in range(B)] for t in range(T)])
+        offsets = np.concatenate(([0], np.cumsum(lengths.ravel()))).astype(np.int32)
+        idx = np.empty(offsets[-1], dtype=np.int32)
+        for t in range(T):
+            lo, hi = offsets[t * B], offsets[(t + 1) * B]
+            idx[lo:hi] = rng.integers(0, wl.rows[t], hi - lo)
+            if hot is not None and t == 1:
+                idx[lo:hi][rng.random(hi - lo) < 0.9] = hot
+        x = rng.standard_normal((B, 13)).astype(np.float32)
+        y = (rng.random(B) < 0.3).astype(np.float32)
+        return synth.Batch(x, y, idx, offsets)
+
+    batches = [
+        make(64, lambda t, b: 0 if (b + t) % 3 == 0 else 2),     # many empty bags
+        make(64, lambda t, b: 0),                                # no ids at all
+        make(1, lambda t, b: 5),                                 # single sample
+        make(64, lambda t, b: 40, hot=7),                        # ~2300 hits on one row
+        make(64, lambda t, b: 130 if b == 0 else 1),             # a bag longer than a wave
+    ]
+    gpu, orc = H.make_pair(wl, batches)
+    H.run_lockstep(gpu, orc, batches, 1, "ma", 1.0)
+    H.compare_state(gpu, orc, H.FP32_RTOL, "edge cases", wl.row_base)
+
+
+def test_bf16_mid_scaled():
+    """Mid CTR architecture (bf16 MLP GEMMs, fp32 master weights) on a compacted table set."""
+    wl = synth.mid().scaled(batch=512, num_replicas=2, sync_gap=2)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(8)]
+    cp = synth.compact_problem(wl, batches)
+    gpu, orc = H.make_pair(wl, cp.batches, h0=cp.h0, rows=cp.rows)
+    H.run_lockstep(gpu, orc, cp.batches, wl.sync_gap, wl.algo, wl.alpha, rtol=H.BF16_RTOL)
+    row_base = np.concatenate(([0], np.cumsum(cp.rows)))
+    H.compare_state(gpu, orc, H.BF16_RTOL, "bf16 mid", row_base)
+
+
+def test_validation_errors_through_the_abi():
+    wl = synth.tiny()
+    gen = synth.BatchGenerator(wl)
+    b = gen.batch(0)
+    gpu, _ = H.make_pair(wl, [b])
+    dev = binding.upload_batch(b)
+    with pytest.raises(binding.ShadowSyncError):
+        gpu.ss_train_step(5, 0, dev)
+    with pytest.raises(binding.ShadowSyncError):
+        gpu.ss_train_step(0, 3, dev)
+    big = binding.DeviceBatch(dev.dense, dev.labels, dev.indices, dev.offsets, dev.batch, 10 ** 7)
+    with pytest.raises(binding.ShadowSyncError):
+        gpu.ss_train_step(0, 0, big)
+    with pytest.raises(binding.ShadowSyncError):
+        gpu.ss_shadow_sync(9, 0.1)
+    with pytest.raises(binding.ShadowSyncError):
+        gpu.ss_read_dense(17)
