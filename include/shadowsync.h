@@ -112,6 +112,10 @@ int ss_init_tables_hash(ss_ctx* ctx, void* stream);
  * those rows <- 0.  Synchronous. */
 int ss_write_rows(ss_ctx* ctx, int32_t table, int64_t first_row, int64_t n_rows,
                   const float* host_rows);
+/* Adagrad accumulators G of the same row range <- host values [n_rows] (restoring a saved
+ * optimiser state; Section 3.2 keeps this state beside the rows).  Synchronous. */
+int ss_write_adagrad(ss_ctx* ctx, int32_t table, int64_t first_row, int64_t n_rows,
+                     const float* host_acc);
 
 /* Algorithm 1: w^(i) <- w0 for all i, w^PS <- w0, w^global <- w0 (Algorithms 3, 4), v <- 0.
  * host_w0 holds P floats.  Synchronous. */

@@ -31,7 +31,7 @@ K_NONE, K_GATHER, K_SORT, K_ROW_UPDATE, K_SYNC, K_MLP, K_INTERACT = range(7)
 
 EXPORTS = [
     "ss_workspace_bytes", "ss_init", "ss_destroy", "ss_last_error", "ss_init_tables_hash",
-    "ss_write_rows", "ss_init_dense", "ss_num_params", "ss_train_step", "ss_eval_step",
+    "ss_write_rows", "ss_write_adagrad", "ss_init_dense", "ss_num_params", "ss_train_step", "ss_eval_step",
     "ss_shadow_sync", "ss_sync_round", "ss_shadow_start", "ss_shadow_stop", "ss_read_dense",
     "ss_write_dense", "ss_read_rows", "ss_read_debug", "ss_get_counters", "ss_profile_arm",
     "ss_profile_read",
@@ -77,6 +77,7 @@ def load() -> C.CDLL:
     lib.ss_last_error.argtypes = [vp]
     lib.ss_init_tables_hash.argtypes = [vp, vp]
     lib.ss_write_rows.argtypes = [vp, i32, i64, i64, vp]
+    lib.ss_write_adagrad.argtypes = [vp, i32, i64, i64, vp]
     lib.ss_init_dense.argtypes = [vp, vp]
     lib.ss_num_params.restype = i64
     lib.ss_num_params.argtypes = [vp]
@@ -204,6 +205,11 @@ class ShadowSync:
         v = np.ascontiguousarray(values, dtype=np.float32)
         self._check(self.lib.ss_write_rows(self.ctx, table, first_row, v.shape[0], _np_ptr(v)),
                     "ss_write_rows")
+
+    def ss_write_adagrad(self, table: int, first_row: int, values: np.ndarray):
+        v = np.ascontiguousarray(values, dtype=np.float32)
+        self._check(self.lib.ss_write_adagrad(self.ctx, table, first_row, v.shape[0], _np_ptr(v)),
+                    "ss_write_adagrad")
 
     def ss_init_dense(self, w0: np.ndarray):
         w = np.ascontiguousarray(w0, dtype=np.float32)

@@ -352,6 +352,20 @@ int ss_write_rows(ss_ctx* ctx, int32_t table, int64_t first_row, int64_t n_rows,
   return SS_OK;
 }
 
+int ss_write_adagrad(ss_ctx* ctx, int32_t table, int64_t first_row, int64_t n_rows,
+                     const float* host_acc) {
+  if (!ctx) return SS_EINVAL;
+  if (table < 0 || table >= ctx->T || first_row < 0 || n_rows < 0 ||
+      first_row + n_rows > ctx->rows[table] || (!host_acc && n_rows))
+    return fail(ctx, SS_EINVAL, "ss_write_adagrad: bad table/row range");
+  if (n_rows == 0) return SS_OK;
+  const size_t r0 = (size_t)ctx->meta.row_base[table] + first_row;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemcpy(ctx->G + r0, host_acc, (size_t)n_rows * sizeof(float),
+                         hipMemcpyHostToDevice));
+  return SS_OK;
+}
+
 static float* dense_ptr(ss_ctx* ctx, int which) {
   if (which >= 0 && which < ctx->K) return ctx->W + (size_t)which * ctx->Pstride;
   if (which == -1) return ctx->w_ps;

@@ -11,20 +11,31 @@ BF16_RTOL = 2e-2   # spec bound for values that passed through bf16 MLP GE
 def close(got, want, rtol, what, scale=None):
     """|got - want| <= rtol * (|want| + scale), scale = largest magnitude in `want`: the
     bound is relative to each element where that element is large and to the tensor's own
-    scale where cancellation made it small."""
+    scale where cancellation made it small.
+
+    fp32 (rtol 1e-5): every element must satisfy it.  bf16 (rtol 2e-2): a ReLU gate is a
+    floating-point comparison with zero, and operands that differ in the last fp32 bit can
+    round to different bfloat16 values, so a handful of gates per step open on one side and
+    not on the other; each flips one hidden unit of one sample.  There the bound must hold
+    for all but 0.5 % of the elements and, for the tensor as a whole, in the Frobenius norm."""
     got = np.asarray(got, dtype=np.float64).ravel()
     want = np.asarray(want, dtype=np.float64).ravel()
     assert got.shape == want.shape, f"{what}: shape {got.shape} vs {want.shape}"
     if want.size == 0:
         return
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values"
     sc = float(np.max(np.abs(want))) if scale is None else scale
     err = np.abs(got - want)
     bound = rtol * (np.abs(want) + sc)
     bad = err > bound
-    if bad.any():
+    allowed = 0 if rtol <= FP32_RTOL else int(0.005 * want.size)
+    if int(bad.sum()) > allowed:
         k = int(np.argmax(err - bound))
         raise AssertionError(f"{what}: {int(bad.sum())}/{want.size} outside rtol {rtol}: worst at "
                              f"{k}: got {got[k]!r} want {want[k]!r} (scale {sc:.3g})")
+    if allowed:
+        fro = float(np.linalg.norm(got - want)) / max(float(np.linalg.norm(want)), 1e-300)
+        assert fro <= rtol, f"{what}: relative Frobenius error {fro:.3g} > {rtol}"
 
 
 def make_pair(wl, batches, h0=None, rows=None, slots=1, dtype=np.float64):
@@ -47,8 +58,11 @@ def make_pair(wl, batches, h0=None, rows=None, slots=1, dtype=np.float64):
     return gpu, orc
 
 
-def compare_step(gpu, orc, slot, rtol, step_name):
-    """Element-wise comparison of one step's intermediates (index work bit-exact)."""
+def compare_step(gpu, orc, slot, rtol, step_name, tables_exact=False):
+    """Element-wise comparison of one step's intermediates (index work bit-exact).  The
+    pooled embeddings are pure fp32 work, so they are held to the fp32 bound whenever the
+    tables they read are known to match to that bound (always in fp32 runs; in bf16 runs only
+    before the first table update, since later rows carry bf16-level gradient differences)."""
     last = orc.last
     B = last["e"].shape[0]
     for item, key in ((binding.DBG_SORTED_ROWS, "sorted_keys"), (binding.DBG_SORTED_POS, "sorted_pos"),
@@ -56,7 +70,8 @@ def compare_step(gpu, orc, slot, rtol, step_name):
         got = gpu.ss_read_debug(slot, item).astype(np.int64)
         assert np.array_equal(got, np.asarray(last[key], dtype=np.int64)), f"{step_name}: {key} differs"
     assert int(gpu.ss_read_debug(slot, binding.DBG_NUM_UNIQUE)[0]) == len(last["seg_starts"])
-    close(gpu.ss_read_debug(slot, binding.DBG_POOLED), last["e"], FP32_RTOL, f"{step_name}: pooled e")
+    close(gpu.ss_read_debug(slot, binding.DBG_POOLED), last["e"],
+          FP32_RTOL if (tables_exact or rtol <= FP32_RTOL) else rtol, f"{step_name}: pooled e")
     close(gpu.ss_read_debug(slot, binding.DBG_INTERACT), last["f"], rtol, f"{step_name}: interaction f")
     close(gpu.ss_read_debug(slot, binding.DBG_LOGITS), last["logit"], rtol, f"{step_name}: logits")
     close(gpu.ss_read_debug(slot, binding.DBG_DENSE_GRAD), last["g"], rtol, f"{step_name}: dense grad")
@@ -77,9 +92,28 @@ def compare_state(gpu, orc, rtol, name, row_base):
         close(acc, orc.G[row_base[t]:row_base[t + 1]], rtol, f"{name}: adagrad state {t}")
 
 
+def push_oracle_state(gpu, orc, row_base):
+    """Overwrite the device state with the oracle's (rounded to fp32)."""
+    for i in range(orc.W.shape[0]):
+        gpu.ss_write_dense(i, orc.W[i])
+    gpu.ss_write_dense(-1, orc.w_ps)
+    gpu.ss_write_dense(-2, orc.w_global)
+    gpu.ss_write_dense(-3, orc.v)
+    for t in range(len(row_base) - 1):
+        gpu.ss_write_rows(t, 0, orc.h[row_base[t]:row_base[t + 1]])
+        gpu.ss_write_adagrad(t, 0, orc.G[row_base[t]:row_base[t + 1]])
+
+
 def run_lockstep(gpu, orc, batches, gap, algo, alpha, eta=1.0, mu=0.0, rtol=FP32_RTOL,
-                 check_every=1, loss_rtol=None):
-    """The deterministic schedule (one worker per replica, sync at fixed steps) on both."""
+                 check_every=1, loss_rtol=None, resync_row_base=None):
+    """The deterministic schedule (one worker per replica, sync at fixed steps) on both.
+
+    With resync_row_base set, every step and every round is checked from a COMMON state: the
+    full state is compared after each of them and the device state is then overwritten with
+    the oracle's.  bf16 runs need this: row-wise Adagrad's update has magnitude ~lr whatever
+    the gradient's scale, so a 1 % gradient difference (bf16 rounding, a flipped ReLU gate)
+    becomes a 1e-4 difference in the row and the two trajectories separate beyond the 2e-2
+    bound within a few steps, although each single step meets it."""
     K = orc.W.shape[0]
     dev = [binding.upload_batch(b) for b in batches]
     losses = []
@@ -91,8 +125,15 @@ def run_lockstep(gpu, orc, batches, gap, algo, alpha, eta=1.0, mu=0.0, rtol=FP32
             losses.append((lg, lo))
             assert abs(lg - lo) <= (loss_rtol or rtol) * abs(lo), f"step {k}: loss {lg} vs {lo}"
             if k % check_every == 0:
-                compare_step(gpu, orc, 0, rtol, f"step {k}")
+                compare_step(gpu, orc, 0, rtol, f"step {k}",
+                             tables_exact=(k == 0 or resync_row_base is not None))
+            if resync_row_base is not None:
+                compare_state(gpu, orc, rtol, f"after step {k}", resync_row_base)
+                push_oracle_state(gpu, orc, resync_row_base)
         if (s + 1) % gap == 0:
             orc.shadow_sync(algo, alpha, eta, mu)
             gpu.ss_shadow_sync(algo, alpha, eta, mu)
+            if resync_row_base is not None:
+                compare_state(gpu, orc, FP32_RTOL, f"after round at sweep {s}", resync_row_base)
+                push_oracle_state(gpu, orc, resync_row_base)
     return losses
