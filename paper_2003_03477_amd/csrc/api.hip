@@ -46,6 +46,7 @@ struct Slot {
   // embedding backward
   uint32_t* keys;                  // [max_ids]
   int32_t* bag_of_pos;             // [max_ids]
+  int32_t* sorted_bag;             // [max_ids] bag_of_pos in sorted order
   SortScratch sort;
   SegScratch seg;
   // results of the last step (for ss_read_debug)
@@ -215,6 +216,7 @@ static size_t layout(ss_ctx* x, void* base) {
     s.de = cv.take<float>((size_t)B * x->T * x->d);
     s.keys = cv.take<uint32_t>(n);
     s.bag_of_pos = cv.take<int32_t>(n);
+    s.sorted_bag = cv.take<int32_t>(n);
     s.sort.keys_alt = cv.take<uint32_t>(n);
     s.sort.vals = cv.take<uint32_t>(n);
     s.sort.vals_alt = cv.take<uint32_t>(n);
@@ -464,7 +466,12 @@ static int check_batch(ss_ctx* x, int replica, int slot, const ss_batch* b) {
   return SS_OK;
 }
 
-static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipStream_t st) {
+// bf16 models with at least one hidden top layer run the one-unit output layer and the loss
+// (and that layer's backward) as fused kernels instead of GEMMs with a single column.
+static bool fused_last(const ss_ctx* x) { return x->prec == SS_BF16 && x->n_top_layers >= 2; }
+
+static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, float* loss,
+                    bool train, hipStream_t st) {
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
   const bool bf = x->prec == SS_BF16;
   // ---- bottom MLP
@@ -496,7 +503,7 @@ static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipS
   {
     ProfScope ps(x, SS_K_GATHER, st);
     launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e, s.keys,
-                             s.bag_of_pos, st);
+                             s.bag_of_pos, fused_last(x) ? loss : nullptr, st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT, st);
@@ -516,6 +523,10 @@ static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipS
         launch_gemm_f32((const float*)in, ld_in, 1, w + ly.w_off, 1, ly.in, out, ly.out, B, ly.out,
                         ly.in, epi, w + ly.b_off, nullptr, 0, st);
         in = out; ld_in = ly.out;
+      } else if (last && fused_last(x)) {
+        launch_last_layer_fwd_loss((const uint16_t*)in, ld_in, w + ly.w_off, w + ly.b_off,
+                                   bt->labels, B, ly.in, s.logits, train ? s.dlogit : nullptr,
+                                   loss, st);
       } else {
         GemmBf16Args a{};
         a.A = in; a.a_is_f32 = 0; a.lda = ld_in; a.a_kcontig = 1;
@@ -569,15 +580,18 @@ static void backward_dense(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
                           to_df ? nullptr : (const float*)xin, ldx, st);
           dcur = out; ldd = ldo; pp ^= 1;
         }
+      } else if (l == L - 1 && fused_last(x)) {
+        launch_last_layer_bwd((const uint16_t*)xin, ldx, w + ly.w_off, (const float*)dcur, B,
+                              ly.in, s.dbuf16[pp], ly.in, gW, gb, st);
+        dcur = s.dbuf16[pp]; ldd = ly.in; d_f32 = false; pp ^= 1;
       } else {
         GemmBf16Args a{};
         a.A = dcur; a.a_is_f32 = d_f32; a.lda = ldd; a.a_kcontig = 0;
         a.B = xin; a.b_is_f32 = x_f32; a.ldb = ldx; a.b_kcontig = 0;
         a.M = ly.out; a.N = ly.in; a.K = B; a.C_f32 = gW; a.ldc = ly.in; a.epi = EPI_NONE;
         a.split_k = choose_split(ly.out, ly.in, B);
+        a.row_sum = gb;  // bias gradient = row sums of dY^T
         launch_gemm_bf16(a, st);
-        if (d_f32) launch_col_sum_f32((const float*)dcur, ldd, B, ly.out, gb, st);
-        else launch_col_sum_bf16((const uint16_t*)dcur, ldd, B, ly.out, gb, st);
         if (need_dx) {
           GemmBf16Args g{};
           g.A = dcur; g.a_is_f32 = d_f32; g.lda = ldd; g.a_kcontig = 1;
@@ -620,9 +634,9 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
   float* w = x->W + (size_t)replica * x->Pstride;
   const int B = bt->batch;
   const uint32_t n = (uint32_t)bt->num_ids;
-  forward(x, s, w, bt, st);
   float* loss = dev_loss_out ? dev_loss_out : s.loss;
-  launch_bce_loss(s.logits, bt->labels, B, loss, train ? s.dlogit : nullptr, st);
+  forward(x, s, w, bt, loss, train, st);
+  if (!fused_last(x)) launch_bce_loss(s.logits, bt->labels, B, loss, train ? s.dlogit : nullptr, st);
   s.last_B = B;
   s.last_n = n;
   if (train) {
@@ -632,13 +646,14 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
     // "update h": stable sort by row, one Adagrad update per distinct row
     {
       ProfScope ps(x, SS_K_SORT, st);
-      launch_sort_pairs(s.keys, n, x->key_bits, s.sort, &s.sorted_keys, &s.sorted_pos, st);
+      launch_sort_pairs(s.keys, n, x->key_bits, s.sort, &s.sorted_keys, &s.sorted_pos,
+                        s.bag_of_pos, s.sorted_bag, st);
       launch_segment_starts(s.sorted_keys, n, s.seg, st);
     }
     {
       ProfScope ps(x, SS_K_ROW_UPDATE, st);
-      launch_row_update(s.sorted_keys, s.sorted_pos, s.bag_of_pos, s.de, n, s.seg, x->d, x->h, x->G,
-                        x->lr_emb, x->eps, st);
+      launch_row_update(s.sorted_keys, s.sorted_bag, s.de, n, s.seg, x->d, x->h, x->G, x->lr_emb,
+                        x->eps, st);
     }
     x->steps[replica].fetch_add(1);
     x->examples.fetch_add((uint64_t)B);

@@ -17,9 +17,12 @@ template <int LPR>
 __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
     const float* __restrict__ h, const int32_t* __restrict__ indices,
     const int32_t* __restrict__ offsets, TableMeta meta, int B, int T, float* __restrict__ e,
-    uint32_t* __restrict__ keys, int32_t* __restrict__ bag_of_pos) {
+    uint32_t* __restrict__ keys, int32_t* __restrict__ bag_of_pos,
+    float* __restrict__ zero_scalar) {
   constexpr int D = LPR * 4;
   constexpr int RPW = SS_WAVE / LPR;  // rows per wave-wide load
+  // the step's loss accumulator is cleared here, ahead of the kernel that adds into it
+  if (zero_scalar && blockIdx.x == 0 && threadIdx.x == 0) *zero_scalar = 0.f;
   const int lane = threadIdx.x & 63;
   const int bag = (int)((blockIdx.x * (uint64_t)blockDim.x + threadIdx.x) >> 6);  // t*B + b
   if (bag >= T * B) return;
@@ -63,13 +66,14 @@ __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
 
 void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int32_t* offsets,
                               const TableMeta& meta, int B, int T, int d, float* e,
-                              uint32_t* keys, int32_t* bag_of_pos, hipStream_t s) {
+                              uint32_t* keys, int32_t* bag_of_pos, float* zero_scalar,
+                              hipStream_t s) {
   const int64_t bags = (int64_t)B * T;
   if (bags == 0) return;
   dim3 grid((unsigned)ceil_div(bags, 4)), block(256);
 #define L(LPR)                                                                               \
   hipLaunchKernelGGL((embedding_bag_fwd_kernel<LPR>), grid, block, 0, s, h, indices, offsets, \
-                     meta, B, T, e, keys, bag_of_pos)
+                     meta, B, T, e, keys, bag_of_pos, zero_scalar)
   switch (d) {
     case 16: L(4); break;
     case 32: L(8); break;
@@ -202,11 +206,11 @@ __device__ __forceinline__ void adagrad_apply(float4 g, uint32_t row, int c4, fl
 
 template <int LPR>
 __global__ __launch_bounds__(256) void row_update_kernel(
-    const uint32_t* __restrict__ sorted_keys, const uint32_t* __restrict__ sorted_pos,
-    const int32_t* __restrict__ bag_of_pos, const float* __restrict__ de,
-    const uint32_t* __restrict__ seg_starts, const uint32_t* __restrict__ num_unique,
-    uint32_t* __restrict__ long_list, uint32_t* __restrict__ long_count, float* __restrict__ h,
-    float* __restrict__ G, float lr, float eps) {
+    const uint32_t* __restrict__ sorted_keys, const int32_t* __restrict__ sorted_bag,
+    const float* __restrict__ de, const uint32_t* __restrict__ seg_starts,
+    const uint32_t* __restrict__ num_unique, uint32_t* __restrict__ long_list,
+    uint32_t* __restrict__ long_count, float* __restrict__ h, float* __restrict__ G, float lr,
+    float eps) {
   constexpr int D = LPR * 4;
   const uint32_t U = *num_unique;
   const int lane = threadIdx.x & 63;
@@ -222,7 +226,7 @@ __global__ __launch_bounds__(256) void row_update_kernel(
     for (uint32_t k0 = start; k0 < end; k0 += LPR) {
       const uint32_t k = k0 + c4;
       int bag = 0;
-      if (k < end) bag = bag_of_pos[sorted_pos[k]];
+      if (k < end) bag = sorted_bag[k];
       const int cnt = (int)min((uint32_t)LPR, end - k0);
       // group-uniform trip count: the source lane of every permute is an active lane
       for (int i = 0; i < cnt; ++i) {
@@ -235,15 +239,15 @@ __global__ __launch_bounds__(256) void row_update_kernel(
   }
 }
 
-// One block per long segment: the 256/LPR groups take interleaved occurrences, partial sums
-// are folded through LDS, group 0 applies the update.
+// One block per long segment: the 256/LPR groups take interleaved occurrences, four at a
+// time so that several gradient rows are in flight per group; partial sums are folded
+// through LDS and group 0 applies the update.
 template <int LPR>
 __global__ __launch_bounds__(256) void row_update_long_kernel(
-    const uint32_t* __restrict__ sorted_keys, const uint32_t* __restrict__ sorted_pos,
-    const int32_t* __restrict__ bag_of_pos, const float* __restrict__ de,
-    const uint32_t* __restrict__ seg_starts, const uint32_t* __restrict__ long_list,
-    const uint32_t* __restrict__ long_count, float* __restrict__ h, float* __restrict__ G,
-    float lr, float eps) {
+    const uint32_t* __restrict__ sorted_keys, const int32_t* __restrict__ sorted_bag,
+    const float* __restrict__ de, const uint32_t* __restrict__ seg_starts,
+    const uint32_t* __restrict__ long_list, const uint32_t* __restrict__ long_count,
+    float* __restrict__ h, float* __restrict__ G, float lr, float eps) {
   constexpr int D = LPR * 4;
   constexpr int NG = 256 / LPR;
   __shared__ float4 part[256];
@@ -252,12 +256,27 @@ __global__ __launch_bounds__(256) void row_update_long_kernel(
   for (uint32_t li = blockIdx.x; li < nlong; li += gridDim.x) {
     const uint32_t u = long_list[li];
     const uint32_t start = seg_starts[u], end = seg_starts[u + 1];
-    float4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (uint32_t k = start + grp; k < end; k += NG) {
-      const int bg = bag_of_pos[sorted_pos[k]];
-      const float4 v = *(const float4*)(de + (size_t)bg * D + c4 * 4);
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    float4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0, a2 = a0, a3 = a0;
+    uint32_t k = start + grp;
+    for (; k + 3 * NG < end; k += 4 * NG) {
+      const int b0 = sorted_bag[k], b1 = sorted_bag[k + NG], b2 = sorted_bag[k + 2 * NG],
+                b3 = sorted_bag[k + 3 * NG];
+      const float4 v0 = *(const float4*)(de + (size_t)b0 * D + c4 * 4);
+      const float4 v1 = *(const float4*)(de + (size_t)b1 * D + c4 * 4);
+      const float4 v2 = *(const float4*)(de + (size_t)b2 * D + c4 * 4);
+      const float4 v3 = *(const float4*)(de + (size_t)b3 * D + c4 * 4);
+      a0.x += v0.x; a0.y += v0.y; a0.z += v0.z; a0.w += v0.w;
+      a1.x += v1.x; a1.y += v1.y; a1.z += v1.z; a1.w += v1.w;
+      a2.x += v2.x; a2.y += v2.y; a2.z += v2.z; a2.w += v2.w;
+      a3.x += v3.x; a3.y += v3.y; a3.z += v3.z; a3.w += v3.w;
     }
+    for (; k < end; k += NG) {
+      const int b0 = sorted_bag[k];
+      const float4 v0 = *(const float4*)(de + (size_t)b0 * D + c4 * 4);
+      a0.x += v0.x; a0.y += v0.y; a0.z += v0.z; a0.w += v0.w;
+    }
+    float4 acc = {(a0.x + a1.x) + (a2.x + a3.x), (a0.y + a1.y) + (a2.y + a3.y),
+                  (a0.z + a1.z) + (a2.z + a3.z), (a0.w + a1.w) + (a2.w + a3.w)};
     part[threadIdx.x] = acc;
     __syncthreads();
     for (int half = NG / 2; half >= 1; half >>= 1) {
@@ -273,22 +292,20 @@ __global__ __launch_bounds__(256) void row_update_long_kernel(
   }
 }
 
-void launch_row_update(const uint32_t* sorted_keys, const uint32_t* sorted_pos,
-                       const int32_t* bag_of_pos, const float* de, uint32_t n,
-                       const SegScratch& sc, int d, float* h, float* G, float lr, float eps,
-                       hipStream_t s) {
+void launch_row_update(const uint32_t* sorted_keys, const int32_t* sorted_bag, const float* de,
+                       uint32_t n, const SegScratch& sc, int d, float* h, float* G, float lr,
+                       float eps, hipStream_t s) {
   if (n == 0) return;
   const int lpr = d / 4;
   const int groups_per_block = 256 / lpr;
   int blocks = ceil_div(n, groups_per_block);
-  if (blocks > 256 * 8) blocks = 256 * 8;
+  if (blocks > 256 * 16) blocks = 256 * 16;
 #define L(LPR)                                                                                 \
   hipLaunchKernelGGL((row_update_kernel<LPR>), dim3(blocks), dim3(256), 0, s, sorted_keys,     \
-                     sorted_pos, bag_of_pos, de, sc.seg_starts, sc.num_unique, sc.long_list,   \
-                     sc.long_count, h, G, lr, eps);                                            \
-  hipLaunchKernelGGL((row_update_long_kernel<LPR>), dim3(128), dim3(256), 0, s, sorted_keys,   \
-                     sorted_pos, bag_of_pos, de, sc.seg_starts, sc.long_list, sc.long_count, h, \
-                     G, lr, eps)
+                     sorted_bag, de, sc.seg_starts, sc.num_unique, sc.long_list, sc.long_count, \
+                     h, G, lr, eps);                                                           \
+  hipLaunchKernelGGL((row_update_long_kernel<LPR>), dim3(256), dim3(256), 0, s, sorted_keys,   \
+                     sorted_bag, de, sc.seg_starts, sc.long_list, sc.long_count, h, G, lr, eps)
   switch (d) {
     case 16: L(4); break;
     case 32: L(8); break;

@@ -74,24 +74,27 @@ void launch_gemm_f32(const float* A, int64_t sam, int64_t sak, const float* Bm, 
                      K, epi, bias, mask, ldmask);
 }
 
-// db[n] = sum_m dY[m, n]; one block per 64 columns, 4 row strips folded through LDS.
-__global__ __launch_bounds__(256) void col_sum_f32_kernel(const float* __restrict__ dY, int ld,
-                                                          int M, int N, float* __restrict__ db) {
-  __shared__ float part[4][64];
-  const int c = blockIdx.x * 64 + (threadIdx.x & 63), strip = threadIdx.x >> 6;
+// db[n] = sum_m dY[m, n]; one block per 64 columns, 16 row strips folded through LDS.
+__global__ __launch_bounds__(1024) void col_sum_f32_kernel(const float* __restrict__ dY, int ld,
+                                                           int M, int N, float* __restrict__ db) {
+  __shared__ float part[16][64];
+  const int cl = threadIdx.x & 63, c = blockIdx.x * 64 + cl, strip = threadIdx.x >> 6;
   float s = 0.f;
   if (c < N)
-    for (int m = strip; m < M; m += 4) s += dY[(size_t)m * ld + c];
-  part[strip][threadIdx.x & 63] = s;
+    for (int m = strip; m < M; m += 16) s += dY[(size_t)m * ld + c];
+  part[strip][cl] = s;
   __syncthreads();
-  if (strip == 0 && c < N)
-    db[c] = (part[0][threadIdx.x] + part[1][threadIdx.x]) +
-            (part[2][threadIdx.x] + part[3][threadIdx.x]);
+  if (strip == 0 && c < N) {
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tot += part[i][cl];
+    db[c] = tot;
+  }
 }
 
 void launch_col_sum_f32(const float* dY, int ld, int M, int N, float* db, hipStream_t s) {
   if (N == 0) return;
-  hipLaunchKernelGGL(col_sum_f32_kernel, dim3(ceil_div(N, 64)), dim3(256), 0, s, dY, ld, M, N, db);
+  hipLaunchKernelGGL(col_sum_f32_kernel, dim3(ceil_div(N, 64)), dim3(1024), 0, s, dY, ld, M, N, db);
 }
 
 // Mean binary cross-entropy on the logit, max(l,0) - l*y + log1p(exp(-|l|)), and its

@@ -80,7 +80,8 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
     const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in, uint32_t n,
     int shift, int rounds, int nblocks, const uint32_t* __restrict__ block_hist,
     const uint32_t* __restrict__ digit_tot, uint32_t* __restrict__ keys_out,
-    uint32_t* __restrict__ vals_out) {
+    uint32_t* __restrict__ vals_out, const int32_t* __restrict__ lookup,
+    int32_t* __restrict__ lookup_out) {
   // per-wave running digit counts; volatile: lanes of one wave hand values to each other
   // through it between rounds without a barrier
   __shared__ volatile uint32_t wrun[SORT_WAVES][RADIX];
@@ -150,14 +151,17 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
         const uint32_t dg = (key[r] >> shift) & (RADIX - 1);
         const uint32_t dst = dbase[dg] + wrun[wave][dg] + rank[r];
         keys_out[dst] = key[r];
-        vals_out[dst] = vals_in ? vals_in[j] : j;
+        const uint32_t val = vals_in ? vals_in[j] : j;
+        vals_out[dst] = val;
+        if (lookup) lookup_out[dst] = lookup[val];
       }
     }
   }
 }
 
 void launch_sort_pairs(uint32_t* keys, uint32_t n, int key_bits, const SortScratch& sc,
-                       uint32_t** sorted_keys, uint32_t** sorted_vals, hipStream_t s) {
+                       uint32_t** sorted_keys, uint32_t** sorted_vals, const int32_t* lookup,
+                       int32_t* lookup_out, hipStream_t s) {
   uint32_t* kin = keys;
   uint32_t* kout = sc.keys_alt;
   const uint32_t* vin = nullptr;  // first pass: the value is the element's own position
@@ -179,7 +183,8 @@ void launch_sort_pairs(uint32_t* keys, uint32_t n, int key_bits, const SortScrat
     hipLaunchKernelGGL(radix_scan_kernel, dim3(RADIX), dim3(256), 0, s, sc.block_hist, nblocks,
                        sc.digit_tot);
     hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, vin, n,
-                       shift, rounds, nblocks, sc.block_hist, sc.digit_tot, kout, vout);
+                       shift, rounds, nblocks, sc.block_hist, sc.digit_tot, kout, vout,
+                       (p == passes - 1) ? lookup : nullptr, lookup_out);
     uint32_t* t = kin; kin = kout; kout = t;
     vin = vout;
     uint32_t* tv = vout; vout = vother; vother = tv;

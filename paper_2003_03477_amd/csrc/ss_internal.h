@@ -27,7 +27,8 @@ void launch_fill_u32(uint32_t* p, uint64_t n, uint32_t v, hipStream_t s);
 // position.
 void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int32_t* offsets,
                               const TableMeta& meta, int B, int T, int d, float* e,
-                              uint32_t* keys, int32_t* bag_of_pos, hipStream_t s);
+                              uint32_t* keys, int32_t* bag_of_pos, float* zero_scalar,
+                              hipStream_t s);
 
 struct SegScratch {
   uint32_t* block_counts;  // [seg_blocks]
@@ -40,8 +41,8 @@ struct SegScratch {
 void launch_segment_starts(const uint32_t* sorted_keys, uint32_t n, const SegScratch& sc,
                            hipStream_t s);
 // Per distinct row: g = sum of de over its occurrences; row-wise Adagrad on h and G.
-void launch_row_update(const uint32_t* sorted_keys, const uint32_t* sorted_pos,
-                       const int32_t* bag_of_pos, const float* de, uint32_t n,
+void launch_row_update(const uint32_t* sorted_keys, const int32_t* sorted_bag, const float* de,
+                       uint32_t n,
                        const SegScratch& sc, int d, float* h, float* G, float lr, float eps,
                        hipStream_t s);
 
@@ -58,8 +59,10 @@ int sort_max_blocks(uint32_t max_n);
 // Stable LSD radix sort of (key, position) pairs on key_bits bits.  keys is overwritten or
 // left as is depending on the pass count; the sorted arrays are returned through the out
 // pointers (each one of the two ping-pong buffers).
+// If lookup != nullptr the last pass also writes lookup_out[j] = lookup[sorted_vals[j]].
 void launch_sort_pairs(uint32_t* keys, uint32_t n, int key_bits, const SortScratch& sc,
-                       uint32_t** sorted_keys, uint32_t** sorted_vals, hipStream_t s);
+                       uint32_t** sorted_keys, uint32_t** sorted_vals, const int32_t* lookup,
+                       int32_t* lookup_out, hipStream_t s);
 
 // ---------------------------------------------------------------------------- interaction.hip
 // f[b] = [z0[b], <V_r, V_c> for r>c], V = [z0[b]; e[b,0..T-1]].  Writes fp32 f (ldf floats per
@@ -93,9 +96,16 @@ struct GemmBf16Args {
   float* C_f32; uint16_t* C_bf16; int ldc;                   // one of the two outputs
   int epi; const float* bias; const uint16_t* mask; int ldmask;
   int split_k;                                               // >1: atomicAdd into C_f32
+  float* row_sum;                                            // [M] (+)= sum_k A(m,k), or null
 };
 void launch_gemm_bf16(const GemmBf16Args& a, hipStream_t s);
-void launch_col_sum_bf16(const uint16_t* dY, int ld, int M, int N, float* db, hipStream_t s);
+// Last top layer (one output unit) fused with the mean log-loss (accumulated into *loss,
+// which must be zero) and its gradient; and the whole backward of that layer.
+void launch_last_layer_fwd_loss(const uint16_t* X, int ldx, const float* w, const float* bias,
+                                const float* y, int B, int in, float* logits, float* dlogit,
+                                float* loss, hipStream_t s);
+void launch_last_layer_bwd(const uint16_t* X, int ldx, const float* w, const float* dlogit, int B,
+                           int in, uint16_t* dX, int lddx, float* gW, float* gb, hipStream_t s);
 
 // ---------------------------------------------------------------------------- sync.hip
 int launch_sync_round(int algo, int K, int64_t P, int64_t stride, float* W, float* w_ps,
