@@ -49,6 +49,7 @@ struct Slot {
   int32_t* sorted_bag;             // [max_ids] bag_of_pos in sorted order
   SortScratch sort;
   SegScratch seg;
+  RowUpdateScratch upd;
   // results of the last step (for ss_read_debug)
   uint32_t* sorted_keys = nullptr;
   uint32_t* sorted_pos = nullptr;
@@ -225,8 +226,10 @@ static size_t layout(ss_ctx* x, void* base) {
     s.seg.block_counts = cv.take<uint32_t>(seg_blocks);
     s.seg.seg_starts = cv.take<uint32_t>(n + 1);
     s.seg.num_unique = cv.take<uint32_t>(64);
-    s.seg.long_list = cv.take<uint32_t>(n / 256 + 2);
-    s.seg.long_count = cv.take<uint32_t>(64);
+    s.upd.parts = cv.take<float>((size_t)row_update_chunks(n, x->d) * 2 * x->d);
+    s.upd.flags = cv.take<uint32_t>((size_t)row_update_chunks(n, x->d));
+    s.upd.long_list = cv.take<uint32_t>(2 * ((size_t)row_update_chunks(n, x->d) / 30 + 2));
+    s.upd.long_count = cv.take<uint32_t>(64);
   }
   return (cv.off + ALIGN - 1) / ALIGN * ALIGN;
 }
@@ -652,7 +655,7 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
     }
     {
       ProfScope ps(x, SS_K_ROW_UPDATE, st);
-      launch_row_update(s.sorted_keys, s.sorted_bag, s.de, n, s.seg, x->d, x->h, x->G, x->lr_emb,
+      launch_row_update(s.sorted_keys, s.sorted_bag, s.de, n, s.upd, x->d, x->h, x->G, x->lr_emb,
                         x->eps, st);
     }
     x->steps[replica].fetch_add(1);

@@ -1,8 +1,6 @@
-// Embedding kernels (gfx950): sum-pooled gather (forward) and, for the backward pass,
-// segment detection over the row-sorted (row, position) pairs followed by one fused
-// "sum the occurrences' gradients, then row-wise Adagrad" pass per distinct row
-// (Section 3.1: pooling happens where the table lives; Section 3.2: lock-free optimiser
-// updates with the Adagrad accumulator co-located with each row).
+// Embedding kernels (gfx950): sum-pooled gather (forward, Section 3.1: pooling happens where
+// the table lives) and the compaction of segment starts over the row-sorted (row, position)
+// pairs of the backward pass.  The row update itself lives in row_update.hip.
 #include "ss_internal.h"
 
 namespace ss {
@@ -87,7 +85,6 @@ void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int3
 // Segment starts: flag j where sorted_keys[j] != sorted_keys[j-1], count per block, scan the
 // block counts, compact.  SEG_TILE elements per block.
 constexpr int SEG_TILE = 2048;   // 256 threads x 8
-constexpr uint32_t LONG_SEG = 256;  // segments longer than this go to the block-wide kernel
 
 __device__ __forceinline__ bool is_head(const uint32_t* __restrict__ k, uint32_t j) {
   return j == 0 || k[j] != k[j - 1];
@@ -110,12 +107,11 @@ __global__ __launch_bounds__(256) void seg_count_kernel(const uint32_t* __restri
 }
 
 // Single block: exclusive scan of block_counts in place, total -> num_unique, sentinel
-// seg_starts[U] = n, long-segment counter reset.
+// seg_starts[U] = n.
 __global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* __restrict__ block_counts,
                                                         int nblocks, uint32_t n,
                                                         uint32_t* __restrict__ num_unique,
-                                                        uint32_t* __restrict__ seg_starts,
-                                                        uint32_t* __restrict__ long_count) {
+                                                        uint32_t* __restrict__ seg_starts) {
   __shared__ uint32_t part[1024];
   const int tid = threadIdx.x;
   const int per = (nblocks + 1023) / 1024;
@@ -140,7 +136,6 @@ __global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* __restrict__ b
     uint32_t U = part[1023];
     *num_unique = U;
     seg_starts[U] = n;
-    *long_count = 0;
   }
 }
 
@@ -176,143 +171,10 @@ void launch_segment_starts(const uint32_t* sorted_keys, uint32_t n, const SegScr
     hipLaunchKernelGGL(seg_count_kernel, dim3(nb), dim3(256), 0, s, sorted_keys, n,
                        sc.block_counts);
   hipLaunchKernelGGL(seg_scan_kernel, dim3(1), dim3(1024), 0, s, sc.block_counts, nb, n,
-                     sc.num_unique, sc.seg_starts, sc.long_count);
+                     sc.num_unique, sc.seg_starts);
   if (nb > 0)
     hipLaunchKernelGGL(seg_compact_kernel, dim3(nb), dim3(256), 0, s, sorted_keys, n,
                        sc.block_counts, sc.seg_starts);
-}
-
-// ------------------------------------------------------------------------------------------
-// Row update.  One LPR-lane group per distinct row; the group walks the row's occurrences
-// in sorted order (ascending flat position), LPR occurrences per batch of index loads, adds
-// the pooled-vector gradients they point at, then applies row-wise Adagrad:
-//   G_r += mean_c g_r[c]^2 ;  h[r,:] -= lr * g_r / (sqrt(G_r) + eps).
-// Segments longer than LONG_SEG are queued for the block-wide kernel below.
-template <int LPR>
-__device__ __forceinline__ void adagrad_apply(float4 g, uint32_t row, int c4, float* __restrict__ h,
-                                              float* __restrict__ G, float lr, float eps) {
-  constexpr int D = LPR * 4;
-  float ss = g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
-#pragma unroll
-  for (int off = 1; off < LPR; off <<= 1) ss += __shfl_xor(ss, off);
-  const float Gn = G[row] + ss * (1.0f / (float)D);
-  const float scale = lr / (sqrtf(Gn) + eps);
-  float4* hp = (float4*)(h + (size_t)row * D + c4 * 4);
-  float4 hv = *hp;
-  hv.x -= scale * g.x; hv.y -= scale * g.y; hv.z -= scale * g.z; hv.w -= scale * g.w;
-  *hp = hv;
-  if (c4 == 0) G[row] = Gn;
-}
-
-template <int LPR>
-__global__ __launch_bounds__(256) void row_update_kernel(
-    const uint32_t* __restrict__ sorted_keys, const int32_t* __restrict__ sorted_bag,
-    const float* __restrict__ de, const uint32_t* __restrict__ seg_starts,
-    const uint32_t* __restrict__ num_unique, uint32_t* __restrict__ long_list,
-    uint32_t* __restrict__ long_count, float* __restrict__ h, float* __restrict__ G, float lr,
-    float eps) {
-  constexpr int D = LPR * 4;
-  const uint32_t U = *num_unique;
-  const int lane = threadIdx.x & 63;
-  const int c4 = lane % LPR;
-  const uint32_t groups = (uint32_t)(gridDim.x * (blockDim.x / LPR));
-  for (uint32_t u = blockIdx.x * (blockDim.x / LPR) + threadIdx.x / LPR; u < U; u += groups) {
-    const uint32_t start = seg_starts[u], end = seg_starts[u + 1];
-    if (end - start > LONG_SEG) {
-      if (c4 == 0) long_list[atomicAdd(long_count, 1u)] = u;
-      continue;
-    }
-    float4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (uint32_t k0 = start; k0 < end; k0 += LPR) {
-      const uint32_t k = k0 + c4;
-      int bag = 0;
-      if (k < end) bag = sorted_bag[k];
-      const int cnt = (int)min((uint32_t)LPR, end - k0);
-      // group-uniform trip count: the source lane of every permute is an active lane
-      for (int i = 0; i < cnt; ++i) {
-        const int bg = __shfl(bag, i, LPR);
-        const float4 v = *(const float4*)(de + (size_t)bg * D + c4 * 4);
-        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-      }
-    }
-    adagrad_apply<LPR>(acc, sorted_keys[start], c4, h, G, lr, eps);
-  }
-}
-
-// One block per long segment: the 256/LPR groups take interleaved occurrences, four at a
-// time so that several gradient rows are in flight per group; partial sums are folded
-// through LDS and group 0 applies the update.
-template <int LPR>
-__global__ __launch_bounds__(256) void row_update_long_kernel(
-    const uint32_t* __restrict__ sorted_keys, const int32_t* __restrict__ sorted_bag,
-    const float* __restrict__ de, const uint32_t* __restrict__ seg_starts,
-    const uint32_t* __restrict__ long_list, const uint32_t* __restrict__ long_count,
-    float* __restrict__ h, float* __restrict__ G, float lr, float eps) {
-  constexpr int D = LPR * 4;
-  constexpr int NG = 256 / LPR;
-  __shared__ float4 part[256];
-  const uint32_t nlong = *long_count;
-  const int c4 = threadIdx.x % LPR, grp = threadIdx.x / LPR;
-  for (uint32_t li = blockIdx.x; li < nlong; li += gridDim.x) {
-    const uint32_t u = long_list[li];
-    const uint32_t start = seg_starts[u], end = seg_starts[u + 1];
-    float4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0, a2 = a0, a3 = a0;
-    uint32_t k = start + grp;
-    for (; k + 3 * NG < end; k += 4 * NG) {
-      const int b0 = sorted_bag[k], b1 = sorted_bag[k + NG], b2 = sorted_bag[k + 2 * NG],
-                b3 = sorted_bag[k + 3 * NG];
-      const float4 v0 = *(const float4*)(de + (size_t)b0 * D + c4 * 4);
-      const float4 v1 = *(const float4*)(de + (size_t)b1 * D + c4 * 4);
-      const float4 v2 = *(const float4*)(de + (size_t)b2 * D + c4 * 4);
-      const float4 v3 = *(const float4*)(de + (size_t)b3 * D + c4 * 4);
-      a0.x += v0.x; a0.y += v0.y; a0.z += v0.z; a0.w += v0.w;
-      a1.x += v1.x; a1.y += v1.y; a1.z += v1.z; a1.w += v1.w;
-      a2.x += v2.x; a2.y += v2.y; a2.z += v2.z; a2.w += v2.w;
-      a3.x += v3.x; a3.y += v3.y; a3.z += v3.z; a3.w += v3.w;
-    }
-    for (; k < end; k += NG) {
-      const int b0 = sorted_bag[k];
-      const float4 v0 = *(const float4*)(de + (size_t)b0 * D + c4 * 4);
-      a0.x += v0.x; a0.y += v0.y; a0.z += v0.z; a0.w += v0.w;
-    }
-    float4 acc = {(a0.x + a1.x) + (a2.x + a3.x), (a0.y + a1.y) + (a2.y + a3.y),
-                  (a0.z + a1.z) + (a2.z + a3.z), (a0.w + a1.w) + (a2.w + a3.w)};
-    part[threadIdx.x] = acc;
-    __syncthreads();
-    for (int half = NG / 2; half >= 1; half >>= 1) {
-      if (grp < half) {
-        float4 o = part[threadIdx.x + half * LPR];
-        acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
-        part[threadIdx.x] = acc;
-      }
-      __syncthreads();
-    }
-    if (grp == 0) adagrad_apply<LPR>(acc, sorted_keys[start], c4, h, G, lr, eps);
-    __syncthreads();
-  }
-}
-
-void launch_row_update(const uint32_t* sorted_keys, const int32_t* sorted_bag, const float* de,
-                       uint32_t n, const SegScratch& sc, int d, float* h, float* G, float lr,
-                       float eps, hipStream_t s) {
-  if (n == 0) return;
-  const int lpr = d / 4;
-  const int groups_per_block = 256 / lpr;
-  int blocks = ceil_div(n, groups_per_block);
-  if (blocks > 256 * 16) blocks = 256 * 16;
-#define L(LPR)                                                                                 \
-  hipLaunchKernelGGL((row_update_kernel<LPR>), dim3(blocks), dim3(256), 0, s, sorted_keys,     \
-                     sorted_bag, de, sc.seg_starts, sc.num_unique, sc.long_list, sc.long_count, \
-                     h, G, lr, eps);                                                           \
-  hipLaunchKernelGGL((row_update_long_kernel<LPR>), dim3(256), dim3(256), 0, s, sorted_keys,   \
-                     sorted_bag, de, sc.seg_starts, sc.long_list, sc.long_count, h, G, lr, eps)
-  switch (d) {
-    case 16: L(4); break;
-    case 32: L(8); break;
-    case 64: L(16); break;
-    default: L(32); break;
-  }
-#undef L
 }
 
 }  // namespace ss

@@ -1,0 +1,254 @@
+// Embedding backward, second half (gfx950): per distinct row, the sum of the pooled-vector
+// gradients of all its occurrences, then one row-wise Adagrad update
+//   G_r += mean_c g_r[c]^2 ;  h[r,:] -= lr * g_r / (sqrt(G_r) + eps)
+// (Section 3.2: lock-free optimiser updates on the single shared copy of the tables, with the
+// Adagrad accumulator kept beside each row).
+//
+// Input: the (row, position) pairs sorted by row, as `sorted_keys` and the pooled-vector id
+// `sorted_bag` of every sorted entry.  With Zipf-distributed ids the run lengths range from 1
+// to thousands, so work is split by POSITION, not by row: a group of LPR = d/4 lanes owns a
+// chunk of C = LPR consecutive sorted entries, whatever runs they belong to.
+//   pass 1 (chunk kernel): walk the chunk; a run that begins and ends inside the chunk is
+//     finished on the spot (gradient rows and table rows of a sub-block of 8 entries are all
+//     in flight together).  A run cut by the chunk's edges leaves a partial sum: slot 0 for
+//     the piece that continues a run from the previous chunk (flag 1 = the run ends here,
+//     flag 4 = the whole chunk lies inside the run), slot 1 for the piece that opens a run
+//     continuing into the next chunk (flag 2).
+//   pass 2 (stitch kernel): the chunk that opened a run adds the slot-0 partials of the
+//     following chunks up to the one that ends the run and applies the update; a run that
+//     spans more than 30 further chunks is queued instead.
+//   pass 3 (long-run kernel): one 1024-thread block per queued run finds the run's last chunk
+//     by scanning the flags and sums the partials in parallel.
+#include "ss_internal.h"
+
+namespace ss {
+
+int64_t row_update_chunks(int64_t max_ids, int d) {
+  const int C = d / 4;
+  return (max_ids + C - 1) / C + 1;
+}
+
+template <int LPR>
+__device__ __forceinline__ void adagrad_store(float4 g, float4 hv, float Gv, uint32_t row, int c4,
+                                              float* __restrict__ h, float* __restrict__ G,
+                                              float lr, float eps) {
+  constexpr int D = LPR * 4;
+  float ss = g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
+#pragma unroll
+  for (int off = 1; off < LPR; off <<= 1) ss += __shfl_xor(ss, off);
+  const float Gn = Gv + ss * (1.0f / (float)D);
+  const float scale = lr / (sqrtf(Gn) + eps);
+  hv.x -= scale * g.x; hv.y -= scale * g.y; hv.z -= scale * g.z; hv.w -= scale * g.w;
+  *(float4*)(h + (size_t)row * D + c4 * 4) = hv;
+  if (c4 == 0) G[row] = Gn;
+}
+
+template <int LPR>
+__global__ __launch_bounds__(256) void row_update_chunk_kernel(
+    const uint32_t* __restrict__ keys, const int32_t* __restrict__ bags,
+    const float* __restrict__ de, uint32_t n, float* __restrict__ h, float* __restrict__ G,
+    float lr, float eps, float* __restrict__ parts, uint32_t* __restrict__ flags,
+    uint32_t* __restrict__ long_count) {
+  constexpr int D = LPR * 4, C = LPR, SUB = (C < 8 ? C : 8);
+  if (blockIdx.x == 0 && threadIdx.x == 0) *long_count = 0;  // consumed by the later passes
+  const int lane = threadIdx.x & 63, c = lane % LPR, gw = lane / LPR;
+  const uint32_t nchunks = (n + C - 1) / C;
+  const uint32_t g = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+  const bool live = g < nchunks;
+  const uint32_t j = g * C + c;
+  const bool valid = live && j < n;
+  const uint32_t key = valid ? keys[j] : 0u;
+  const int bag = valid ? bags[j] : 0;
+  const bool head = valid && (j == 0 || keys[j - 1] != key);
+  const bool tail = valid && (j + 1 == n || keys[j + 1] != key);
+  const uint64_t hb = __ballot(head), tb = __ballot(tail), vb = __ballot(valid);
+  if (!live) return;
+  const uint32_t gmask = (C == 32) ? 0xFFFFFFFFu : ((1u << C) - 1u);
+  const uint32_t hm = (uint32_t)(hb >> (gw * C)) & gmask;
+  const uint32_t tm = (uint32_t)(tb >> (gw * C)) & gmask;
+  const uint32_t vm = (uint32_t)(vb >> (gw * C)) & gmask;
+  const int nv = __popc(vm);  // valid entries form a prefix of the chunk
+  float4 acc = {0.f, 0.f, 0.f, 0.f};
+  bool started = false;  // the current run began at a head inside this chunk
+  uint32_t fl = 0;
+  float4* part0 = (float4*)(parts + ((size_t)g * 2 + 0) * D) + c;
+  float4* part1 = (float4*)(parts + ((size_t)g * 2 + 1) * D) + c;
+  for (int s0 = 0; s0 < nv; s0 += SUB) {
+    float4 v[SUB], hv[SUB];
+    float Gv[SUB];
+    uint32_t rw[SUB];
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) {
+      const int p = s0 + i;
+      const int bg = __shfl(bag, p, LPR);
+      rw[i] = (uint32_t)__shfl((int)key, p, LPR);
+      v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      hv[i] = v[i];
+      Gv[i] = 0.f;
+      if (p < nv) {
+        v[i] = *(const float4*)(de + (size_t)bg * D + c * 4);
+        if ((tm >> p) & 1u) {
+          hv[i] = *(const float4*)(h + (size_t)rw[i] * D + c * 4);
+          Gv[i] = G[rw[i]];
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) {
+      const int p = s0 + i;
+      if (p < nv) {
+        if ((hm >> p) & 1u) {
+          acc = make_float4(0.f, 0.f, 0.f, 0.f);
+          started = true;
+        }
+        acc.x += v[i].x; acc.y += v[i].y; acc.z += v[i].z; acc.w += v[i].w;
+        if ((tm >> p) & 1u) {
+          if (started) {
+            adagrad_store<LPR>(acc, hv[i], Gv[i], rw[i], c, h, G, lr, eps);
+          } else {
+            *part0 = acc;  // end of a run that came in from the previous chunk
+            fl |= 1u;
+          }
+          acc = make_float4(0.f, 0.f, 0.f, 0.f);
+          started = false;
+        }
+      }
+    }
+  }
+  if (nv > 0 && !((tm >> (nv - 1)) & 1u)) {  // the last run goes on into the next chunk
+    if (started) { *part1 = acc; fl |= 2u; }
+    else { *part0 = acc; fl |= 4u; }
+  }
+  if (c == 0) flags[g] = fl;
+}
+
+template <int LPR>
+__global__ __launch_bounds__(256) void row_update_stitch_kernel(
+    const uint32_t* __restrict__ keys, uint32_t n, float* __restrict__ parts,
+    const uint32_t* __restrict__ flags, float* __restrict__ h, float* __restrict__ G, float lr,
+    float eps, uint32_t* __restrict__ long_list, uint32_t* __restrict__ long_count) {
+  constexpr int D = LPR * 4, C = LPR, MAXB = 16;
+  const int c = threadIdx.x % LPR;
+  const uint32_t nchunks = (n + C - 1) / C;
+  const uint32_t g = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+  if (g >= nchunks) return;
+  if (!(flags[g] & 2u)) return;
+  // an open run at the end of chunk g means the chunk is full: its last entry is (g+1)*C-1
+  const uint32_t row = keys[(g + 1) * C - 1];
+  const float4 hv = *(const float4*)(h + (size_t)row * D + c * 4);
+  const float Gv = G[row];
+  float4* mine = (float4*)(parts + ((size_t)g * 2 + 1) * D) + c;
+  float4 acc = *mine;
+  uint32_t g2 = g + 1;
+  int batch = 2;
+  bool done = false;
+  for (int round = 0; round < 4 && !done; ++round) {  // 2 + 4 + 8 + 16 chunks
+    float4 p[MAXB];
+    uint32_t f[MAXB];
+#pragma unroll
+    for (int i = 0; i < MAXB; ++i) {
+      const uint32_t gi = g2 + i;
+      p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      f[i] = 1u;  // past the last chunk: treat as the end of the run
+      if (i < batch && gi < nchunks) {
+        f[i] = flags[gi];
+        p[i] = *((const float4*)(parts + ((size_t)gi * 2 + 0) * D) + c);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < MAXB; ++i) {
+      if (!done && i < batch) {
+        acc.x += p[i].x; acc.y += p[i].y; acc.z += p[i].z; acc.w += p[i].w;
+        if (!(f[i] & 4u)) done = true;
+      }
+    }
+    g2 += batch;
+    batch = min(MAXB, batch * 2);
+  }
+  if (done) {
+    adagrad_store<LPR>(acc, hv, Gv, row, c, h, G, lr, eps);
+  } else {
+    *mine = acc;  // sum so far; the long-run kernel continues from chunk g2
+    if (c == 0) {
+      const uint32_t slot = atomicAdd(long_count, 1u);
+      long_list[2 * slot] = g;
+      long_list[2 * slot + 1] = g2;
+    }
+  }
+}
+
+template <int LPR>
+__global__ __launch_bounds__(1024) void row_update_long_kernel(
+    const uint32_t* __restrict__ keys, uint32_t n, const float* __restrict__ parts,
+    const uint32_t* __restrict__ flags, float* __restrict__ h, float* __restrict__ G, float lr,
+    float eps, const uint32_t* __restrict__ long_list, const uint32_t* __restrict__ long_count) {
+  constexpr int D = LPR * 4, C = LPR, NG = 1024 / LPR;
+  __shared__ float4 red[1024];
+  __shared__ uint32_t last_chunk;
+  const uint32_t nchunks = (n + C - 1) / C;
+  const uint32_t nlong = *long_count;
+  const int c = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  for (uint32_t li = blockIdx.x; li < nlong; li += gridDim.x) {
+    const uint32_t g = long_list[2 * li], g2 = long_list[2 * li + 1];
+    // the run's last chunk: the first one at or after g2 whose flags lack "whole chunk inside"
+    if (threadIdx.x == 0) last_chunk = nchunks - 1;
+    __syncthreads();
+    for (uint32_t base = g2; base < nchunks; base += 1024) {
+      const uint32_t gi = base + threadIdx.x;
+      if (gi < nchunks && !(flags[gi] & 4u)) atomicMin(&last_chunk, gi);
+      __syncthreads();
+      if (last_chunk < base + 1024) break;  // block-uniform: read after the barrier
+      __syncthreads();
+    }
+    __syncthreads();
+    const uint32_t ge = last_chunk;
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t gi = g2 + grp; gi <= ge; gi += NG) {
+      const float4 v = *((const float4*)(parts + ((size_t)gi * 2 + 0) * D) + c);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int half = NG / 2; half >= 1; half >>= 1) {
+      if (grp < half) {
+        const float4 o = red[threadIdx.x + half * LPR];
+        acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+        red[threadIdx.x] = acc;
+      }
+      __syncthreads();
+    }
+    if (grp == 0) {
+      const float4 first = *((const float4*)(parts + ((size_t)g * 2 + 1) * D) + c);
+      acc.x += first.x; acc.y += first.y; acc.z += first.z; acc.w += first.w;
+      const uint32_t row = keys[(g + 1) * C - 1];
+      const float4 hv = *(const float4*)(h + (size_t)row * D + c * 4);
+      adagrad_store<LPR>(acc, hv, G[row], row, c, h, G, lr, eps);
+    }
+    __syncthreads();
+  }
+}
+
+void launch_row_update(const uint32_t* sorted_keys, const int32_t* sorted_bag, const float* de,
+                       uint32_t n, const RowUpdateScratch& sc, int d, float* h, float* G, float lr,
+                       float eps, hipStream_t s) {
+  if (n == 0) return;
+  const int lpr = d / 4;
+  const int64_t nchunks = ((int64_t)n + lpr - 1) / lpr;
+  const int blocks = ceil_div(nchunks, 256 / lpr);
+#define L(LPR)                                                                                    \
+  hipLaunchKernelGGL((row_update_chunk_kernel<LPR>), dim3(blocks), dim3(256), 0, s, sorted_keys,  \
+                     sorted_bag, de, n, h, G, lr, eps, sc.parts, sc.flags, sc.long_count);        \
+  hipLaunchKernelGGL((row_update_stitch_kernel<LPR>), dim3(blocks), dim3(256), 0, s, sorted_keys, \
+                     n, sc.parts, sc.flags, h, G, lr, eps, sc.long_list, sc.long_count);          \
+  hipLaunchKernelGGL((row_update_long_kernel<LPR>), dim3(64), dim3(1024), 0, s, sorted_keys, n,   \
+                     sc.parts, sc.flags, h, G, lr, eps, sc.long_list, sc.long_count)
+  switch (d) {
+    case 16: L(4); break;
+    case 32: L(8); break;
+    case 64: L(16); break;
+    default: L(32); break;
+  }
+#undef L
+}
+
+}  // namespace ss

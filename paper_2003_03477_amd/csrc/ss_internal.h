@@ -34,17 +34,23 @@ struct SegScratch {
   uint32_t* block_counts;  // [seg_blocks]
   uint32_t* seg_starts;    // [max_ids + 1]
   uint32_t* num_unique;    // [1]
-  uint32_t* long_list;     // [max_ids / LONG_SEG + 1] segment ids longer than the threshold
-  uint32_t* long_count;    // [1]
 };
 // Heads of runs of equal keys in a sorted key array -> compacted start offsets.
 void launch_segment_starts(const uint32_t* sorted_keys, uint32_t n, const SegScratch& sc,
                            hipStream_t s);
-// Per distinct row: g = sum of de over its occurrences; row-wise Adagrad on h and G.
+// ---------------------------------------------------------------------------- row_update.hip
+struct RowUpdateScratch {
+  float* parts;     // [row_update_chunks(max_ids, d) * 2 * d] partial sums of runs cut by chunks
+  uint32_t* flags;  // [row_update_chunks(max_ids, d)]
+  uint32_t* long_list;   // [2 * (row_update_chunks(max_ids, d) / 30 + 2)] (first, next) chunk pairs
+  uint32_t* long_count;  // [1]
+};
+int64_t row_update_chunks(int64_t max_ids, int d);
+// Per distinct row: g = sum of de over its occurrences (all of them first), then row-wise
+// Adagrad on h and G.  Input: keys sorted ascending with the pooled-vector id of each entry.
 void launch_row_update(const uint32_t* sorted_keys, const int32_t* sorted_bag, const float* de,
-                       uint32_t n,
-                       const SegScratch& sc, int d, float* h, float* G, float lr, float eps,
-                       hipStream_t s);
+                       uint32_t n, const RowUpdateScratch& sc, int d, float* h, float* G, float lr,
+                       float eps, hipStream_t s);
 
 // ---------------------------------------------------------------------------- sort.hip
 struct SortScratch {
