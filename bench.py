@@ -4,12 +4,18 @@
 Workload (default): the Mid CTR model -- 13 dense features, 8 tables x 1e6 rows x dim 64
 fp32, ids Zipf(1.05), bag length Poisson(20)+1, bottom MLP 13-256-128-64, top MLP
 100-512-256-1 with bf16 MFMA GEMMs over fp32 master weights, batch 2048, K=4 replicas each
-fed by its own worker stream, Shadow EASGD (alpha 0.1) enqueued on a separate stream once per
-5 trainer iterations of a replica.  One bench "step" = one ss_train_step on one batch; steps
-go round-robin over the K replicas.  Inputs are seeded synthetic batches already resident in
-HBM when the clock starts.
+fed by its own worker stream (one host thread per stream), Shadow EASGD (alpha 0.1) enqueued
+on a separate stream once per 5 trainer iterations of a replica.  One bench "step" = one
+ss_train_step on one batch (forward, loss, backward, SGD on the replica, sort + segmented
+reduction + row-wise Adagrad on the tables); steps go round-robin over the K replicas.
+Inputs are seeded synthetic batches already resident in HBM when the clock starts.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline      the dominant single memory-bound kernel (largest summed time of the gather
+                and the row-update chunk pass), timed with HIP events inside the timed region
+  kernels       the same event timing for every kernel class
+  sync_isolation  the three shadow rules on K=8 x 50M-parameter replicas (GB/s vs HBM peak)
+  cpu_baseline  the numpy oracle on the host cores, on a bounded sample of the same workload
 """
 from __future__ import annotations
 
@@ -25,6 +31,13 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X datasheet
 
+# HBM bytes per launch measured with `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` on the
+# Mid workload (KiB per dispatch * 1024; both counters read 1.00x the known size of a plain
+# streaming kernel).  Source: profiles/mid_hbm_traffic.txt.  None = not measured.
+MEASURED_TRAFFIC = {
+    "mid": {"gather": None, "row_update_chunk": None},
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -33,16 +46,19 @@ def parse():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="mid", choices=["mid", "tiny", "hogwild"])
     ap.add_argument("--batches", type=int, default=16, help="distinct batches cycled through")
+    ap.add_argument("--workers-per-replica", type=int, default=1,
+                    help="Hogwild worker streams per replica")
     ap.add_argument("--no-shadow", action="store_true", help="run without the shadow stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--profile-kernel", default="gather",
-                    choices=["gather", "sort", "row_update", "mlp", "interact", "none"])
+    ap.add_argument("--no-sync-isolation", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket kernels with events in the timed region")
     ap.add_argument("--single-thread", action="store_true",
-                    help="enqueue all replicas from one host thread")
+                    help="enqueue all streams from one host thread")
     return ap.parse_args()
 
 
-def algorithmic_bytes(kernel, wl, batch_np, n_unique=None):
+def algorithmic_bytes(kernel, wl, batch_np, n_unique):
     """Bytes the method itself must move per launch of `kernel` on this batch."""
     n = int(batch_np.offsets[-1])
     B, T, d = wl.batch, wl.num_tables, wl.emb_dim
@@ -50,14 +66,11 @@ def algorithmic_bytes(kernel, wl, batch_np, n_unique=None):
         # per id: one row (4d) + its index (4) + sort key and pooled-vector id written (8);
         # per bag: pooled vector written (4d) + its offset (4)
         return n * (4 * d + 4 + 8) + B * T * (4 * d + 4)
-    if kernel == "row_update":
-        # per occurrence: de row (4d) + sorted position and bag id (8); per distinct row:
-        # row read + written (8d) + accumulator read + written (8) + key and segment start (8)
-        return n * (4 * d + 8) + n_unique * (8 * d + 16)
-    if kernel == "sort":
-        passes = 3
-        return n * 16 * passes + n * 4  # key+value read and written per pass, + segment scan
-    return None
+    if kernel == "row_update_chunk":
+        # per occurrence: gradient row (4d) + sorted key and bag id (8); per distinct row:
+        # row read + written (8d) + accumulator read + written (8)
+        return n * (4 * d + 8) + n_unique * (8 * d + 8)
+    raise KeyError(kernel)
 
 
 def cpu_baseline(wl, gen, seconds=20.0):
@@ -76,7 +89,7 @@ def cpu_baseline(wl, gen, seconds=20.0):
     while True:
         orc.train_step(steps % wl.num_replicas, *cp.batches[steps % len(cp.batches)].as_tuple())
         steps += 1
-        if steps % (5 * wl.num_replicas) == 0:
+        if steps % (wl.sync_gap * wl.num_replicas) == 0:
             orc.shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu)
         if time.perf_counter() - t0 > seconds or steps >= 64:
             break
@@ -88,8 +101,39 @@ def cpu_baseline(wl, gen, seconds=20.0):
         cores = 1
     return {"value": wl.batch * steps / dt, "unit": "examples/s", "cores": cores,
             "kind": "oracle",
-            "sample": f"{steps} train steps of batch {wl.batch} (fp64 numpy oracle, tables "
-                      f"compacted to the {sum(cp.rows)} touched rows) in {dt:.1f} s"}
+            "sample": f"{steps} train steps of batch {wl.batch} (+ sync rounds) of the fp64 "
+                      f"numpy oracle, tables compacted to the {sum(cp.rows)} touched rows, "
+                      f"{dt:.1f} s; BLAS may use up to `cores` threads, the rest is one thread"}
+
+
+def sync_isolation(binding, torch, rounds=20):
+    """K=8 replicas of 50M fp32 parameters + centre copy: rounds of each rule back to back."""
+    K, P = 8, 50_000_000
+    g = torch.Generator(device="cuda").manual_seed(4)
+    W = torch.randn(K * P, device="cuda", generator=g) * 0.02
+    ps = torch.randn(P, device="cuda", generator=g) * 0.02
+    wg = ps.clone()
+    v = torch.zeros(P, device="cuda")
+    st = torch.cuda.Stream()
+    out = {}
+    per_param = {"easgd": 8 * (K + 1), "ma": 8 * K + 4, "bmuf": 8 * K + 16}
+    args = {"easgd": dict(alpha=0.05), "ma": dict(alpha=0.5), "bmuf": dict(alpha=0.5, eta=1.0, momentum=0.9)}
+    for algo in ("easgd", "ma", "bmuf"):
+        with torch.cuda.stream(st):
+            for _ in range(3):
+                binding.ss_sync_round(algo, K, P, P, W, ps, wg, v, stream=st, **args[algo])
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            for _ in range(rounds):
+                binding.ss_sync_round(algo, K, P, P, W, ps, wg, v, stream=st, **args[algo])
+            e1.record(st)
+        e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / rounds
+        gbs = per_param[algo] * P / us / 1e3
+        out[algo] = {"us_per_round": us, "algorithmic_bytes": per_param[algo] * P,
+                     "GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    out["config"] = f"K={K} replicas x {P} fp32 parameters, {rounds} rounds per rule back to back"
+    return out
 
 
 def main():
@@ -104,37 +148,40 @@ def main():
 
     wl = synth.WORKLOADS[args.workload]()
     K = wl.num_replicas
+    WPR = args.workers_per_replica
+    NS = K * WPR                           # worker streams = worker slots
     gen = synth.BatchGenerator(wl)
     host_batches = [gen.batch(s) for s in range(args.batches)]
     max_ids = max(int(b.offsets[-1]) for b in host_batches) + 4096
-    gpu = binding.from_workload(wl, num_worker_slots=K, max_ids=max_ids)
+    gpu = binding.from_workload(wl, num_worker_slots=NS, max_ids=max_ids)
     gpu.ss_init_tables_hash()
     gpu.ss_init_dense(synth.dense_w0(wl))
     dev_batches = [binding.upload_batch(b) for b in host_batches]
-    streams = [torch.cuda.Stream() for _ in range(K)]
+    streams = [torch.cuda.Stream() for _ in range(NS)]
     shadow = torch.cuda.Stream()
-    losses = torch.zeros(K, dtype=torch.float32, device="cuda")
+    losses = torch.zeros(NS, dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
 
     def run(total_steps, first_step):
-        """Round-robin: step s trains replica s % K on stream s % K (one host thread per
-        replica, as a trainer's worker threads would)."""
-        def worker(i):
-            mine = range(first_step + i, first_step + total_steps, K)
-            for j, s in enumerate(mine):
-                gpu.ss_train_step(i, i, dev_batches[s % len(dev_batches)], streams[i],
-                                  losses[i:i + 1])
-                if i == 0 and not args.no_shadow and (j + 1) % wl.sync_gap == 0:
+        """Step s runs on worker stream s % NS, which trains replica (s % NS) % K."""
+        def one(s):
+            w = s % NS
+            gpu.ss_train_step(w % K, w, dev_batches[s % len(dev_batches)], streams[w],
+                              losses[w:w + 1])
+
+        def worker(w):
+            for j, s in enumerate(range(first_step + w, first_step + total_steps, NS)):
+                one(s)
+                # the shadow loop is paced off replica 0's first worker
+                if w == 0 and not args.no_shadow and (j + 1) % max(1, wl.sync_gap // WPR) == 0:
                     gpu.ss_shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
         if args.single_thread:
             for s in range(first_step, first_step + total_steps):
-                i = s % K
-                gpu.ss_train_step(i, i, dev_batches[s % len(dev_batches)], streams[i],
-                                  losses[i:i + 1])
-                if not args.no_shadow and (s + 1) % (wl.sync_gap * K) == 0:
+                one(s)
+                if not args.no_shadow and (s + 1 - first_step) % (wl.sync_gap * K) == 0:
                     gpu.ss_shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
             return
-        ts = [threading.Thread(target=worker, args=(i,)) for i in range(K)]
+        ts = [threading.Thread(target=worker, args=(w,)) for w in range(NS)]
         for t in ts:
             t.start()
         for t in ts:
@@ -142,10 +189,14 @@ def main():
 
     run(args.warmup, 0)
     torch.cuda.synchronize()
-    kid = {"gather": binding.K_GATHER, "sort": binding.K_SORT, "row_update": binding.K_ROW_UPDATE,
-           "mlp": binding.K_MLP, "interact": binding.K_INTERACT, "none": binding.K_NONE}[args.profile_kernel]
-    if kid:
-        gpu.ss_profile_arm(kid)
+    # Inside the timed region only the two roofline candidates are bracketed (two event pairs
+    # per step); the other classes are timed in a short extra pass after the clock stops.
+    classes = {"gather": binding.K_GATHER, "row_update_chunk": binding.K_ROW_UPDATE_CHUNK}
+    extra = {"row_update_all": binding.K_ROW_UPDATE, "sort_and_segments": binding.K_SORT,
+             "mlp_groups": binding.K_MLP, "interaction_fwd": binding.K_INTERACT_FWD,
+             "interaction_bwd": binding.K_INTERACT_BWD, "sync_round": binding.K_SYNC}
+    if not args.no_kernel_events:
+        gpu.ss_profile_arm(*classes.values())
     steps0, rounds0, _ = gpu.ss_get_counters()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -153,31 +204,46 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     steps1, rounds1, _ = gpu.ss_get_counters()
-    launches, kernel_ms = gpu.ss_profile_read() if kid else (0, 0.0)
 
-    roofline = None
-    if kid and launches and args.profile_kernel in ("gather", "row_update", "sort"):
-        # average algorithmic bytes over the batches cycled through
-        uniq = None
-        if args.profile_kernel == "row_update":
-            uniq = [sum(len(np.unique(b.indices[b.offsets[t * wl.batch]:b.offsets[(t + 1) * wl.batch]]))
-                        for t in range(wl.num_tables)) for b in host_batches]
-        per = [algorithmic_bytes(args.profile_kernel, wl, b, None if uniq is None else uniq[k])
-               for k, b in enumerate(host_batches)]
-        bytes_per_launch = float(np.mean(per))
-        avg_s = kernel_ms / launches / 1e3
-        achieved = bytes_per_launch / avg_s / 1e9
-        roofline = {"bound": "hbm", "kernel": args.profile_kernel, "achieved": achieved,
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": None, "avg_launch_us": avg_s * 1e6, "launches": launches,
-                    "algorithmic_bytes_per_launch": bytes_per_launch}
-    elif kid and launches:
-        roofline = {"bound": "mfma" if args.profile_kernel == "mlp" else "hbm",
-                    "kernel": args.profile_kernel, "achieved": None, "peak": None, "unit": None,
-                    "frac": None, "traffic": None, "avg_launch_us": kernel_ms / launches * 1e3,
-                    "launches": launches}
+    kernels, roofline = {}, None
+    if not args.no_kernel_events:
+        for name, kid in classes.items():
+            n, ms = gpu.ss_profile_read(kid)
+            if n:
+                kernels[name] = {"brackets": n, "avg_us": ms / n * 1e3, "total_ms": ms,
+                                 "where": "timed region"}
+        gpu.ss_profile_arm(*extra.values())
+        run(min(args.steps, 10 * wl.sync_gap * K), args.warmup + args.steps)
+        for name, kid in extra.items():
+            n, ms = gpu.ss_profile_read(kid)
+            if n:
+                kernels[name] = {"brackets": n, "avg_us": ms / n * 1e3, "total_ms": ms,
+                                 "where": "extra pass after the timed region"}
+        uniq = [sum(len(np.unique(b.indices[b.offsets[t * wl.batch]:b.offsets[(t + 1) * wl.batch]]))
+                    for t in range(wl.num_tables)) for b in host_batches]
+        for name in ("gather", "row_update_chunk"):
+            if name not in kernels:
+                continue
+            per = [algorithmic_bytes(name, wl, b, uniq[k]) for k, b in enumerate(host_batches)]
+            bpl = float(np.mean(per))
+            ach = bpl / (kernels[name]["avg_us"] * 1e-6) / 1e9
+            kernels[name].update({"algorithmic_bytes_per_launch": bpl, "GBps": ach,
+                                  "frac_of_hbm_peak": ach / HBM_PEAK_GBS})
+        cand = [k for k in ("gather", "row_update_chunk") if k in kernels]
+        if cand:
+            dom = max(cand, key=lambda k: kernels[k]["total_ms"])
+            kd = kernels[dom]
+            traffic = MEASURED_TRAFFIC.get(wl.name, {}).get(dom)
+            roofline = {"bound": "hbm", "kernel": dom, "achieved": kd["GBps"],
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kd["frac_of_hbm_peak"],
+                        "traffic": traffic, "avg_launch_us": kd["avg_us"],
+                        "launches": kd["brackets"],
+                        "algorithmic_bytes_per_launch": kd["algorithmic_bytes_per_launch"]}
 
     rounds = rounds1 - rounds0
+    shadow_txt = ("no shadow sync" if args.no_shadow else
+                  f"S-{wl.algo.upper()} alpha={wl.alpha} on a shadow stream every {wl.sync_gap} "
+                  f"trainer steps")
     out = {
         "metric": "train examples/s on 1 GPU with background sync",
         "value": wl.batch * args.steps / dt,
@@ -188,13 +254,19 @@ def main():
         "dtype": "bf16" if wl.bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.batch}, {wl.num_tables} tables x {wl.rows[0]} "
                                f"rows x d{wl.emb_dim} fp32, Zipf({wl.zipf_s}), bag Poisson("
-                               f"{wl.bag_lambda:g})+1, K={K} replicas on {K} worker streams, "
-                               f"{'no shadow sync' if args.no_shadow else 'S-' + wl.algo.upper() + ' alpha=' + str(wl.alpha) + ' on a shadow stream every ' + str(wl.sync_gap) + ' trainer steps'}",
+                               f"{wl.bag_lambda:g})+1, K={K} replicas x {WPR} worker stream(s), "
+                               f"{shadow_txt}",
                    "shadow_rounds": int(rounds),
                    "avg_sync_gap": (float((steps1 - steps0).mean()) / rounds) if rounds else None,
-                   "host_threads": 1 if args.single_thread else K},
+                   "host_threads": 1 if args.single_thread else NS},
         "roofline": roofline,
+        "kernels": kernels,
     }
+    gpu.close()
+    del gpu
+    torch.cuda.empty_cache()
+    if not args.no_sync_isolation:
+        out["sync_isolation"] = sync_isolation(binding, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, gen)
     print(json.dumps(out))

@@ -195,20 +195,26 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
 int ss_get_counters(ss_ctx* ctx, uint64_t* steps_per_replica, uint64_t* rounds,
                     uint64_t* examples);
 
-/* Kernel timing with HIP events on the launching stream: bracket every launch of the named
- * kernel class until ss_profile_read, which synchronises, returns the number of bracketed
- * launches and their summed duration in ms, and disarms.  kernel ids: ss_kernel_id. */
+/* Kernel timing with HIP events recorded on the launching stream.  ss_profile_arm takes a bit
+ * mask (bit i = ss_kernel_id i); from then on every launch of an armed class is bracketed by
+ * an event pair (at most 4096 brackets per class).  ss_profile_read synchronises the device,
+ * returns the number of brackets of one class and their summed duration in ms, and disarms
+ * that class.  Classes marked "one kernel" bracket exactly one kernel launch, so their average
+ * is comparable with a profiler's per-kernel average; the others bracket a group of launches. */
 typedef enum {
   SS_K_NONE = 0,
-  SS_K_GATHER = 1,      /* embedding gather + sum pooling                              */
-  SS_K_SORT = 2,        /* all radix-sort passes of one step, as one bracket           */
-  SS_K_ROW_UPDATE = 3,  /* segmented reduction + row-wise Adagrad                       */
-  SS_K_SYNC = 4,        /* one shadow round                                             */
-  SS_K_MLP = 5,         /* all MLP GEMM kernels of one step (fwd+bwd), one bracket each */
-  SS_K_INTERACT = 6
+  SS_K_GATHER = 1,            /* one kernel: embedding gather + sum pooling                  */
+  SS_K_SORT = 2,              /* group: all radix-sort passes + segment compaction of a step */
+  SS_K_ROW_UPDATE_CHUNK = 3,  /* one kernel: chunk pass of the segmented reduction + Adagrad */
+  SS_K_SYNC = 4,              /* one kernel: one shadow round                                */
+  SS_K_MLP = 5,               /* group: MLP kernels (bottom fwd / top fwd / top bwd / bottom bwd) */
+  SS_K_INTERACT_FWD = 6,      /* one kernel                                                  */
+  SS_K_INTERACT_BWD = 7,      /* one kernel                                                  */
+  SS_K_ROW_UPDATE = 8,        /* group: chunk + stitch + long-run passes                     */
+  SS_K_COUNT = 9
 } ss_kernel_id;
-int ss_profile_arm(ss_ctx* ctx, int32_t kernel_id);
-int ss_profile_read(ss_ctx* ctx, int64_t* launches, double* total_ms);
+int ss_profile_arm(ss_ctx* ctx, uint32_t kernel_mask);
+int ss_profile_read(ss_ctx* ctx, int32_t kernel_id, int64_t* launches, double* total_ms);
 
 #ifdef __cplusplus
 }

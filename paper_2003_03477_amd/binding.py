@@ -27,7 +27,8 @@ _DBG_DTYPE = {DBG_POOLED: np.float32, DBG_INTERACT: np.float32, DBG_LOGITS: np.f
               DBG_SORTED_ROWS: np.uint32, DBG_SORTED_POS: np.uint32,
               DBG_SEG_STARTS: np.uint32, DBG_NUM_UNIQUE: np.uint32, DBG_BAG_OF_POS: np.int32}
 
-K_NONE, K_GATHER, K_SORT, K_ROW_UPDATE, K_SYNC, K_MLP, K_INTERACT = range(7)
+(K_NONE, K_GATHER, K_SORT, K_ROW_UPDATE_CHUNK, K_SYNC, K_MLP, K_INTERACT_FWD, K_INTERACT_BWD,
+ K_ROW_UPDATE) = range(9)
 
 EXPORTS = [
     "ss_workspace_bytes", "ss_init", "ss_destroy", "ss_last_error", "ss_init_tables_hash",
@@ -92,8 +93,8 @@ def load() -> C.CDLL:
     lib.ss_read_rows.argtypes = [vp, i32, vp, i64, vp, vp]
     lib.ss_read_debug.argtypes = [vp, i32, i32, vp, C.c_size_t, C.POINTER(C.c_size_t)]
     lib.ss_get_counters.argtypes = [vp, vp, vp, vp]
-    lib.ss_profile_arm.argtypes = [vp, i32]
-    lib.ss_profile_read.argtypes = [vp, C.POINTER(i64), C.POINTER(C.c_double)]
+    lib.ss_profile_arm.argtypes = [vp, C.c_uint32]
+    lib.ss_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double)]
     for name in EXPORTS:
         fn = getattr(lib, name)
         if fn.restype is C.c_int:
@@ -288,12 +289,15 @@ class ShadowSync:
                                              C.byref(examples)), "ss_get_counters")
         return steps, int(rounds.value), int(examples.value)
 
-    def ss_profile_arm(self, kernel_id: int):
-        self._check(self.lib.ss_profile_arm(self.ctx, kernel_id), "ss_profile_arm")
+    def ss_profile_arm(self, *kernel_ids: int):
+        mask = 0
+        for k in kernel_ids:
+            mask |= 1 << k
+        self._check(self.lib.ss_profile_arm(self.ctx, mask), "ss_profile_arm")
 
-    def ss_profile_read(self):
+    def ss_profile_read(self, kernel_id: int):
         n, ms = C.c_int64(0), C.c_double(0.0)
-        self._check(self.lib.ss_profile_read(self.ctx, C.byref(n), C.byref(ms)),
+        self._check(self.lib.ss_profile_read(self.ctx, kernel_id, C.byref(n), C.byref(ms)),
                     "ss_profile_read")
         return int(n.value), float(ms.value)
 

@@ -105,9 +105,11 @@ struct ss_ctx {
   std::atomic<bool> shadow_run{false};
   // profiling
   std::mutex prof_mu;
-  int prof_kernel = 0;
-  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
-  size_t prof_used = 0;
+  std::atomic<uint32_t> prof_mask{0};
+  struct ProfPool {
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
+    size_t used = 0;
+  } prof[SS_K_COUNT];
 
   explicit ss_ctx(int k) : steps(k) {
     for (auto& a : steps) a.store(0);
@@ -323,7 +325,8 @@ void ss_destroy(ss_ctx* ctx) {
   if (!ctx) return;
   ss_shadow_stop(ctx);
   (void)hipDeviceSynchronize();
-  for (auto& p : ctx->prof_events) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+  for (auto& pool : ctx->prof)
+    for (auto& p : pool.ev) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
   delete ctx;
 }
 
@@ -442,10 +445,11 @@ namespace {
 struct ProfScope {
   ss_ctx* x; hipStream_t s; hipEvent_t stop = nullptr;
   ProfScope(ss_ctx* ctx, int id, hipStream_t st) : x(ctx), s(st) {
-    if (x->prof_kernel != id) return;
+    if (!(x->prof_mask.load(std::memory_order_relaxed) & (1u << id))) return;
     std::lock_guard<std::mutex> lk(x->prof_mu);
-    if (x->prof_kernel != id || x->prof_used >= x->prof_events.size()) return;
-    auto& p = x->prof_events[x->prof_used++];
+    auto& pool = x->prof[id];
+    if (!(x->prof_mask.load() & (1u << id)) || pool.used >= pool.ev.size()) return;
+    auto& p = pool.ev[pool.used++];
     (void)hipEventRecord(p.first, s);
     stop = p.second;
   }
@@ -509,7 +513,7 @@ static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, floa
                              s.bag_of_pos, fused_last(x) ? loss : nullptr, st);
   }
   {
-    ProfScope ps(x, SS_K_INTERACT, st);
+    ProfScope ps(x, SS_K_INTERACT_FWD, st);
     launch_interaction_fwd(s.z0, s.e, B, x->T, x->d, s.f, x->ldf, s.f_bf16, x->ldf16, st);
   }
   // ---- top MLP
@@ -618,7 +622,7 @@ static void backward_dense(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
     run_layers(L - 1, nb, s.dlogit, 1, true);
   }
   {
-    ProfScope ps(x, SS_K_INTERACT, st);
+    ProfScope ps(x, SS_K_INTERACT_BWD, st);
     launch_interaction_bwd(s.z0, s.e, s.df, x->ldf, B, x->T, x->d, s.dz0, s.de, st);
   }
   {
@@ -654,9 +658,13 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
       launch_segment_starts(s.sorted_keys, n, s.seg, st);
     }
     {
-      ProfScope ps(x, SS_K_ROW_UPDATE, st);
-      launch_row_update(s.sorted_keys, s.sorted_bag, s.de, n, s.upd, x->d, x->h, x->G, x->lr_emb,
-                        x->eps, st);
+      ProfScope all(x, SS_K_ROW_UPDATE, st);
+      {
+        ProfScope ps(x, SS_K_ROW_UPDATE_CHUNK, st);
+        launch_row_update_chunk(s.sorted_keys, s.sorted_bag, s.de, n, s.upd, x->d, x->h, x->G,
+                                x->lr_emb, x->eps, st);
+      }
+      launch_row_update_finish(s.sorted_keys, n, s.upd, x->d, x->h, x->G, x->lr_emb, x->eps, st);
     }
     x->steps[replica].fetch_add(1);
     x->examples.fetch_add((uint64_t)B);
@@ -786,36 +794,42 @@ int ss_get_counters(ss_ctx* ctx, uint64_t* steps_per_replica, uint64_t* rounds, 
   return SS_OK;
 }
 
-int ss_profile_arm(ss_ctx* ctx, int32_t kernel_id) {
+int ss_profile_arm(ss_ctx* ctx, uint32_t kernel_mask) {
   if (!ctx) return SS_EINVAL;
-  if (kernel_id < SS_K_NONE || kernel_id > SS_K_INTERACT) return fail(ctx, SS_EINVAL, "bad kernel id");
+  if (kernel_mask >> SS_K_COUNT) return fail(ctx, SS_EINVAL, "bad kernel mask");
   std::lock_guard<std::mutex> lk(ctx->prof_mu);
-  if (ctx->prof_events.empty()) {
-    ctx->prof_events.resize(8192);
-    for (auto& p : ctx->prof_events) {
-      HIP_TRY(ctx, hipEventCreate(&p.first));
-      HIP_TRY(ctx, hipEventCreate(&p.second));
+  for (int id = 1; id < SS_K_COUNT; ++id) {
+    if (!(kernel_mask & (1u << id))) continue;
+    auto& pool = ctx->prof[id];
+    if (pool.ev.empty()) {
+      pool.ev.resize(4096);
+      for (auto& p : pool.ev) {
+        HIP_TRY(ctx, hipEventCreate(&p.first));
+        HIP_TRY(ctx, hipEventCreate(&p.second));
+      }
     }
+    pool.used = 0;
   }
-  ctx->prof_used = 0;
-  ctx->prof_kernel = kernel_id;
+  ctx->prof_mask = kernel_mask & ~1u;
   return SS_OK;
 }
 
-int ss_profile_read(ss_ctx* ctx, int64_t* launches, double* total_ms) {
+int ss_profile_read(ss_ctx* ctx, int32_t kernel_id, int64_t* launches, double* total_ms) {
   if (!ctx) return SS_EINVAL;
+  if (kernel_id < 1 || kernel_id >= SS_K_COUNT) return fail(ctx, SS_EINVAL, "bad kernel id");
   HIP_TRY(ctx, hipDeviceSynchronize());
   std::lock_guard<std::mutex> lk(ctx->prof_mu);
+  ctx->prof_mask = ctx->prof_mask.load() & ~(1u << kernel_id);
+  auto& pool = ctx->prof[kernel_id];
   double tot = 0;
-  for (size_t i = 0; i < ctx->prof_used; ++i) {
+  for (size_t i = 0; i < pool.used; ++i) {
     float ms = 0;
-    HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->prof_events[i].first, ctx->prof_events[i].second));
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, pool.ev[i].first, pool.ev[i].second));
     tot += ms;
   }
-  if (launches) *launches = (int64_t)ctx->prof_used;
+  if (launches) *launches = (int64_t)pool.used;
   if (total_ms) *total_ms = tot;
-  ctx->prof_kernel = SS_K_NONE;
-  ctx->prof_used = 0;
+  pool.used = 0;
   return SS_OK;
 }
 

@@ -228,16 +228,32 @@ __global__ __launch_bounds__(1024) void row_update_long_kernel(
   }
 }
 
-void launch_row_update(const uint32_t* sorted_keys, const int32_t* sorted_bag, const float* de,
-                       uint32_t n, const RowUpdateScratch& sc, int d, float* h, float* G, float lr,
-                       float eps, hipStream_t s) {
+void launch_row_update_chunk(const uint32_t* sorted_keys, const int32_t* sorted_bag,
+                             const float* de, uint32_t n, const RowUpdateScratch& sc, int d,
+                             float* h, float* G, float lr, float eps, hipStream_t s) {
+  if (n == 0) return;
+  const int lpr = d / 4;
+  const int64_t nchunks = ((int64_t)n + lpr - 1) / lpr;
+  const int blocks = ceil_div(nchunks, 256 / lpr);
+#define L(LPR)                                                                                   \
+  hipLaunchKernelGGL((row_update_chunk_kernel<LPR>), dim3(blocks), dim3(256), 0, s, sorted_keys, \
+                     sorted_bag, de, n, h, G, lr, eps, sc.parts, sc.flags, sc.long_count)
+  switch (d) {
+    case 16: L(4); break;
+    case 32: L(8); break;
+    case 64: L(16); break;
+    default: L(32); break;
+  }
+#undef L
+}
+
+void launch_row_update_finish(const uint32_t* sorted_keys, uint32_t n, const RowUpdateScratch& sc,
+                              int d, float* h, float* G, float lr, float eps, hipStream_t s) {
   if (n == 0) return;
   const int lpr = d / 4;
   const int64_t nchunks = ((int64_t)n + lpr - 1) / lpr;
   const int blocks = ceil_div(nchunks, 256 / lpr);
 #define L(LPR)                                                                                    \
-  hipLaunchKernelGGL((row_update_chunk_kernel<LPR>), dim3(blocks), dim3(256), 0, s, sorted_keys,  \
-                     sorted_bag, de, n, h, G, lr, eps, sc.parts, sc.flags, sc.long_count);        \
   hipLaunchKernelGGL((row_update_stitch_kernel<LPR>), dim3(blocks), dim3(256), 0, s, sorted_keys, \
                      n, sc.parts, sc.flags, h, G, lr, eps, sc.long_list, sc.long_count);          \
   hipLaunchKernelGGL((row_update_long_kernel<LPR>), dim3(64), dim3(1024), 0, s, sorted_keys, n,   \

@@ -48,9 +48,11 @@ struct RowUpdateScratch {
 int64_t row_update_chunks(int64_t max_ids, int d);
 // Per distinct row: g = sum of de over its occurrences (all of them first), then row-wise
 // Adagrad on h and G.  Input: keys sorted ascending with the pooled-vector id of each entry.
-void launch_row_update(const uint32_t* sorted_keys, const int32_t* sorted_bag, const float* de,
-                       uint32_t n, const RowUpdateScratch& sc, int d, float* h, float* G, float lr,
-                       float eps, hipStream_t s);
+void launch_row_update_chunk(const uint32_t* sorted_keys, const int32_t* sorted_bag,
+                             const float* de, uint32_t n, const RowUpdateScratch& sc, int d,
+                             float* h, float* G, float lr, float eps, hipStream_t s);
+void launch_row_update_finish(const uint32_t* sorted_keys, uint32_t n, const RowUpdateScratch& sc,
+                              int d, float* h, float* G, float lr, float eps, hipStream_t s);
 
 // ---------------------------------------------------------------------------- sort.hip
 struct SortScratch {
