@@ -4,6 +4,7 @@
 #include <atomic>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <string>
@@ -43,6 +44,11 @@ struct Slot {
   float* df;                       // [B,ldf]
   float* dz0;                      // [B,d]
   float* de;                       // [B,T,d]
+  // fused-MLP path: transposed bf16 copies [unit][ldT]
+  uint16_t* xT;                    // dense input
+  uint16_t* fT;                    // interaction output
+  uint16_t* actT[MAX_LAYERS];      // output of hidden layer l
+  uint16_t* dYT[MAX_LAYERS];       // gradient w.r.t. the output of layer l
   // embedding backward
   uint32_t* keys;                  // [max_ids]
   int32_t* bag_of_pos;             // [max_ids]
@@ -82,6 +88,12 @@ struct ss_ctx {
   int64_t P, Pstride;
   int F, ldf, ldf16, maxw;
   int key_bits;
+  bool fused = false;              // small-network regime: fused per-sample-tile MLP kernels
+  int ldT = 0;
+  size_t lds_fwd_bot = 0, lds_fwd_top = 0, lds_bwd_bot = 0, lds_bwd_top = 0;
+  size_t e0_fwd_bot = 0, e0_fwd_top = 0, e0_bwd_bot = 0, e0_bwd_top = 0;
+  std::vector<int4> wgrad_tiles;   // host copy of the tile table
+  int4* wgrad_tiles_dev = nullptr;
   float lr_dense, lr_emb, eps;
   uint64_t seed;
   int device;
@@ -189,6 +201,7 @@ static size_t layout(ss_ctx* x, void* base) {
   x->w_global = cv.take<float>(x->Pstride);
   x->v = cv.take<float>(x->Pstride);
   const int L = (int)x->layers.size();
+  x->wgrad_tiles_dev = x->fused ? cv.take<int4>(x->wgrad_tiles.size()) : nullptr;
   const int sort_blocks = sort_max_blocks((uint32_t)n);
   const int seg_blocks = ceil_div(n, 2048) + 1;
   for (Slot& s : x->slots) {
@@ -217,6 +230,16 @@ static size_t layout(ss_ctx* x, void* base) {
     s.df = cv.take<float>((size_t)B * x->ldf);
     s.dz0 = cv.take<float>((size_t)B * x->d);
     s.de = cv.take<float>((size_t)B * x->T * x->d);
+    s.xT = s.fT = nullptr;
+    for (int l = 0; l < L; ++l) s.actT[l] = s.dYT[l] = nullptr;
+    if (x->fused) {
+      s.xT = cv.take<uint16_t>((size_t)x->num_dense * x->ldT);
+      s.fT = cv.take<uint16_t>((size_t)x->F * x->ldT);
+      for (int l = 0; l < L - 1; ++l) {
+        if (l != x->n_bot_layers - 1) s.actT[l] = cv.take<uint16_t>((size_t)x->layers[l].out * x->ldT);
+        s.dYT[l] = cv.take<uint16_t>((size_t)x->layers[l].out * x->ldT);
+      }
+    }
     s.keys = cv.take<uint32_t>(n);
     s.bag_of_pos = cv.take<int32_t>(n);
     s.sorted_bag = cv.take<int32_t>(n);
@@ -272,6 +295,37 @@ static ss_ctx* make_ctx(const ss_config* c) {
   x->ldf16 = (x->F + 7) / 8 * 8;
   x->maxw = maxw;
   x->slots.resize(x->num_slots);
+  // Fused MLP kernels: bf16, at least one hidden top layer, every width <= 512, stacks of at
+  // most SS_FUSED_MAX_LAYERS layers, and the two LDS activation buffers within 64 KB.
+  {
+    const int nb = x->n_bot_layers, nt = x->n_top_layers, nh = nt - 1;
+    bool ok = x->prec == SS_BF16 && nh >= 1 && nb <= SS_FUSED_MAX_LAYERS &&
+              nh <= SS_FUSED_MAX_LAYERS && maxw <= 512 && !getenv("SS_NO_FUSED_MLP");
+    if (ok) {
+      std::vector<int> wb, wt;
+      wb.push_back(x->num_dense);
+      for (int l = 0; l < nb; ++l) wb.push_back(x->layers[l].out);
+      wt.push_back(x->F);
+      for (int l = nb; l < nb + nh; ++l) wt.push_back(x->layers[l].out);
+      std::vector<int> rb(wb.rbegin(), wb.rend()), rt(wt.rbegin(), wt.rend());
+      x->lds_fwd_bot = fused_lds_bytes(wb.data(), (int)wb.size(), &x->e0_fwd_bot);
+      x->lds_fwd_top = fused_lds_bytes(wt.data(), (int)wt.size(), &x->e0_fwd_top);
+      x->lds_bwd_bot = fused_lds_bytes(rb.data(), (int)rb.size(), &x->e0_bwd_bot);
+      x->lds_bwd_top = fused_lds_bytes(rt.data(), (int)rt.size(), &x->e0_bwd_top);
+      const size_t lim = 60 * 1024;
+      ok = x->lds_fwd_bot <= lim && x->lds_fwd_top <= lim && x->lds_bwd_bot <= lim &&
+           x->lds_bwd_top <= lim;
+    }
+    x->fused = ok;
+    x->ldT = (x->max_batch + 7) / 8 * 8;
+    if (ok) {
+      // weight-gradient tiles of every layer except the one-unit output layer
+      for (int l = 0; l < nb + nh; ++l)
+        for (int n0 = 0; n0 < x->layers[l].out; n0 += 32)
+          for (int k0 = 0; k0 < x->layers[l].in; k0 += 32)
+            x->wgrad_tiles.push_back(make_int4(l, n0, k0, 0));
+    }
+  }
   return x;
 }
 
@@ -312,6 +366,9 @@ int ss_init(const ss_config* cfg, void* dev_workspace, size_t bytes, ss_ctx** ou
   launch_fill_f32(x->w_ps, (uint64_t)x->Pstride, 0.f, nullptr);
   launch_fill_f32(x->w_global, (uint64_t)x->Pstride, 0.f, nullptr);
   for (Slot& s : x->slots) launch_fill_f32(s.grads, (uint64_t)x->Pstride, 0.f, nullptr);
+  if (x->fused)
+    (void)hipMemcpy(x->wgrad_tiles_dev, x->wgrad_tiles.data(), x->wgrad_tiles.size() * sizeof(int4),
+                    hipMemcpyHostToDevice);
   e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     delete x;
@@ -476,6 +533,98 @@ static int check_batch(ss_ctx* x, int replica, int slot, const ss_batch* b) {
 // bf16 models with at least one hidden top layer run the one-unit output layer and the loss
 // (and that layer's backward) as fused kernels instead of GEMMs with a single column.
 static bool fused_last(const ss_ctx* x) { return x->prec == SS_BF16 && x->n_top_layers >= 2; }
+
+// ---- fused-MLP path -------------------------------------------------------------------------
+static void fill_stack(const ss_ctx* x, const float* w, int l0, int n, FusedLayer* out) {
+  for (int i = 0; i < n; ++i) {
+    const Layer& ly = x->layers[l0 + i];
+    out[i].W = w + ly.w_off; out[i].b = w + ly.b_off; out[i].in = ly.in; out[i].out = ly.out;
+  }
+}
+
+static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, float* loss,
+                          bool train, hipStream_t st) {
+  const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers, nh = x->n_top_layers - 1;
+  {
+    ProfScope ps(x, SS_K_MLP, st);
+    FusedFwdArgs a{};
+    a.n_layers = nb; fill_stack(x, w, 0, nb, a.L);
+    a.B = B; a.ldT = x->ldT;
+    a.x = bt->dense; a.x_is_f32 = 1; a.ldx = x->num_dense; a.in0 = x->num_dense;
+    a.xT = train ? s.xT : nullptr;
+    for (int l = 0; l < nb; ++l) a.actT[l] = s.actT[l];
+    a.out_f32 = s.z0; a.relu_last = 1; a.has_tail = 0;
+    a.lds_elems0 = (unsigned)x->e0_fwd_bot;
+    launch_mlp_fused_fwd(a, x->lds_fwd_bot, st);
+  }
+  {
+    ProfScope ps(x, SS_K_GATHER, st);
+    launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e, s.keys,
+                             s.bag_of_pos, loss, st);
+  }
+  {
+    ProfScope ps(x, SS_K_INTERACT_FWD, st);
+    launch_interaction_fwd(s.z0, s.e, B, x->T, x->d, s.f, x->ldf, s.f_bf16, x->ldf16, st);
+  }
+  {
+    ProfScope ps(x, SS_K_MLP, st);
+    FusedFwdArgs a{};
+    a.n_layers = nh; fill_stack(x, w, nb, nh, a.L);
+    a.B = B; a.ldT = x->ldT;
+    a.x = s.f_bf16; a.x_is_f32 = 0; a.ldx = x->ldf16; a.in0 = x->F;
+    a.xT = train ? s.fT : nullptr;
+    for (int l = 0; l < nh; ++l) a.actT[l] = s.actT[nb + l];
+    a.out_f32 = nullptr; a.relu_last = 1; a.has_tail = 1;
+    const Layer& last = x->layers[L - 1];
+    a.w_last = w + last.w_off; a.b_last = w + last.b_off; a.y = bt->labels;
+    a.logits = s.logits; a.dlogit = train ? s.dlogit : nullptr; a.loss = loss;
+    a.lds_elems0 = (unsigned)x->e0_fwd_top;
+    launch_mlp_fused_fwd(a, x->lds_fwd_top, st);
+  }
+}
+
+static void backward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipStream_t st) {
+  const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers, nh = x->n_top_layers - 1;
+  {
+    ProfScope ps(x, SS_K_MLP, st);
+    launch_fill_f32(s.grads, (uint64_t)x->P, 0.f, st);  // gradients accumulate atomically
+    FusedBwdArgs a{};
+    a.n_layers = nh; fill_stack(x, w, nb, nh, a.L);
+    a.B = B; a.ldT = x->ldT;
+    const Layer& last = x->layers[L - 1];
+    a.dlogit = s.dlogit; a.w_last = w + last.w_off;
+    a.g_w_last = s.grads + last.w_off; a.g_b_last = s.grads + last.b_off;
+    for (int l = 0; l < nh; ++l) { a.actT[l] = s.actT[nb + l]; a.dYT[l] = s.dYT[nb + l]; }
+    a.d_out_f32 = s.df; a.ld_d_out = x->ldf;
+    a.lds_elems0 = (unsigned)x->e0_bwd_top;
+    launch_mlp_fused_bwd(a, x->lds_bwd_top, st);
+  }
+  {
+    ProfScope ps(x, SS_K_INTERACT_BWD, st);
+    launch_interaction_bwd(s.z0, s.e, s.df, x->ldf, B, x->T, x->d, s.dz0, s.de, st);
+  }
+  {
+    ProfScope ps(x, SS_K_MLP, st);
+    FusedBwdArgs a{};
+    a.n_layers = nb; fill_stack(x, w, 0, nb, a.L);
+    a.B = B; a.ldT = x->ldT;
+    a.d_in_f32 = s.dz0; a.ld_d_in = x->d;
+    for (int l = 0; l < nb; ++l) { a.actT[l] = s.actT[l]; a.dYT[l] = s.dYT[l]; }
+    a.d_out_f32 = nullptr;
+    a.lds_elems0 = (unsigned)x->e0_bwd_bot;
+    launch_mlp_fused_bwd(a, x->lds_bwd_bot, st);
+    WgradArgs g{};
+    for (int l = 0; l < nb + nh; ++l) {
+      const Layer& ly = x->layers[l];
+      g.L[l].dYT = s.dYT[l];
+      g.L[l].XT = (l == 0) ? s.xT : (l == nb) ? s.fT : s.actT[l - 1];
+      g.L[l].gW = s.grads + ly.w_off; g.L[l].gb = s.grads + ly.b_off;
+      g.L[l].in = ly.in; g.L[l].out = ly.out;
+    }
+    g.tiles = x->wgrad_tiles_dev; g.B = B; g.ldT = x->ldT;
+    launch_mlp_wgrad_grouped(g, (int)x->wgrad_tiles.size(), st);
+  }
+}
 
 static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, float* loss,
                     bool train, hipStream_t st) {
@@ -642,12 +791,14 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
   const int B = bt->batch;
   const uint32_t n = (uint32_t)bt->num_ids;
   float* loss = dev_loss_out ? dev_loss_out : s.loss;
-  forward(x, s, w, bt, loss, train, st);
+  if (x->fused) forward_fused(x, s, w, bt, loss, train, st);
+  else forward(x, s, w, bt, loss, train, st);
   if (!fused_last(x)) launch_bce_loss(s.logits, bt->labels, B, loss, train ? s.dlogit : nullptr, st);
   s.last_B = B;
   s.last_n = n;
   if (train) {
-    backward_dense(x, s, w, bt, st);
+    if (x->fused) backward_fused(x, s, w, bt, st);
+    else backward_dense(x, s, w, bt, st);
     // "update local param w^(i)": lock-free SGD on the replica
     launch_sgd(w, s.grads, x->P, x->lr_dense, st);
     // "update h": stable sort by row, one Adagrad update per distinct row

@@ -115,6 +115,56 @@ void launch_last_layer_fwd_loss(const uint16_t* X, int ldx, const float* w, cons
 void launch_last_layer_bwd(const uint16_t* X, int ldx, const float* w, const float* dlogit, int B,
                            int in, uint16_t* dX, int lddx, float* gW, float* gb, hipStream_t s);
 
+// ---------------------------------------------------------------------------- mlp_fused.hip
+#define SS_FUSED_MAX_LAYERS 8
+struct FusedLayer {
+  const float* W;  // [out][in] fp32 master weights
+  const float* b;  // [out]
+  int in, out;
+};
+struct FusedFwdArgs {
+  int n_layers;
+  FusedLayer L[SS_FUSED_MAX_LAYERS];
+  int B, ldT;
+  const void* x; int x_is_f32; int ldx; int in0;  // stack input [B, in0]
+  uint16_t* xT;                                   // [in0][ldT] transposed bf16 copy, or null
+  uint16_t* actT[SS_FUSED_MAX_LAYERS];            // [out_l][ldT] transposed bf16 output, or null
+  float* out_f32;                                 // last layer's output [B, out] fp32, or null
+  int relu_last;
+  int has_tail;                                   // top stack: one-unit layer + loss
+  const float* w_last; const float* b_last; const float* y;
+  float* logits; float* dlogit; float* loss;
+  unsigned lds_elems0;                            // bf16 elements of LDS buffer 0
+};
+struct FusedBwdArgs {
+  int n_layers;
+  FusedLayer L[SS_FUSED_MAX_LAYERS];
+  int B, ldT;
+  const float* d_in_f32; int ld_d_in;             // bottom stack: gated dL/dz0 [B, d]
+  const float* dlogit; const float* w_last;       // top stack: tail
+  float* g_w_last; float* g_b_last;
+  const uint16_t* actT[SS_FUSED_MAX_LAYERS];      // outputs of layer l (for the ReLU gates)
+  uint16_t* dYT[SS_FUSED_MAX_LAYERS];             // [out_l][ldT] gradient w.r.t. layer l's output
+  float* d_out_f32; int ld_d_out;                 // gradient w.r.t. the stack input, or null
+  unsigned lds_elems0;
+};
+struct WgradLayer {
+  const uint16_t* dYT;  // [out][ldT]
+  const uint16_t* XT;   // [in][ldT]
+  float* gW;            // [out][in]
+  float* gb;            // [out]
+  int in, out;
+};
+struct WgradArgs {
+  WgradLayer L[2 * SS_FUSED_MAX_LAYERS];
+  const int4* tiles;    // device: (layer, n0, k0, 0) per 32x32 tile
+  int B, ldT;
+};
+size_t fused_lds_bytes(const int* widths, int n_widths, size_t* elems0);
+void launch_mlp_fused_fwd(const FusedFwdArgs& a, size_t lds_bytes, hipStream_t s);
+void launch_mlp_fused_bwd(const FusedBwdArgs& a, size_t lds_bytes, hipStream_t s);
+void launch_mlp_wgrad_grouped(const WgradArgs& a, int n_tiles, hipStream_t s);
+
 // ---------------------------------------------------------------------------- sync.hip
 int launch_sync_round(int algo, int K, int64_t P, int64_t stride, float* W, float* w_ps,
                       float* w_global, float* v, float alpha, float eta, float mu,

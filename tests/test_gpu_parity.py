@@ -140,9 +140,13 @@ def test_empty_bags_single_sample_and_hot_row():
     H.compare_state(gpu, orc, H.FP32_RTOL, "edge cases", wl.row_base)
 
 
-def test_bf16_mid_scaled():
-    """Mid CTR architecture (bf16 MLP GEMMs, fp32 master weights) on a compacted table set."""
-    wl = synth.mid().scaled(batch=512, num_replicas=2, sync_gap=2)
+@pytest.mark.parametrize("path", ["fused", "layerwise"])
+def test_bf16_mid_scaled(path, monkeypatch):
+    """Mid CTR architecture (bf16 MLP GEMMs, fp32 master weights) on a compacted table set,
+    through the fused per-sample-tile MLP kernels and through the layer-by-layer GEMMs."""
+    if path == "layerwise":
+        monkeypatch.setenv("SS_NO_FUSED_MLP", "1")
+    wl = synth.mid().scaled(batch=500, num_replicas=2, sync_gap=2)
     gen = synth.BatchGenerator(wl)
     batches = [gen.batch(s) for s in range(8)]
     cp = synth.compact_problem(wl, batches)
@@ -150,6 +154,21 @@ def test_bf16_mid_scaled():
     row_base = np.concatenate(([0], np.cumsum(cp.rows)))
     H.run_lockstep(gpu, orc, cp.batches, wl.sync_gap, wl.algo, wl.alpha, rtol=H.BF16_RTOL,
                    resync_row_base=row_base)
+
+
+@pytest.mark.parametrize("path", ["fused", "layerwise"])
+def test_bf16_odd_widths(path, monkeypatch):
+    """bf16 with layer widths that are not multiples of the MFMA tile (guards, padding)."""
+    if path == "layerwise":
+        monkeypatch.setenv("SS_NO_FUSED_MLP", "1")
+    wl = synth.tiny().scaled(batch=77, rows=(3000, 17, 900), emb_dim=64, bag_lambda=4.0,
+                             bot_dims=(13, 40, 64), top_dims=(64 + 6, 72, 24, 1),
+                             num_replicas=1, bf16=True, algo="ma", alpha=1.0)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(4)]
+    gpu, orc = H.make_pair(wl, batches)
+    H.run_lockstep(gpu, orc, batches, 1, "ma", 1.0, rtol=H.BF16_RTOL,
+                   resync_row_base=wl.row_base)
 
 
 def test_validation_errors_through_the_abi():
