@@ -4,7 +4,7 @@
 Workload (default): the Mid CTR model -- 13 dense features, 8 tables x 1e6 rows x dim 64
 fp32, ids Zipf(1.05), bag length Poisson(20)+1, bottom MLP 13-256-128-64, top MLP
 100-512-256-1 with bf16 MFMA GEMMs over fp32 master weights, batch 2048, K=4 replicas each
-fed by its own worker stream (one host thread per stream), Shadow EASGD (alpha 0.1) enqueued
+fed by 2 lock-free worker streams (one host thread per stream), Shadow EASGD (alpha 0.1) enqueued
 on a separate stream once per 5 trainer iterations of a replica.  One bench "step" = one
 ss_train_step on one batch (forward, loss, backward, SGD on the replica, sort + segmented
 reduction + row-wise Adagrad on the tables); steps go round-robin over the K replicas.
@@ -46,7 +46,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="mid", choices=["mid", "tiny", "hogwild"])
     ap.add_argument("--batches", type=int, default=16, help="distinct batches cycled through")
-    ap.add_argument("--workers-per-replica", type=int, default=1,
+    ap.add_argument("--workers-per-replica", type=int, default=2,
                     help="Hogwild worker streams per replica")
     ap.add_argument("--no-shadow", action="store_true", help="run without the shadow stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -169,12 +169,19 @@ def main():
             gpu.ss_train_step(w % K, w, dev_batches[s % len(dev_batches)], streams[w],
                               losses[w:w + 1])
 
+        r0_steps = [0]
+        r0_lock = threading.Lock()
+
         def worker(w):
-            for j, s in enumerate(range(first_step + w, first_step + total_steps, NS)):
+            for s in range(first_step + w, first_step + total_steps, NS):
                 one(s)
-                # the shadow loop is paced off replica 0's first worker
-                if w == 0 and not args.no_shadow and (j + 1) % max(1, wl.sync_gap // WPR) == 0:
-                    gpu.ss_shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
+                # one shadow round per sync_gap iterations of replica 0 (all its workers)
+                if w % K == 0 and not args.no_shadow:
+                    with r0_lock:
+                        r0_steps[0] += 1
+                        due = r0_steps[0] % wl.sync_gap == 0
+                    if due:
+                        gpu.ss_shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
         if args.single_thread:
             for s in range(first_step, first_step + total_steps):
                 one(s)

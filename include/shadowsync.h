@@ -204,7 +204,7 @@ int ss_get_counters(ss_ctx* ctx, uint64_t* steps_per_replica, uint64_t* rounds,
 typedef enum {
   SS_K_NONE = 0,
   SS_K_GATHER = 1,            /* one kernel: embedding gather + sum pooling                  */
-  SS_K_SORT = 2,              /* group: all radix-sort passes + segment compaction of a step */
+  SS_K_SORT = 2,              /* group: all radix-sort passes of a step                      */
   SS_K_ROW_UPDATE_CHUNK = 3,  /* one kernel: chunk pass of the segmented reduction + Adagrad */
   SS_K_SYNC = 4,              /* one kernel: one shadow round                                */
   SS_K_MLP = 5,               /* group: MLP kernels (bottom fwd / top fwd / top bwd / bottom bwd) */

@@ -49,6 +49,7 @@ struct Slot {
   uint16_t* fT;                    // interaction output
   uint16_t* actT[MAX_LAYERS];      // output of hidden layer l
   uint16_t* dYT[MAX_LAYERS];       // gradient w.r.t. the output of layer l
+  uint16_t* wsw;                   // bf16 fragment-ordered weights of the step's replica
   // embedding backward
   uint32_t* keys;                  // [max_ids]
   int32_t* bag_of_pos;             // [max_ids]
@@ -61,6 +62,8 @@ struct Slot {
   uint32_t* sorted_pos = nullptr;
   uint32_t last_n = 0;
   int last_B = 0;
+  bool seg_valid = false;
+  bool trained = false;
 };
 
 struct Carver {
@@ -92,6 +95,8 @@ struct ss_ctx {
   int ldT = 0;
   size_t lds_fwd_bot = 0, lds_fwd_top = 0, lds_bwd_bot = 0, lds_bwd_top = 0;
   size_t e0_fwd_bot = 0, e0_fwd_top = 0, e0_bwd_bot = 0, e0_bwd_top = 0;
+  std::vector<int64_t> wsw_f, wsw_r;  // per layer: offsets of the two fragment-ordered copies
+  int64_t wsw_elems = 0;
   std::vector<int4> wgrad_tiles;   // host copy of the tile table
   int4* wgrad_tiles_dev = nullptr;
   float lr_dense, lr_emb, eps;
@@ -232,7 +237,9 @@ static size_t layout(ss_ctx* x, void* base) {
     s.de = cv.take<float>((size_t)B * x->T * x->d);
     s.xT = s.fT = nullptr;
     for (int l = 0; l < L; ++l) s.actT[l] = s.dYT[l] = nullptr;
+    s.wsw = nullptr;
     if (x->fused) {
+      s.wsw = cv.take<uint16_t>((size_t)x->wsw_elems);
       s.xT = cv.take<uint16_t>((size_t)x->num_dense * x->ldT);
       s.fT = cv.take<uint16_t>((size_t)x->F * x->ldT);
       for (int l = 0; l < L - 1; ++l) {
@@ -312,13 +319,20 @@ static ss_ctx* make_ctx(const ss_config* c) {
       x->lds_fwd_top = fused_lds_bytes(wt.data(), (int)wt.size(), &x->e0_fwd_top);
       x->lds_bwd_bot = fused_lds_bytes(rb.data(), (int)rb.size(), &x->e0_bwd_bot);
       x->lds_bwd_top = fused_lds_bytes(rt.data(), (int)rt.size(), &x->e0_bwd_top);
-      const size_t lim = 60 * 1024;
+      const size_t lim = 150 * 1024;
       ok = x->lds_fwd_bot <= lim && x->lds_fwd_top <= lim && x->lds_bwd_bot <= lim &&
            x->lds_bwd_top <= lim;
     }
     x->fused = ok;
     x->ldT = (x->max_batch + 7) / 8 * 8;
     if (ok) {
+      for (int l = 0; l < nb + nh; ++l) {
+        const Layer& ly = x->layers[l];
+        x->wsw_f.push_back(x->wsw_elems);
+        x->wsw_elems += (int64_t)((ly.out + 31) / 32 * 32) * ((ly.in + 63) / 64 * 64);
+        x->wsw_r.push_back(x->wsw_elems);
+        x->wsw_elems += (int64_t)((ly.in + 31) / 32 * 32) * ((ly.out + 63) / 64 * 64);
+      }
       // weight-gradient tiles of every layer except the one-unit output layer
       for (int l = 0; l < nb + nh; ++l)
         for (int n0 = 0; n0 < x->layers[l].out; n0 += 32)
@@ -535,10 +549,12 @@ static int check_batch(ss_ctx* x, int replica, int slot, const ss_batch* b) {
 static bool fused_last(const ss_ctx* x) { return x->prec == SS_BF16 && x->n_top_layers >= 2; }
 
 // ---- fused-MLP path -------------------------------------------------------------------------
-static void fill_stack(const ss_ctx* x, const float* w, int l0, int n, FusedLayer* out) {
+static void fill_stack(const ss_ctx* x, const Slot& s, const float* w, int l0, int n,
+                       FusedLayer* out) {
   for (int i = 0; i < n; ++i) {
     const Layer& ly = x->layers[l0 + i];
-    out[i].W = w + ly.w_off; out[i].b = w + ly.b_off; out[i].in = ly.in; out[i].out = ly.out;
+    out[i].Wf = s.wsw + x->wsw_f[l0 + i]; out[i].Wr = s.wsw + x->wsw_r[l0 + i];
+    out[i].b = w + ly.b_off; out[i].in = ly.in; out[i].out = ly.out;
   }
 }
 
@@ -547,8 +563,24 @@ static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers, nh = x->n_top_layers - 1;
   {
     ProfScope ps(x, SS_K_MLP, st);
+    // this step's snapshot of the replica, bf16, in MFMA fragment order
+    PrepArgs pa{};
+    pa.n_layers = nb + nh;
+    int64_t base = 0;
+    for (int l = 0; l < nb + nh; ++l) {
+      const Layer& ly = x->layers[l];
+      PrepLayer& pl = pa.L[l];
+      pl.W = w + ly.w_off; pl.Wf = s.wsw + x->wsw_f[l]; pl.Wr = s.wsw + x->wsw_r[l];
+      pl.in = ly.in; pl.out = ly.out; pl.frag_base = base;
+      pl.frags_fwd = (x->wsw_r[l] - x->wsw_f[l]) / 8;
+      const int64_t end = (l + 1 < nb + nh) ? x->wsw_f[l + 1] : x->wsw_elems;
+      base += (end - x->wsw_f[l]) / 8;
+    }
+    pa.total_frags = base;
+    pa.zero = train ? s.grads : nullptr; pa.zero_n = x->P;
+    launch_mlp_prep(pa, st);
     FusedFwdArgs a{};
-    a.n_layers = nb; fill_stack(x, w, 0, nb, a.L);
+    a.n_layers = nb; fill_stack(x, s, w, 0, nb, a.L);
     a.B = B; a.ldT = x->ldT;
     a.x = bt->dense; a.x_is_f32 = 1; a.ldx = x->num_dense; a.in0 = x->num_dense;
     a.xT = train ? s.xT : nullptr;
@@ -569,7 +601,7 @@ static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
   {
     ProfScope ps(x, SS_K_MLP, st);
     FusedFwdArgs a{};
-    a.n_layers = nh; fill_stack(x, w, nb, nh, a.L);
+    a.n_layers = nh; fill_stack(x, s, w, nb, nh, a.L);
     a.B = B; a.ldT = x->ldT;
     a.x = s.f_bf16; a.x_is_f32 = 0; a.ldx = x->ldf16; a.in0 = x->F;
     a.xT = train ? s.fT : nullptr;
@@ -587,9 +619,8 @@ static void backward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers, nh = x->n_top_layers - 1;
   {
     ProfScope ps(x, SS_K_MLP, st);
-    launch_fill_f32(s.grads, (uint64_t)x->P, 0.f, st);  // gradients accumulate atomically
-    FusedBwdArgs a{};
-    a.n_layers = nh; fill_stack(x, w, nb, nh, a.L);
+    FusedBwdArgs a{};  // (the gradient accumulator was cleared by the step's prep launch)
+    a.n_layers = nh; fill_stack(x, s, w, nb, nh, a.L);
     a.B = B; a.ldT = x->ldT;
     const Layer& last = x->layers[L - 1];
     a.dlogit = s.dlogit; a.w_last = w + last.w_off;
@@ -606,7 +637,7 @@ static void backward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
   {
     ProfScope ps(x, SS_K_MLP, st);
     FusedBwdArgs a{};
-    a.n_layers = nb; fill_stack(x, w, 0, nb, a.L);
+    a.n_layers = nb; fill_stack(x, s, w, 0, nb, a.L);
     a.B = B; a.ldT = x->ldT;
     a.d_in_f32 = s.dz0; a.ld_d_in = x->d;
     for (int l = 0; l < nb; ++l) { a.actT[l] = s.actT[l]; a.dYT[l] = s.dYT[l]; }
@@ -806,7 +837,7 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
       ProfScope ps(x, SS_K_SORT, st);
       launch_sort_pairs(s.keys, n, x->key_bits, s.sort, &s.sorted_keys, &s.sorted_pos,
                         s.bag_of_pos, s.sorted_bag, st);
-      launch_segment_starts(s.sorted_keys, n, s.seg, st);
+      s.seg_valid = false;  // compacted segment starts are produced on demand (ss_read_debug)
     }
     {
       ProfScope all(x, SS_K_ROW_UPDATE, st);
@@ -817,6 +848,7 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
       }
       launch_row_update_finish(s.sorted_keys, n, s.upd, x->d, x->h, x->G, x->lr_emb, x->eps, st);
     }
+    s.trained = true;
     x->steps[replica].fetch_add(1);
     x->examples.fetch_add((uint64_t)B);
   }
@@ -909,8 +941,17 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
   const size_t B = (size_t)s.last_B, n = s.last_n;
   const void* src = nullptr; size_t size = 0; size_t pitch_src = 0, width = 0, rows = 0;
   uint32_t U = 0;
-  if (item == SS_DBG_SEG_STARTS || item == SS_DBG_NUM_UNIQUE)
+  if (item == SS_DBG_SEG_STARTS || item == SS_DBG_NUM_UNIQUE) {
+    if (!s.trained) return fail(ctx, SS_ESTATE, "no training step has run on this slot yet");
+    if (!s.seg_valid) {
+      // the row update works on the runs of equal keys directly; the compacted list of run
+      // starts is derived from the same sorted keys when somebody asks for it
+      launch_segment_starts(s.sorted_keys, s.last_n, s.seg, nullptr);
+      HIP_TRY(ctx, hipDeviceSynchronize());
+      s.seg_valid = true;
+    }
     HIP_TRY(ctx, hipMemcpy(&U, s.seg.num_unique, 4, hipMemcpyDeviceToHost));
+  }
   switch (item) {
     case SS_DBG_POOLED: src = s.e; size = B * ctx->T * ctx->d * 4; break;
     case SS_DBG_INTERACT: src = s.f; rows = B; width = (size_t)ctx->F * 4; pitch_src = (size_t)ctx->ldf * 4; size = rows * width; break;

@@ -4,10 +4,14 @@
 // every single layer is far too little work for the chip: layer-by-layer GEMM launches are
 // latency bound.  Here one workgroup owns a tile of 32 samples and carries it through ALL
 // layers of a stack (bottom or top network, Section 3.1): the tile's activations stay in
-// LDS as the MFMA A operand, the weights are streamed from L2/HBM straight into MFMA B
-// fragments (each weight is used once per tile, so staging them in LDS would buy nothing)
-// and are rounded from the fp32 master copy to bfloat16 on the way, exactly as the
-// layer-wise path does.  Three kernels:
+// LDS as the MFMA A operand, the weights are streamed from L2 straight into MFMA B fragments
+// (each weight is used once per tile, so staging them in LDS would buy nothing).  A small
+// prep kernel at the start of every step rounds the replica's fp32 master weights to
+// bfloat16 (nearest even, as the layer-wise path does on load) and lays them out in fragment
+// order -- for every (32-column tile, 16-deep reduction step) the 64 lanes' 8 values are
+// contiguous -- once for X W^T and once for dY W, so each fragment load is one fully
+// coalesced 1 KB wave access and several reduction steps can be kept in flight.  Kernels:
+//   prep     : fp32 W -> the two bf16 fragment-ordered copies;
 //   forward  : x -> a_1 -> ... -> a_L (+ for the top stack the one-unit output layer, the
 //              mean log-loss and dL/dlogit);
 //   backward : dL/da_L -> ... -> dL/da_0 (data gradients only), ReLU-gated;
@@ -18,6 +22,7 @@
 // an MFMA accumulator holds 4 consecutive samples of one unit per lane, so this is the cheap
 // direction to store, it is the layout the ReLU gate wants to read, and it makes the batch
 // dimension contiguous for the weight-gradient fragments (no LDS transpose anywhere).
+#include <cstdlib>
 #include "ss_internal.h"
 
 namespace ss {
@@ -47,80 +52,56 @@ union Frag {
   uint4 q;
 };
 
-// B fragment for the forward product X W^T: 8 consecutive k of weight row n (fp32 -> bf16).
-struct RawK {
-  float4 a, b;
-};
-__device__ __forceinline__ RawK load_w_rowk(const float* __restrict__ W, int ld, int n, int k,
-                                            int N, int K) {
-  RawK r;
-  r.a = make_float4(0.f, 0.f, 0.f, 0.f);
-  r.b = r.a;
-  if (n < N) {
-    const float* p = W + (size_t)n * ld + k;
-    if (k + 8 <= K && ((((uintptr_t)p) & 15) == 0)) {
-      r.a = *(const float4*)p;
-      r.b = *(const float4*)(p + 4);
-    } else {
-      float e[8];
+// Fragment-ordered bf16 weights: element (tile, step, lane, j), 8 values per lane.
+//   forward copy : tile = n/32, step = k/16, lane = n%32 + 32*((k%16)/8), j = k%8
+//   backward copy: tile = k/32, step = n/16, lane = k%32 + 32*((n%16)/8), j = n%8
+__device__ __forceinline__ Frag load_frag(const uint16_t* __restrict__ Wsw, int tile, int steps,
+                                          int step, int lane) {
+  Frag f;
+  f.q = *(const uint4*)(Wsw + (((size_t)tile * steps + step) * 64 + lane) * 8);
+  return f;
+}
+
+constexpr int DEPTH = 4;  // reduction steps kept in flight per tile
+constexpr int KGRAN = 16 * DEPTH;  // reduction lengths are zero-padded to a multiple of this
+
+// acc[j] += A_tile[32 x 16*steps] * B for this wave's MINE column tiles (tile index wave + 4j).
+// A comes from LDS (row stride lda bf16), B fragments from the fragment-ordered copy.  steps is
+// a multiple of DEPTH; the loop body has no branches so the loads of the next DEPTH steps stay
+// in flight behind the MFMAs (the trailing refills re-read the last group and are dropped).
+template <int MINE>
+__device__ __forceinline__ void tile_gemm(f32x16 (&acc)[MAXT], const uint16_t* __restrict__ A,
+                                          int lda, int steps, int wave, int lane,
+                                          const uint16_t* __restrict__ Wsw) {
+  const int frow = lane & 31, fk = (lane >> 5) * 8;
+  Frag q[DEPTH][MINE];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) e[j] = (k + j < K) ? p[j] : 0.f;
-      r.a = make_float4(e[0], e[1], e[2], e[3]);
-      r.b = make_float4(e[4], e[5], e[6], e[7]);
+  for (int d = 0; d < DEPTH; ++d)
+#pragma unroll
+    for (int j = 0; j < MINE; ++j) q[d][j] = load_frag(Wsw, wave + 4 * j, steps, d, lane);
+  for (int s0 = 0; s0 < steps; s0 += DEPTH) {
+    const int nx = min(s0 + DEPTH, steps - DEPTH);
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const bf16x8 a = *(const bf16x8*)(A + frow * lda + (s0 + d) * 16 + fk);
+#pragma unroll
+      for (int j = 0; j < MINE; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[d][j].v, acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < MINE; ++j) q[d][j] = load_frag(Wsw, wave + 4 * j, steps, nx + d, lane);
     }
   }
-  return r;
-}
-__device__ __forceinline__ bf16x8 cvt(const RawK& r) {
-  Frag f;
-  f.u[0] = pk(r.a.x, r.a.y); f.u[1] = pk(r.a.z, r.a.w);
-  f.u[2] = pk(r.b.x, r.b.y); f.u[3] = pk(r.b.z, r.b.w);
-  return f.v;
 }
 
-// B fragment for the data gradient dY W: 8 consecutive rows n of weight column k.
-struct RawN {
-  float e[8];
-};
-__device__ __forceinline__ RawN load_w_coln(const float* __restrict__ W, int ld, int n, int k,
-                                            int N, int K) {
-  RawN r;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) r.e[j] = (k < K && n + j < N) ? W[(size_t)(n + j) * ld + k] : 0.f;
-  return r;
-}
-__device__ __forceinline__ bf16x8 cvt(const RawN& r) {
-  Frag f;
-  f.u[0] = pk(r.e[0], r.e[1]); f.u[1] = pk(r.e[2], r.e[3]);
-  f.u[2] = pk(r.e[4], r.e[5]); f.u[3] = pk(r.e[6], r.e[7]);
-  return f.v;
-}
-
-// acc[j] (+)= A_tile[32 x Kred] * B, for this wave's column tiles j (tile index w + 4j).
-// A comes from LDS (row stride lda bf16), B fragments from global through `loadB(tile_col,
-// kred)`; the fragments of reduction step s+1 are in flight during the MFMAs of step s.
-template <typename Raw, typename LoadB>
-__device__ __forceinline__ void tile_gemm(f32x16 (&acc)[MAXT], const uint16_t* __restrict__ A,
-                                          int lda, int Kred_pad, int ntiles_mine, int lane,
-                                          LoadB loadB) {
-  const int frow = lane & 31, fk = (lane >> 5) * 8;
-  Raw cur[MAXT], nxt[MAXT];
-#pragma unroll
-  for (int j = 0; j < MAXT; ++j)
-    if (j < ntiles_mine) cur[j] = loadB(j, fk);
-  for (int k0 = 0; k0 < Kred_pad; k0 += 16) {
-    if (k0 + 16 < Kred_pad) {
-#pragma unroll
-      for (int j = 0; j < MAXT; ++j)
-        if (j < ntiles_mine) nxt[j] = loadB(j, k0 + 16 + fk);
-    }
-    const bf16x8 a = *(const bf16x8*)(A + frow * lda + k0 + fk);
-#pragma unroll
-    for (int j = 0; j < MAXT; ++j)
-      if (j < ntiles_mine)
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, cvt(cur[j]), acc[j], 0, 0, 0);
-#pragma unroll
-    for (int j = 0; j < MAXT; ++j) cur[j] = nxt[j];
+__device__ __forceinline__ void tile_gemm_n(int mine, f32x16 (&acc)[MAXT],
+                                            const uint16_t* __restrict__ A, int lda, int steps,
+                                            int wave, int lane, const uint16_t* __restrict__ Wsw) {
+  switch (mine) {
+    case 1: tile_gemm<1>(acc, A, lda, steps, wave, lane, Wsw); break;
+    case 2: tile_gemm<2>(acc, A, lda, steps, wave, lane, Wsw); break;
+    case 3: tile_gemm<3>(acc, A, lda, steps, wave, lane, Wsw); break;
+    case 4: tile_gemm<4>(acc, A, lda, steps, wave, lane, Wsw); break;
+    default: break;
   }
 }
 
@@ -131,9 +112,46 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[MAXT]) {
     for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
 }
 
-__device__ __forceinline__ int pad16(int k) { return (k + 15) & ~15; }
+__device__ __forceinline__ int padk(int k) { return (k + KGRAN - 1) / KGRAN * KGRAN; }
 
 }  // namespace
+
+// ------------------------------------------------------------------------------------------
+// Prep: fp32 master weights -> bf16 in fragment order (both copies), one thread per 8 values.
+__global__ __launch_bounds__(256) void mlp_prep_kernel(PrepArgs g) {
+  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;  // index of an 8-value fragment
+  // the step's dense-gradient accumulator is cleared here (the later kernels add into it)
+  if (g.zero) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = v; i < g.zero_n; i += stride) g.zero[i] = 0.f;
+  }
+  if (v >= g.total_frags) return;
+  int l = 0;
+  while (l + 1 < g.n_layers && v >= g.L[l + 1].frag_base) ++l;
+  const PrepLayer L = g.L[l];
+  int64_t r = v - L.frag_base;
+  const bool bwd = r >= L.frags_fwd;
+  if (bwd) r -= L.frags_fwd;
+  const int lane = (int)(r & 63);
+  const int64_t ts = r >> 6;
+  Frag f;
+  float e[8];
+  if (!bwd) {
+    const int steps = (L.in + KGRAN - 1) / KGRAN * DEPTH;
+    const int tile = (int)(ts / steps), step = (int)(ts - (int64_t)tile * steps);
+    const int n = tile * 32 + (lane & 31), k = step * 16 + (lane >> 5) * 8;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) e[j] = (n < L.out && k + j < L.in) ? L.W[(size_t)n * L.in + k + j] : 0.f;
+  } else {
+    const int steps = (L.out + KGRAN - 1) / KGRAN * DEPTH;
+    const int tile = (int)(ts / steps), step = (int)(ts - (int64_t)tile * steps);
+    const int k = tile * 32 + (lane & 31), n = step * 16 + (lane >> 5) * 8;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) e[j] = (k < L.in && n + j < L.out) ? L.W[(size_t)(n + j) * L.in + k] : 0.f;
+  }
+  f.u[0] = pk(e[0], e[1]); f.u[1] = pk(e[2], e[3]); f.u[2] = pk(e[4], e[5]); f.u[3] = pk(e[6], e[7]);
+  *(uint4*)((bwd ? L.Wr : L.Wf) + r * 8) = f.q;
+}
 
 // ------------------------------------------------------------------------------------------
 // Forward.
@@ -142,28 +160,64 @@ __global__ __launch_bounds__(256) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
   uint16_t* buf[2] = {smem, smem + g.lds_elems0};
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b0 = blockIdx.x * TB;
-  // ---- stage the input tile (bf16, zero padded to a multiple of 16 columns and 32 rows),
-  //      and its transposed copy for the weight-gradient kernel
+  // ---- stage the input tile (bf16, zero padded to KGRAN columns and 32 rows), then write its
+  //      transposed copy for the weight-gradient kernel from LDS
   {
-    const int Kp = pad16(g.in0), lda = Kp + APAD;
-    for (int i = tid; i < TB * Kp; i += 256) {
-      const int r = i / Kp, k = i - r * Kp, b = b0 + r;
-      uint16_t v = 0;
-      if (b < g.B && k < g.in0)
-        v = g.x_is_f32 ? f2b(((const float*)g.x)[(size_t)b * g.ldx + k])
-                       : ((const uint16_t*)g.x)[(size_t)b * g.ldx + k];
-      buf[0][r * lda + k] = v;
-    }
-    if (g.xT) {
-      for (int i = tid; i < g.in0 * TB; i += 256) {
-        const int k = i / TB, r = i - k * TB, b = b0 + r;
+    const int Kp = padk(g.in0), lda = Kp + APAD;
+    const bool vec = !g.x_is_f32 && (g.ldx % 8 == 0) && ((((uintptr_t)g.x) & 15) == 0);
+    if (vec) {
+      const uint16_t* xs = (const uint16_t*)g.x;
+      for (int i = tid; i < TB * (Kp / 8); i += 256) {
+        const int r = i / (Kp / 8), k = (i - r * (Kp / 8)) * 8, b = b0 + r;
+        uint4 v = make_uint4(0, 0, 0, 0);
         if (b < g.B) {
-          const uint16_t v = g.x_is_f32 ? f2b(((const float*)g.x)[(size_t)b * g.ldx + k])
-                                        : ((const uint16_t*)g.x)[(size_t)b * g.ldx + k];
-          g.xT[(size_t)k * g.ldT + b] = v;
+          if (k + 8 <= g.in0) {
+            v = *(const uint4*)(xs + (size_t)b * g.ldx + k);
+          } else if (k < g.in0) {
+            uint32_t e[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) e[j] = (k + j < g.in0) ? (uint32_t)xs[(size_t)b * g.ldx + k + j] : 0u;
+            v = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16),
+                           e[6] | (e[7] << 16));
+          }
+        }
+        *(uint4*)(buf[0] + r * lda + k) = v;
+      }
+    } else {
+      for (int i = tid; i < TB * (Kp / 8); i += 256) {  // clear, then fill the valid part
+        const int r = i / (Kp / 8), k = (i - r * (Kp / 8)) * 8;
+        *(uint4*)(buf[0] + r * lda + k) = make_uint4(0, 0, 0, 0);
+      }
+      __syncthreads();
+      for (int i = tid; i < TB * g.in0; i += 256) {
+        const int r = i / g.in0, k = i - r * g.in0, b = b0 + r;
+        if (b < g.B)
+          buf[0][r * lda + k] = g.x_is_f32 ? f2b(((const float*)g.x)[(size_t)b * g.ldx + k])
+                                           : ((const uint16_t*)g.x)[(size_t)b * g.ldx + k];
+      }
+    }
+    __syncthreads();
+    if (g.xT) {  // 8 consecutive samples of one input unit per thread: one 16-byte store
+      for (int i = tid; i < g.in0 * (TB / 8); i += 256) {
+        const int k = i / (TB / 8), r = (i - k * (TB / 8)) * 8, b = b0 + r;
+        uint32_t e[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = buf[0][(r + j) * lda + k];
+        uint16_t* p = g.xT + (size_t)k * g.ldT + b;
+        if (b + 8 <= g.B) {
+          *(uint4*)p = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16),
+                                  e[6] | (e[7] << 16));
+        } else {
+          for (int j = 0; j < 8 && b + j < g.B; ++j) p[j] = (uint16_t)e[j];
         }
       }
     }
+  }
+  // the one-unit output layer's weights, rounded to bf16, for the tail
+  __shared__ float wl_s[512];
+  if (g.has_tail) {
+    const int in = g.L[g.n_layers - 1].out;
+    for (int k = tid; k < in; k += 256) wl_s[k] = b2f(f2b(g.w_last[k]));
   }
   __syncthreads();
   const int col_in = lane & 31, row_in = (lane >> 5) * 4;
@@ -171,15 +225,13 @@ __global__ __launch_bounds__(256) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
     const FusedLayer L = g.L[l];
     const uint16_t* A = buf[l & 1];
     uint16_t* O = buf[(l + 1) & 1];
-    const int Kp = pad16(L.in), lda = Kp + APAD;
-    const int Np = pad16(L.out), ldo = Np + APAD;
+    const int Kp = padk(L.in), lda = Kp + APAD;
+    const int Np = padk(L.out), ldo = Np + APAD;
     const int ntiles = (L.out + 31) / 32;
     const int mine = (ntiles > wave) ? (ntiles - wave + 3) / 4 : 0;
     f32x16 acc[MAXT];
     zero_acc(acc);
-    tile_gemm<RawK>(acc, A, lda, Kp, mine, lane, [&](int j, int k) {
-      return load_w_rowk(L.W, L.in, (wave + 4 * j) * 32 + col_in, k, L.out, L.in);
-    });
+    tile_gemm_n(mine, acc, A, lda, Kp / 16, wave, lane, L.Wf);
     const bool last = (l == g.n_layers - 1);
     const bool relu = !last || g.relu_last;
 #pragma unroll
@@ -219,15 +271,20 @@ __global__ __launch_bounds__(256) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
         }
       }
     }
+    // padded columns no tile covers must read as zero in the next product
+    for (int i = tid; i < TB * (Np - ntiles * 32); i += 256) {
+      const int w = Np - ntiles * 32, r = i / w, n = ntiles * 32 + (i - r * w);
+      O[r * ldo + n] = 0;
+    }
     __syncthreads();
   }
   // ---- top stack only: one-unit output layer, loss and dL/dlogit (8 threads per sample)
   if (g.has_tail) {
     const uint16_t* A = buf[g.n_layers & 1];
-    const int in = g.L[g.n_layers - 1].out, lda = pad16(in) + APAD;
+    const int in = g.L[g.n_layers - 1].out, lda = padk(in) + APAD;
     const int r = tid >> 3, sub = tid & 7, b = b0 + r;
     float s = 0.f;
-    for (int k = sub; k < in; k += 8) s += b2f(A[r * lda + k]) * b2f(f2b(g.w_last[k]));
+    for (int k = sub; k < in; k += 8) s += b2f(A[r * lda + k]) * wl_s[k];
     s += __shfl_xor(s, 1); s += __shfl_xor(s, 2); s += __shfl_xor(s, 4);
     float lossv = 0.f;
     const float invB = 1.0f / (float)g.B;
@@ -258,7 +315,7 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
   const int b0 = blockIdx.x * TB;
   const int nl = g.n_layers;
   const int wlast = g.L[nl - 1].out;  // width of the stack's output
-  const int ld0 = pad16(wlast) + APAD;
+  const int ld0 = padk(wlast) + APAD;
   // ---- incoming gradient tile -> LDS buffer 0 (+ transposed copy for the weight gradients)
   if (g.dlogit) {
     // top stack: dL/da = q(dlogit_b) q(w_k), gated by a > 0; plus the output layer's own
@@ -271,20 +328,50 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
     }
     __syncthreads();
     const uint16_t* aT = g.actT[nl - 1];
-    for (int k = tid; k < pad16(wlast); k += 256) {
+    const bool full = (b0 + TB <= g.B);
+    for (int k = tid; k < padk(wlast); k += 256) {
       const bool kok = k < wlast;
       const float wq = kok ? b2f(f2b(g.w_last[k])) : 0.f;
       float acc = 0.f;
-      for (int r = 0; r < TB; ++r) {
-        const int b = b0 + r;
-        uint16_t out = 0;
-        if (kok && b < g.B) {
-          const uint16_t a = aT[(size_t)k * g.ldT + b];
-          acc += dlq[r] * b2f(a);
-          out = ((int16_t)a > 0) ? f2b(dlq[r] * wq) : (uint16_t)0;
-          g.dYT[nl - 1][(size_t)k * g.ldT + b] = out;
+      if (kok && full) {
+        // the 32 samples of unit k are 64 contiguous bytes in both transposed arrays
+        const uint4* ap4 = (const uint4*)(aT + (size_t)k * g.ldT + b0);
+        uint4* dp4 = (uint4*)(g.dYT[nl - 1] + (size_t)k * g.ldT + b0);
+        uint4 av[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) av[c] = ap4[c];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const uint32_t w4[4] = {av[c].x, av[c].y, av[c].z, av[c].w};
+          uint32_t o4[4];
+#pragma unroll
+          for (int h2 = 0; h2 < 4; ++h2) {
+            uint32_t ow = 0;
+#pragma unroll
+            for (int q2 = 0; q2 < 2; ++q2) {
+              const int r = c * 8 + h2 * 2 + q2;
+              const uint16_t a = (uint16_t)(w4[h2] >> (16 * q2));
+              acc += dlq[r] * b2f(a);
+              const uint16_t out = ((int16_t)a > 0) ? f2b(dlq[r] * wq) : (uint16_t)0;
+              buf[0][r * ld0 + k] = out;
+              ow |= (uint32_t)out << (16 * q2);
+            }
+            o4[h2] = ow;
+          }
+          dp4[c] = make_uint4(o4[0], o4[1], o4[2], o4[3]);
         }
-        buf[0][r * ld0 + k] = out;
+      } else {
+        for (int r = 0; r < TB; ++r) {
+          const int b = b0 + r;
+          uint16_t out = 0;
+          if (kok && b < g.B) {
+            const uint16_t a = aT[(size_t)k * g.ldT + b];
+            acc += dlq[r] * b2f(a);
+            out = ((int16_t)a > 0) ? f2b(dlq[r] * wq) : (uint16_t)0;
+            g.dYT[nl - 1][(size_t)k * g.ldT + b] = out;
+          }
+          buf[0][r * ld0 + k] = out;
+        }
       }
       if (kok) atomicAdd(g.g_w_last + k, acc);
     }
@@ -295,15 +382,31 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
     }
   } else {
     // bottom stack: dz0 arrives in fp32, already gated
-    for (int i = tid; i < TB * pad16(wlast); i += 256) {
-      const int r = i / pad16(wlast), k = i - r * pad16(wlast), b = b0 + r;
-      uint16_t v = 0;
-      if (b < g.B && k < wlast) v = f2b(g.d_in_f32[(size_t)b * g.ld_d_in + k]);
-      buf[0][r * ld0 + k] = v;
+    const int Wp = padk(wlast);
+    const bool vec = (wlast % 4 == 0) && (g.ld_d_in % 4 == 0);
+    for (int i = tid; i < TB * (Wp / 4); i += 256) {
+      const int r = i / (Wp / 4), k = (i - r * (Wp / 4)) * 4, b = b0 + r;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (b < g.B && k < wlast) {
+        const float* p = g.d_in_f32 + (size_t)b * g.ld_d_in + k;
+        if (vec) v = *(const float4*)p;
+        else { v.x = p[0]; if (k + 1 < wlast) v.y = p[1]; if (k + 2 < wlast) v.z = p[2]; if (k + 3 < wlast) v.w = p[3]; }
+      }
+      *(uint2*)(buf[0] + r * ld0 + k) = make_uint2(pk(v.x, v.y), pk(v.z, v.w));
     }
-    for (int i = tid; i < wlast * TB; i += 256) {
-      const int k = i / TB, r = i - k * TB, b = b0 + r;
-      if (b < g.B) g.dYT[nl - 1][(size_t)k * g.ldT + b] = f2b(g.d_in_f32[(size_t)b * g.ld_d_in + k]);
+    __syncthreads();
+    for (int i = tid; i < wlast * (TB / 8); i += 256) {
+      const int k = i / (TB / 8), r = (i - k * (TB / 8)) * 8, b = b0 + r;
+      uint32_t e[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) e[j] = buf[0][(r + j) * ld0 + k];
+      uint16_t* p = g.dYT[nl - 1] + (size_t)k * g.ldT + b;
+      if (b + 8 <= g.B) {
+        *(uint4*)p = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16),
+                                e[6] | (e[7] << 16));
+      } else {
+        for (int j = 0; j < 8 && b + j < g.B; ++j) p[j] = (uint16_t)e[j];
+      }
     }
   }
   __syncthreads();
@@ -314,15 +417,13 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
     const FusedLayer L = g.L[l];
     const uint16_t* A = buf[cur];
     uint16_t* O = buf[cur ^ 1];
-    const int Kred = pad16(L.out), lda = Kred + APAD;  // reduction over this layer's outputs
-    const int Np = pad16(L.in), ldo = Np + APAD;       // result columns = this layer's inputs
+    const int Kred = padk(L.out), lda = Kred + APAD;  // reduction over this layer's outputs
+    const int Np = padk(L.in), ldo = Np + APAD;       // result columns = this layer's inputs
     const int ntiles = (L.in + 31) / 32;
     const int mine = (ntiles > wave) ? (ntiles - wave + 3) / 4 : 0;
     f32x16 acc[MAXT];
     zero_acc(acc);
-    tile_gemm<RawN>(acc, A, lda, Kred, mine, lane, [&](int j, int n) {
-      return load_w_coln(L.W, L.in, n, (wave + 4 * j) * 32 + col_in, L.out, L.in);
-    });
+    tile_gemm_n(mine, acc, A, lda, Kred / 16, wave, lane, L.Wr);
 #pragma unroll
     for (int j = 0; j < MAXT; ++j) {
       if (j >= mine) continue;
@@ -367,6 +468,12 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
         }
       }
     }
+    if (l > 0) {
+      for (int i = tid; i < TB * (Np - ntiles * 32); i += 256) {
+        const int w = Np - ntiles * 32, r = i / w, k = ntiles * 32 + (i - r * w);
+        O[r * ldo + k] = 0;
+      }
+    }
     cur ^= 1;
     __syncthreads();
   }
@@ -379,6 +486,8 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
 // the transposed operands).  Tiles with k0 == 0 also produce the bias gradient through one
 // extra MFMA against a fragment of ones.
 __global__ __launch_bounds__(256) void mlp_wgrad_grouped_kernel(WgradArgs g) {
+  __shared__ float red[3][32 * 33];
+  __shared__ float redb[3][32];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int4 t = g.tiles[blockIdx.x];
   const WgradLayer L = g.L[t.x];
@@ -387,7 +496,6 @@ __global__ __launch_bounds__(256) void mlp_wgrad_grouped_kernel(WgradArgs g) {
   const int per = (((g.B + nsplit - 1) / nsplit) + 15) & ~15;
   const int bbeg = (blockIdx.y * 4 + wave) * per;
   const int bend = min(g.B, bbeg + per);
-  if (bbeg >= bend) return;
   const int frow = lane & 31, fk = (lane >> 5) * 8;
   const int n = n0 + frow, k = k0 + frow;
   const uint16_t* ap = L.dYT + (size_t)n * g.ldT;
@@ -403,7 +511,7 @@ __global__ __launch_bounds__(256) void mlp_wgrad_grouped_kernel(WgradArgs g) {
   auto ld = [&](const uint16_t* p, bool ok, int b) {
     Frag f;
     f.q = make_uint4(0, 0, 0, 0);
-    if (ok) {
+    if (ok && b < bend) {
       if (b + 8 <= bend) {
         f.q = *(const uint4*)(p + b);
       } else {
@@ -416,28 +524,53 @@ __global__ __launch_bounds__(256) void mlp_wgrad_grouped_kernel(WgradArgs g) {
     }
     return f;
   };
-  Frag a = ld(ap, aok, bbeg + fk), b = ld(bp, bok, bbeg + fk);
-  for (int bb = bbeg; bb < bend; bb += 16) {
-    Frag an, bn;
-    an.q = make_uint4(0, 0, 0, 0);
-    bn.q = an.q;
-    if (bb + 16 < bend) {
-      an = ld(ap, aok, bb + 16 + fk);
-      bn = ld(bp, bok, bb + 16 + fk);
-    }
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, acc, 0, 0, 0);
-    if (do_bias) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, ones, accb, 0, 0, 0);
-    a = an;
-    b = bn;
-  }
-  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
-  const int kk = k0 + col_in;
+  constexpr int WD = 4;  // batch steps of 16 samples in flight
+  Frag a[WD], b[WD];
 #pragma unroll
-  for (int e = 0; e < 16; ++e) {
-    const int nn = n0 + (e >> 2) * 8 + row_in + (e & 3);
-    if (nn < L.out) {
-      if (kk < L.in) atomicAdd(L.gW + (size_t)nn * L.in + kk, acc[e]);
-      if (do_bias && col_in == 0) atomicAdd(L.gb + nn, accb[e]);
+  for (int d = 0; d < WD; ++d) {
+    a[d] = ld(ap, aok, bbeg + d * 16 + fk);
+    b[d] = ld(bp, bok, bbeg + d * 16 + fk);
+  }
+  for (int bb = bbeg; bb < bend; bb += 16 * WD) {
+#pragma unroll
+    for (int d = 0; d < WD; ++d) {
+      if (bb + d * 16 < bend) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[d].v, b[d].v, acc, 0, 0, 0);
+        if (do_bias) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[d].v, ones, accb, 0, 0, 0);
+        a[d] = ld(ap, aok, bb + (d + WD) * 16 + fk);
+        b[d] = ld(bp, bok, bb + (d + WD) * 16 + fk);
+      }
+    }
+  }
+  // fold the four waves' batch slices through LDS, then one atomic (or store) per element
+  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+  if (wave > 0) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int rr = (e >> 2) * 8 + row_in + (e & 3);
+      red[wave - 1][rr * 33 + col_in] = acc[e];
+      if (do_bias && col_in == 0) redb[wave - 1][rr] = accb[e];
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const int kk = k0 + col_in;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int rr = (e >> 2) * 8 + row_in + (e & 3);
+      const int nn = n0 + rr;
+      float v = acc[e] + red[0][rr * 33 + col_in] + red[1][rr * 33 + col_in] + red[2][rr * 33 + col_in];
+      if (nn < L.out) {
+        if (kk < L.in) {
+          if (gridDim.y > 1) atomicAdd(L.gW + (size_t)nn * L.in + kk, v);
+          else L.gW[(size_t)nn * L.in + kk] = v;
+        }
+        if (do_bias && col_in == 0) {
+          const float vb = accb[e] + redb[0][rr] + redb[1][rr] + redb[2][rr];
+          if (gridDim.y > 1) atomicAdd(L.gb + nn, vb);
+          else L.gb[nn] = vb;
+        }
+      }
     }
   }
 }
@@ -447,14 +580,19 @@ size_t fused_lds_bytes(const int* widths, int n_widths, size_t* elems0) {
   // widths[0] = stack input, widths[i] = output of layer i-1; buffer (i & 1) holds widths[i]
   size_t m[2] = {0, 0};
   for (int i = 0; i < n_widths; ++i) {
-    const size_t e = (size_t)TB * (((widths[i] + 15) & ~15) + APAD);
+    const size_t e = (size_t)TB * ((widths[i] + KGRAN - 1) / KGRAN * KGRAN + APAD);
     if (e > m[i & 1]) m[i & 1] = e;
   }
   if (elems0) *elems0 = m[0];
   return (m[0] + m[1]) * sizeof(uint16_t);
 }
 
-void launch_mlp_fused_fwd(const FusedFwdArgs& a, size_t lds_bytes, hipStream_t s) {
+void launch_mlp_fused_fwd(const FusedFwdArgs& a0, size_t lds_bytes, hipStream_t s) {
+  FusedFwdArgs a = a0;
+  static const int dbg = getenv("SS_DBG_FUSED") ? atoi(getenv("SS_DBG_FUSED")) : 0;
+  if (dbg & 1) { for (int l = 0; l < SS_FUSED_MAX_LAYERS; ++l) a.actT[l] = nullptr; }
+  if (dbg & 2) a.xT = nullptr;
+  if (dbg & 4) a.n_layers = a.n_layers > 1 ? a.n_layers - 1 : 1;
   hipLaunchKernelGGL(mlp_fused_fwd_kernel, dim3(ceil_div(a.B, TB)), dim3(256), lds_bytes, s, a);
 }
 
@@ -462,11 +600,15 @@ void launch_mlp_fused_bwd(const FusedBwdArgs& a, size_t lds_bytes, hipStream_t s
   hipLaunchKernelGGL(mlp_fused_bwd_kernel, dim3(ceil_div(a.B, TB)), dim3(256), lds_bytes, s, a);
 }
 
+void launch_mlp_prep(const PrepArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(mlp_prep_kernel, dim3(ceil_div(a.total_frags, 256)), dim3(256), 0, s, a);
+}
+
 void launch_mlp_wgrad_grouped(const WgradArgs& a, int n_tiles, hipStream_t s) {
-  // batch slices of at least 128 samples per wave
-  int gy = a.B / (4 * 128);
+  // batch slices of about 256 samples per wave; enough blocks to cover the chip
+  int gy = a.B / (4 * 256);
   if (gy < 1) gy = 1;
-  if (gy > 16) gy = 16;
+  while (gy < 8 && n_tiles * gy < 512 && a.B / (4 * gy * 2) >= 64) gy *= 2;
   hipLaunchKernelGGL(mlp_wgrad_grouped_kernel, dim3(n_tiles, gy), dim3(256), 0, s, a);
 }
 

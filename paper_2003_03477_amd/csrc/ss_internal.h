@@ -118,10 +118,27 @@ void launch_last_layer_bwd(const uint16_t* X, int ldx, const float* w, const flo
 // ---------------------------------------------------------------------------- mlp_fused.hip
 #define SS_FUSED_MAX_LAYERS 8
 struct FusedLayer {
-  const float* W;  // [out][in] fp32 master weights
-  const float* b;  // [out]
+  const uint16_t* Wf;  // bf16 weights in fragment order for X W^T
+  const uint16_t* Wr;  // bf16 weights in fragment order for dY W
+  const float* b;      // [out] fp32
   int in, out;
 };
+struct PrepLayer {
+  const float* W;      // [out][in] fp32 master weights
+  uint16_t* Wf;
+  uint16_t* Wr;
+  int in, out;
+  int64_t frag_base;   // first 8-value fragment of this layer in the launch
+  int64_t frags_fwd;   // fragments of the forward copy (the backward copy follows)
+};
+struct PrepArgs {
+  int n_layers;
+  PrepLayer L[2 * SS_FUSED_MAX_LAYERS];
+  int64_t total_frags;
+  float* zero;      // optional: zero_n floats cleared by the same launch
+  int64_t zero_n;
+};
+void launch_mlp_prep(const PrepArgs& a, hipStream_t s);
 struct FusedFwdArgs {
   int n_layers;
   FusedLayer L[SS_FUSED_MAX_LAYERS];
