@@ -104,6 +104,22 @@ def push_oracle_state(gpu, orc, row_base):
         gpu.ss_write_adagrad(t, 0, orc.G[row_base[t]:row_base[t + 1]])
 
 
+def push_oracle_state_sparse(gpu, orc, cp, row_base_c):
+    """Same, for a full-size device table set against a compacted oracle: only the touched
+    rows (contiguous runs of original ids are written in one call)."""
+    for i in range(orc.W.shape[0]):
+        gpu.ss_write_dense(i, orc.W[i])
+    for t, touched in enumerate(cp.touched):
+        h = orc.h[row_base_c[t]:row_base_c[t + 1]]
+        G = orc.G[row_base_c[t]:row_base_c[t + 1]]
+        breaks = np.flatnonzero(np.diff(touched) != 1) + 1
+        starts = np.concatenate(([0], breaks))
+        ends = np.concatenate((breaks, [len(touched)]))
+        for a, b in zip(starts, ends):
+            gpu.ss_write_rows(t, int(touched[a]), h[a:b])
+            gpu.ss_write_adagrad(t, int(touched[a]), G[a:b])
+
+
 def run_lockstep(gpu, orc, batches, gap, algo, alpha, eta=1.0, mu=0.0, rtol=FP32_RTOL,
                  check_every=1, loss_rtol=None, resync_row_base=None):
     """The deterministic schedule (one worker per replica, sync at fixed steps) on both.

@@ -1,0 +1,76 @@
+"""Hogwild mode: several lock-free worker streams on one replica plus a continuously looping
+shadow stream.  The racy run has no unique result, so the check is statistical: the
+window-averaged log-loss curve of the device run must stay within 1 % of the oracle's curve on
+the serialised schedule (worker 0's batch, worker 1's batch, ...; one sync round per `gap`
+global steps, gap = the device run's measured average sync gap) over the same batches."""
+import threading
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2003_03477_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def test_hogwild_logloss_curve_tracks_serialised_oracle():
+    import torch
+    # Mid architecture, heavy row contention (Zipf 1.3), shrunk so the oracle runs in seconds
+    wl = synth.hogwild().scaled(batch=256, rows=(20_000,) * 8, bag_lambda=6.0, num_replicas=2)
+    W0, W1 = 4, 1                      # worker streams on replica 0 / replica 1
+    S = 30                             # steps per worker
+    NW = W0 + W1
+    gen = synth.BatchGenerator(wl)
+    batches = [[gen.batch(s * NW + w) for s in range(S)] for w in range(NW)]
+    max_ids = max(int(b.offsets[-1]) for bs in batches for b in bs) + 64
+    gpu = binding.from_workload(wl, num_worker_slots=NW, max_ids=max_ids)
+    gpu.ss_init_tables_hash()
+    w0 = synth.dense_w0(wl)
+    gpu.ss_init_dense(w0)
+    dev = [[binding.upload_batch(b) for b in bs] for bs in batches]
+    streams = [torch.cuda.Stream() for _ in range(NW)]
+    shadow = torch.cuda.Stream()
+    losses = torch.zeros(NW, S, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+
+    def worker(w):
+        replica = 0 if w < W0 else 1
+        for s in range(S):
+            gpu.ss_train_step(replica, w, dev[w][s], streams[w], losses[w, s:s + 1])
+
+    gpu.ss_shadow_start(wl.algo, wl.alpha, stream=shadow)
+    ts = [threading.Thread(target=worker, args=(w,)) for w in range(NW)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    torch.cuda.synchronize()
+    gpu.ss_shadow_stop()
+    steps, rounds, examples = gpu.ss_get_counters()
+    assert steps.tolist() == [W0 * S, W1 * S] and examples == NW * S * wl.batch
+    assert rounds >= 1
+    got = losses.cpu().numpy().astype(np.float64)          # [worker, step]
+    assert np.all(np.isfinite(got)) and np.all(got > 0)
+
+    # oracle: serialised schedule on the same batches
+    gap = max(1, int(round(NW * S / rounds)))
+    orc = oracle.OracleTrainer(wl.bot_dims, wl.top_dims, wl.row_base, synth.full_tables_h0(wl), w0,
+                               wl.num_replicas, wl.lr_dense, wl.lr_emb, wl.adagrad_eps,
+                               bf16=wl.bf16)
+    want = np.zeros_like(got)
+    g = 0
+    for s in range(S):
+        for w in range(NW):
+            want[w, s] = orc.train_step(0 if w < W0 else 1, *batches[w][s].as_tuple())
+            g += 1
+            if g % gap == 0:
+                orc.shadow_sync(wl.algo, wl.alpha)
+    # window-averaged curves (all workers, windows of 10 steps = 50 batches)
+    win = 10
+    gc = got.mean(axis=0).reshape(S // win, win).mean(axis=1)
+    wc = want.mean(axis=0).reshape(S // win, win).mean(axis=1)
+    rel = np.abs(gc - wc) / wc
+    assert np.all(rel < 0.01), f"log-loss curves differ: device {gc}, oracle {wc}"
+    assert wc[-1] < wc[0]                                   # the model is actually learning
+    gpu.close()

@@ -188,3 +188,63 @@ def test_validation_errors_through_the_abi():
         gpu.ss_shadow_sync(9, 0.1)
     with pytest.raises(binding.ShadowSyncError):
         gpu.ss_read_dense(17)
+
+
+# ----------------------------------------------------------------------------- full sizes
+def _full_size_step_check(wl, n_batches, rtol):
+    """Full-size tables filled by the device hash, the bench's launch configuration; the
+    oracle works on the rows the batches touch (order-preserving relabelling), so every
+    per-step output can be compared element by element and the touched rows one by one."""
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(n_batches)]
+    cp = synth.compact_problem(wl, batches)
+    row_base_c = np.concatenate(([0], np.cumsum(cp.rows)))
+    gpu = binding.from_workload(wl, num_worker_slots=1,
+                                max_ids=max(int(b.offsets[-1]) for b in batches) + 64)
+    gpu.ss_init_tables_hash()
+    w0 = synth.dense_w0(wl)
+    gpu.ss_init_dense(w0)
+    import oracle
+    orc = oracle.OracleTrainer(wl.bot_dims, wl.top_dims, row_base_c, cp.h0, w0, wl.num_replicas,
+                               wl.lr_dense, wl.lr_emb, wl.adagrad_eps, bf16=wl.bf16)
+    B = wl.batch
+    for k, (b, cb) in enumerate(zip(batches, cp.batches)):
+        dev = binding.upload_batch(b)
+        lo = orc.train_step(0, *cb.as_tuple())
+        lg = float(gpu.ss_train_step(0, 0, dev).cpu()[0])
+        assert abs(lg - lo) <= rtol * abs(lo), f"step {k}: loss {lg} vs {lo}"
+        last = orc.last
+        # sort order: positions bit-exact; keys equal after mapping compact ids back
+        assert np.array_equal(gpu.ss_read_debug(0, binding.DBG_SORTED_POS).astype(np.int64),
+                              last["sorted_pos"])
+        glob = np.concatenate([wl.row_base[t] + cp.touched[t] for t in range(wl.num_tables)])
+        assert np.array_equal(gpu.ss_read_debug(0, binding.DBG_SORTED_ROWS).astype(np.int64),
+                              glob[last["sorted_keys"]])
+        assert np.array_equal(gpu.ss_read_debug(0, binding.DBG_SEG_STARTS).astype(np.int64),
+                              last["seg_starts"])
+        H.close(gpu.ss_read_debug(0, binding.DBG_POOLED), last["e"],
+                H.FP32_RTOL if k == 0 else rtol, f"step {k}: pooled e")
+        H.close(gpu.ss_read_debug(0, binding.DBG_LOGITS), last["logit"], rtol, f"step {k}: logits")
+        H.close(gpu.ss_read_debug(0, binding.DBG_DENSE_GRAD), last["g"], rtol, f"step {k}: dense grad")
+        H.close(gpu.ss_read_debug(0, binding.DBG_POOLED_GRAD), last["de"], rtol, f"step {k}: de")
+        H.close(gpu.ss_read_dense(0), orc.W[0], rtol, f"step {k}: replica 0")
+        for t in range(wl.num_tables):
+            vals, acc = gpu.ss_read_rows(t, cp.touched[t])
+            H.close(vals, orc.h[row_base_c[t]:row_base_c[t + 1]], rtol, f"step {k}: table {t} rows")
+            H.close(acc, orc.G[row_base_c[t]:row_base_c[t + 1]], rtol, f"step {k}: table {t} G")
+        # a sample of untouched rows is still the hash value, accumulator still zero
+        rng = np.random.default_rng(k)
+        for t in range(0, wl.num_tables, 3):
+            cand = rng.integers(0, wl.rows[t], 64)
+            cand = np.setdiff1d(cand, cp.touched[t])
+            vals, acc = gpu.ss_read_rows(t, cand)
+            assert np.array_equal(vals, synth.table_rows_h0(wl.seed, t, cand, wl.emb_dim))
+            assert not acc.any()
+        if k + 1 < len(batches):
+            H.push_oracle_state_sparse(gpu, orc, cp, row_base_c)
+    gpu.close()
+
+
+def test_mid_full_size_steps():
+    """Mid config at its real sizes (B=2048, 8 x 1e6 x 64 tables, ~344k ids per step)."""
+    _full_size_step_check(synth.mid(), 2, H.BF16_RTOL)
