@@ -44,8 +44,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="mid", choices=["mid", "tiny", "hogwild"])
+    ap.add_argument("--workload", default="mid", choices=["mid", "tiny", "hogwild", "large"])
     ap.add_argument("--batches", type=int, default=16, help="distinct batches cycled through")
+    ap.add_argument("--continuous-shadow", action="store_true",
+                    help="loop shadow rounds back to back (ss_shadow_start) instead of pacing them")
     ap.add_argument("--workers-per-replica", type=int, default=2,
                     help="Hogwild worker streams per replica")
     ap.add_argument("--no-shadow", action="store_true", help="run without the shadow stream")
@@ -176,7 +178,7 @@ def main():
             for s in range(first_step + w, first_step + total_steps, NS):
                 one(s)
                 # one shadow round per sync_gap iterations of replica 0 (all its workers)
-                if w % K == 0 and not args.no_shadow:
+                if w % K == 0 and not args.no_shadow and not args.continuous_shadow:
                     with r0_lock:
                         r0_steps[0] += 1
                         due = r0_steps[0] % wl.sync_gap == 0
@@ -185,7 +187,8 @@ def main():
         if args.single_thread:
             for s in range(first_step, first_step + total_steps):
                 one(s)
-                if not args.no_shadow and (s + 1 - first_step) % (wl.sync_gap * K) == 0:
+                if not args.no_shadow and not args.continuous_shadow and \
+                        (s + 1 - first_step) % (wl.sync_gap * K) == 0:
                     gpu.ss_shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
             return
         ts = [threading.Thread(target=worker, args=(w,)) for w in range(NS)]
@@ -194,6 +197,8 @@ def main():
         for t in ts:
             t.join()
 
+    if args.continuous_shadow and not args.no_shadow:
+        gpu.ss_shadow_start(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
     run(args.warmup, 0)
     torch.cuda.synchronize()
     # Inside the timed region only the two roofline candidates are bracketed (two event pairs
@@ -247,8 +252,12 @@ def main():
                         "launches": kd["brackets"],
                         "algorithmic_bytes_per_launch": kd["algorithmic_bytes_per_launch"]}
 
+    if args.continuous_shadow and not args.no_shadow:
+        gpu.ss_shadow_stop()
     rounds = rounds1 - rounds0
     shadow_txt = ("no shadow sync" if args.no_shadow else
+                  f"S-{wl.algo.upper()} alpha={wl.alpha} looping continuously on a shadow stream"
+                  if args.continuous_shadow else
                   f"S-{wl.algo.upper()} alpha={wl.alpha} on a shadow stream every {wl.sync_gap} "
                   f"trainer steps")
     out = {
@@ -259,7 +268,7 @@ def main():
         "ms_per_step": dt / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: B={wl.batch}, {wl.num_tables} tables x {wl.rows[0]} "
+        "config": {"workload": f"{wl.name}: B={wl.batch}, {wl.num_tables} tables, {sum(wl.rows)} "
                                f"rows x d{wl.emb_dim} fp32, Zipf({wl.zipf_s}), bag Poisson("
                                f"{wl.bag_lambda:g})+1, K={K} replicas x {WPR} worker stream(s), "
                                f"{shadow_txt}",

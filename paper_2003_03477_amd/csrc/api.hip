@@ -96,6 +96,7 @@ struct ss_ctx {
   size_t lds_fwd_bot = 0, lds_fwd_top = 0, lds_bwd_bot = 0, lds_bwd_top = 0;
   size_t e0_fwd_bot = 0, e0_fwd_top = 0, e0_bwd_bot = 0, e0_bwd_top = 0;
   std::vector<int64_t> wsw_f, wsw_r;  // per layer: offsets of the two fragment-ordered copies
+  std::vector<int> kp_f, kp_r, depth_f, depth_r;  // per layer: padded reduction lengths, prefetch depths
   int64_t wsw_elems = 0;
   std::vector<int4> wgrad_tiles;   // host copy of the tile table
   int4* wgrad_tiles_dev = nullptr;
@@ -309,14 +310,30 @@ static ss_ctx* make_ctx(const ss_config* c) {
     bool ok = x->prec == SS_BF16 && nh >= 1 && nb <= SS_FUSED_MAX_LAYERS &&
               nh <= SS_FUSED_MAX_LAYERS && maxw <= 512 && !getenv("SS_NO_FUSED_MLP");
     if (ok) {
-      std::vector<int> wb, wt;
-      wb.push_back(x->num_dense);
-      for (int l = 0; l < nb; ++l) wb.push_back(x->layers[l].out);
-      wt.push_back(x->F);
-      for (int l = nb; l < nb + nh; ++l) wt.push_back(x->layers[l].out);
-      std::vector<int> rb(wb.rbegin(), wb.rend()), rt(wt.rbegin(), wt.rend());
-      x->lds_fwd_bot = fused_lds_bytes(wb.data(), (int)wb.size(), &x->e0_fwd_bot);
-      x->lds_fwd_top = fused_lds_bytes(wt.data(), (int)wt.size(), &x->e0_fwd_top);
+      // reduction lengths are zero padded to a multiple of 64; the prefetch depth of a layer is
+      // the larger of 8 / 4 reduction steps that divides its step count
+      auto round_up = [](int v, int m) { return (v + m - 1) / m * m; };
+      auto depth_for = [](int kp) {
+        const int steps = kp / 16;
+        return steps % 8 == 0 ? 8 : 4;
+      };
+      for (int l = 0; l < nb + nh; ++l) {
+        const Layer& ly = x->layers[l];
+        x->kp_f.push_back(round_up(ly.in, 64));
+        x->depth_f.push_back(depth_for(x->kp_f.back()));
+        x->kp_r.push_back(round_up(ly.out, 64));
+        x->depth_r.push_back(depth_for(x->kp_r.back()));
+      }
+      // LDS tiles of each launch, in the order they are produced (tile i -> buffer i & 1)
+      std::vector<int> fb, ft, rb, rt;
+      for (int l = 0; l < nb; ++l) fb.push_back(x->kp_f[l]);
+      fb.push_back(round_up(x->layers[nb - 1].out, 64));
+      for (int l = nb; l < nb + nh; ++l) ft.push_back(x->kp_f[l]);
+      ft.push_back(round_up(x->layers[nb + nh - 1].out, 64));
+      for (int l = nb - 1; l >= 0; --l) rb.push_back(x->kp_r[l]);
+      for (int l = nb + nh - 1; l >= nb; --l) rt.push_back(x->kp_r[l]);
+      x->lds_fwd_bot = fused_lds_bytes(fb.data(), (int)fb.size(), &x->e0_fwd_bot);
+      x->lds_fwd_top = fused_lds_bytes(ft.data(), (int)ft.size(), &x->e0_fwd_top);
       x->lds_bwd_bot = fused_lds_bytes(rb.data(), (int)rb.size(), &x->e0_bwd_bot);
       x->lds_bwd_top = fused_lds_bytes(rt.data(), (int)rt.size(), &x->e0_bwd_top);
       const size_t lim = 150 * 1024;
@@ -329,9 +346,9 @@ static ss_ctx* make_ctx(const ss_config* c) {
       for (int l = 0; l < nb + nh; ++l) {
         const Layer& ly = x->layers[l];
         x->wsw_f.push_back(x->wsw_elems);
-        x->wsw_elems += (int64_t)((ly.out + 31) / 32 * 32) * ((ly.in + 63) / 64 * 64);
+        x->wsw_elems += (int64_t)((ly.out + 31) / 32 * 32) * x->kp_f[l];
         x->wsw_r.push_back(x->wsw_elems);
-        x->wsw_elems += (int64_t)((ly.in + 31) / 32 * 32) * ((ly.out + 63) / 64 * 64);
+        x->wsw_elems += (int64_t)((ly.in + 31) / 32 * 32) * x->kp_r[l];
       }
       // weight-gradient tiles of every layer except the one-unit output layer
       for (int l = 0; l < nb + nh; ++l)
@@ -555,6 +572,8 @@ static void fill_stack(const ss_ctx* x, const Slot& s, const float* w, int l0, i
     const Layer& ly = x->layers[l0 + i];
     out[i].Wf = s.wsw + x->wsw_f[l0 + i]; out[i].Wr = s.wsw + x->wsw_r[l0 + i];
     out[i].b = w + ly.b_off; out[i].in = ly.in; out[i].out = ly.out;
+    out[i].kp_f = x->kp_f[l0 + i]; out[i].depth_f = x->depth_f[l0 + i];
+    out[i].kp_r = x->kp_r[l0 + i]; out[i].depth_r = x->depth_r[l0 + i];
   }
 }
 
@@ -572,6 +591,7 @@ static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
       PrepLayer& pl = pa.L[l];
       pl.W = w + ly.w_off; pl.Wf = s.wsw + x->wsw_f[l]; pl.Wr = s.wsw + x->wsw_r[l];
       pl.in = ly.in; pl.out = ly.out; pl.frag_base = base;
+      pl.kp_f = x->kp_f[l]; pl.kp_r = x->kp_r[l];
       pl.frags_fwd = (x->wsw_r[l] - x->wsw_f[l]) / 8;
       const int64_t end = (l + 1 < nb + nh) ? x->wsw_f[l + 1] : x->wsw_elems;
       base += (end - x->wsw_f[l]) / 8;
@@ -586,6 +606,7 @@ static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
     a.xT = train ? s.xT : nullptr;
     for (int l = 0; l < nb; ++l) a.actT[l] = s.actT[l];
     a.out_f32 = s.z0; a.relu_last = 1; a.has_tail = 0;
+    a.kp_tail = (x->layers[nb - 1].out + 63) / 64 * 64;
     a.lds_elems0 = (unsigned)x->e0_fwd_bot;
     launch_mlp_fused_fwd(a, x->lds_fwd_bot, st);
   }
@@ -607,6 +628,7 @@ static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
     a.xT = train ? s.fT : nullptr;
     for (int l = 0; l < nh; ++l) a.actT[l] = s.actT[nb + l];
     a.out_f32 = nullptr; a.relu_last = 1; a.has_tail = 1;
+    a.kp_tail = (x->layers[nb + nh - 1].out + 63) / 64 * 64;
     const Layer& last = x->layers[L - 1];
     a.w_last = w + last.w_off; a.b_last = w + last.b_off; a.y = bt->labels;
     a.logits = s.logits; a.dlogit = train ? s.dlogit : nullptr; a.loss = loss;

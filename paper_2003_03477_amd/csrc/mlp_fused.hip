@@ -22,7 +22,6 @@
 // an MFMA accumulator holds 4 consecutive samples of one unit per lane, so this is the cheap
 // direction to store, it is the layout the ReLU gate wants to read, and it makes the batch
 // dimension contiguous for the weight-gradient fragments (no LDS transpose anywhere).
-#include <cstdlib>
 #include "ss_internal.h"
 
 namespace ss {
@@ -34,7 +33,7 @@ namespace {
 
 constexpr int TB = 32;     // samples per workgroup
 constexpr int APAD = 8;    // bf16 elements of LDS row padding
-constexpr int MAXT = 4;    // 32-column tiles per wave (4 waves -> widths up to 512)
+constexpr int NT = 1024;   // threads per workgroup: 16 waves, one 32-column tile each (widths <= 512)
 
 __device__ __forceinline__ uint16_t f2b(float f) {
   uint32_t u = __float_as_uint(f);
@@ -62,57 +61,49 @@ __device__ __forceinline__ Frag load_frag(const uint16_t* __restrict__ Wsw, int 
   return f;
 }
 
-constexpr int DEPTH = 4;  // reduction steps kept in flight per tile
-constexpr int KGRAN = 16 * DEPTH;  // reduction lengths are zero-padded to a multiple of this
+// One layer's product for a 32-sample tile.  A workgroup has 16 waves; wave w owns the 32
+// output columns of tile w (widths up to 512), so acc is one 32x32 accumulator.  A comes from
+// LDS (row stride lda bf16), B fragments from the fragment-ordered copy.  DEPTH reduction
+// steps (8 or 4) are kept in flight per wave (16 waves x 8 steps x 1 KB = 128 KB of weights
+// requested at once); steps is a multiple of DEPTH (the reduction length is zero padded) and
+// the loop body has no branches, so the loads stay in flight behind the MFMAs.  The first
+// group is loaded separately (load_group) so that the caller can issue it early -- before the
+// input tile is staged, or before the previous layer's epilogue -- and its latency is hidden.
+template <int DEPTH>
+__device__ __forceinline__ void load_group(Frag (&q)[8], const uint16_t* __restrict__ Wsw,
+                                           int steps, int tile, int lane) {
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) q[d] = load_frag(Wsw, tile, steps, d, lane);
+}
 
-// acc[j] += A_tile[32 x 16*steps] * B for this wave's MINE column tiles (tile index wave + 4j).
-// A comes from LDS (row stride lda bf16), B fragments from the fragment-ordered copy.  steps is
-// a multiple of DEPTH; the loop body has no branches so the loads of the next DEPTH steps stay
-// in flight behind the MFMAs (the trailing refills re-read the last group and are dropped).
-template <int MINE>
-__device__ __forceinline__ void tile_gemm(f32x16 (&acc)[MAXT], const uint16_t* __restrict__ A,
-                                          int lda, int steps, int wave, int lane,
-                                          const uint16_t* __restrict__ Wsw) {
+template <int DEPTH>
+__device__ __forceinline__ void run_gemm(f32x16& acc, Frag (&q)[8],
+                                         const uint16_t* __restrict__ A, int lda, int steps,
+                                         int tile, int lane, const uint16_t* __restrict__ Wsw) {
   const int frow = lane & 31, fk = (lane >> 5) * 8;
-  Frag q[DEPTH][MINE];
-#pragma unroll
-  for (int d = 0; d < DEPTH; ++d)
-#pragma unroll
-    for (int j = 0; j < MINE; ++j) q[d][j] = load_frag(Wsw, wave + 4 * j, steps, d, lane);
   for (int s0 = 0; s0 < steps; s0 += DEPTH) {
-    const int nx = min(s0 + DEPTH, steps - DEPTH);
+    const int nx = min(s0 + DEPTH, steps - DEPTH);  // trailing refills re-read the last group
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
       const bf16x8 a = *(const bf16x8*)(A + frow * lda + (s0 + d) * 16 + fk);
-#pragma unroll
-      for (int j = 0; j < MINE; ++j)
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[d][j].v, acc[j], 0, 0, 0);
-#pragma unroll
-      for (int j = 0; j < MINE; ++j) q[d][j] = load_frag(Wsw, wave + 4 * j, steps, nx + d, lane);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[d].v, acc, 0, 0, 0);
+      if (steps > DEPTH) q[d] = load_frag(Wsw, tile, steps, nx + d, lane);
     }
   }
 }
 
-__device__ __forceinline__ void tile_gemm_n(int mine, f32x16 (&acc)[MAXT],
-                                            const uint16_t* __restrict__ A, int lda, int steps,
-                                            int wave, int lane, const uint16_t* __restrict__ Wsw) {
-  switch (mine) {
-    case 1: tile_gemm<1>(acc, A, lda, steps, wave, lane, Wsw); break;
-    case 2: tile_gemm<2>(acc, A, lda, steps, wave, lane, Wsw); break;
-    case 3: tile_gemm<3>(acc, A, lda, steps, wave, lane, Wsw); break;
-    case 4: tile_gemm<4>(acc, A, lda, steps, wave, lane, Wsw); break;
-    default: break;
-  }
+__device__ __forceinline__ void load_group_n(int depth, Frag (&q)[8],
+                                             const uint16_t* __restrict__ Wsw, int steps, int tile,
+                                             int lane) {
+  if (depth == 8) load_group<8>(q, Wsw, steps, tile, lane);
+  else load_group<4>(q, Wsw, steps, tile, lane);
 }
-
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[MAXT]) {
-#pragma unroll
-  for (int j = 0; j < MAXT; ++j)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+__device__ __forceinline__ void run_gemm_n(int depth, f32x16& acc, Frag (&q)[8],
+                                           const uint16_t* __restrict__ A, int lda, int steps,
+                                           int tile, int lane, const uint16_t* __restrict__ Wsw) {
+  if (depth == 8) run_gemm<8>(acc, q, A, lda, steps, tile, lane, Wsw);
+  else run_gemm<4>(acc, q, A, lda, steps, tile, lane, Wsw);
 }
-
-__device__ __forceinline__ int padk(int k) { return (k + KGRAN - 1) / KGRAN * KGRAN; }
 
 }  // namespace
 
@@ -137,13 +128,13 @@ __global__ __launch_bounds__(256) void mlp_prep_kernel(PrepArgs g) {
   Frag f;
   float e[8];
   if (!bwd) {
-    const int steps = (L.in + KGRAN - 1) / KGRAN * DEPTH;
+    const int steps = L.kp_f / 16;
     const int tile = (int)(ts / steps), step = (int)(ts - (int64_t)tile * steps);
     const int n = tile * 32 + (lane & 31), k = step * 16 + (lane >> 5) * 8;
 #pragma unroll
     for (int j = 0; j < 8; ++j) e[j] = (n < L.out && k + j < L.in) ? L.W[(size_t)n * L.in + k + j] : 0.f;
   } else {
-    const int steps = (L.out + KGRAN - 1) / KGRAN * DEPTH;
+    const int steps = L.kp_r / 16;
     const int tile = (int)(ts / steps), step = (int)(ts - (int64_t)tile * steps);
     const int k = tile * 32 + (lane & 31), n = step * 16 + (lane >> 5) * 8;
 #pragma unroll
@@ -155,19 +146,35 @@ __global__ __launch_bounds__(256) void mlp_prep_kernel(PrepArgs g) {
 
 // ------------------------------------------------------------------------------------------
 // Forward.
-__global__ __launch_bounds__(256) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
+__global__ __launch_bounds__(NT) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   uint16_t* buf[2] = {smem, smem + g.lds_elems0};
+  __shared__ float wl_s[512];
+  __shared__ float wloss[16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b0 = blockIdx.x * TB;
-  // ---- stage the input tile (bf16, zero padded to KGRAN columns and 32 rows), then write its
-  //      transposed copy for the weight-gradient kernel from LDS
+  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+  // ---- first layer's weights and bias, and the tail's weights: requested before anything else
+  Frag q[8];
+  float bcur = 0.f, bnext = 0.f;
   {
-    const int Kp = padk(g.in0), lda = Kp + APAD;
+    const FusedLayer L = g.L[0];
+    if (wave * 32 < L.out) {
+      load_group_n(L.depth_f, q, L.Wf, L.kp_f / 16, wave, lane);
+      const int n = wave * 32 + col_in;
+      if (n < L.out) bcur = L.b[n];
+    }
+  }
+  float wl_r = 0.f;
+  if (g.has_tail && tid < g.L[g.n_layers - 1].out) wl_r = g.w_last[tid];
+  // ---- stage the input tile (bf16, zero padded columns and rows), then write its transposed
+  //      copy for the weight-gradient kernel from LDS
+  {
+    const int Kp = g.L[0].kp_f, lda = Kp + APAD;
     const bool vec = !g.x_is_f32 && (g.ldx % 8 == 0) && ((((uintptr_t)g.x) & 15) == 0);
     if (vec) {
       const uint16_t* xs = (const uint16_t*)g.x;
-      for (int i = tid; i < TB * (Kp / 8); i += 256) {
+      for (int i = tid; i < TB * (Kp / 8); i += NT) {
         const int r = i / (Kp / 8), k = (i - r * (Kp / 8)) * 8, b = b0 + r;
         uint4 v = make_uint4(0, 0, 0, 0);
         if (b < g.B) {
@@ -184,21 +191,19 @@ __global__ __launch_bounds__(256) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
         *(uint4*)(buf[0] + r * lda + k) = v;
       }
     } else {
-      for (int i = tid; i < TB * (Kp / 8); i += 256) {  // clear, then fill the valid part
-        const int r = i / (Kp / 8), k = (i - r * (Kp / 8)) * 8;
-        *(uint4*)(buf[0] + r * lda + k) = make_uint4(0, 0, 0, 0);
-      }
-      __syncthreads();
-      for (int i = tid; i < TB * g.in0; i += 256) {
-        const int r = i / g.in0, k = i - r * g.in0, b = b0 + r;
-        if (b < g.B)
-          buf[0][r * lda + k] = g.x_is_f32 ? f2b(((const float*)g.x)[(size_t)b * g.ldx + k])
-                                           : ((const uint16_t*)g.x)[(size_t)b * g.ldx + k];
+      for (int i = tid; i < TB * Kp; i += NT) {
+        const int r = i / Kp, k = i - r * Kp, b = b0 + r;
+        uint16_t v = 0;
+        if (b < g.B && k < g.in0)
+          v = g.x_is_f32 ? f2b(((const float*)g.x)[(size_t)b * g.ldx + k])
+                         : ((const uint16_t*)g.x)[(size_t)b * g.ldx + k];
+        buf[0][r * lda + k] = v;
       }
     }
+    if (g.has_tail && tid < 512) wl_s[tid] = b2f(f2b(wl_r));
     __syncthreads();
     if (g.xT) {  // 8 consecutive samples of one input unit per thread: one 16-byte store
-      for (int i = tid; i < g.in0 * (TB / 8); i += 256) {
+      for (int i = tid; i < g.in0 * (TB / 8); i += NT) {
         const int k = i / (TB / 8), r = (i - k * (TB / 8)) * 8, b = b0 + r;
         uint32_t e[8];
 #pragma unroll
@@ -213,40 +218,39 @@ __global__ __launch_bounds__(256) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
       }
     }
   }
-  // the one-unit output layer's weights, rounded to bf16, for the tail
-  __shared__ float wl_s[512];
-  if (g.has_tail) {
-    const int in = g.L[g.n_layers - 1].out;
-    for (int k = tid; k < in; k += 256) wl_s[k] = b2f(f2b(g.w_last[k]));
-  }
-  __syncthreads();
-  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
   for (int l = 0; l < g.n_layers; ++l) {
     const FusedLayer L = g.L[l];
     const uint16_t* A = buf[l & 1];
     uint16_t* O = buf[(l + 1) & 1];
-    const int Kp = padk(L.in), lda = Kp + APAD;
-    const int Np = padk(L.out), ldo = Np + APAD;
-    const int ntiles = (L.out + 31) / 32;
-    const int mine = (ntiles > wave) ? (ntiles - wave + 3) / 4 : 0;
-    f32x16 acc[MAXT];
-    zero_acc(acc);
-    tile_gemm_n(mine, acc, A, lda, Kp / 16, wave, lane, L.Wf);
+    const int Kp = L.kp_f, lda = Kp + APAD;
     const bool last = (l == g.n_layers - 1);
-    const bool relu = !last || g.relu_last;
+    const int Np = last ? g.kp_tail : g.L[l + 1].kp_f, ldo = Np + APAD;
+    const int ntiles = (L.out + 31) / 32;
+    const bool active = wave < ntiles;
+    f32x16 acc;
 #pragma unroll
-    for (int j = 0; j < MAXT; ++j) {
-      if (j >= mine) continue;
-      const int n = (wave + 4 * j) * 32 + col_in;
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    if (active) run_gemm_n(L.depth_f, acc, q, A, lda, Kp / 16, wave, lane, L.Wf);
+    if (!last) {  // next layer's first fragments and bias fly during this layer's epilogue
+      const FusedLayer N = g.L[l + 1];
+      bnext = 0.f;
+      if (wave * 32 < N.out) {
+        load_group_n(N.depth_f, q, N.Wf, N.kp_f / 16, wave, lane);
+        const int n = wave * 32 + col_in;
+        if (n < N.out) bnext = N.b[n];
+      }
+    }
+    const bool relu = !last || g.relu_last;
+    if (active) {
+      const int n = wave * 32 + col_in;
       const bool nok = n < L.out;
-      const float bv = nok ? L.b[n] : 0.f;
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
         const int r = e4 * 8 + row_in;  // rows r .. r+3
         float v[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          v[i] = acc[j][e4 * 4 + i] + bv;
+          v[i] = acc[e4 * 4 + i] + bcur;
           if (relu) v[i] = fmaxf(v[i], 0.f);
         }
         if (n < Np) {
@@ -272,20 +276,22 @@ __global__ __launch_bounds__(256) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
       }
     }
     // padded columns no tile covers must read as zero in the next product
-    for (int i = tid; i < TB * (Np - ntiles * 32); i += 256) {
+    for (int i = tid; i < TB * (Np - ntiles * 32); i += NT) {
       const int w = Np - ntiles * 32, r = i / w, n = ntiles * 32 + (i - r * w);
       O[r * ldo + n] = 0;
     }
+    bcur = bnext;
     __syncthreads();
   }
-  // ---- top stack only: one-unit output layer, loss and dL/dlogit (8 threads per sample)
+  // ---- top stack only: one-unit output layer, loss and dL/dlogit (32 threads per sample)
   if (g.has_tail) {
     const uint16_t* A = buf[g.n_layers & 1];
-    const int in = g.L[g.n_layers - 1].out, lda = padk(in) + APAD;
-    const int r = tid >> 3, sub = tid & 7, b = b0 + r;
+    const int in = g.L[g.n_layers - 1].out, lda = g.kp_tail + APAD;
+    const int r = tid >> 5, sub = tid & 31, b = b0 + r;
     float s = 0.f;
-    for (int k = sub; k < in; k += 8) s += b2f(A[r * lda + k]) * wl_s[k];
-    s += __shfl_xor(s, 1); s += __shfl_xor(s, 2); s += __shfl_xor(s, 4);
+    for (int k = sub; k < in; k += 32) s += b2f(A[r * lda + k]) * wl_s[k];
+#pragma unroll
+    for (int off = 1; off < 32; off <<= 1) s += __shfl_xor(s, off);
     float lossv = 0.f;
     const float invB = 1.0f / (float)g.B;
     if (sub == 0 && b < g.B) {
@@ -296,31 +302,43 @@ __global__ __launch_bounds__(256) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
       g.logits[b] = lg;
       if (g.dlogit) g.dlogit[b] = (p - t) * invB;
     }
-    // block sum of the 32 per-sample losses
-    __shared__ float wl[4];
-    float ws = lossv;
-    for (int off = 32; off > 0; off >>= 1) ws += __shfl_xor(ws, off);
-    if (lane == 0) wl[wave] = ws;
+    // block sum of the 32 per-sample losses (two samples per wave)
+    lossv += __shfl_xor(lossv, 32);
+    if (lane == 0) wloss[wave] = lossv;
     __syncthreads();
-    if (tid == 0) atomicAdd(g.loss, (wl[0] + wl[1] + wl[2] + wl[3]) * invB);
+    if (tid == 0) {
+      float tot = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) tot += wloss[i];
+      atomicAdd(g.loss, tot * invB);
+    }
   }
 }
 
 // ------------------------------------------------------------------------------------------
 // Backward (data gradients through the stack).
-__global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
+__global__ __launch_bounds__(NT) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   uint16_t* buf[2] = {smem, smem + g.lds_elems0};
+  __shared__ float dl[TB], dlq[TB];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b0 = blockIdx.x * TB;
   const int nl = g.n_layers;
   const int wlast = g.L[nl - 1].out;  // width of the stack's output
-  const int ld0 = padk(wlast) + APAD;
+  const int Wp0 = g.L[nl - 1].kp_r, ld0 = Wp0 + APAD;
+  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+  const bool full_tile = (b0 + TB <= g.B);
+  // ---- the first product's weight fragments are requested before anything else
+  Frag q[8];
+  const bool any_product = !(nl == 1 && !g.d_out_f32);
+  if (any_product) {
+    const FusedLayer L = g.L[nl - 1];
+    if (wave * 32 < L.in) load_group_n(L.depth_r, q, L.Wr, L.kp_r / 16, wave, lane);
+  }
   // ---- incoming gradient tile -> LDS buffer 0 (+ transposed copy for the weight gradients)
   if (g.dlogit) {
     // top stack: dL/da = q(dlogit_b) q(w_k), gated by a > 0; plus the output layer's own
     // weight and bias gradients
-    __shared__ float dl[TB], dlq[TB];
     if (tid < TB) {
       const float v = (b0 + tid < g.B) ? g.dlogit[b0 + tid] : 0.f;
       dl[tid] = v;
@@ -328,12 +346,11 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
     }
     __syncthreads();
     const uint16_t* aT = g.actT[nl - 1];
-    const bool full = (b0 + TB <= g.B);
-    for (int k = tid; k < padk(wlast); k += 256) {
+    for (int k = tid; k < Wp0; k += NT) {
       const bool kok = k < wlast;
       const float wq = kok ? b2f(f2b(g.w_last[k])) : 0.f;
       float acc = 0.f;
-      if (kok && full) {
+      if (kok && full_tile) {
         // the 32 samples of unit k are 64 contiguous bytes in both transposed arrays
         const uint4* ap4 = (const uint4*)(aT + (size_t)k * g.ldT + b0);
         uint4* dp4 = (uint4*)(g.dYT[nl - 1] + (size_t)k * g.ldT + b0);
@@ -382,9 +399,9 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
     }
   } else {
     // bottom stack: dz0 arrives in fp32, already gated
-    const int Wp = padk(wlast);
+    const int Wp = Wp0;
     const bool vec = (wlast % 4 == 0) && (g.ld_d_in % 4 == 0);
-    for (int i = tid; i < TB * (Wp / 4); i += 256) {
+    for (int i = tid; i < TB * (Wp / 4); i += NT) {
       const int r = i / (Wp / 4), k = (i - r * (Wp / 4)) * 4, b = b0 + r;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (b < g.B && k < wlast) {
@@ -395,7 +412,7 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
       *(uint2*)(buf[0] + r * ld0 + k) = make_uint2(pk(v.x, v.y), pk(v.z, v.w));
     }
     __syncthreads();
-    for (int i = tid; i < wlast * (TB / 8); i += 256) {
+    for (int i = tid; i < wlast * (TB / 8); i += NT) {
       const int k = i / (TB / 8), r = (i - k * (TB / 8)) * 8, b = b0 + r;
       uint32_t e[8];
 #pragma unroll
@@ -410,40 +427,50 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
     }
   }
   __syncthreads();
-  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
   int cur = 0;
   for (int l = nl - 1; l >= 0; --l) {
     if (l == 0 && !g.d_out_f32) break;  // the stack's input needs no gradient
     const FusedLayer L = g.L[l];
     const uint16_t* A = buf[cur];
     uint16_t* O = buf[cur ^ 1];
-    const int Kred = padk(L.out), lda = Kred + APAD;  // reduction over this layer's outputs
-    const int Np = padk(L.in), ldo = Np + APAD;       // result columns = this layer's inputs
+    const int Kred = L.kp_r, lda = Kred + APAD;  // reduction over this layer's outputs
+    const int Np = (l > 0) ? g.L[l - 1].kp_r : 0, ldo = Np + APAD;  // result = next reduction
     const int ntiles = (L.in + 31) / 32;
-    const int mine = (ntiles > wave) ? (ntiles - wave + 3) / 4 : 0;
-    f32x16 acc[MAXT];
-    zero_acc(acc);
-    tile_gemm_n(mine, acc, A, lda, Kred / 16, wave, lane, L.Wr);
+    const bool active = wave < ntiles;
+    const int k = wave * 32 + col_in;
+    const bool kok = active && k < L.in;
+    // ReLU gates of this lane's results (activations of the layer below), requested now so
+    // that they arrive while the product runs
+    uint2 gate[4];
 #pragma unroll
-    for (int j = 0; j < MAXT; ++j) {
-      if (j >= mine) continue;
-      const int k = (wave + 4 * j) * 32 + col_in;
-      const bool kok = k < L.in;
+    for (int e4 = 0; e4 < 4; ++e4) {
+      gate[e4] = make_uint2(0, 0);
+      if (l > 0 && full_tile && kok)
+        gate[e4] = *(const uint2*)(g.actT[l - 1] + (size_t)k * g.ldT + b0 + e4 * 8 + row_in);
+    }
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    if (active) run_gemm_n(L.depth_r, acc, q, A, lda, Kred / 16, wave, lane, L.Wr);
+    if (l > 1 || (l == 1 && g.d_out_f32)) {  // next product's first fragments
+      const FusedLayer N = g.L[l - 1];
+      if (wave * 32 < N.in) load_group_n(N.depth_r, q, N.Wr, N.kp_r / 16, wave, lane);
+    }
+    if (active) {
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
         const int r = e4 * 8 + row_in, b = b0 + r;
         float v[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = acc[j][e4 * 4 + i];
+        for (int i = 0; i < 4; ++i) v[i] = acc[e4 * 4 + i];
         if (l > 0) {
           // gate with the previous layer's activation, keep for the next product and for
           // the weight gradients
           uint16_t o[4] = {0, 0, 0, 0};
           if (kok && b < g.B) {
-            const uint16_t* ap = g.actT[l - 1] + (size_t)k * g.ldT + b;
             uint16_t* dp = g.dYT[l - 1] + (size_t)k * g.ldT + b;
-            if (b + 3 < g.B) {
-              const uint2 a = *(const uint2*)ap;
+            if (full_tile) {
+              const uint2 a = gate[e4];
               const uint16_t av[4] = {(uint16_t)a.x, (uint16_t)(a.x >> 16), (uint16_t)a.y,
                                       (uint16_t)(a.y >> 16)};
 #pragma unroll
@@ -451,6 +478,7 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
               *(uint2*)dp = make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16),
                                        (uint32_t)o[2] | ((uint32_t)o[3] << 16));
             } else {
+              const uint16_t* ap = g.actT[l - 1] + (size_t)k * g.ldT + b;
               for (int i = 0; i < 4 && b + i < g.B; ++i) {
                 o[i] = ((int16_t)ap[i] > 0) ? f2b(v[i]) : (uint16_t)0;
                 dp[i] = o[i];
@@ -469,9 +497,9 @@ __global__ __launch_bounds__(256) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
       }
     }
     if (l > 0) {
-      for (int i = tid; i < TB * (Np - ntiles * 32); i += 256) {
-        const int w = Np - ntiles * 32, r = i / w, k = ntiles * 32 + (i - r * w);
-        O[r * ldo + k] = 0;
+      for (int i = tid; i < TB * (Np - ntiles * 32); i += NT) {
+        const int w = Np - ntiles * 32, r = i / w, kk = ntiles * 32 + (i - r * w);
+        O[r * ldo + kk] = 0;
       }
     }
     cur ^= 1;
@@ -577,27 +605,22 @@ __global__ __launch_bounds__(256) void mlp_wgrad_grouped_kernel(WgradArgs g) {
 
 // ------------------------------------------------------------------------------------------
 size_t fused_lds_bytes(const int* widths, int n_widths, size_t* elems0) {
-  // widths[0] = stack input, widths[i] = output of layer i-1; buffer (i & 1) holds widths[i]
+  // widths[i] = padded row length of the i-th LDS tile of a launch; tile i lives in buffer i & 1
   size_t m[2] = {0, 0};
   for (int i = 0; i < n_widths; ++i) {
-    const size_t e = (size_t)TB * ((widths[i] + KGRAN - 1) / KGRAN * KGRAN + APAD);
+    const size_t e = (size_t)TB * (widths[i] + APAD);
     if (e > m[i & 1]) m[i & 1] = e;
   }
   if (elems0) *elems0 = m[0];
   return (m[0] + m[1]) * sizeof(uint16_t);
 }
 
-void launch_mlp_fused_fwd(const FusedFwdArgs& a0, size_t lds_bytes, hipStream_t s) {
-  FusedFwdArgs a = a0;
-  static const int dbg = getenv("SS_DBG_FUSED") ? atoi(getenv("SS_DBG_FUSED")) : 0;
-  if (dbg & 1) { for (int l = 0; l < SS_FUSED_MAX_LAYERS; ++l) a.actT[l] = nullptr; }
-  if (dbg & 2) a.xT = nullptr;
-  if (dbg & 4) a.n_layers = a.n_layers > 1 ? a.n_layers - 1 : 1;
-  hipLaunchKernelGGL(mlp_fused_fwd_kernel, dim3(ceil_div(a.B, TB)), dim3(256), lds_bytes, s, a);
+void launch_mlp_fused_fwd(const FusedFwdArgs& a, size_t lds_bytes, hipStream_t s) {
+  hipLaunchKernelGGL(mlp_fused_fwd_kernel, dim3(ceil_div(a.B, TB)), dim3(NT), lds_bytes, s, a);
 }
 
 void launch_mlp_fused_bwd(const FusedBwdArgs& a, size_t lds_bytes, hipStream_t s) {
-  hipLaunchKernelGGL(mlp_fused_bwd_kernel, dim3(ceil_div(a.B, TB)), dim3(256), lds_bytes, s, a);
+  hipLaunchKernelGGL(mlp_fused_bwd_kernel, dim3(ceil_div(a.B, TB)), dim3(NT), lds_bytes, s, a);
 }
 
 void launch_mlp_prep(const PrepArgs& a, hipStream_t s) {

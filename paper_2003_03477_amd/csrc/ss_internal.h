@@ -122,12 +122,15 @@ struct FusedLayer {
   const uint16_t* Wr;  // bf16 weights in fragment order for dY W
   const float* b;      // [out] fp32
   int in, out;
+  int kp_f, depth_f;   // X W^T: zero-padded reduction length (multiple of 16*depth_f)
+  int kp_r, depth_r;   // dY W:  zero-padded reduction length (multiple of 16*depth_r)
 };
 struct PrepLayer {
   const float* W;      // [out][in] fp32 master weights
   uint16_t* Wf;
   uint16_t* Wr;
   int in, out;
+  int kp_f, kp_r;
   int64_t frag_base;   // first 8-value fragment of this layer in the launch
   int64_t frags_fwd;   // fragments of the forward copy (the backward copy follows)
 };
@@ -148,6 +151,7 @@ struct FusedFwdArgs {
   uint16_t* actT[SS_FUSED_MAX_LAYERS];            // [out_l][ldT] transposed bf16 output, or null
   float* out_f32;                                 // last layer's output [B, out] fp32, or null
   int relu_last;
+  int kp_tail;                                    // padded row length of the last output tile
   int has_tail;                                   // top stack: one-unit layer + loss
   const float* w_last; const float* b_last; const float* y;
   float* logits; float* dlogit; float* loss;

@@ -248,3 +248,9 @@ def _full_size_step_check(wl, n_batches, rtol):
 def test_mid_full_size_steps():
     """Mid config at its real sizes (B=2048, 8 x 1e6 x 64 tables, ~344k ids per step)."""
     _full_size_step_check(synth.mid(), 2, H.BF16_RTOL)
+
+
+def test_large_full_size_step():
+    """Large config at its real sizes: 26 tables, ~1.8e8 rows x 64 (46 GB) filled on the
+    device, B=8192 (~6.6M ids), 1024-wide top MLP through the layer-wise MFMA GEMMs."""
+    _full_size_step_check(synth.large(), 1, H.BF16_RTOL)
