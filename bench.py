@@ -224,6 +224,12 @@ def main():
             if n:
                 kernels[name] = {"brackets": n, "avg_us": ms / n * 1e3, "total_ms": ms,
                                  "where": "timed region"}
+        # the two roofline candidates once more with ONE stream active (no queueing behind, and
+        # no bandwidth shared with, other streams' kernels): comparable with a profiler's figure
+        gpu.ss_profile_arm(*classes.values())
+        for s in range(24):
+            gpu.ss_train_step(0, 0, dev_batches[s % len(dev_batches)], streams[0], losses[0:1])
+        alone = {name: gpu.ss_profile_read(kid) for name, kid in classes.items()}
         gpu.ss_profile_arm(*extra.values())
         run(min(args.steps, 10 * wl.sync_gap * K), args.warmup + args.steps)
         for name, kid in extra.items():
@@ -241,6 +247,11 @@ def main():
             ach = bpl / (kernels[name]["avg_us"] * 1e-6) / 1e9
             kernels[name].update({"algorithmic_bytes_per_launch": bpl, "GBps": ach,
                                   "frac_of_hbm_peak": ach / HBM_PEAK_GBS})
+            n1, ms1 = alone[name]
+            if n1:
+                us1 = ms1 / n1 * 1e3
+                kernels[name].update({"alone_avg_us": us1, "alone_GBps": bpl / us1 / 1e3,
+                                      "alone_frac_of_hbm_peak": bpl / us1 / 1e3 / HBM_PEAK_GBS})
         cand = [k for k in ("gather", "row_update_chunk") if k in kernels]
         if cand:
             dom = max(cand, key=lambda k: kernels[k]["total_ms"])
@@ -250,7 +261,13 @@ def main():
                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kd["frac_of_hbm_peak"],
                         "traffic": traffic, "avg_launch_us": kd["avg_us"],
                         "launches": kd["brackets"],
-                        "algorithmic_bytes_per_launch": kd["algorithmic_bytes_per_launch"]}
+                        "algorithmic_bytes_per_launch": kd["algorithmic_bytes_per_launch"],
+                        "alone_avg_launch_us": kd.get("alone_avg_us"),
+                        "alone_achieved": kd.get("alone_GBps"),
+                        "alone_frac": kd.get("alone_frac_of_hbm_peak"),
+                        "note": "achieved/frac: HIP events inside the timed region, where "
+                                f"{NS + 1} streams share the GPU (includes queueing and shared "
+                                "bandwidth); alone_*: the same kernel with one stream active"}
 
     if args.continuous_shadow and not args.no_shadow:
         gpu.ss_shadow_stop()
