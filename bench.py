@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="mid", choices=["mid", "tiny", "hogwild", "large"])
     ap.add_argument("--batches", type=int, default=16, help="distinct batches cycled through")
+    ap.add_argument("--foreground", type=int, default=0, metavar="K",
+                    help="foreground variant (FR-EASGD-k): every worker stream exchanges its "
+                         "replica with the centre copy on ITS OWN stream every k of its steps")
     ap.add_argument("--continuous-shadow", action="store_true",
                     help="loop shadow rounds back to back (ss_shadow_start) instead of pacing them")
     ap.add_argument("--workers-per-replica", type=int, default=2,
@@ -175,10 +178,14 @@ def main():
         r0_lock = threading.Lock()
 
         def worker(w):
-            for s in range(first_step + w, first_step + total_steps, NS):
+            for j, s in enumerate(range(first_step + w, first_step + total_steps, NS)):
                 one(s)
+                if args.foreground and (j + 1) % args.foreground == 0:
+                    gpu.ss_easgd_exchange(w % K, wl.alpha, streams[w])
+                    continue
                 # one shadow round per sync_gap iterations of replica 0 (all its workers)
-                if w % K == 0 and not args.no_shadow and not args.continuous_shadow:
+                if w % K == 0 and not args.no_shadow and not args.continuous_shadow \
+                        and not args.foreground:
                     with r0_lock:
                         r0_steps[0] += 1
                         due = r0_steps[0] % wl.sync_gap == 0
@@ -272,7 +279,10 @@ def main():
     if args.continuous_shadow and not args.no_shadow:
         gpu.ss_shadow_stop()
     rounds = rounds1 - rounds0
-    shadow_txt = ("no shadow sync" if args.no_shadow else
+    shadow_txt = (f"FOREGROUND EASGD alpha={wl.alpha}: every worker stream exchanges with the "
+                  f"centre copy on its own stream every {args.foreground} of its steps"
+                  if args.foreground else
+                  "no shadow sync" if args.no_shadow else
                   f"S-{wl.algo.upper()} alpha={wl.alpha} looping continuously on a shadow stream"
                   if args.continuous_shadow else
                   f"S-{wl.algo.upper()} alpha={wl.alpha} on a shadow stream every {wl.sync_gap} "

@@ -147,6 +147,13 @@ int ss_eval_step(ss_ctx* ctx, int32_t replica, int32_t worker_slot, const ss_bat
 int ss_shadow_sync(ss_ctx* ctx, int32_t algo, float alpha, float eta, float momentum,
                    void* stream);
 
+/* Algorithm 2 for ONE trainer: the elastic exchange of w^(replica) with w^PS only (what a
+ * single trainer's shadow thread does per iteration; a round of ss_shadow_sync(SS_EASGD) is
+ * this for replica 0..K-1 in order).  algo is SS_EASGD or SS_EASGD_LITERAL.  Enqueued on
+ * `stream`: the shadow stream for background sync, or a worker's own stream for the
+ * foreground variant (FR-EASGD, Section 4) in which the worker syncs every k iterations. */
+int ss_easgd_exchange(ss_ctx* ctx, int32_t algo, int32_t replica, float alpha, void* stream);
+
 /* The same round on caller-owned device vectors (no context needed): `dev_replicas` holds
  * K vectors of P floats, vector i starting at dev_replicas + i*stride (stride >= P,
  * multiple of 4; all pointers 16-byte aligned).  dev_w_ps is used by the EASGD rules,

@@ -33,7 +33,7 @@ _DBG_DTYPE = {DBG_POOLED: np.float32, DBG_INTERACT: np.float32, DBG_LOGITS: np.f
 EXPORTS = [
     "ss_workspace_bytes", "ss_init", "ss_destroy", "ss_last_error", "ss_init_tables_hash",
     "ss_write_rows", "ss_write_adagrad", "ss_init_dense", "ss_num_params", "ss_train_step", "ss_eval_step",
-    "ss_shadow_sync", "ss_sync_round", "ss_shadow_start", "ss_shadow_stop", "ss_read_dense",
+    "ss_shadow_sync", "ss_easgd_exchange", "ss_sync_round", "ss_shadow_start", "ss_shadow_stop", "ss_read_dense",
     "ss_write_dense", "ss_read_rows", "ss_read_debug", "ss_get_counters", "ss_profile_arm",
     "ss_profile_read",
 ]
@@ -85,6 +85,7 @@ def load() -> C.CDLL:
     lib.ss_train_step.argtypes = [vp, i32, i32, C.POINTER(ss_batch), vp, vp]
     lib.ss_eval_step.argtypes = [vp, i32, i32, C.POINTER(ss_batch), vp, vp]
     lib.ss_shadow_sync.argtypes = [vp, i32, f32, f32, f32, vp]
+    lib.ss_easgd_exchange.argtypes = [vp, i32, i32, f32, vp]
     lib.ss_sync_round.argtypes = [i32, i32, i64, i64, vp, vp, vp, vp, f32, f32, f32, vp]
     lib.ss_shadow_start.argtypes = [vp, i32, f32, f32, f32, vp]
     lib.ss_shadow_stop.argtypes = [vp]
@@ -244,6 +245,11 @@ class ShadowSync:
         self._check(self.lib.ss_shadow_sync(self.ctx, a, alpha, eta, momentum,
                                             _stream_handle(stream)), "ss_shadow_sync")
 
+    def ss_easgd_exchange(self, replica: int, alpha: float, stream=None, algo="easgd"):
+        a = ALGOS[algo] if isinstance(algo, str) else int(algo)
+        self._check(self.lib.ss_easgd_exchange(self.ctx, a, replica, alpha,
+                                               _stream_handle(stream)), "ss_easgd_exchange")
+
     def ss_shadow_start(self, algo, alpha: float, eta: float = 1.0, momentum: float = 0.0,
                         stream=None):
         a = ALGOS[algo] if isinstance(algo, str) else int(algo)
@@ -312,6 +318,13 @@ def ss_sync_round(algo, K: int, P: int, stride: int, replicas, w_ps=None, w_glob
                            alpha, eta, momentum, _stream_handle(stream))
     if rc != 0:
         raise ShadowSyncError(f"ss_sync_round failed ({rc})")
+
+
+def normalized_entropy(mean_logloss: float, ctr: float) -> float:
+    """NE (Section 4, "Evaluation Metrics"): mean log-loss of the predictions divided by the
+    entropy of the empirical click rate `ctr` of the same examples."""
+    import math
+    return mean_logloss / -(ctr * math.log(ctr) + (1.0 - ctr) * math.log(1.0 - ctr))
 
 
 def from_workload(wl, rows=None, num_worker_slots: int = 1, max_ids: Optional[int] = None,

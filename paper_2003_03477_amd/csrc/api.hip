@@ -117,7 +117,7 @@ struct ss_ctx {
   std::string err;
   std::atomic<int> sticky{0};
   std::vector<std::atomic<uint64_t>> steps;
-  std::atomic<uint64_t> rounds{0}, examples{0};
+  std::atomic<uint64_t> rounds{0}, examples{0}, exchanges{0};
   // shadow loop
   std::thread shadow;
   std::atomic<bool> shadow_run{false};
@@ -925,6 +925,22 @@ int ss_shadow_sync(ss_ctx* ctx, int32_t algo, float alpha, float eta, float mome
   if (algo < SS_EASGD || algo > SS_EASGD_LITERAL) return fail(ctx, SS_EINVAL, "unknown sync rule %d", algo);
   if (ctx->shadow_run) return fail(ctx, SS_ESTATE, "shadow loop is running");
   return sync_once(ctx, algo, alpha, eta, momentum, (hipStream_t)stream);
+}
+
+int ss_easgd_exchange(ss_ctx* ctx, int32_t algo, int32_t replica, float alpha, void* stream) {
+  if (!ctx) return SS_EINVAL;
+  if (ctx->sticky) return SS_EDEVICE;
+  if (algo != SS_EASGD && algo != SS_EASGD_LITERAL)
+    return fail(ctx, SS_EINVAL, "ss_easgd_exchange: rule %d is not an EASGD rule", algo);
+  if (replica < 0 || replica >= ctx->K) return fail(ctx, SS_EINVAL, "replica %d out of range", replica);
+  hipStream_t st = (hipStream_t)stream;
+  {
+    ProfScope ps(ctx, SS_K_SYNC, st);
+    launch_sync_round(algo, 1, ctx->Pstride, ctx->Pstride, ctx->W + (size_t)replica * ctx->Pstride,
+                      ctx->w_ps, nullptr, nullptr, alpha, 1.f, 0.f, st);
+  }
+  ctx->exchanges.fetch_add(1);
+  return check_hip(ctx, hipGetLastError(), "ss_easgd_exchange");
 }
 
 int ss_shadow_start(ss_ctx* ctx, int32_t algo, float alpha, float eta, float momentum, void* stream) {

@@ -254,3 +254,36 @@ def test_large_full_size_step():
     """Large config at its real sizes: 26 tables, ~1.8e8 rows x 64 (46 GB) filled on the
     device, B=8192 (~6.6M ids), 1024-wide top MLP through the layer-wise MFMA GEMMs."""
     _full_size_step_check(synth.large(), 1, H.BF16_RTOL)
+
+
+# ----------------------------------------------------------------------------- extras
+def test_single_trainer_easgd_exchange_and_eval_ne():
+    """Algorithm 2 for one trainer (the unit the foreground variant enqueues on a worker
+    stream), and the forward-only evaluation whose loss, divided by the label entropy, is the
+    paper's normalised entropy."""
+    wl = synth.tiny().scaled(num_replicas=3)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(4)]
+    gpu, orc = H.make_pair(wl, batches)
+    dev = [binding.upload_batch(b) for b in batches]
+    for i in range(3):                      # make the replicas differ
+        orc.train_step(i, *batches[i].as_tuple())
+        gpu.ss_train_step(i, 0, dev[i])
+    from oracle import sync as osync
+    osync.easgd_round(orc.W[1:2], orc.w_ps, 0.3)
+    gpu.ss_easgd_exchange(1, 0.3)
+    osync.easgd_round_literal(orc.W[2:3], orc.w_ps, 0.2)
+    gpu.ss_easgd_exchange(2, 0.2, algo="easgd_literal")
+    H.compare_state(gpu, orc, H.FP32_RTOL, "after single-trainer exchanges", wl.row_base)
+    with pytest.raises(binding.ShadowSyncError):
+        gpu.ss_easgd_exchange(1, 0.3, algo="ma")
+    # eval: nothing changes, loss matches, NE = loss / H(ctr)
+    before = gpu.ss_read_dense(0)
+    lg = float(gpu.ss_eval_step(0, 0, dev[3]).cpu()[0])
+    lo = orc.eval_logloss(0, *batches[3].as_tuple())
+    assert abs(lg - lo) <= H.FP32_RTOL * lo
+    assert np.array_equal(before, gpu.ss_read_dense(0))
+    ctr = float(batches[3].labels.mean())
+    ne_gpu = binding.normalized_entropy(lg, ctr)
+    ent = -(ctr * np.log(ctr) + (1 - ctr) * np.log(1 - ctr))
+    assert abs(ne_gpu - lo / ent) < 1e-5
