@@ -50,6 +50,9 @@ struct Slot {
   uint16_t* actT[MAX_LAYERS];      // output of hidden layer l
   uint16_t* dYT[MAX_LAYERS];       // gradient w.r.t. the output of layer l
   uint16_t* wsw;                   // bf16 fragment-ordered weights of the step's replica
+  // wide-layer path: bf16 snapshot of the weights in both orientations, bf16 dense input
+  uint16_t* wb;
+  uint16_t* xb;                    // [B][p64(num_dense)]
   // embedding backward
   uint32_t* keys;                  // [max_ids]
   int32_t* bag_of_pos;             // [max_ids]
@@ -98,6 +101,14 @@ struct ss_ctx {
   std::vector<int64_t> wsw_f, wsw_r;  // per layer: offsets of the two fragment-ordered copies
   std::vector<int> kp_f, kp_r, depth_f, depth_r;  // per layer: padded reduction lengths, prefetch depths
   int64_t wsw_elems = 0;
+  bool wide = false;               // wide-layer regime: one 128x128-tile GEMM per layer and pass
+  std::vector<int> kin, kout;      // per layer: in / out rounded up to 64 (reduction lengths)
+  std::vector<int> pin, pout;      // per layer: row pitches of bf16 matrices with in / out columns
+  std::vector<int64_t> wb_off, wbt_off;  // per layer: offsets of W and W^T inside Slot::wb
+  std::vector<int> wb_tile_base;
+  std::vector<char> wgrad_grouped;  // per layer: weight gradient through the grouped 32x32-tile kernel
+  int64_t wb_elems = 0;
+  int wb_tiles = 0;
   std::vector<int4> wgrad_tiles;   // host copy of the tile table
   int4* wgrad_tiles_dev = nullptr;
   float lr_dense, lr_emb, eps;
@@ -207,7 +218,7 @@ static size_t layout(ss_ctx* x, void* base) {
   x->w_global = cv.take<float>(x->Pstride);
   x->v = cv.take<float>(x->Pstride);
   const int L = (int)x->layers.size();
-  x->wgrad_tiles_dev = x->fused ? cv.take<int4>(x->wgrad_tiles.size()) : nullptr;
+  x->wgrad_tiles_dev = x->wgrad_tiles.empty() ? nullptr : cv.take<int4>(x->wgrad_tiles.size());
   const int sort_blocks = sort_max_blocks((uint32_t)n);
   const int seg_blocks = ceil_div(n, 2048) + 1;
   for (Slot& s : x->slots) {
@@ -217,7 +228,7 @@ static size_t layout(ss_ctx* x, void* base) {
       const bool is_z0 = (l == x->n_bot_layers - 1), is_logit = (l == L - 1);
       if (is_z0 || is_logit) continue;
       if (x->prec == SS_FP32) s.act_f32[l] = cv.take<float>((size_t)B * x->layers[l].out);
-      else s.act_bf16[l] = cv.take<uint16_t>((size_t)B * x->layers[l].out);
+      else s.act_bf16[l] = cv.take<uint16_t>((size_t)B * (x->wide ? x->pout[l] : x->layers[l].out));
     }
     s.z0 = cv.take<float>((size_t)B * x->d);
     s.e = cv.take<float>((size_t)B * x->T * x->d);
@@ -231,7 +242,7 @@ static size_t layout(ss_ctx* x, void* base) {
       s.dbuf[i] = nullptr;
       s.dbuf16[i] = nullptr;
       if (x->prec == SS_FP32) s.dbuf[i] = cv.take<float>((size_t)B * x->maxw);
-      else s.dbuf16[i] = cv.take<uint16_t>((size_t)B * x->maxw);
+      else s.dbuf16[i] = cv.take<uint16_t>((size_t)B * ((x->maxw + 63) / 64 * 64 + 64));
     }
     s.df = cv.take<float>((size_t)B * x->ldf);
     s.dz0 = cv.take<float>((size_t)B * x->d);
@@ -239,8 +250,13 @@ static size_t layout(ss_ctx* x, void* base) {
     s.xT = s.fT = nullptr;
     for (int l = 0; l < L; ++l) s.actT[l] = s.dYT[l] = nullptr;
     s.wsw = nullptr;
-    if (x->fused) {
-      s.wsw = cv.take<uint16_t>((size_t)x->wsw_elems);
+    s.wb = s.xb = nullptr;
+    if (x->wide) {
+      s.wb = cv.take<uint16_t>((size_t)x->wb_elems);
+      s.xb = cv.take<uint16_t>((size_t)B * x->pin[0]);
+    }
+    if (x->fused || x->wide) {
+      if (x->fused) s.wsw = cv.take<uint16_t>((size_t)x->wsw_elems);
       s.xT = cv.take<uint16_t>((size_t)x->num_dense * x->ldT);
       s.fT = cv.take<uint16_t>((size_t)x->F * x->ldT);
       for (int l = 0; l < L - 1; ++l) {
@@ -342,6 +358,36 @@ static ss_ctx* make_ctx(const ss_config* c) {
     }
     x->fused = ok;
     x->ldT = (x->max_batch + 7) / 8 * 8;
+    // Wide-layer regime: every other bf16 model with a hidden top layer.  Row pitches of all
+    // bf16 operands are multiples of 64 so that no GEMM needs edge handling along its reduction.
+    const int64_t pw = (maxw + 63) / 64 * 64 + 64, pb = (x->max_batch + 63) / 64 * 64 + 64;
+    x->wide = !ok && x->prec == SS_BF16 && nt >= 2 && (int)x->layers.size() <= SS_NT_MAX_LAYERS &&
+              pw * pb < (1ll << 31) && !getenv("SS_NO_WIDE_GEMM");
+    if (x->wide) {
+      // row pitches: multiples of 64 elements, never a multiple of 256 (rows that are a power
+      // of two apart would all fall on the same memory channel)
+      auto pitch = [](int v) { const int p = (v + 63) / 64 * 64; return (p % 256 == 0) ? p + 64 : p; };
+      x->ldT = pitch(x->max_batch);
+      x->ldf16 = pitch(x->F);
+      for (size_t l = 0; l + 1 < x->layers.size(); ++l) {
+        const Layer& ly = x->layers[l];
+        const int pi = pitch(ly.in), po = pitch(ly.out);
+        x->kin.push_back((ly.in + 63) / 64 * 64); x->kout.push_back((ly.out + 63) / 64 * 64);
+        x->pin.push_back(pi); x->pout.push_back(po);
+        x->wb_off.push_back(x->wb_elems); x->wb_elems += (int64_t)ly.out * pi;
+        x->wbt_off.push_back(x->wb_elems); x->wb_elems += (int64_t)ly.in * po;
+        x->wb_tile_base.push_back(x->wb_tiles);
+        x->wb_tiles += ((ly.out + 63) / 64) * (pi / 64);
+        // layers whose weight matrix has fewer than sixteen 128x128 tiles cannot fill the chip
+        // with one GEMM; their weight gradients share one launch of the grouped kernel
+        const bool small = ceil_div(ly.out, 128) * ceil_div(ly.in, 128) < 16;
+        x->wgrad_grouped.push_back(small ? 1 : 0);
+        if (small)
+          for (int n0 = 0; n0 < ly.out; n0 += 32)
+            for (int k0 = 0; k0 < ly.in; k0 += 32)
+              x->wgrad_tiles.push_back(make_int4((int)l, n0, k0, 0));
+      }
+    }
     if (ok) {
       for (int l = 0; l < nb + nh; ++l) {
         const Layer& ly = x->layers[l];
@@ -397,7 +443,14 @@ int ss_init(const ss_config* cfg, void* dev_workspace, size_t bytes, ss_ctx** ou
   launch_fill_f32(x->w_ps, (uint64_t)x->Pstride, 0.f, nullptr);
   launch_fill_f32(x->w_global, (uint64_t)x->Pstride, 0.f, nullptr);
   for (Slot& s : x->slots) launch_fill_f32(s.grads, (uint64_t)x->Pstride, 0.f, nullptr);
-  if (x->fused)
+  if (x->wide) {
+    // the reduction-dimension padding of these buffers is read (against zero weights) before
+    // anything writes it, so it must hold finite values from the start
+    const uint64_t words = (uint64_t)x->max_batch * ((x->maxw + 63) / 64 * 64 + 64) / 2;
+    for (Slot& s : x->slots)
+      for (int i = 0; i < 2; ++i) launch_fill_f32((float*)s.dbuf16[i], words, 0.f, nullptr);
+  }
+  if (!x->wgrad_tiles.empty())
     (void)hipMemcpy(x->wgrad_tiles_dev, x->wgrad_tiles.data(), x->wgrad_tiles.size() * sizeof(int4),
                     hipMemcpyHostToDevice);
   e = hipDeviceSynchronize();
@@ -679,6 +732,150 @@ static void backward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
   }
 }
 
+// ---- wide-layer path ------------------------------------------------------------------------
+static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, float* loss,
+                         bool train, hipStream_t st) {
+  const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
+  auto layer_fwd = [&](int l, const uint16_t* in, int ld_in) {
+    const Layer& ly = x->layers[l];
+    GemmNtArgs a{};
+    a.A = in; a.lda = ld_in; a.B = s.wb + x->wb_off[l]; a.ldb = x->pin[l];
+    a.M = B; a.N = ly.out; a.K = x->kin[l];
+    a.epi = EPI_BIAS | EPI_RELU; a.bias = w + ly.b_off; a.split_k = 1;
+    if (l == nb - 1) { a.C_f32 = s.z0; a.ldc32 = x->d; }
+    else {
+      a.C = s.act_bf16[l]; a.ldc = x->pout[l];
+      a.CT = train ? s.actT[l] : nullptr; a.ldct = x->ldT;
+    }
+    launch_gemm_nt(a, st);
+  };
+  {
+    ProfScope ps(x, SS_K_MLP, st);
+    WeightsBf16Args wa{};
+    wa.n_layers = L - 1;
+    for (int l = 0; l < L - 1; ++l) {
+      const Layer& ly = x->layers[l];
+      WeightsBf16Layer& q = wa.L[l];
+      q.W = w + ly.w_off; q.Wb = s.wb + x->wb_off[l]; q.WbT = s.wb + x->wbt_off[l];
+      q.in = ly.in; q.out = ly.out; q.ldw = x->pin[l]; q.ldwt = x->pout[l];
+      q.tile_base = x->wb_tile_base[l];
+    }
+    wa.zero = train ? s.grads : nullptr; wa.zero_n = x->P;
+    launch_weights_bf16(wa, x->wb_tiles, st);
+    launch_cast_transpose(bt->dense, 1, x->num_dense, B, x->num_dense, s.xb, x->pin[0],
+                          train ? s.xT : nullptr, x->ldT, st);
+    const uint16_t* in = s.xb; int ld_in = x->pin[0];
+    for (int l = 0; l < nb; ++l) {
+      layer_fwd(l, in, ld_in);
+      in = s.act_bf16[l]; ld_in = x->pout[l];
+    }
+  }
+  {
+    ProfScope ps(x, SS_K_GATHER, st);
+    launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e, s.keys,
+                             s.bag_of_pos, loss, st);
+  }
+  {
+    ProfScope ps(x, SS_K_INTERACT_FWD, st);
+    launch_interaction_fwd(s.z0, s.e, B, x->T, x->d, s.f, x->ldf, s.f_bf16, x->ldf16, st);
+  }
+  {
+    ProfScope ps(x, SS_K_MLP, st);
+    if (train)
+      launch_cast_transpose(s.f_bf16, 0, x->ldf16, B, x->F, nullptr, 0, s.fT, x->ldT, st);
+    const uint16_t* in = s.f_bf16; int ld_in = x->ldf16;
+    for (int l = nb; l < L - 1; ++l) {
+      layer_fwd(l, in, ld_in);
+      in = s.act_bf16[l]; ld_in = x->pout[l];
+    }
+    const Layer& last = x->layers[L - 1];
+    launch_last_layer_fwd_loss(in, ld_in, w + last.w_off, w + last.b_off, bt->labels, B, last.in,
+                               s.logits, train ? s.dlogit : nullptr, loss, st);
+  }
+}
+
+static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipStream_t st) {
+  const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
+  const int Bp = (B + 63) / 64 * 64;
+  // weight gradient of layer l (and its bias gradient), then the gradient w.r.t. its input
+  auto layer_bwd = [&](int l, const uint16_t* dcur, int ldd, int& pp) -> const uint16_t* {
+    const Layer& ly = x->layers[l];
+    if (!x->wgrad_grouped[l]) {
+    GemmNtArgs g{};
+    g.A = s.dYT[l]; g.lda = x->ldT;
+    g.B = (l == 0) ? s.xT : (l == nb) ? s.fT : s.actT[l - 1]; g.ldb = x->ldT;
+    g.M = ly.out; g.N = ly.in; g.K = Bp;
+    g.C_f32 = s.grads + ly.w_off; g.ldc32 = ly.in; g.epi = EPI_NONE;
+    g.row_sum = s.grads + ly.b_off;
+    const int tiles = ceil_div(ly.out, 128) * ceil_div(ly.in, 128);
+    // batch slices are added with fp32 atomics, whose cost grows with the number of slices
+    // that meet on one element: at most 8 slices, each at least 512 samples long
+    int split = ceil_div(256, tiles);
+    if (split > 8) split = 8;
+    if (split > Bp / 512) split = Bp / 512;
+    g.split_k = split < 1 ? 1 : split;
+    launch_gemm_nt(g, st);
+    }
+    if (l == 0) return nullptr;
+    GemmNtArgs a{};
+    a.A = dcur; a.lda = ldd; a.B = s.wb + x->wbt_off[l]; a.ldb = x->pout[l];
+    a.M = B; a.N = ly.in; a.K = x->kout[l]; a.split_k = 1;
+    if (l == nb) {
+      a.C_f32 = s.df; a.ldc32 = x->ldf; a.epi = EPI_NONE;
+      launch_gemm_nt(a, st);
+      return nullptr;
+    }
+    a.C = s.dbuf16[pp]; a.ldc = x->pout[l - 1];
+    a.CT = s.dYT[l - 1]; a.ldct = x->ldT;
+    a.epi = EPI_MASK;
+    a.mask = s.act_bf16[l - 1]; a.ldmask = x->pout[l - 1];
+    a.maskT = s.actT[l - 1]; a.ldmaskT = x->ldT;
+    launch_gemm_nt(a, st);
+    const uint16_t* out = s.dbuf16[pp];
+    pp ^= 1;
+    return out;
+  };
+  {
+    ProfScope ps(x, SS_K_MLP, st);  // (the gradient accumulator was cleared by the weight snapshot)
+    const Layer& last = x->layers[L - 1];
+    const int ld = x->pout[L - 2];
+    launch_last_layer_bwd(s.act_bf16[L - 2], ld, w + last.w_off, s.dlogit, B, last.in, s.dbuf16[0],
+                          ld, s.grads + last.w_off, s.grads + last.b_off, st);
+    launch_cast_transpose(s.dbuf16[0], 0, ld, B, last.in, nullptr, 0, s.dYT[L - 2], x->ldT, st);
+    const uint16_t* dcur = s.dbuf16[0]; int ldd = ld; int pp = 1;
+    for (int l = L - 2; l >= nb; --l) {
+      dcur = layer_bwd(l, dcur, ldd, pp);
+      if (l > nb) ldd = x->pout[l - 1];
+    }
+  }
+  {
+    ProfScope ps(x, SS_K_INTERACT_BWD, st);
+    launch_interaction_bwd(s.z0, s.e, s.df, x->ldf, B, x->T, x->d, s.dz0, s.de, st);
+  }
+  {
+    ProfScope ps(x, SS_K_MLP, st);
+    const int ld = x->pout[nb - 1];
+    launch_cast_transpose(s.dz0, 1, x->d, B, x->d, s.dbuf16[0], ld, s.dYT[nb - 1], x->ldT, st);
+    const uint16_t* dcur = s.dbuf16[0]; int ldd = ld; int pp = 1;
+    for (int l = nb - 1; l >= 0; --l) {
+      dcur = layer_bwd(l, dcur, ldd, pp);
+      if (l > 0) ldd = x->pout[l - 1];
+    }
+    if (!x->wgrad_tiles.empty()) {
+      WgradArgs g{};
+      for (int l = 0; l < L - 1; ++l) {
+        const Layer& ly = x->layers[l];
+        g.L[l].dYT = s.dYT[l];
+        g.L[l].XT = (l == 0) ? s.xT : (l == nb) ? s.fT : s.actT[l - 1];
+        g.L[l].gW = s.grads + ly.w_off; g.L[l].gb = s.grads + ly.b_off;
+        g.L[l].in = ly.in; g.L[l].out = ly.out;
+      }
+      g.tiles = x->wgrad_tiles_dev; g.B = B; g.ldT = x->ldT;
+      launch_mlp_wgrad_grouped(g, (int)x->wgrad_tiles.size(), st);
+    }
+  }
+}
+
 static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, float* loss,
                     bool train, hipStream_t st) {
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
@@ -845,12 +1042,14 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
   const uint32_t n = (uint32_t)bt->num_ids;
   float* loss = dev_loss_out ? dev_loss_out : s.loss;
   if (x->fused) forward_fused(x, s, w, bt, loss, train, st);
+  else if (x->wide) forward_wide(x, s, w, bt, loss, train, st);
   else forward(x, s, w, bt, loss, train, st);
   if (!fused_last(x)) launch_bce_loss(s.logits, bt->labels, B, loss, train ? s.dlogit : nullptr, st);
   s.last_B = B;
   s.last_n = n;
   if (train) {
     if (x->fused) backward_fused(x, s, w, bt, st);
+    else if (x->wide) backward_wide(x, s, w, bt, st);
     else backward_dense(x, s, w, bt, st);
     // "update local param w^(i)": lock-free SGD on the replica
     launch_sgd(w, s.grads, x->P, x->lr_dense, st);

@@ -115,6 +115,45 @@ void launch_last_layer_fwd_loss(const uint16_t* X, int ldx, const float* w, cons
 void launch_last_layer_bwd(const uint16_t* X, int ldx, const float* w, const float* dlogit, int B,
                            int in, uint16_t* dX, int lddx, float* gW, float* gb, hipStream_t s);
 
+// ---------------------------------------------------------------------------- gemm_nt.hip
+// C[M,N] = A[M,K] B[N,K]^T, bf16 operands with the reduction dimension contiguous, K a multiple
+// of 64 (zero padded in at least one operand, finite in the other), 16-byte aligned rows.
+// Outputs: bf16 row-major C and / or transposed CT (both through EPI_BIAS / EPI_RELU, then
+// gated by mask / maskT > 0 under EPI_MASK), or fp32 C_f32 (stored; atomically added when
+// split_k > 1).  row_sum (+)= row sums of A (first column of tiles only).
+struct GemmNtArgs {
+  const uint16_t* A; int lda;
+  const uint16_t* B; int ldb;
+  int M, N, K;
+  uint16_t* C; int ldc;
+  uint16_t* CT; int ldct;
+  float* C_f32; int ldc32;
+  int epi; const float* bias;
+  const uint16_t* mask; int ldmask;
+  const uint16_t* maskT; int ldmaskT;
+  float* row_sum;
+  int split_k;
+};
+void launch_gemm_nt(const GemmNtArgs& a, hipStream_t s);
+// in [M][ld_in] (fp32 or bf16, N columns) -> out [M][ld_out] bf16 (optional, zero padded) and
+// outT [N][ldt] bf16 (optional, zero padded to the end of the last 64-sample tile)
+void launch_cast_transpose(const void* in, int in_is_f32, int ld_in, int M, int N, uint16_t* out,
+                           int ld_out, uint16_t* outT, int ldt, hipStream_t s);
+#define SS_NT_MAX_LAYERS 16
+struct WeightsBf16Layer {
+  const float* W;    // [out][in] fp32
+  uint16_t* Wb;      // [out][ldw] bf16, ldw = in rounded up to 64
+  uint16_t* WbT;     // [in][ldwt] bf16, ldwt = out rounded up to 64
+  int in, out, ldw, ldwt;
+  int tile_base;     // first block of this layer: ceil(out/64) * (ldw/64) blocks per layer
+};
+struct WeightsBf16Args {
+  WeightsBf16Layer L[SS_NT_MAX_LAYERS];
+  int n_layers;
+  float* zero; int64_t zero_n;   // gradient accumulator to clear (or null)
+};
+void launch_weights_bf16(const WeightsBf16Args& a, int total_tiles, hipStream_t s);
+
 // ---------------------------------------------------------------------------- mlp_fused.hip
 #define SS_FUSED_MAX_LAYERS 8
 struct FusedLayer {

@@ -140,12 +140,20 @@ def test_empty_bags_single_sample_and_hot_row():
     H.compare_state(gpu, orc, H.FP32_RTOL, "edge cases", wl.row_base)
 
 
-@pytest.mark.parametrize("path", ["fused", "layerwise"])
+def _select_mlp_path(path, monkeypatch):
+    """fused: per-sample-tile kernels; wide: one 128x128-tile GEMM per layer and pass;
+    generic: the layout-agnostic GEMM that serves every remaining bf16 model."""
+    if path in ("wide", "generic"):
+        monkeypatch.setenv("SS_NO_FUSED_MLP", "1")
+    if path == "generic":
+        monkeypatch.setenv("SS_NO_WIDE_GEMM", "1")
+
+
+@pytest.mark.parametrize("path", ["fused", "wide", "generic"])
 def test_bf16_mid_scaled(path, monkeypatch):
     """Mid CTR architecture (bf16 MLP GEMMs, fp32 master weights) on a compacted table set,
-    through the fused per-sample-tile MLP kernels and through the layer-by-layer GEMMs."""
-    if path == "layerwise":
-        monkeypatch.setenv("SS_NO_FUSED_MLP", "1")
+    through each of the three bf16 MLP code paths."""
+    _select_mlp_path(path, monkeypatch)
     wl = synth.mid().scaled(batch=500, num_replicas=2, sync_gap=2)
     gen = synth.BatchGenerator(wl)
     batches = [gen.batch(s) for s in range(8)]
@@ -156,11 +164,10 @@ def test_bf16_mid_scaled(path, monkeypatch):
                    resync_row_base=row_base)
 
 
-@pytest.mark.parametrize("path", ["fused", "layerwise"])
+@pytest.mark.parametrize("path", ["fused", "wide", "generic"])
 def test_bf16_odd_widths(path, monkeypatch):
     """bf16 with layer widths that are not multiples of the MFMA tile (guards, padding)."""
-    if path == "layerwise":
-        monkeypatch.setenv("SS_NO_FUSED_MLP", "1")
+    _select_mlp_path(path, monkeypatch)
     wl = synth.tiny().scaled(batch=77, rows=(3000, 17, 900), emb_dim=64, bag_lambda=4.0,
                              bot_dims=(13, 40, 64), top_dims=(64 + 6, 72, 24, 1),
                              num_replicas=1, bf16=True, algo="ma", alpha=1.0)

@@ -1,8 +1,8 @@
 """Hogwild mode: several lock-free worker streams on one replica plus a continuously looping
 shadow stream.  The racy run has no unique result, so the check is statistical: the
 window-averaged log-loss curve of the device run must stay within 1 % of the oracle's curve on
-the serialised schedule (worker 0's batch, worker 1's batch, ...; one sync round per `gap`
-global steps, gap = the device run's measured average sync gap) over the same batches."""
+the serialised schedule (worker 0's batch, worker 1's batch, ...; sync rounds spread evenly
+at the device run's measured rate of rounds per step) over the same batches."""
 import threading
 
 import numpy as np
@@ -24,6 +24,17 @@ def test_hogwild_logloss_curve_tracks_serialised_oracle():
     gen = synth.BatchGenerator(wl)
     batches = [[gen.batch(s * NW + w) for s in range(S)] for w in range(NW)]
     max_ids = max(int(b.offsets[-1]) for bs in batches for b in bs) + 64
+    # first launches of every kernel (code loading) happen on a throw-away context, so that the
+    # measured run starts with all workers moving at their steady pace
+    warm = binding.from_workload(wl, num_worker_slots=1, max_ids=max_ids)
+    warm.ss_init_tables_hash()
+    warm.ss_init_dense(synth.dense_w0(wl))
+    wb = binding.upload_batch(batches[0][0])
+    for _ in range(3):
+        warm.ss_train_step(0, 0, wb, None, None)
+    warm.ss_shadow_sync(wl.algo, wl.alpha)
+    torch.cuda.synchronize()
+    warm.close()
     gpu = binding.from_workload(wl, num_worker_slots=NW, max_ids=max_ids)
     gpu.ss_init_tables_hash()
     w0 = synth.dense_w0(wl)
@@ -34,8 +45,11 @@ def test_hogwild_logloss_curve_tracks_serialised_oracle():
     losses = torch.zeros(NW, S, dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
 
+    go = threading.Barrier(NW)
+
     def worker(w):
         replica = 0 if w < W0 else 1
+        go.wait()
         for s in range(S):
             gpu.ss_train_step(replica, w, dev[w][s], streams[w], losses[w, s:s + 1])
 
@@ -54,23 +68,25 @@ def test_hogwild_logloss_curve_tracks_serialised_oracle():
     assert np.all(np.isfinite(got)) and np.all(got > 0)
 
     # oracle: serialised schedule on the same batches
-    gap = max(1, int(round(NW * S / rounds)))
+    per_step = rounds / float(NW * S)      # sync rounds per global step (either side of 1)
     orc = oracle.OracleTrainer(wl.bot_dims, wl.top_dims, wl.row_base, synth.full_tables_h0(wl), w0,
                                wl.num_replicas, wl.lr_dense, wl.lr_emb, wl.adagrad_eps,
                                bf16=wl.bf16)
     want = np.zeros_like(got)
-    g = 0
+    due = 0.0
     for s in range(S):
         for w in range(NW):
             want[w, s] = orc.train_step(0 if w < W0 else 1, *batches[w][s].as_tuple())
-            g += 1
-            if g % gap == 0:
+            due += per_step
+            while due >= 1.0:
                 orc.shadow_sync(wl.algo, wl.alpha)
+                due -= 1.0
     # window-averaged curves (all workers, windows of 10 steps = 50 batches)
     win = 10
     gc = got.mean(axis=0).reshape(S // win, win).mean(axis=1)
     wc = want.mean(axis=0).reshape(S // win, win).mean(axis=1)
     rel = np.abs(gc - wc) / wc
+    print(f"hogwild windows: device {gc}, oracle {wc}, rel {rel}, rounds {rounds}")
     assert np.all(rel < 0.01), f"log-loss curves differ: device {gc}, oracle {wc}"
     assert wc[-1] < wc[0]                                   # the model is actually learning
     gpu.close()
