@@ -51,7 +51,7 @@ def parse():
                          "replica with the centre copy on ITS OWN stream every k of its steps")
     ap.add_argument("--continuous-shadow", action="store_true",
                     help="loop shadow rounds back to back (ss_shadow_start) instead of pacing them")
-    ap.add_argument("--workers-per-replica", type=int, default=2,
+    ap.add_argument("--workers-per-replica", type=int, default=4,
                     help="Hogwild worker streams per replica")
     ap.add_argument("--no-shadow", action="store_true", help="run without the shadow stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")

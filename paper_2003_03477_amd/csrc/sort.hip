@@ -6,7 +6,8 @@
 // A block owns a contiguous tile of 256*rounds elements; wave w of the block owns the w-th
 // quarter of the tile and walks it 64 elements at a time, so "earlier in the tile" is
 // (wave, round, lane) order.  Ranks among equal digits inside a wave come from 8 ballots
-// (one per digit bit); running per-wave digit counts live in LDS.
+// (one per digit bit); running per-wave digit counts live in LDS.  The scatter first reorders
+// its tile by digit inside LDS, so that elements with equal digits leave as contiguous runs.
 #include "ss_internal.h"
 
 namespace ss {
@@ -18,8 +19,9 @@ constexpr int SORT_WAVES = SORT_THREADS / SS_WAVE;
 constexpr int MAX_ROUNDS = 16;
 
 int sort_num_blocks(uint32_t n, int* rounds_out) {
-  // aim at >= 512 blocks once there is enough work, tiles of at most 4096 elements
-  int rounds = (int)((n + 512u * SORT_THREADS - 1) / (512u * SORT_THREADS));
+  // one block per CU once there is enough work, tiles of at most 4096 elements: long tiles
+  // give the scatter longer runs of equal digits, i.e. wider contiguous stores
+  int rounds = (int)((n + 256u * SORT_THREADS - 1) / (256u * SORT_THREADS));
   if (rounds < 1) rounds = 1;
   if (rounds > MAX_ROUNDS) rounds = MAX_ROUNDS;
   if (rounds_out) *rounds_out = rounds;
@@ -27,9 +29,9 @@ int sort_num_blocks(uint32_t n, int* rounds_out) {
 }
 
 int sort_max_blocks(uint32_t max_n) {
-  // below the round cap a sort never uses more than 512 blocks; above it, tiles of 4096
+  // below the round cap a sort never uses more than 256 blocks; above it, tiles of 4096
   int b = ceil_div(max_n, (int64_t)SORT_THREADS * MAX_ROUNDS);
-  return (b > 512 ? b : 512) + 1;
+  return (b > 256 ? b : 256) + 1;
 }
 
 __global__ __launch_bounds__(SORT_THREADS) void radix_hist_kernel(
@@ -85,36 +87,33 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
   // per-wave running digit counts; volatile: lanes of one wave hand values to each other
   // through it between rounds without a barrier
   __shared__ volatile uint32_t wrun[SORT_WAVES][RADIX];
-  __shared__ uint32_t dbase[RADIX];             // global start of this block's digit run
+  __shared__ uint32_t gbase[RADIX];             // global start of this block's run of a digit
+  __shared__ uint32_t lbase[RADIX];             // start of the digit inside the block's tile
+  __shared__ uint32_t skey[SORT_THREADS * MAX_ROUNDS], sval[SORT_THREADS * MAX_ROUNDS];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // digit base = exclusive scan of the 256 totals + this block's offset inside the digit
-  {
-    uint32_t v = digit_tot[tid];
-    dbase[tid] = v;
-    __syncthreads();
-    for (int off = 1; off < RADIX; off <<= 1) {
-      uint32_t a = (tid >= off) ? dbase[tid - off] : 0;
-      __syncthreads();
-      dbase[tid] += a;
-      __syncthreads();
+  const uint32_t tile = (uint32_t)(SORT_THREADS * rounds);
+  const uint32_t wbase = blockIdx.x * tile + wave * (uint32_t)(SS_WAVE * rounds);
+  // issue the loads first: this tile's keys and values, the digit totals, this block's offsets
+  uint32_t key[MAX_ROUNDS], val[MAX_ROUNDS], rank[MAX_ROUNDS];
+#pragma unroll
+  for (int r = 0; r < MAX_ROUNDS; ++r) {
+    if (r < rounds) {
+      const uint32_t j = wbase + r * SS_WAVE + lane;
+      key[r] = (j < n) ? keys_in[j] : 0xFFFFFFFFu;
+      val[r] = (j < n && vals_in) ? vals_in[j] : j;
     }
-    uint32_t excl = dbase[tid] - v;
-    __syncthreads();
-    dbase[tid] = excl + block_hist[(size_t)tid * nblocks + blockIdx.x];
   }
+  const uint32_t dtot = digit_tot[tid];
+  const uint32_t boff = block_hist[(size_t)tid * nblocks + blockIdx.x];
   for (int w = 0; w < SORT_WAVES; ++w) wrun[w][tid] = 0;
   __syncthreads();
 
-  const uint32_t tile = (uint32_t)(SORT_THREADS * rounds);
-  const uint32_t wbase = blockIdx.x * tile + wave * (uint32_t)(SS_WAVE * rounds);
-  uint32_t key[MAX_ROUNDS], rank[MAX_ROUNDS];
 #pragma unroll
   for (int r = 0; r < MAX_ROUNDS; ++r) {
     if (r < rounds) {
       const uint32_t j = wbase + r * SS_WAVE + lane;
       const bool valid = j < n;
-      const uint32_t k = valid ? keys_in[j] : 0xFFFFFFFFu;
-      const uint32_t dg = (k >> shift) & (RADIX - 1);
+      const uint32_t dg = (key[r] >> shift) & (RADIX - 1);
       uint64_t m = __ballot(valid);
 #pragma unroll
       for (int b = 0; b < RADIX_BITS; ++b) {
@@ -128,34 +127,60 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
       // every lane has read the running count before the group's last lane bumps it: LDS
       // operations of one wave complete in program order
       if (valid && (m >> lane) == 1ull) wrun[wave][dg] = prev + (uint32_t)__popcll(m);
-      key[r] = k;
       rank[r] = prev + before;
     }
   }
   __syncthreads();
-  // exclusive prefix of the per-wave totals over the waves of this block, per digit
-  {
-    uint32_t run = 0;
-    for (int w = 0; w < SORT_WAVES; ++w) {
-      uint32_t c = wrun[w][tid];
-      wrun[w][tid] = run;
-      run += c;
-    }
+  // per digit: exclusive prefix of the per-wave counts over the waves; the digit's count in
+  // this tile feeds the scan over digits below
+  uint32_t cnt = 0;
+  for (int w = 0; w < SORT_WAVES; ++w) {
+    const uint32_t c = wrun[w][tid];
+    wrun[w][tid] = cnt;
+    cnt += c;
   }
+  // two exclusive scans over the 256 digits at once: digit totals of the whole array (global
+  // digit starts) and digit counts of this tile (starts inside the tile)
+  gbase[tid] = dtot;
+  lbase[tid] = cnt;
   __syncthreads();
+  for (int off = 1; off < RADIX; off <<= 1) {
+    const uint32_t a = (tid >= off) ? gbase[tid - off] : 0;
+    const uint32_t b = (tid >= off) ? lbase[tid - off] : 0;
+    __syncthreads();
+    gbase[tid] += a;
+    lbase[tid] += b;
+    __syncthreads();
+  }
+  const uint32_t gex = gbase[tid] - dtot, lex = lbase[tid] - cnt;
+  __syncthreads();
+  gbase[tid] = gex + boff;
+  lbase[tid] = lex;
+  __syncthreads();
+  // reorder the tile by digit inside LDS (stable: wave, round, lane order within a digit)
 #pragma unroll
   for (int r = 0; r < MAX_ROUNDS; ++r) {
     if (r < rounds) {
       const uint32_t j = wbase + r * SS_WAVE + lane;
       if (j < n) {
         const uint32_t dg = (key[r] >> shift) & (RADIX - 1);
-        const uint32_t dst = dbase[dg] + wrun[wave][dg] + rank[r];
-        keys_out[dst] = key[r];
-        const uint32_t val = vals_in ? vals_in[j] : j;
-        vals_out[dst] = val;
-        if (lookup) lookup_out[dst] = lookup[val];
+        const uint32_t lp = lbase[dg] + wrun[wave][dg] + rank[r];
+        skey[lp] = key[r];
+        sval[lp] = val[r];
       }
     }
+  }
+  __syncthreads();
+  // element i of the reordered tile goes to the i-th slot of its digit's run: neighbours in
+  // the tile with the same digit are neighbours in the output
+  const uint32_t count = min(tile, n - min(n, blockIdx.x * tile));
+  for (uint32_t i = tid; i < count; i += SORT_THREADS) {
+    const uint32_t k = skey[i], v = sval[i];
+    const uint32_t dg = (k >> shift) & (RADIX - 1);
+    const uint32_t dst = gbase[dg] + (i - lbase[dg]);
+    keys_out[dst] = k;
+    vals_out[dst] = v;
+    if (lookup) lookup_out[dst] = lookup[v];
   }
 }
 
