@@ -203,9 +203,25 @@ __global__ __launch_bounds__(1024) void row_update_long_kernel(
     __syncthreads();
     const uint32_t ge = last_chunk;
     float4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (uint32_t gi = g2 + grp; gi <= ge; gi += NG) {
-      const float4 v = *((const float4*)(parts + ((size_t)gi * 2 + 0) * D) + c);
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    {
+      // four partial sums in flight per lane: the loop is bound by load latency otherwise
+      float4 a4[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) a4[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (uint32_t gi = g2 + grp; gi <= ge; gi += 4 * NG) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t gu = gi + u * NG;
+          if (gu <= ge) {
+            const float4 v = *((const float4*)(parts + ((size_t)gu * 2 + 0) * D) + c);
+            a4[u].x += v.x; a4[u].y += v.y; a4[u].z += v.z; a4[u].w += v.w;
+          }
+        }
+      }
+      acc.x = (a4[0].x + a4[1].x) + (a4[2].x + a4[3].x);
+      acc.y = (a4[0].y + a4[1].y) + (a4[2].y + a4[3].y);
+      acc.z = (a4[0].z + a4[1].z) + (a4[2].z + a4[3].z);
+      acc.w = (a4[0].w + a4[1].w) + (a4[2].w + a4[3].w);
     }
     red[threadIdx.x] = acc;
     __syncthreads();
@@ -253,10 +269,14 @@ void launch_row_update_finish(const uint32_t* sorted_keys, uint32_t n, const Row
   const int lpr = d / 4;
   const int64_t nchunks = ((int64_t)n + lpr - 1) / lpr;
   const int blocks = ceil_div(nchunks, 256 / lpr);
+  // one block per long run; their number is only known on the device, so the grid is sized
+  // for the worst case that matters (a run is long from about 30 chunks on) and capped
+  const int64_t lb = nchunks / 512 + 16;
+  const int long_blocks = (int)(lb > 512 ? 512 : lb);
 #define L(LPR)                                                                                    \
   hipLaunchKernelGGL((row_update_stitch_kernel<LPR>), dim3(blocks), dim3(256), 0, s, sorted_keys, \
                      n, sc.parts, sc.flags, h, G, lr, eps, sc.long_list, sc.long_count);          \
-  hipLaunchKernelGGL((row_update_long_kernel<LPR>), dim3(64), dim3(1024), 0, s, sorted_keys, n,   \
+  hipLaunchKernelGGL((row_update_long_kernel<LPR>), dim3(long_blocks), dim3(1024), 0, s, sorted_keys, n, \
                      sc.parts, sc.flags, h, G, lr, eps, sc.long_list, sc.long_count)
   switch (d) {
     case 16: L(4); break;

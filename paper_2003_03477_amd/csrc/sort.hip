@@ -41,10 +41,47 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_hist_kernel(
   hist[threadIdx.x] = 0;
   __syncthreads();
   const uint32_t base = blockIdx.x * (uint32_t)(SORT_THREADS * rounds);
-  for (int r = 0; r < rounds; ++r) {
-    const uint32_t j = base + r * SORT_THREADS + threadIdx.x;
-    if (j < n) atomicAdd(&hist[(keys[j] >> shift) & (RADIX - 1)], 1u);
+  // the order inside the tile does not matter here: 16-byte loads, all issued up front
+  const uint32_t end = min(n, base + (uint32_t)(SORT_THREADS * rounds));
+  const uint32_t cnt = end > base ? end - base : 0u;
+  const uint32_t nv = cnt / 4;
+  const uint4* kv = (const uint4*)(keys + base);
+  uint4 q[MAX_ROUNDS / 4];
+#pragma unroll
+  for (int i = 0; i < MAX_ROUNDS / 4; ++i) {
+    const uint32_t v = threadIdx.x + i * SORT_THREADS;
+    if (v < nv) q[i] = kv[v];
   }
+#pragma unroll
+  for (int i = 0; i < MAX_ROUNDS / 4; ++i) {
+    const uint32_t v = threadIdx.x + i * SORT_THREADS;
+    const bool valid = v < nv;
+    const uint32_t d0 = valid ? (q[i].x >> shift) & (RADIX - 1) : 0u;
+    const uint32_t d1 = valid ? (q[i].y >> shift) & (RADIX - 1) : 0u;
+    const uint32_t d2 = valid ? (q[i].z >> shift) & (RADIX - 1) : 0u;
+    const uint32_t d3 = valid ? (q[i].w >> shift) & (RADIX - 1) : 0u;
+    // in the later passes the input is sorted by the lower digits and whole waves share one
+    // digit: count those with a single LDS atomic instead of 256 colliding ones
+    const bool same4 = (d0 == d1) && (d1 == d2) && (d2 == d3);
+    const uint64_t vm = __ballot(valid);
+    if (vm == 0) continue;
+    const uint32_t lead = __builtin_amdgcn_readlane(d0, __builtin_ctzll(vm));
+    const bool uniform = __ballot(valid && !(same4 && d0 == lead)) == 0;
+    if (uniform) {
+      if ((threadIdx.x & 63) == (uint32_t)__builtin_ctzll(vm)) atomicAdd(&hist[lead], 4u * (uint32_t)__popcll(vm));
+    } else if (valid) {
+      if (same4) {
+        atomicAdd(&hist[d0], 4u);
+      } else {
+        atomicAdd(&hist[d0], 1u);
+        atomicAdd(&hist[d1], 1u);
+        atomicAdd(&hist[d2], 1u);
+        atomicAdd(&hist[d3], 1u);
+      }
+    }
+  }
+  for (uint32_t j = base + nv * 4 + threadIdx.x; j < end; j += SORT_THREADS)
+    atomicAdd(&hist[(keys[j] >> shift) & (RADIX - 1)], 1u);
   __syncthreads();
   block_hist[(size_t)threadIdx.x * nblocks + blockIdx.x] = hist[threadIdx.x];  // digit-major
 }
