@@ -204,7 +204,9 @@ int ss_get_counters(ss_ctx* ctx, uint64_t* steps_per_replica, uint64_t* rounds,
 
 /* Kernel timing with HIP events recorded on the launching stream.  ss_profile_arm takes a bit
  * mask (bit i = ss_kernel_id i); from then on every launch of an armed class is bracketed by
- * an event pair (at most 4096 brackets per class).  ss_profile_read synchronises the device,
+ * an event pair (at most 4096 brackets per class); ss_profile_sample(every) thins that to every
+ * `every`-th launch of each armed class (default 1), which keeps the cost of the brackets out
+ * of a timed run.  ss_profile_read synchronises the device,
  * returns the number of brackets of one class and their summed duration in ms, and disarms
  * that class.  Classes marked "one kernel" bracket exactly one kernel launch, so their average
  * is comparable with a profiler's per-kernel average; the others bracket a group of launches. */
@@ -221,6 +223,7 @@ typedef enum {
   SS_K_COUNT = 9
 } ss_kernel_id;
 int ss_profile_arm(ss_ctx* ctx, uint32_t kernel_mask);
+int ss_profile_sample(ss_ctx* ctx, int32_t every);
 int ss_profile_read(ss_ctx* ctx, int32_t kernel_id, int64_t* launches, double* total_ms);
 
 #ifdef __cplusplus

@@ -135,6 +135,8 @@ struct ss_ctx {
   // profiling
   std::mutex prof_mu;
   std::atomic<uint32_t> prof_mask{0};
+  std::atomic<uint32_t> prof_every{1};
+  std::atomic<uint32_t> prof_seen[SS_K_COUNT];
   struct ProfPool {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
     size_t used = 0;
@@ -142,6 +144,7 @@ struct ss_ctx {
 
   explicit ss_ctx(int k) : steps(k) {
     for (auto& a : steps) a.store(0);
+    for (auto& a : prof_seen) a.store(0);
   }
 };
 
@@ -587,6 +590,8 @@ struct ProfScope {
   ss_ctx* x; hipStream_t s; hipEvent_t stop = nullptr;
   ProfScope(ss_ctx* ctx, int id, hipStream_t st) : x(ctx), s(st) {
     if (!(x->prof_mask.load(std::memory_order_relaxed) & (1u << id))) return;
+    const uint32_t every = x->prof_every.load(std::memory_order_relaxed);
+    if (every > 1 && x->prof_seen[id].fetch_add(1, std::memory_order_relaxed) % every != 0) return;
     std::lock_guard<std::mutex> lk(x->prof_mu);
     auto& pool = x->prof[id];
     if (!(x->prof_mask.load() & (1u << id)) || pool.used >= pool.ev.size()) return;
@@ -1238,8 +1243,16 @@ int ss_profile_arm(ss_ctx* ctx, uint32_t kernel_mask) {
       }
     }
     pool.used = 0;
+    ctx->prof_seen[id] = 0;
   }
   ctx->prof_mask = kernel_mask & ~1u;
+  return SS_OK;
+}
+
+int ss_profile_sample(ss_ctx* ctx, int32_t every) {
+  if (!ctx) return SS_EINVAL;
+  if (every < 1) return fail(ctx, SS_EINVAL, "sampling interval must be >= 1");
+  ctx->prof_every = (uint32_t)every;
   return SS_OK;
 }
 
