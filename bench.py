@@ -49,6 +49,10 @@ def parse():
     ap.add_argument("--foreground", type=int, default=0, metavar="K",
                     help="foreground variant (FR-EASGD-k): every worker stream exchanges its "
                          "replica with the centre copy on ITS OWN stream every k of its steps")
+    ap.add_argument("--foreground-rule", default="easgd", choices=["easgd", "ma", "bmuf"],
+                    help="with --foreground: easgd = per-worker exchange (FR-EASGD-k); ma / bmuf "
+                         "= every k steps all worker streams meet, one S-MA / S-BMUF round runs "
+                         "after all of them and all of them wait for it (FR-MA / FR-BMUF)")
     ap.add_argument("--continuous-shadow", action="store_true",
                     help="loop shadow rounds back to back (ss_shadow_start) instead of pacing them")
     ap.add_argument("--workers-per-replica", type=int, default=4,
@@ -177,11 +181,38 @@ def main():
         r0_steps = [0]
         r0_lock = threading.Lock()
 
+        fg_collective = args.foreground and args.foreground_rule != "easgd"
+        meet = threading.Barrier(NS)
+        arrive = [torch.cuda.Event() for _ in range(NS)]
+        done = [torch.cuda.Event()]
+
+        def foreground_collective(w):
+            """All worker streams stop, one averaging round runs, all resume (the foreground
+            form of Algorithms 3 and 4): stream order is enforced with events, host threads
+            only meet to enqueue them."""
+            arrive[w].record(streams[w])
+            meet.wait()
+            if w == 0:
+                for e in arrive:
+                    shadow.wait_event(e)
+                mu = wl.mu if args.foreground_rule == "bmuf" else 0.0
+                gpu.ss_shadow_sync(args.foreground_rule, wl.alpha, wl.eta, mu, shadow)
+                done[0] = torch.cuda.Event()
+                done[0].record(shadow)
+            meet.wait()
+            streams[w].wait_event(done[0])
+
         def worker(w):
             for j, s in enumerate(range(first_step + w, first_step + total_steps, NS)):
                 one(s)
                 if args.foreground and (j + 1) % args.foreground == 0:
-                    gpu.ss_easgd_exchange(w % K, wl.alpha, streams[w])
+                    if fg_collective:
+                        # every worker must come to every meeting: none after the step count
+                        # that all workers reach
+                        if j + 1 <= total_steps // NS:
+                            foreground_collective(w)
+                    else:
+                        gpu.ss_easgd_exchange(w % K, wl.alpha, streams[w])
                     continue
                 # one shadow round per sync_gap iterations of replica 0 (all its workers)
                 if w % K == 0 and not args.no_shadow and not args.continuous_shadow \
@@ -283,7 +314,10 @@ def main():
     if args.continuous_shadow and not args.no_shadow:
         gpu.ss_shadow_stop()
     rounds = rounds1 - rounds0
-    shadow_txt = (f"FOREGROUND EASGD alpha={wl.alpha}: every worker stream exchanges with the "
+    shadow_txt = (f"FOREGROUND {args.foreground_rule.upper()} alpha={wl.alpha}: all worker "
+                  f"streams stop for one averaging round every {args.foreground} of their steps"
+                  if args.foreground and args.foreground_rule != "easgd" else
+                  f"FOREGROUND EASGD alpha={wl.alpha}: every worker stream exchanges with the "
                   f"centre copy on its own stream every {args.foreground} of its steps"
                   if args.foreground else
                   "no shadow sync" if args.no_shadow else
