@@ -20,6 +20,7 @@ namespace {
 
 constexpr int MAX_LAYERS = 16;
 constexpr size_t ALIGN = 256;
+constexpr int WG_MAX_SLICES = 8;  // batch slices of a weight-gradient GEMM (wide-layer path)
 
 struct Layer {
   int in, out;
@@ -53,6 +54,7 @@ struct Slot {
   // wide-layer path: bf16 snapshot of the weights in both orientations, bf16 dense input
   uint16_t* wb;
   uint16_t* xb;                    // [B][p64(num_dense)]
+  float* wg_part;                  // batch slices of the big layers' weight gradients
   // embedding backward
   uint32_t* keys;                  // [max_ids]
   int32_t* bag_of_pos;             // [max_ids]
@@ -106,7 +108,9 @@ struct ss_ctx {
   std::vector<int> pin, pout;      // per layer: row pitches of bf16 matrices with in / out columns
   std::vector<int64_t> wb_off, wbt_off;  // per layer: offsets of W and W^T inside Slot::wb
   std::vector<int> wb_tile_base;
-  std::vector<char> wgrad_grouped;  // per layer: weight gradient through the grouped 32x32-tile kernel
+  std::vector<char> wgrad_grouped;  // per layer: weight gradient through the grouped 64x64-tile kernel
+  std::vector<int64_t> wg_off, wg_stride;  // per layer: its slices inside Slot::wg_part (-1: none)
+  int64_t wg_elems = 0;
   int64_t wb_elems = 0;
   int wb_tiles = 0;
   std::vector<int4> wgrad_tiles;   // host copy of the tile table
@@ -254,7 +258,9 @@ static size_t layout(ss_ctx* x, void* base) {
     for (int l = 0; l < L; ++l) s.actT[l] = s.dYT[l] = nullptr;
     s.wsw = nullptr;
     s.wb = s.xb = nullptr;
+    s.wg_part = nullptr;
     if (x->wide) {
+      s.wg_part = cv.take<float>((size_t)x->wg_elems);
       s.wb = cv.take<uint16_t>((size_t)x->wb_elems);
       s.xb = cv.take<uint16_t>((size_t)B * x->pin[0]);
     }
@@ -385,9 +391,15 @@ static ss_ctx* make_ctx(const ss_config* c) {
         // with one GEMM; their weight gradients share one launch of the grouped kernel
         const bool small = ceil_div(ly.out, 128) * ceil_div(ly.in, 128) < 16;
         x->wgrad_grouped.push_back(small ? 1 : 0);
+        // the other layers split the batch into up to WG_MAX_SLICES slices, each stored to its
+        // own copy and summed by one reduction launch at the end of the backward pass
+        const int64_t stride = ((int64_t)ly.out * ly.in + 3) / 4 * 4;
+        x->wg_off.push_back(small ? -1 : x->wg_elems);
+        x->wg_stride.push_back(stride);
+        if (!small) x->wg_elems += stride * WG_MAX_SLICES;
         if (small)
-          for (int n0 = 0; n0 < ly.out; n0 += 32)
-            for (int k0 = 0; k0 < ly.in; k0 += 32)
+          for (int n0 = 0; n0 < ly.out; n0 += 64)
+            for (int k0 = 0; k0 < ly.in; k0 += 64)
               x->wgrad_tiles.push_back(make_int4((int)l, n0, k0, 0));
       }
     }
@@ -401,8 +413,8 @@ static ss_ctx* make_ctx(const ss_config* c) {
       }
       // weight-gradient tiles of every layer except the one-unit output layer
       for (int l = 0; l < nb + nh; ++l)
-        for (int n0 = 0; n0 < x->layers[l].out; n0 += 32)
-          for (int k0 = 0; k0 < x->layers[l].in; k0 += 32)
+        for (int n0 = 0; n0 < x->layers[l].out; n0 += 64)
+          for (int k0 = 0; k0 < x->layers[l].in; k0 += 64)
             x->wgrad_tiles.push_back(make_int4(l, n0, k0, 0));
     }
   }
@@ -802,6 +814,8 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
 static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipStream_t st) {
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
   const int Bp = (B + 63) / 64 * 64;
+  ReduceArgs red{};
+  int red_blocks = 0;
   // weight gradient of layer l (and its bias gradient), then the gradient w.r.t. its input
   auto layer_bwd = [&](int l, const uint16_t* dcur, int ldd, int& pp) -> const uint16_t* {
     const Layer& ly = x->layers[l];
@@ -813,12 +827,21 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
     g.C_f32 = s.grads + ly.w_off; g.ldc32 = ly.in; g.epi = EPI_NONE;
     g.row_sum = s.grads + ly.b_off;
     const int tiles = ceil_div(ly.out, 128) * ceil_div(ly.in, 128);
-    // batch slices are added with fp32 atomics, whose cost grows with the number of slices
-    // that meet on one element: at most 8 slices, each at least 512 samples long
-    int split = ceil_div(256, tiles);
-    if (split > 8) split = 8;
+    // enough batch slices for two blocks per CU, each at least 512 samples long; a slice is
+    // stored to its own copy (fp32 atomics from 512 blocks onto one matrix run at ~1.2 TB/s)
+    int split = ceil_div(512, tiles);
+    if (split > WG_MAX_SLICES) split = WG_MAX_SLICES;
     if (split > Bp / 512) split = Bp / 512;
-    g.split_k = split < 1 ? 1 : split;
+    if (split < 1) split = 1;
+    g.split_k = split;
+    if (split > 1) {
+      g.C_f32 = s.wg_part + x->wg_off[l];
+      g.split_stride = x->wg_stride[l];
+      ReduceSegment& sg = red.seg[red.n_seg++];
+      sg.part = g.C_f32; sg.out = s.grads + ly.w_off; sg.n = (int64_t)ly.out * ly.in;
+      sg.stride = g.split_stride; sg.slices = split; sg.block_base = red_blocks;
+      red_blocks += ceil_div(sg.n, 1024);
+    }
     launch_gemm_nt(g, st);
     }
     if (l == 0) return nullptr;
@@ -866,6 +889,7 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
       dcur = layer_bwd(l, dcur, ldd, pp);
       if (l > 0) ldd = x->pout[l - 1];
     }
+    launch_reduce_slices(red, red_blocks, st);
     if (!x->wgrad_tiles.empty()) {
       WgradArgs g{};
       for (int l = 0; l < L - 1; ++l) {

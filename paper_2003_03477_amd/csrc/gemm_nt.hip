@@ -49,6 +49,7 @@ struct Dev {
   const uint16_t* maskT; int ldmaskT;   // [N][ldmaskT]: the same gate for CT
   float* row_sum;                   // [M] (+)= sum_k A(m,k), or null
   int tiles_m, tiles_n, split, k_per_split;
+  long long split_stride;           // > 0: slice z of a split reduction stores to C32 + z * stride
 };
 
 __device__ __forceinline__ uint4 gate8(uint4 x, uint4 m) {
@@ -221,8 +222,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           if (gm >= g.M) continue;
           float v = acc[i][j][e] + bv;
           if (g.epi & EPI_RELU) v = fmaxf(v, 0.f);
-          if (g.split > 1) atomicAdd(g.C32 + (size_t)gm * g.ldc32 + gn, v);
-          else g.C32[(size_t)gm * g.ldc32 + gn] = v;
+          if (g.split > 1 && g.split_stride == 0) atomicAdd(g.C32 + (size_t)gm * g.ldc32 + gn, v);
+          else g.C32[(size_t)blockIdx.y * g.split_stride + (size_t)gm * g.ldc32 + gn] = v;
         }
       }
     return;
@@ -350,7 +351,40 @@ __global__ __launch_bounds__(256) void weights_bf16_kernel(WeightsBf16Args a) {
   }
 }
 
+__global__ __launch_bounds__(256) void reduce_slices_kernel(ReduceArgs a) {
+  int k = 0;
+  while (k + 1 < a.n_seg && (int)blockIdx.x >= a.seg[k + 1].block_base) ++k;
+  const ReduceSegment sg = a.seg[k];
+  const int64_t base = (int64_t)(blockIdx.x - sg.block_base) * 1024;  // 1024 elements per block
+  const bool vec = ((sg.n & 3) == 0) && ((((uintptr_t)sg.out) & 15) == 0);
+  if (vec) {
+    const int64_t i = base + threadIdx.x * 4;
+    if (i >= sg.n) return;
+    float4 acc = *(const float4*)(sg.part + i);
+    for (int z = 1; z < sg.slices; ++z) {
+      const float4 v = *(const float4*)(sg.part + (int64_t)z * sg.stride + i);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    *(float4*)(sg.out + i) = acc;
+  } else {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = base + threadIdx.x + 256 * u;
+      if (i < sg.n) {
+        float acc = sg.part[i];
+        for (int z = 1; z < sg.slices; ++z) acc += sg.part[(int64_t)z * sg.stride + i];
+        sg.out[i] = acc;
+      }
+    }
+  }
+}
+
 }  // namespace
+
+void launch_reduce_slices(const ReduceArgs& a, int total_blocks, hipStream_t s) {
+  if (total_blocks > 0)
+    hipLaunchKernelGGL(reduce_slices_kernel, dim3(total_blocks), dim3(256), 0, s, a);
+}
 
 void launch_gemm_nt(const GemmNtArgs& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return;
@@ -365,6 +399,7 @@ void launch_gemm_nt(const GemmNtArgs& a, hipStream_t s) {
   int kps = ceil_div(ceil_div(a.K, split), TK) * TK;
   split = ceil_div(a.K, kps);
   g.split = split; g.k_per_split = kps;
+  g.split_stride = split > 1 ? a.split_stride : 0;
   const dim3 grid(g.tiles_m * g.tiles_n, split);
   if (a.row_sum) {
     if (!attr_done[1]) {

@@ -521,14 +521,17 @@ __global__ __launch_bounds__(NT) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Grouped weight gradients.  One wave = one 32x32 tile of one layer's dW over one slice of
-// the batch; blockIdx.x walks the tile table, the 4 waves of a block and blockIdx.y split the
-// batch.  Both fragments are 16-byte global loads (the batch is the contiguous dimension of
-// the transposed operands).  Tiles with k0 == 0 also produce the bias gradient through one
-// extra MFMA against a fragment of ones.
-__global__ __launch_bounds__(256) void mlp_wgrad_grouped_kernel(WgradArgs g) {
-  __shared__ float red[3][32 * 33];
-  __shared__ float redb[3][32];
+// Grouped weight gradients.  One block = one 64x64 tile of one layer's dW over one slice of
+// the batch (blockIdx.x walks the tile table, blockIdx.y the slices); its four waves split the
+// slice's samples, each keeping the whole 64x64 tile (2x2 MFMA tiles) in registers, and fold
+// their sums through LDS.  Both fragments are 16-byte global loads (the batch is the
+// contiguous dimension of the transposed operands).  Tiles with k0 == 0 also produce the bias
+// gradient through one extra MFMA per row block against a fragment of ones.
+constexpr int WG_T = 64;            // tile edge
+constexpr int WG_LD = WG_T + 1;     // LDS row pitch (floats)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void mlp_wgrad_grouped_kernel(WgradArgs g) {
+  extern __shared__ float wg_red[];  // [4][64][65] tile sums + [4][64] bias sums
+  float* const redb = wg_red + 4 * WG_T * WG_LD;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int4 t = g.tiles[blockIdx.x];
   const WgradLayer L = g.L[t.x];
@@ -538,14 +541,23 @@ __global__ __launch_bounds__(256) void mlp_wgrad_grouped_kernel(WgradArgs g) {
   const int bbeg = (blockIdx.y * 4 + wave) * per;
   const int bend = min(g.B, bbeg + per);
   const int frow = lane & 31, fk = (lane >> 5) * 8;
-  const int n = n0 + frow, k = k0 + frow;
-  const uint16_t* ap = L.dYT + (size_t)n * g.ldT;
-  const uint16_t* bp = L.XT + (size_t)k * g.ldT;
-  const bool aok = n < L.out, bok = k < L.in;
-  const bool do_bias = (k0 == 0);
-  f32x16 acc, accb;
+  const uint16_t* ap[2];
+  const uint16_t* bp[2];
+  bool aok[2], bok[2];
 #pragma unroll
-  for (int e = 0; e < 16; ++e) { acc[e] = 0.f; accb[e] = 0.f; }
+  for (int i = 0; i < 2; ++i) {
+    const int n = n0 + i * 32 + frow, k = k0 + i * 32 + frow;
+    aok[i] = n < L.out; bok[i] = k < L.in;
+    ap[i] = L.dYT + (size_t)(aok[i] ? n : 0) * g.ldT;
+    bp[i] = L.XT + (size_t)(bok[i] ? k : 0) * g.ldT;
+  }
+  const bool do_bias = (k0 == 0);
+  f32x16 acc[2][2], accb[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { accb[i][e] = 0.f; acc[i][0][e] = 0.f; acc[i][1][e] = 0.f; }
+  }
   bf16x8 ones;
 #pragma unroll
   for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
@@ -566,52 +578,68 @@ __global__ __launch_bounds__(256) void mlp_wgrad_grouped_kernel(WgradArgs g) {
     return f;
   };
   constexpr int WD = 4;  // batch steps of 16 samples in flight
-  Frag a[WD], b[WD];
+  Frag a[WD][2], b[WD][2];
 #pragma unroll
-  for (int d = 0; d < WD; ++d) {
-    a[d] = ld(ap, aok, bbeg + d * 16 + fk);
-    b[d] = ld(bp, bok, bbeg + d * 16 + fk);
-  }
+  for (int d = 0; d < WD; ++d)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      a[d][i] = ld(ap[i], aok[i], bbeg + d * 16 + fk);
+      b[d][i] = ld(bp[i], bok[i], bbeg + d * 16 + fk);
+    }
   for (int bb = bbeg; bb < bend; bb += 16 * WD) {
 #pragma unroll
     for (int d = 0; d < WD; ++d) {
       if (bb + d * 16 < bend) {
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[d].v, b[d].v, acc, 0, 0, 0);
-        if (do_bias) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[d].v, ones, accb, 0, 0, 0);
-        a[d] = ld(ap, aok, bb + (d + WD) * 16 + fk);
-        b[d] = ld(bp, bok, bb + (d + WD) * 16 + fk);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[d][i].v, b[d][j].v, acc[i][j], 0, 0, 0);
+          if (do_bias) accb[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[d][i].v, ones, accb[i], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          a[d][i] = ld(ap[i], aok[i], bb + (d + WD) * 16 + fk);
+          b[d][i] = ld(bp[i], bok[i], bb + (d + WD) * 16 + fk);
+        }
       }
     }
   }
-  // fold the four waves' batch slices through LDS, then one atomic (or store) per element
+  // every wave lays its tile down in LDS; then all 256 threads add the four copies, 16
+  // outputs each, and store (or add atomically when the batch is split over blocks)
   const int col_in = lane & 31, row_in = (lane >> 5) * 4;
-  if (wave > 0) {
+  float* mine = wg_red + wave * WG_T * WG_LD;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      const int rr = (e >> 2) * 8 + row_in + (e & 3);
-      red[wave - 1][rr * 33 + col_in] = acc[e];
-      if (do_bias && col_in == 0) redb[wave - 1][rr] = accb[e];
+      const int rr = i * 32 + (e >> 2) * 8 + row_in + (e & 3);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) mine[rr * WG_LD + j * 32 + col_in] = acc[i][j][e];
+      if (do_bias && col_in == 0) redb[wave * WG_T + rr] = accb[i][e];
     }
   }
   __syncthreads();
-  if (wave == 0) {
-    const int kk = k0 + col_in;
+  const bool atomic = gridDim.y > 1;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int rr = (e >> 2) * 8 + row_in + (e & 3);
-      const int nn = n0 + rr;
-      float v = acc[e] + red[0][rr * 33 + col_in] + red[1][rr * 33 + col_in] + red[2][rr * 33 + col_in];
-      if (nn < L.out) {
-        if (kk < L.in) {
-          if (gridDim.y > 1) atomicAdd(L.gW + (size_t)nn * L.in + kk, v);
-          else L.gW[(size_t)nn * L.in + kk] = v;
-        }
-        if (do_bias && col_in == 0) {
-          const float vb = accb[e] + redb[0][rr] + redb[1][rr] + redb[2][rr];
-          if (gridDim.y > 1) atomicAdd(L.gb + nn, vb);
-          else L.gb[nn] = vb;
-        }
-      }
+  for (int u = 0; u < 16; ++u) {
+    const int idx = threadIdx.x + 256 * u;   // consecutive threads: consecutive columns
+    const int rr = idx >> 6, cc = idx & 63;
+    const int nn = n0 + rr, kk = k0 + cc;
+    const float v = (wg_red[rr * WG_LD + cc] + wg_red[WG_T * WG_LD + rr * WG_LD + cc]) +
+                    (wg_red[2 * WG_T * WG_LD + rr * WG_LD + cc] + wg_red[3 * WG_T * WG_LD + rr * WG_LD + cc]);
+    if (nn < L.out && kk < L.in) {
+      if (atomic) atomicAdd(L.gW + (size_t)nn * L.in + kk, v);
+      else L.gW[(size_t)nn * L.in + kk] = v;
+    }
+  }
+  if (do_bias && threadIdx.x < WG_T) {
+    const int nn = n0 + threadIdx.x;
+    const float vb = (redb[threadIdx.x] + redb[WG_T + threadIdx.x]) +
+                     (redb[2 * WG_T + threadIdx.x] + redb[3 * WG_T + threadIdx.x]);
+    if (nn < L.out) {
+      if (atomic) atomicAdd(L.gb + nn, vb);
+      else L.gb[nn] = vb;
     }
   }
 }
@@ -647,11 +675,11 @@ void launch_mlp_prep(const PrepArgs& a, hipStream_t s) {
 }
 
 void launch_mlp_wgrad_grouped(const WgradArgs& a, int n_tiles, hipStream_t s) {
-  // batch slices of about 256 samples per wave; enough blocks to cover the chip
-  int gy = a.B / (4 * 256);
-  if (gy < 1) gy = 1;
+  // batch slices of 64 to 256 samples per wave; about two blocks per CU
+  int gy = 1;
   while (gy < 8 && n_tiles * gy < 512 && a.B / (4 * gy * 2) >= 64) gy *= 2;
-  hipLaunchKernelGGL(mlp_wgrad_grouped_kernel, dim3(n_tiles, gy), dim3(256), 0, s, a);
+  const size_t lds = (size_t)(4 * WG_T * WG_LD + 4 * WG_T) * sizeof(float);
+  hipLaunchKernelGGL(mlp_wgrad_grouped_kernel, dim3(n_tiles, gy), dim3(256), lds, s, a);
 }
 
 }  // namespace ss

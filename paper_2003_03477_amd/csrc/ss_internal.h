@@ -119,8 +119,9 @@ void launch_last_layer_bwd(const uint16_t* X, int ldx, const float* w, const flo
 // C[M,N] = A[M,K] B[N,K]^T, bf16 operands with the reduction dimension contiguous, K a multiple
 // of 64 (zero padded in at least one operand, finite in the other), 16-byte aligned rows.
 // Outputs: bf16 row-major C and / or transposed CT (both through EPI_BIAS / EPI_RELU, then
-// gated by mask / maskT > 0 under EPI_MASK), or fp32 C_f32 (stored; atomically added when
-// split_k > 1).  row_sum (+)= row sums of A (first column of tiles only).
+// gated by mask / maskT > 0 under EPI_MASK), or fp32 C_f32 (stored; with split_k > 1 either
+// atomically added, or -- split_stride > 0 -- slice z stored to C_f32 + z * split_stride for a
+// later launch_reduce_slices).  row_sum (+)= row sums of A (first column of tiles only).
 struct GemmNtArgs {
   const uint16_t* A; int lda;
   const uint16_t* B; int ldb;
@@ -133,8 +134,14 @@ struct GemmNtArgs {
   const uint16_t* maskT; int ldmaskT;
   float* row_sum;
   int split_k;
+  int64_t split_stride;
 };
 void launch_gemm_nt(const GemmNtArgs& a, hipStream_t s);
+// out[i] = sum over the slices of part[z * stride + i], for up to SS_NT_MAX_LAYERS segments in
+// one launch (n and stride multiples of 4, 16-byte aligned pointers)
+struct ReduceSegment { const float* part; float* out; int64_t n, stride; int slices; int block_base; };
+struct ReduceArgs { ReduceSegment seg[16]; int n_seg; };
+void launch_reduce_slices(const ReduceArgs& a, int total_blocks, hipStream_t s);
 // in [M][ld_in] (fp32 or bf16, N columns) -> out [M][ld_out] bf16 (optional, zero padded) and
 // outT [N][ldt] bf16 (optional, zero padded to the end of the last 64-sample tile)
 void launch_cast_transpose(const void* in, int in_is_f32, int ld_in, int M, int N, uint16_t* out,
@@ -217,7 +224,7 @@ struct WgradLayer {
 };
 struct WgradArgs {
   WgradLayer L[2 * SS_FUSED_MAX_LAYERS];
-  const int4* tiles;    // device: (layer, n0, k0, 0) per 32x32 tile
+  const int4* tiles;    // device: (layer, n0, k0, 0) per 64x64 tile
   int B, ldT;
 };
 size_t fused_lds_bytes(const int* widths, int n_widths, size_t* elems0);
