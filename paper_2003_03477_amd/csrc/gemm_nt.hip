@@ -143,23 +143,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   const int frow = lane & 31, fk = (lane >> 5) * 8;
   auto compute = [&](const uint16_t* as, const uint16_t* bs) {
+    // fragments of reduction sub-step kk+1 are requested from LDS before the MFMAs of kk
+    bf16x8 a[2][2], b[2][2];
+    const uint16_t* ar = as + (wm * 64 + frow) * LDK + fk;
+    const uint16_t* br = bs + (wn * 64 + frow) * LDK + fk;
 #pragma unroll
-    for (int kk = 0; kk < TK; kk += 16) {
-      bf16x8 a[2], b[2];
+    for (int i = 0; i < 2; ++i) {
+      a[0][i] = *(const bf16x8*)(ar + i * 32 * LDK);
+      b[0][i] = *(const bf16x8*)(br + i * 32 * LDK);
+    }
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = *(const bf16x8*)(as + (wm * 64 + i * 32 + frow) * LDK + kk + fk);
+    for (int q = 0; q < TK / 16; ++q) {
+      const int cur = q & 1, nxt = cur ^ 1;
+      if (q + 1 < TK / 16) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = *(const bf16x8*)(bs + (wn * 64 + j * 32 + frow) * LDK + kk + fk);
+        for (int i = 0; i < 2; ++i) {
+          a[nxt][i] = *(const bf16x8*)(ar + i * 32 * LDK + (q + 1) * 16);
+          b[nxt][i] = *(const bf16x8*)(br + i * 32 * LDK + (q + 1) * 16);
+        }
+      }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
       if (ROWSUM) {
         if (do_rs) {
 #pragma unroll
           for (int i = 0; i < 2; ++i)
-            accr[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], ones, accr[i], 0, 0, 0);
+            accr[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], ones, accr[i], 0, 0, 0);
         }
       }
     }
