@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libshadowsync.so")
 SOURCES = ["api.hip", "init.hip", "embedding.hip", "row_update.hip", "sort.hip", "interaction.hip",
            "mlp_fp32.hip", "mlp_bf16.hip", "mlp_fused.hip", "gemm_nt.hip", "sync.hip"]
-FLAGS = (["-DSS_FUSED_TIMING"] if os.environ.get("SS_FUSED_TIMING") else []) + ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result"]
 
 

@@ -837,12 +837,14 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
     if (split > 1) {
       g.C_f32 = s.wg_part + x->wg_off[l];
       g.split_stride = x->wg_stride[l];
+    }
+    const int slices = launch_gemm_nt(g, st);
+    if (split > 1) {  // (a single slice is stored to the slice area as well)
       ReduceSegment& sg = red.seg[red.n_seg++];
       sg.part = g.C_f32; sg.out = s.grads + ly.w_off; sg.n = (int64_t)ly.out * ly.in;
-      sg.stride = g.split_stride; sg.slices = split; sg.block_base = red_blocks;
+      sg.stride = g.split_stride; sg.slices = slices; sg.block_base = red_blocks;
       red_blocks += ceil_div(sg.n, 1024);
     }
-    launch_gemm_nt(g, st);
     }
     if (l == 0) return nullptr;
     GemmNtArgs a{};

@@ -15,6 +15,8 @@
 // Operand rows beyond M / N are clamped to the last valid row on load and discarded on store;
 // the reduction length must be a multiple of 64 with zero padding in at least one operand
 // (and finite values in the other), so the main loop has no edge handling at all.
+#include <mutex>
+
 #include "ss_internal.h"
 
 namespace ss {
@@ -398,9 +400,16 @@ void launch_reduce_slices(const ReduceArgs& a, int total_blocks, hipStream_t s) 
     hipLaunchKernelGGL(reduce_slices_kernel, dim3(total_blocks), dim3(256), 0, s, a);
 }
 
-void launch_gemm_nt(const GemmNtArgs& a, hipStream_t s) {
-  if (a.M <= 0 || a.N <= 0 || a.K <= 0) return;
-  static bool attr_done[2] = {false, false};
+int launch_gemm_nt(const GemmNtArgs& a, hipStream_t s) {
+  if (a.M <= 0 || a.N <= 0 || a.K <= 0) return 0;
+  // the kernels use more than 64 KB of dynamic LDS: raise their limit once per process
+  static std::once_flag attr_once;
+  std::call_once(attr_once, [] {
+    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<true>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)NT_LDS_BYTES);
+    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<false>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)NT_LDS_BYTES);
+  });
   Dev g;
   g.A = a.A; g.lda = a.lda; g.B = a.B; g.ldb = a.ldb; g.M = a.M; g.N = a.N; g.K = a.K;
   g.C = a.C; g.ldc = a.ldc; g.CT = a.CT; g.ldct = a.ldct; g.C32 = a.C_f32; g.ldc32 = a.ldc32;
@@ -413,21 +422,11 @@ void launch_gemm_nt(const GemmNtArgs& a, hipStream_t s) {
   g.split = split; g.k_per_split = kps;
   g.split_stride = split > 1 ? a.split_stride : 0;
   const dim3 grid(g.tiles_m * g.tiles_n, split);
-  if (a.row_sum) {
-    if (!attr_done[1]) {
-      (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<true>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)NT_LDS_BYTES);
-      attr_done[1] = true;
-    }
+  if (a.row_sum)
     hipLaunchKernelGGL(gemm_nt_kernel<true>, grid, dim3(256), NT_LDS_BYTES, s, g);
-  } else {
-    if (!attr_done[0]) {
-      (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<false>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)NT_LDS_BYTES);
-      attr_done[0] = true;
-    }
+  else
     hipLaunchKernelGGL(gemm_nt_kernel<false>, grid, dim3(256), NT_LDS_BYTES, s, g);
-  }
+  return split;
 }
 
 void launch_cast_transpose(const void* in, int in_is_f32, int ld_in, int M, int N, uint16_t* out,

@@ -146,15 +146,8 @@ __global__ __launch_bounds__(256) void mlp_prep_kernel(PrepArgs g) {
 
 // ------------------------------------------------------------------------------------------
 // Forward.
-#ifdef SS_FUSED_TIMING
-__device__ long long ss_fused_ts[64];
-#define TS(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) ss_fused_ts[(i) + (g.has_tail ? 32 : 0)] = wall_clock64(); } while (0)
-#else
-#define TS(i)
-#endif
 __global__ __launch_bounds__(NT) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  TS(0);
   uint16_t* buf[2] = {smem, smem + g.lds_elems0};
   __shared__ float wl_s[512];
   __shared__ float wloss[16];
@@ -174,7 +167,6 @@ __global__ __launch_bounds__(NT) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
   }
   float wl_r = 0.f;
   if (g.has_tail && tid < g.L[g.n_layers - 1].out) wl_r = g.w_last[tid];
-  TS(1);
   // ---- stage the input tile (bf16, zero padded columns and rows), then write its transposed
   //      copy for the weight-gradient kernel from LDS
   {
@@ -210,7 +202,6 @@ __global__ __launch_bounds__(NT) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
     }
     if (g.has_tail && tid < 512) wl_s[tid] = b2f(f2b(wl_r));
     __syncthreads();
-    TS(2);
     if (g.xT) {  // 8 consecutive samples of one input unit per thread: one 16-byte store
       for (int i = tid; i < g.in0 * (TB / 8); i += NT) {
         const int k = i / (TB / 8), r = (i - k * (TB / 8)) * 8, b = b0 + r;
@@ -239,9 +230,7 @@ __global__ __launch_bounds__(NT) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
     f32x16 acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-    TS(3 + 3 * l);
     if (active) run_gemm_n(L.depth_f, acc, q, A, lda, Kp / 16, wave, lane, L.Wf);
-    TS(4 + 3 * l);
     if (!last) {  // next layer's first fragments and bias fly during this layer's epilogue
       const FusedLayer N = g.L[l + 1];
       bnext = 0.f;
@@ -293,7 +282,6 @@ __global__ __launch_bounds__(NT) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
     }
     bcur = bnext;
     __syncthreads();
-    TS(5 + 3 * l);
   }
   // ---- top stack only: one-unit output layer, loss and dL/dlogit (32 threads per sample)
   if (g.has_tail) {
@@ -325,7 +313,6 @@ __global__ __launch_bounds__(NT) void mlp_fused_fwd_kernel(FusedFwdArgs g) {
       atomicAdd(g.loss, tot * invB);
     }
   }
-  TS(20);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -656,12 +643,6 @@ size_t fused_lds_bytes(const int* widths, int n_widths, size_t* elems0) {
   return (m[0] + m[1]) * sizeof(uint16_t);
 }
 
-#ifdef SS_FUSED_TIMING
-extern "C" void ss_debug_fused_ts(long long* out) {
-  (void)hipDeviceSynchronize();
-  (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(ss_fused_ts), sizeof(long long) * 64);
-}
-#endif
 void launch_mlp_fused_fwd(const FusedFwdArgs& a, size_t lds_bytes, hipStream_t s) {
   hipLaunchKernelGGL(mlp_fused_fwd_kernel, dim3(ceil_div(a.B, TB)), dim3(NT), lds_bytes, s, a);
 }

@@ -136,7 +136,8 @@ struct GemmNtArgs {
   int split_k;
   int64_t split_stride;
 };
-void launch_gemm_nt(const GemmNtArgs& a, hipStream_t s);
+// Returns the number of reduction slices actually launched (<= split_k).
+int launch_gemm_nt(const GemmNtArgs& a, hipStream_t s);
 // out[i] = sum over the slices of part[z * stride + i], for up to SS_NT_MAX_LAYERS segments in
 // one launch (n and stride multiples of 4, 16-byte aligned pointers)
 struct ReduceSegment { const float* part; float* out; int64_t n, stride; int slices; int block_base; };

@@ -294,3 +294,28 @@ def test_single_trainer_easgd_exchange_and_eval_ne():
     ne_gpu = binding.normalized_entropy(lg, ctr)
     ent = -(ctr * np.log(ctr) + (1 - ctr) * np.log(1 - ctr))
     assert abs(ne_gpu - lo / ent) < 1e-5
+
+
+def test_profile_brackets_and_sampling():
+    """Event brackets: every launch of an armed class by default, every n-th with sampling."""
+    import torch
+    wl = synth.tiny()
+    gen = synth.BatchGenerator(wl)
+    b = gen.batch(0)
+    gpu = binding.from_workload(wl, num_worker_slots=1, max_ids=int(b.offsets[-1]) + 64)
+    gpu.ss_init_tables_hash()
+    gpu.ss_init_dense(synth.dense_w0(wl))
+    db = binding.upload_batch(b)
+    for every, want in ((1, 16), (4, 4), (5, 4)):
+        gpu.ss_profile_sample(every)
+        gpu.ss_profile_arm(binding.K_GATHER, binding.K_ROW_UPDATE)
+        for _ in range(16):
+            gpu.ss_train_step(0, 0, db, None, None)
+        torch.cuda.synchronize()
+        n, ms = gpu.ss_profile_read(binding.K_GATHER)
+        assert n == want and ms > 0.0
+        n2, ms2 = gpu.ss_profile_read(binding.K_ROW_UPDATE)
+        assert n2 == want and ms2 > 0.0
+    with pytest.raises(binding.ShadowSyncError):
+        gpu.ss_profile_sample(0)
+    gpu.close()
