@@ -108,6 +108,21 @@ def test_fp32_other_rules_and_ragged_shapes(algo, alpha, eta, mu, gap):
     assert len(cp.touched[0]) > 500
 
 
+@pytest.mark.parametrize("d", [32, 128])
+def test_fp32_other_embedding_widths(d):
+    """d = 32 and d = 128: the other lane groupings of the gather, interaction and row-update
+    kernels (8 and 32 lanes per row), with hot rows (Zipf 1.3) and long bags."""
+    T = 5
+    wl = synth.tiny().scaled(batch=150, rows=(4000, 7, 900, 25000, 64), emb_dim=d, bag_lambda=9.0,
+                             bot_dims=(13, 24, d), top_dims=(d + T * (T + 1) // 2, 40, 1),
+                             num_replicas=2, algo="ma", alpha=0.5, sync_gap=2, zipf_s=1.3)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(8)]
+    gpu, orc = H.make_pair(wl, batches, h0=synth.full_tables_h0(wl))
+    H.run_lockstep(gpu, orc, batches, wl.sync_gap, wl.algo, wl.alpha)
+    H.compare_state(gpu, orc, H.FP32_RTOL, f"d={d}", wl.row_base)
+
+
 def test_empty_bags_single_sample_and_hot_row():
     """Edge cases: empty bags, batch of one, one row owning a very long segment."""
     wl = synth.tiny().scaled(batch=64, rows=(50, 1000), emb_dim=16, bot_dims=(13, 16),
