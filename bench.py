@@ -57,6 +57,8 @@ def parse():
                     help="loop shadow rounds back to back (ss_shadow_start) instead of pacing them")
     ap.add_argument("--workers-per-replica", type=int, default=4,
                     help="Hogwild worker streams per replica")
+    ap.add_argument("--replicas", type=int, default=0, metavar="K",
+                    help="number of dense replicas (default: the workload's)")
     ap.add_argument("--no-shadow", action="store_true", help="run without the shadow stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sync-isolation", action="store_true")
@@ -156,6 +158,8 @@ def main():
     from paper_2003_03477_amd import binding, synth
 
     wl = synth.WORKLOADS[args.workload]()
+    if args.replicas:
+        wl = wl.scaled(num_replicas=args.replicas)
     K = wl.num_replicas
     WPR = args.workers_per_replica
     NS = K * WPR                           # worker streams = worker slots
@@ -257,6 +261,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     steps1, rounds1, _ = gpu.ss_get_counters()
+    last_losses = losses.cpu().numpy().astype(float)   # mean log-loss of each stream's last batch
 
     kernels, roofline = {}, None
     if not args.no_kernel_events:
@@ -338,6 +343,7 @@ def main():
                                f"{wl.bag_lambda:g})+1, K={K} replicas x {WPR} worker stream(s), "
                                f"{shadow_txt}",
                    "shadow_rounds": int(rounds),
+                   "last_batch_logloss": float(last_losses.mean()),
                    "avg_sync_gap": (float((steps1 - steps0).mean()) / rounds) if rounds else None,
                    "host_threads": 1 if args.single_thread else NS},
         "roofline": roofline,

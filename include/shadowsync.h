@@ -171,7 +171,10 @@ int ss_shadow_start(ss_ctx* ctx, int32_t algo, float alpha, float eta, float mom
 int ss_shadow_stop(ss_ctx* ctx);
 
 /* Read-back (synchronises the device first).  which: 0..K-1 = w^(which), -1 = w^PS,
- * -2 = w^global, -3 = v.  n must equal P. */
+ * -2 = w^global, -3 = v, -4 = the mean of the K replicas, computed on the device at the time
+ * of the call (Section 4, "Experimental Setup": the model returned is the first trainer's
+ * copy, which = 0; the replica average is the alternative).  n must equal P.
+ * ss_write_dense accepts 0..K-1, -1, -2, -3. */
 int ss_read_dense(ss_ctx* ctx, int32_t which, float* host_out, int64_t n);
 int ss_write_dense(ss_ctx* ctx, int32_t which, const float* host_in, int64_t n);
 /* rows: host [n] row ids of `table`; host_rows_out [n, d] and host_adagrad_out [n] may

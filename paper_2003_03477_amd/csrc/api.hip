@@ -127,6 +127,7 @@ struct ss_ctx {
   float* w_ps;
   float* w_global;
   float* v;
+  float* w_mean;  // replica average, filled on request (ss_read_dense with which = -4)
   std::vector<Slot> slots;
   // state
   std::string err;
@@ -224,6 +225,7 @@ static size_t layout(ss_ctx* x, void* base) {
   x->w_ps = cv.take<float>(x->Pstride);
   x->w_global = cv.take<float>(x->Pstride);
   x->v = cv.take<float>(x->Pstride);
+  x->w_mean = cv.take<float>(x->Pstride);
   const int L = (int)x->layers.size();
   x->wgrad_tiles_dev = x->wgrad_tiles.empty() ? nullptr : cv.take<int4>(x->wgrad_tiles.size());
   const int sort_blocks = sort_max_blocks((uint32_t)n);
@@ -551,9 +553,13 @@ int ss_init_dense(ss_ctx* ctx, const float* host_w0) {
 
 int ss_read_dense(ss_ctx* ctx, int32_t which, float* host_out, int64_t n) {
   if (!ctx || !host_out) return SS_EINVAL;
-  float* p = dense_ptr(ctx, which);
+  float* p = (which == -4) ? ctx->w_mean : dense_ptr(ctx, which);
   if (!p || n != ctx->P) return fail(ctx, SS_EINVAL, "ss_read_dense: bad selector or length");
   HIP_TRY(ctx, hipDeviceSynchronize());
+  if (which == -4) {
+    launch_replica_mean(ctx->W, ctx->K, ctx->Pstride, ctx->P, ctx->w_mean, nullptr);
+    HIP_TRY(ctx, hipDeviceSynchronize());
+  }
   HIP_TRY(ctx, hipMemcpy(host_out, p, (size_t)n * sizeof(float), hipMemcpyDeviceToHost));
   return SS_OK;
 }

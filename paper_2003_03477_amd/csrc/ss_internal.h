@@ -237,5 +237,8 @@ void launch_mlp_wgrad_grouped(const WgradArgs& a, int n_tiles, hipStream_t s);
 int launch_sync_round(int algo, int K, int64_t P, int64_t stride, float* W, float* w_ps,
                       float* w_global, float* v, float alpha, float eta, float mu,
                       hipStream_t s);
+// out[0..P) = mean over the K replicas (P rounded up to 4 floats is read and written)
+void launch_replica_mean(const float* W, int K, int64_t stride, int64_t P, float* out,
+                         hipStream_t s);
 
 }  // namespace ss

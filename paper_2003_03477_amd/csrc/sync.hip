@@ -147,4 +147,28 @@ int launch_sync_round(int algo, int K, int64_t P, int64_t stride, float* W, floa
   return 0;
 }
 
+// Mean of the K replicas (the alternative output model of Section 4, "Experimental Setup":
+// the paper returns the first trainer's copy; the replica average is the other candidate),
+// summed in replica order like the averaging rounds.
+__global__ __launch_bounds__(256) void replica_mean_kernel(const float* __restrict__ W, int K,
+                                                           int64_t stride, int64_t n_vec,
+                                                           float* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_vec) return;
+  float4 acc = ((const float4*)W)[i];
+  for (int k = 1; k < K; ++k) {
+    const float4 v = ((const float4*)(W + (size_t)k * stride))[i];
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  const float inv = 1.0f / (float)K;
+  ((float4*)out)[i] = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+}
+
+void launch_replica_mean(const float* W, int K, int64_t stride, int64_t P, float* out,
+                         hipStream_t s) {
+  const int64_t n_vec = (P + 3) / 4;
+  hipLaunchKernelGGL(replica_mean_kernel, dim3(ceil_div(n_vec, 256)), dim3(256), 0, s, W, K, stride,
+                     n_vec, out);
+}
+
 }  // namespace ss

@@ -82,6 +82,7 @@ def compare_state(gpu, orc, rtol, name, row_base):
     K = orc.W.shape[0]
     for i in range(K):
         close(gpu.ss_read_dense(i), orc.W[i], rtol, f"{name}: replica {i}")
+    close(gpu.ss_read_dense(-4), orc.W.mean(axis=0), rtol, f"{name}: replica average")
     close(gpu.ss_read_dense(-1), orc.w_ps, rtol, f"{name}: w_ps")
     close(gpu.ss_read_dense(-2), orc.w_global, rtol, f"{name}: w_global")
     close(gpu.ss_read_dense(-3), orc.v, rtol, f"{name}: v", scale=max(1e-30, float(np.max(np.abs(orc.w_global)))))
