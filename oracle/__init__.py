@@ -31,6 +31,7 @@ from .dlrm import (  # noqa: F401
     dlrm_forward,
     dlrm_backward,
     embedding_bag_forward,
+    bag_lengths,
     embedding_row_gradients,
     interaction_backward,
     interaction_forward,

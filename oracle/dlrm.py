@@ -122,10 +122,12 @@ def mlp_backward(acts, layers, d_out, relu_last: bool, q=_identity):
 
 
 # --------------------------------------------------------------------------- embedding
-def embedding_bag_forward(h, row_base, indices, offsets, B: int):
-    """Sum pooling (Section 3.1, pooling is done where the table lives):
+def embedding_bag_forward(h, row_base, indices, offsets, B: int, pooling: str = "sum"):
+    """Pooling (Section 3.1, done where the table lives).  Sum:
     e[b, t, :] = sum over j in bag(t, b), in j order, of h[row_base[t] + indices[j], :].
-    A row that occurs twice in a bag is added twice; an empty bag gives zeros."""
+    Mean (the pooling of the paper's own example in Section 3.1): the same sum divided by the
+    bag's length.  A row that occurs twice in a bag counts twice; an empty bag gives zeros."""
+    assert pooling in ("sum", "mean")
     T = len(row_base) - 1
     d = h.shape[1]
     e = np.zeros((B, T, d), dtype=h.dtype)
@@ -134,13 +136,16 @@ def embedding_bag_forward(h, row_base, indices, offsets, B: int):
             lo, hi = offsets[t * B + b], offsets[t * B + b + 1]
             for j in range(lo, hi):
                 e[b, t, :] += h[row_base[t] + indices[j], :]
+            if pooling == "mean" and hi > lo:
+                e[b, t, :] /= (hi - lo)
     return e
 
 
-def embedding_bag_forward_fast(h, row_base, indices, offsets, B: int):
+def embedding_bag_forward_fast(h, row_base, indices, offsets, B: int, pooling: str = "sum"):
     """Same definition as embedding_bag_forward with the inner loop handed to numpy's
     row gather + sum (used at sizes where the triple loop is too slow; the two are
     compared in the CPU tests)."""
+    assert pooling in ("sum", "mean")
     T = len(row_base) - 1
     d = h.shape[1]
     e = np.zeros((B, T, d), dtype=h.dtype)
@@ -150,7 +155,15 @@ def embedding_bag_forward_fast(h, row_base, indices, offsets, B: int):
             lo, hi = offsets[t * B + b], offsets[t * B + b + 1]
             if hi > lo:
                 e[b, t, :] = h[base + indices[lo:hi]].sum(axis=0)
+                if pooling == "mean":
+                    e[b, t, :] /= (hi - lo)
     return e
+
+
+def bag_lengths(offsets, B: int, T: int):
+    """Length of the bag behind pooled vector b*T + t."""
+    off = np.asarray(offsets, dtype=np.int64)
+    return (off[1:] - off[:-1]).reshape(T, B).T.reshape(B * T)
 
 
 def global_rows(row_base, indices, offsets, B: int):
@@ -185,15 +198,18 @@ def stable_sort_by_row(keys):
     return sk, perm, heads
 
 
-def embedding_row_gradients(de, keys, bag_of_pos):
+def embedding_row_gradients(de, keys, bag_of_pos, bag_scale=None):
     """Gradient of every touched table row: g_r = sum, over the occurrences of r in
-    ascending flat position, of de[bag that occurrence fed].  de is (B*T, d).
-    Duplicates inside one bag and across the batch are all summed before any update.
-    Returns (unique_rows, g (U, d), sorted_keys, sorted_pos, segment_starts)."""
+    ascending flat position, of de[bag that occurrence fed] (times bag_scale[bag] if given:
+    1 / bag length under mean pooling, the derivative of the mean w.r.t. each member).
+    de is (B*T, d).  Duplicates inside one bag and across the batch are all summed before any
+    update.  Returns (unique_rows, g (U, d), sorted_keys, sorted_pos, segment_starts)."""
     sk, perm, heads = stable_sort_by_row(keys)
     if len(sk) == 0:
         return sk, np.zeros((0, de.shape[1]), de.dtype), sk, perm, heads
     contrib = de[bag_of_pos[perm]]
+    if bag_scale is not None:
+        contrib = contrib * np.asarray(bag_scale, dtype=de.dtype)[bag_of_pos[perm]][:, None]
     g = np.add.reduceat(contrib, heads, axis=0)
     return sk[heads], g, sk, perm, heads
 
@@ -255,7 +271,7 @@ def bce_with_logits(logit, y):
 
 # --------------------------------------------------------------------------- whole model
 def dlrm_forward(layout: DenseLayout, w, h, row_base, x, indices, offsets, bf16=False,
-                 fast=True):
+                 fast=True, pooling="sum"):
     """Forward pass in the paper's order (Section 3.1 "Trainer").  Returns a dict of
     every intermediate the backward pass needs."""
     dtype = w.dtype
@@ -266,7 +282,7 @@ def dlrm_forward(layout: DenseLayout, w, h, row_base, x, indices, offsets, bf16=
     acts_bot = mlp_forward(x.astype(dtype), bot, relu_last=True, q=q)
     z0 = acts_bot[-1]
     bag = embedding_bag_forward_fast if fast else embedding_bag_forward
-    e = bag(h, row_base, indices, offsets, B)
+    e = bag(h, row_base, indices, offsets, B, pooling)
     f = interaction_forward(z0, e)
     acts_top = mlp_forward(f, top, relu_last=False, q=q)
     logit = acts_top[-1][:, 0]

@@ -17,7 +17,7 @@ from . import dlrm, sync
 class OracleTrainer:
     def __init__(self, bot_dims, top_dims, row_base, h0, w0, num_replicas,
                  lr_dense=0.01, lr_emb=0.01, adagrad_eps=1e-8, dtype=np.float64,
-                 bf16=False):
+                 bf16=False, pooling="sum"):
         self.layout = dlrm.DenseLayout(tuple(bot_dims), tuple(top_dims))
         self.row_base = np.asarray(row_base, dtype=np.int64)
         self.T = len(self.row_base) - 1
@@ -27,6 +27,8 @@ class OracleTrainer:
         assert w0.shape == (self.layout.num_params,)
         self.dtype = dtype
         self.bf16 = bf16
+        assert pooling in ("sum", "mean")
+        self.pooling = pooling
         self.h = h0.astype(dtype).copy()
         self.G = np.zeros(h0.shape[0], dtype=dtype)
         self.W = np.tile(w0.astype(dtype), (num_replicas, 1))
@@ -47,12 +49,15 @@ class OracleTrainer:
         L = self.layout
         w = self.W[replica]
         fw = dlrm.dlrm_forward(L, w, self.h, self.row_base, x, indices, offsets,
-                               bf16=self.bf16)
+                               bf16=self.bf16, pooling=self.pooling)
         loss, g, de = dlrm.dlrm_backward(L, fw, y.astype(self.dtype))
         keys = dlrm.global_rows(self.row_base, indices, offsets, B)
         bag = dlrm.bag_of_position(offsets, B, self.T)
+        scale = None
+        if self.pooling == "mean":
+            scale = 1.0 / np.maximum(dlrm.bag_lengths(offsets, B, self.T), 1)
         rows, g_rows, sk, perm, heads = dlrm.embedding_row_gradients(
-            de.reshape(B * self.T, self.d), keys, bag)
+            de.reshape(B * self.T, self.d), keys, bag, scale)
         self.last = dict(e=fw["e"], f=fw["f"], logit=fw["logit"], z0=fw["z0"], g=g,
                          de=de, sorted_keys=sk, sorted_pos=perm, seg_starts=heads,
                          rows=rows, g_rows=g_rows, bag_of_pos=bag)
@@ -65,7 +70,7 @@ class OracleTrainer:
 
     def eval_logloss(self, replica, x, y, indices, offsets):
         fw = dlrm.dlrm_forward(self.layout, self.W[replica], self.h, self.row_base, x,
-                               indices, offsets, bf16=self.bf16)
+                               indices, offsets, bf16=self.bf16, pooling=self.pooling)
         return dlrm.bce_with_logits(fw["logit"], y.astype(self.dtype))[0]
 
     # ------------------------------------------------------------------ shadow thread

@@ -15,40 +15,45 @@ from helpers import random_problem
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
-def _loss(p, w=None, h=None):
+def _loss(p, w=None, h=None, pooling="sum"):
     L = dlrm.DenseLayout(p["bot"], p["top"])
     fw = dlrm.dlrm_forward(L, p["w"] if w is None else w, p["h"] if h is None else h,
-                           p["row_base"], p["x"], p["indices"], p["offsets"], fast=False)
+                           p["row_base"], p["x"], p["indices"], p["offsets"], fast=False,
+                           pooling=pooling)
     return dlrm.bce_with_logits(fw["logit"], p["y"])[0]
 
 
-def _grads(p):
+def _grads(p, pooling="sum"):
     L = dlrm.DenseLayout(p["bot"], p["top"])
     fw = dlrm.dlrm_forward(L, p["w"], p["h"], p["row_base"], p["x"], p["indices"],
-                           p["offsets"], fast=False)
+                           p["offsets"], fast=False, pooling=pooling)
     loss, g, de = dlrm.dlrm_backward(L, fw, p["y"])
     keys = dlrm.global_rows(p["row_base"], p["indices"], p["offsets"], p["B"])
     bag = dlrm.bag_of_position(p["offsets"], p["B"], p["T"])
+    scale = None
+    if pooling == "mean":
+        scale = 1.0 / np.maximum(dlrm.bag_lengths(p["offsets"], p["B"], p["T"]), 1)
     rows, g_rows, sk, perm, heads = dlrm.embedding_row_gradients(
-        de.reshape(p["B"] * p["T"], p["d"]), keys, bag)
+        de.reshape(p["B"] * p["T"], p["d"]), keys, bag, scale)
     dh = np.zeros_like(p["h"])
     dh[rows] = g_rows
     return loss, g, de, dh
 
 
 # ----------------------------------------------------------------------------- gradients
-@pytest.mark.parametrize("seed", [0, 1, 2])
-def test_dense_and_table_gradients_match_finite_differences(seed):
+@pytest.mark.parametrize("seed,pooling", [(0, "sum"), (1, "sum"), (2, "sum"), (3, "mean"),
+                                          (4, "mean")])
+def test_dense_and_table_gradients_match_finite_differences(seed, pooling):
     rng = np.random.default_rng(seed)
     p = random_problem(rng)
-    _, g, _, dh = _grads(p)
+    _, g, _, dh = _grads(p, pooling)
     eps = 1e-6
     num = np.zeros_like(g)
     for k in range(len(g)):
         wp, wm = p["w"].copy(), p["w"].copy()
         wp[k] += eps
         wm[k] -= eps
-        num[k] = (_loss(p, w=wp) - _loss(p, w=wm)) / (2 * eps)
+        num[k] = (_loss(p, w=wp, pooling=pooling) - _loss(p, w=wm, pooling=pooling)) / (2 * eps)
     assert np.max(np.abs(num - g)) < 1e-6 * max(1.0, np.max(np.abs(g)))
     numh = np.zeros_like(dh)
     for r in range(dh.shape[0]):
@@ -56,7 +61,7 @@ def test_dense_and_table_gradients_match_finite_differences(seed):
             hp, hm = p["h"].copy(), p["h"].copy()
             hp[r, c] += eps
             hm[r, c] -= eps
-            numh[r, c] = (_loss(p, h=hp) - _loss(p, h=hm)) / (2 * eps)
+            numh[r, c] = (_loss(p, h=hp, pooling=pooling) - _loss(p, h=hm, pooling=pooling)) / (2 * eps)
     assert np.max(np.abs(numh - dh)) < 1e-6 * max(1.0, np.max(np.abs(dh)))
 
 
@@ -126,6 +131,30 @@ def test_embedding_bag_is_multiplicity_matrix_product(allow_empty):
     for fn in (dlrm.embedding_bag_forward, dlrm.embedding_bag_forward_fast):
         e = fn(p["h"], p["row_base"], p["indices"], p["offsets"], p["B"])
         np.testing.assert_allclose(e, ref, rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("allow_empty", [False, True])
+def test_mean_pooling_is_row_normalised_multiplicity_product(allow_empty):
+    """Mean pooling and its gradient through the row-normalised multiplicity matrix
+    N = diag(1/len) C (rows of empty bags stay zero): e = N h, dL/dh = N^T de."""
+    rng = np.random.default_rng(15)
+    p = random_problem(rng, B=11, T=3, d=4, rows=(6, 3, 11), bot=(3, 4), max_len=5,
+                       allow_empty=allow_empty)
+    C = _multiplicity(p)
+    lens = C.sum(axis=1)
+    N = C / np.maximum(lens, 1)[:, None]
+    ref = (N @ p["h"]).reshape(p["B"], p["T"], p["d"])
+    for fn in (dlrm.embedding_bag_forward, dlrm.embedding_bag_forward_fast):
+        e = fn(p["h"], p["row_base"], p["indices"], p["offsets"], p["B"], "mean")
+        np.testing.assert_allclose(e, ref, rtol=0, atol=1e-14)
+    assert np.array_equal(dlrm.bag_lengths(p["offsets"], p["B"], p["T"]), lens.astype(np.int64))
+    de = rng.standard_normal((p["B"] * p["T"], p["d"]))
+    keys = dlrm.global_rows(p["row_base"], p["indices"], p["offsets"], p["B"])
+    bag = dlrm.bag_of_position(p["offsets"], p["B"], p["T"])
+    rows, g, _, _, _ = dlrm.embedding_row_gradients(de, keys, bag, 1.0 / np.maximum(lens, 1))
+    touched = np.flatnonzero(C.sum(axis=0))
+    assert np.array_equal(rows, touched)
+    np.testing.assert_allclose(g, (N.T @ de)[touched], rtol=0, atol=1e-13)
 
 
 def test_embedding_row_gradients_is_transposed_product_and_sort_is_stable():
