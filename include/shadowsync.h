@@ -58,6 +58,11 @@ typedef enum {
 
 typedef enum { SS_FP32 = 0, SS_BF16 = 1 } ss_mlp_prec;
 
+/* Pooling of a bag's rows (Section 3.1): SS_POOL_SUM adds them, SS_POOL_MEAN (the pooling of
+ * the paper's example) divides the sum by the bag's length; the gradient of every member then
+ * carries 1 / length. */
+typedef enum { SS_POOL_SUM = 0, SS_POOL_MEAN = 1 } ss_pooling;
+
 typedef struct {
   int32_t num_tables;        /* T, 1..64                                                  */
   const int64_t* rows;       /* host [T] rows per table; sum < 2^32                      */
@@ -78,6 +83,7 @@ typedef struct {
   float lr_emb;              /* row-wise Adagrad step on h                               */
   float adagrad_eps;
   uint64_t seed;             /* seed of the counter-based table initialiser             */
+  int32_t pooling;           /* ss_pooling                                               */
 } ss_config;
 
 /* One mini-batch.  All pointers are DEVICE pointers owned by the caller and must stay

@@ -33,6 +33,7 @@ struct Slot {
   uint16_t* act_bf16[MAX_LAYERS];  // bf16 path: output of hidden layers
   float* z0;                       // output of the last bottom layer (fp32 in both paths)
   float* e;                        // [B,T,d]
+  float* inv_len;                  // [B,T] 1 / bag length (mean pooling)
   float* f;                        // [B,ldf]
   uint16_t* f_bf16;                // [B,ldf16]
   float* logits;                   // [B]
@@ -89,6 +90,7 @@ struct Carver {
 struct ss_ctx {
   // configuration
   int T, d, num_dense, K, max_batch, num_slots, prec;
+  bool pool_mean = false;          // mean instead of sum pooling
   int64_t max_ids;
   std::vector<int64_t> rows;
   std::vector<Layer> layers;
@@ -209,6 +211,7 @@ static int validate(const ss_config* c, std::string& why) {
   if ((int64_t)c->max_batch * T >= (1ll << 31)) BAD("max_batch * num_tables too large");
   if (c->num_worker_slots < 1 || c->num_worker_slots > 64) BAD("num_worker_slots must be 1..64");
   if (c->mlp_prec != SS_FP32 && c->mlp_prec != SS_BF16) BAD("bad mlp_prec");
+  if (c->pooling != SS_POOL_SUM && c->pooling != SS_POOL_MEAN) BAD("bad pooling mode");
   const size_t shm = (size_t)4 * ((T + 1) * (c->emb_dim + 4) + (((T + 1) * (T + 1) + 3) & ~3)) * 4;
   if (shm > 64 * 1024) BAD("interaction tile (T+1) x d does not fit the LDS budget");
 #undef BAD
@@ -241,6 +244,7 @@ static size_t layout(ss_ctx* x, void* base) {
     }
     s.z0 = cv.take<float>((size_t)B * x->d);
     s.e = cv.take<float>((size_t)B * x->T * x->d);
+    s.inv_len = cv.take<float>((size_t)B * x->T);
     s.f = cv.take<float>((size_t)B * x->ldf);
     s.f_bf16 = (x->prec == SS_BF16) ? cv.take<uint16_t>((size_t)B * x->ldf16) : nullptr;
     s.logits = cv.take<float>(B);
@@ -299,6 +303,7 @@ static ss_ctx* make_ctx(const ss_config* c) {
   x->T = c->num_tables; x->d = c->emb_dim; x->num_dense = c->num_dense;
   x->K = c->num_replicas; x->max_batch = c->max_batch; x->max_ids = c->max_ids;
   x->num_slots = c->num_worker_slots; x->prec = c->mlp_prec;
+  x->pool_mean = (c->pooling == SS_POOL_MEAN);
   x->lr_dense = c->lr_dense; x->lr_emb = c->lr_emb; x->eps = c->adagrad_eps; x->seed = c->seed;
   x->rows.assign(c->rows, c->rows + c->num_tables);
   uint64_t base = 0;
@@ -689,7 +694,7 @@ static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
   {
     ProfScope ps(x, SS_K_GATHER, st);
     launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e, s.keys,
-                             s.bag_of_pos, loss, st);
+                             s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -796,7 +801,7 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
   {
     ProfScope ps(x, SS_K_GATHER, st);
     launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e, s.keys,
-                             s.bag_of_pos, loss, st);
+                             s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -946,7 +951,7 @@ static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, floa
   {
     ProfScope ps(x, SS_K_GATHER, st);
     launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e, s.keys,
-                             s.bag_of_pos, fused_last(x) ? loss : nullptr, st);
+                             s.bag_of_pos, fused_last(x) ? loss : nullptr, x->pool_mean ? s.inv_len : nullptr, st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -1102,7 +1107,7 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
       {
         ProfScope ps(x, SS_K_ROW_UPDATE_CHUNK, st);
         launch_row_update_chunk(s.sorted_keys, s.sorted_bag, s.de, n, s.upd, x->d, x->h, x->G,
-                                x->lr_emb, x->eps, st);
+                                x->lr_emb, x->eps, x->pool_mean ? s.inv_len : nullptr, st);
       }
       launch_row_update_finish(s.sorted_keys, n, s.upd, x->d, x->h, x->G, x->lr_emb, x->eps, st);
     }

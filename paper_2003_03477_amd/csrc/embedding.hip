@@ -16,7 +16,7 @@ __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
     const float* __restrict__ h, const int32_t* __restrict__ indices,
     const int32_t* __restrict__ offsets, TableMeta meta, int B, int T, float* __restrict__ e,
     uint32_t* __restrict__ keys, int32_t* __restrict__ bag_of_pos,
-    float* __restrict__ zero_scalar) {
+    float* __restrict__ zero_scalar, float* __restrict__ inv_len) {
   constexpr int D = LPR * 4;
   constexpr int RPW = SS_WAVE / LPR;  // rows per wave-wide load
   // the step's loss accumulator is cleared here, ahead of the kernel that adds into it
@@ -59,19 +59,26 @@ __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
     acc.z += __shfl_xor(acc.z, off);
     acc.w += __shfl_xor(acc.w, off);
   }
+  if (inv_len) {
+    // mean pooling: the sum over the bag divided by its length; 1/length is kept per pooled
+    // vector because every member's gradient carries the same factor
+    const float sc = (hi > lo) ? 1.0f / (float)(hi - lo) : 0.f;
+    acc.x *= sc; acc.y *= sc; acc.z *= sc; acc.w *= sc;
+    if (lane == 0) inv_len[ebag] = sc;
+  }
   if (sub == 0) *(float4*)(e + (size_t)ebag * D + c4 * 4) = acc;
 }
 
 void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int32_t* offsets,
                               const TableMeta& meta, int B, int T, int d, float* e,
                               uint32_t* keys, int32_t* bag_of_pos, float* zero_scalar,
-                              hipStream_t s) {
+                              float* inv_len, hipStream_t s) {
   const int64_t bags = (int64_t)B * T;
   if (bags == 0) return;
   dim3 grid((unsigned)ceil_div(bags, 4)), block(256);
 #define L(LPR)                                                                               \
   hipLaunchKernelGGL((embedding_bag_fwd_kernel<LPR>), grid, block, 0, s, h, indices, offsets, \
-                     meta, B, T, e, keys, bag_of_pos, zero_scalar)
+                     meta, B, T, e, keys, bag_of_pos, zero_scalar, inv_len)
   switch (d) {
     case 16: L(4); break;
     case 32: L(8); break;

@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void row_update_chunk_kernel(
     const uint32_t* __restrict__ keys, const int32_t* __restrict__ bags,
     const float* __restrict__ de, uint32_t n, float* __restrict__ h, float* __restrict__ G,
     float lr, float eps, float* __restrict__ parts, uint32_t* __restrict__ flags,
-    uint32_t* __restrict__ long_count) {
+    uint32_t* __restrict__ long_count, const float* __restrict__ inv_len) {
   constexpr int D = LPR * 4, C = LPR, SUB = (C < 8 ? C : 8);
   if (blockIdx.x == 0 && threadIdx.x == 0) *long_count = 0;  // consumed by the later passes
   const int lane = threadIdx.x & 63, c = lane % LPR, gw = lane / LPR;
@@ -87,6 +87,10 @@ __global__ __launch_bounds__(256) void row_update_chunk_kernel(
       Gv[i] = 0.f;
       if (p < nv) {
         v[i] = *(const float4*)(de + (size_t)bg * D + c * 4);
+        if (inv_len) {  // mean pooling: d(mean)/d(member) = 1 / bag length
+          const float sc = inv_len[bg];
+          v[i].x *= sc; v[i].y *= sc; v[i].z *= sc; v[i].w *= sc;
+        }
         if ((tm >> p) & 1u) {
           hv[i] = *(const float4*)(h + (size_t)rw[i] * D + c * 4);
           Gv[i] = G[rw[i]];
@@ -246,14 +250,15 @@ __global__ __launch_bounds__(1024) void row_update_long_kernel(
 
 void launch_row_update_chunk(const uint32_t* sorted_keys, const int32_t* sorted_bag,
                              const float* de, uint32_t n, const RowUpdateScratch& sc, int d,
-                             float* h, float* G, float lr, float eps, hipStream_t s) {
+                             float* h, float* G, float lr, float eps, const float* inv_len,
+                             hipStream_t s) {
   if (n == 0) return;
   const int lpr = d / 4;
   const int64_t nchunks = ((int64_t)n + lpr - 1) / lpr;
   const int blocks = ceil_div(nchunks, 256 / lpr);
 #define L(LPR)                                                                                   \
   hipLaunchKernelGGL((row_update_chunk_kernel<LPR>), dim3(blocks), dim3(256), 0, s, sorted_keys, \
-                     sorted_bag, de, n, h, G, lr, eps, sc.parts, sc.flags, sc.long_count)
+                     sorted_bag, de, n, h, G, lr, eps, sc.parts, sc.flags, sc.long_count, inv_len)
   switch (d) {
     case 16: L(4); break;
     case 32: L(8); break;

@@ -28,7 +28,7 @@ void launch_fill_u32(uint32_t* p, uint64_t n, uint32_t v, hipStream_t s);
 void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int32_t* offsets,
                               const TableMeta& meta, int B, int T, int d, float* e,
                               uint32_t* keys, int32_t* bag_of_pos, float* zero_scalar,
-                              hipStream_t s);
+                              float* inv_len, hipStream_t s);
 
 struct SegScratch {
   uint32_t* block_counts;  // [seg_blocks]
@@ -50,7 +50,8 @@ int64_t row_update_chunks(int64_t max_ids, int d);
 // Adagrad on h and G.  Input: keys sorted ascending with the pooled-vector id of each entry.
 void launch_row_update_chunk(const uint32_t* sorted_keys, const int32_t* sorted_bag,
                              const float* de, uint32_t n, const RowUpdateScratch& sc, int d,
-                             float* h, float* G, float lr, float eps, hipStream_t s);
+                             float* h, float* G, float lr, float eps, const float* inv_len,
+                             hipStream_t s);
 void launch_row_update_finish(const uint32_t* sorted_keys, uint32_t n, const RowUpdateScratch& sc,
                               int d, float* h, float* G, float lr, float eps, hipStream_t s);
 

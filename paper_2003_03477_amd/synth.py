@@ -83,6 +83,7 @@ class Workload:
     lr_dense: float = 0.01
     lr_emb: float = 0.01
     adagrad_eps: float = 1e-8
+    pooling: str = "sum"           # "sum" | "mean"
 
     @property
     def num_tables(self) -> int:

@@ -48,13 +48,13 @@ def make_pair(wl, batches, h0=None, rows=None, slots=1, dtype=np.float64):
     max_ids = max(int(b.offsets[-1]) for b in batches) + 64
     gpu = binding.ShadowSync(rows, wl.emb_dim, wl.bot_dims, wl.top_dims, wl.num_replicas,
                              max(b.dense.shape[0] for b in batches), max_ids, slots, wl.bf16,
-                             wl.lr_dense, wl.lr_emb, wl.adagrad_eps, wl.seed)
+                             wl.lr_dense, wl.lr_emb, wl.adagrad_eps, wl.seed, pooling=wl.pooling)
     for t in range(len(rows)):
         gpu.ss_write_rows(t, 0, h0[row_base[t]:row_base[t + 1]])
     gpu.ss_init_dense(w0)
     orc = oracle.OracleTrainer(wl.bot_dims, wl.top_dims, row_base, h0, w0, wl.num_replicas,
                                wl.lr_dense, wl.lr_emb, wl.adagrad_eps, dtype=dtype,
-                               bf16=wl.bf16)
+                               bf16=wl.bf16, pooling=wl.pooling)
     return gpu, orc
 
 

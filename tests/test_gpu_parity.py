@@ -123,6 +123,32 @@ def test_fp32_other_embedding_widths(d):
     H.compare_state(gpu, orc, H.FP32_RTOL, f"d={d}", wl.row_base)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_mean_pooling(bf16):
+    """Mean pooling (the pooling of the paper's Section 3.1 example): pooled vectors divided
+    by the bag length, member gradients scaled by 1 / length; empty bags included."""
+    wl = synth.tiny().scaled(batch=97, rows=(5000, 11, 800), emb_dim=32, bag_lambda=5.0,
+                             bot_dims=(13, 48, 32), top_dims=(32 + 6, 64, 24, 1),
+                             num_replicas=2, algo="easgd", alpha=0.2, sync_gap=2, zipf_s=1.2,
+                             pooling="mean", bf16=bf16)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(8)]
+    # empty a few bags of the first batch
+    b0 = batches[0]
+    lens = np.diff(b0.offsets).copy()
+    lens[[0, 5, 97, 200]] = 0
+    keep = np.concatenate([np.arange(b0.offsets[i], b0.offsets[i] + lens[i]) for i in range(len(lens))])
+    batches[0] = synth.Batch(b0.dense, b0.labels, b0.indices[keep.astype(np.int64)],
+                             np.concatenate(([0], np.cumsum(lens))).astype(np.int32))
+    gpu, orc = H.make_pair(wl, batches, h0=synth.full_tables_h0(wl))
+    if bf16:
+        H.run_lockstep(gpu, orc, batches, wl.sync_gap, wl.algo, wl.alpha, rtol=H.BF16_RTOL,
+                       resync_row_base=wl.row_base)
+    else:
+        H.run_lockstep(gpu, orc, batches, wl.sync_gap, wl.algo, wl.alpha)
+        H.compare_state(gpu, orc, H.FP32_RTOL, "mean pooling", wl.row_base)
+
+
 def test_empty_bags_single_sample_and_hot_row():
     """Edge cases: empty bags, batch of one, one row owning a very long segment."""
     wl = synth.tiny().scaled(batch=64, rows=(50, 1000), emb_dim=16, bot_dims=(13, 16),
