@@ -40,5 +40,11 @@ from .dlrm import (  # noqa: F401
     rowwise_adagrad_update,
     stable_sort_by_row,
 )
-from .sync import bmuf_round, easgd_round, easgd_round_literal, ma_round  # noqa: F401
+from .sync import (  # noqa: F401
+    bmuf_nesterov_round,
+    bmuf_round,
+    easgd_round,
+    easgd_round_literal,
+    ma_round,
+)
 from .trainer import OracleTrainer, normalized_entropy  # noqa: F401

@@ -71,3 +71,24 @@ def bmuf_round(W, w_global, v, alpha, eta, mu):
     w_global += v
     for i in range(K):
         W[i] = (1 - alpha) * W[i] + alpha * w_global
+
+
+def bmuf_nesterov_round(W, w_global, v, alpha, eta, mu):
+    """Shadow BMUF with Nesterov block momentum, the second option named in Algorithm 4's
+    comment (the paper gives no formula; this is the block-momentum form of the BMUF paper it
+    cites): v and w^global advance exactly as in bmuf_round, but the replicas are pulled
+    towards the look-ahead point w^global + mu v instead of w^global:
+        w^(i) <- (1-alpha) w^(i) + alpha (w^global + mu v).
+    mu = 0 is bmuf_round."""
+    K = W.shape[0]
+    m = W[0].copy()
+    for i in range(1, K):
+        m += W[i]
+    m /= K
+    desc = m - w_global
+    v[:] = mu * v + eta * desc
+    w_global += v
+    ahead = w_global + mu * v
+    for i in range(K):
+        W[i] = (1 - alpha) * W[i] + alpha * ahead
+

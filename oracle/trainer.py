@@ -84,6 +84,8 @@ class OracleTrainer:
             sync.ma_round(self.W, self.w_global, alpha)
         elif algo == "bmuf":
             sync.bmuf_round(self.W, self.w_global, self.v, alpha, eta, mu)
+        elif algo == "bmuf_nesterov":
+            sync.bmuf_nesterov_round(self.W, self.w_global, self.v, alpha, eta, mu)
         else:
             raise ValueError(algo)
         self.rounds += 1

@@ -127,3 +127,52 @@ def test_bmuf_fixed_point():
     W = np.tile(w, (4, 1)); wg = w.copy(); v = np.zeros(11)
     sync.bmuf_round(W, wg, v, 0.5, 1.0, 0.9)
     assert np.array_equal(W, np.tile(w, (4, 1))) and np.array_equal(wg, w) and not v.any()
+
+
+# ----------------------------------------------------------------------------- Nesterov BMUF
+def test_bmuf_nesterov_without_momentum_is_bmuf():
+    W, _, wg, v = _state(10, 4)
+    v[:] = 0
+    W2, wg2, v2 = W.copy(), wg.copy(), v.copy()
+    for _ in range(3):
+        sync.bmuf_nesterov_round(W, wg, v, 0.4, eta=0.7, mu=0.0)
+        sync.bmuf_round(W2, wg2, v2, 0.4, eta=0.7, mu=0.0)
+    np.testing.assert_allclose(W, W2, atol=1e-14)
+    np.testing.assert_allclose(wg, wg2, atol=1e-14)
+
+
+def test_bmuf_nesterov_pulls_towards_the_look_ahead_point():
+    """Same w_global and v as plain BMUF from the same state; with alpha = 1 every replica
+    lands on w_global + mu v, i.e. it differs from plain BMUF's replicas by exactly mu v."""
+    W, _, wg, v = _state(11, 3, P=6)
+    v[:] = np.random.default_rng(12).standard_normal(6) * 0.1
+    W2, wg2, v2 = W.copy(), wg.copy(), v.copy()
+    mu = 0.8
+    sync.bmuf_nesterov_round(W, wg, v, 1.0, eta=0.5, mu=mu)
+    sync.bmuf_round(W2, wg2, v2, 1.0, eta=0.5, mu=mu)
+    np.testing.assert_allclose(wg, wg2, atol=1e-14)
+    np.testing.assert_allclose(v, v2, atol=1e-14)
+    np.testing.assert_allclose(W, W2 + mu * v2, atol=1e-14)
+    np.testing.assert_allclose(W, np.tile(wg + mu * v, (3, 1)), atol=1e-14)
+
+
+def test_bmuf_nesterov_single_trainer_scalar_recurrence():
+    """K = 1, alpha = 1, eta = 1: the replica is the look-ahead point x = g + mu v, and the
+    next round does v <- mu v + (x - g) = 2 mu v... written out: v' = mu v + mu v, g' = g + v',
+    x' = g' + mu v'."""
+    g, v, mu = 0.3, 0.05, 0.5
+    x = g + mu * v
+    W = np.array([[x]]); wg = np.array([g]); vv = np.array([v])
+    for _ in range(5):
+        sync.bmuf_nesterov_round(W, wg, vv, 1.0, 1.0, mu)
+        v = mu * v + (x - g)
+        g = g + v
+        x = g + mu * v
+        assert abs(wg[0] - g) < 1e-14 and abs(vv[0] - v) < 1e-14 and abs(W[0, 0] - x) < 1e-14
+
+
+def test_bmuf_nesterov_fixed_point():
+    w = np.random.default_rng(13).standard_normal(7)
+    W = np.tile(w, (4, 1)); wg = w.copy(); v = np.zeros(7)   # K = 4: the mean is exact
+    sync.bmuf_nesterov_round(W, wg, v, 0.5, 1.0, 0.9)
+    assert np.array_equal(W, np.tile(w, (4, 1))) and np.array_equal(wg, w) and not v.any()
