@@ -53,7 +53,9 @@ typedef enum {
   SS_EASGD = 0,         /* Algorithm 2, symmetric elastic exchange (conserves mass)   */
   SS_MA = 1,            /* Algorithm 3                                               */
   SS_BMUF = 2,          /* Algorithm 4 with optional block momentum                  */
-  SS_EASGD_LITERAL = 3  /* Algorithm 2 with its two lines executed one after another */
+  SS_EASGD_LITERAL = 3, /* Algorithm 2 with its two lines executed one after another */
+  SS_BMUF_NESTEROV = 4  /* Algorithm 4 with Nesterov block momentum: v and w^global as in
+                           SS_BMUF, replicas pulled towards w^global + momentum * v        */
 } ss_algo;
 
 typedef enum { SS_FP32 = 0, SS_BF16 = 1 } ss_mlp_prec;

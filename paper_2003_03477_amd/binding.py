@@ -16,10 +16,11 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libshadowsync.so")
 
-SS_EASGD, SS_MA, SS_BMUF, SS_EASGD_LITERAL = 0, 1, 2, 3
+SS_EASGD, SS_MA, SS_BMUF, SS_EASGD_LITERAL, SS_BMUF_NESTEROV = 0, 1, 2, 3, 4
 SS_FP32, SS_BF16 = 0, 1
 POOLING = {"sum": 0, "mean": 1}
-ALGOS = {"easgd": SS_EASGD, "ma": SS_MA, "bmuf": SS_BMUF, "easgd_literal": SS_EASGD_LITERAL}
+ALGOS = {"easgd": SS_EASGD, "ma": SS_MA, "bmuf": SS_BMUF, "easgd_literal": SS_EASGD_LITERAL,
+         "bmuf_nesterov": SS_BMUF_NESTEROV}
 
 (DBG_POOLED, DBG_INTERACT, DBG_LOGITS, DBG_DENSE_GRAD, DBG_POOLED_GRAD, DBG_SORTED_ROWS,
  DBG_SORTED_POS, DBG_SEG_STARTS, DBG_NUM_UNIQUE, DBG_BAG_OF_POS) = range(10)

@@ -1134,13 +1134,13 @@ int ss_eval_step(ss_ctx* ctx, int32_t replica, int32_t worker_slot, const ss_bat
 int ss_sync_round(int32_t algo, int32_t K, int64_t P, int64_t stride, float* dev_replicas,
                   float* dev_w_ps, float* dev_w_global, float* dev_v, float alpha, float eta,
                   float momentum, void* stream) {
-  if (algo < SS_EASGD || algo > SS_EASGD_LITERAL || K < 1 || K > 16 || P < 1 || (P & 3) ||
+  if (algo < SS_EASGD || algo > SS_BMUF_NESTEROV || K < 1 || K > 16 || P < 1 || (P & 3) ||
       stride < P || (stride & 3) || !dev_replicas)
     return SS_EINVAL;
   const bool easgd = (algo == SS_EASGD || algo == SS_EASGD_LITERAL);
   if (easgd && !dev_w_ps) return SS_EINVAL;
   if (!easgd && !dev_w_global) return SS_EINVAL;
-  if (algo == SS_BMUF && !dev_v) return SS_EINVAL;
+  if ((algo == SS_BMUF || algo == SS_BMUF_NESTEROV) && !dev_v) return SS_EINVAL;
   uintptr_t al = (uintptr_t)dev_replicas | (uintptr_t)dev_w_ps | (uintptr_t)dev_w_global |
                  (uintptr_t)dev_v;
   if (al & 15) return SS_EINVAL;
@@ -1163,7 +1163,7 @@ static int sync_once(ss_ctx* x, int algo, float alpha, float eta, float mu, hipS
 int ss_shadow_sync(ss_ctx* ctx, int32_t algo, float alpha, float eta, float momentum, void* stream) {
   if (!ctx) return SS_EINVAL;
   if (ctx->sticky) return SS_EDEVICE;
-  if (algo < SS_EASGD || algo > SS_EASGD_LITERAL) return fail(ctx, SS_EINVAL, "unknown sync rule %d", algo);
+  if (algo < SS_EASGD || algo > SS_BMUF_NESTEROV) return fail(ctx, SS_EINVAL, "unknown sync rule %d", algo);
   if (ctx->shadow_run) return fail(ctx, SS_ESTATE, "shadow loop is running");
   return sync_once(ctx, algo, alpha, eta, momentum, (hipStream_t)stream);
 }
@@ -1186,7 +1186,7 @@ int ss_easgd_exchange(ss_ctx* ctx, int32_t algo, int32_t replica, float alpha, v
 
 int ss_shadow_start(ss_ctx* ctx, int32_t algo, float alpha, float eta, float momentum, void* stream) {
   if (!ctx) return SS_EINVAL;
-  if (algo < SS_EASGD || algo > SS_EASGD_LITERAL) return fail(ctx, SS_EINVAL, "unknown sync rule %d", algo);
+  if (algo < SS_EASGD || algo > SS_BMUF_NESTEROV) return fail(ctx, SS_EINVAL, "unknown sync rule %d", algo);
   if (ctx->shadow_run.exchange(true)) return fail(ctx, SS_ESTATE, "shadow loop already running");
   hipStream_t st = (hipStream_t)stream;
   ctx->shadow = std::thread([ctx, algo, alpha, eta, momentum, st]() {

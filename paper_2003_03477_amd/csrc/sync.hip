@@ -83,15 +83,19 @@ __global__ __launch_bounds__(256) void sync_round_kernel(float* __restrict__ W, 
       float4 g;
       if constexpr (ALGO == SS_MA) {
         g = m;
-      } else {  // SS_BMUF
+      } else {  // SS_BMUF, SS_BMUF_NESTEROV
         float4 g0 = ld4<NT>(w_global + o), vv = ld4<NT>(v + o);
 #define E(f) mu * vv.f + eta * (m.f - g0.f)
         SS_F4_OP(vv, E)
 #undef E
         g.x = g0.x + vv.x; g.y = g0.y + vv.y; g.z = g0.z + vv.z; g.w = g0.w + vv.w;
         st4<NT>(v + o, vv);
+        st4<NT>(w_global + o, g);
+        if constexpr (ALGO == SS_BMUF_NESTEROV) {  // the replicas aim at the look-ahead point
+          g.x += mu * vv.x; g.y += mu * vv.y; g.z += mu * vv.z; g.w += mu * vv.w;
+        }
       }
-      st4<NT>(w_global + o, g);
+      if constexpr (ALGO == SS_MA) st4<NT>(w_global + o, g);
 #pragma unroll
       for (int k = 0; k < K; ++k) {
 #define E(f) beta * w[k].f + alpha * g.f
@@ -128,6 +132,7 @@ static void launch_k(int algo, int64_t n_vec, float* W, int64_t stride, float* w
     case SS_EASGD: SS_LAUNCH(SS_EASGD); break;
     case SS_EASGD_LITERAL: SS_LAUNCH(SS_EASGD_LITERAL); break;
     case SS_MA: SS_LAUNCH(SS_MA); break;
+    case SS_BMUF_NESTEROV: SS_LAUNCH(SS_BMUF_NESTEROV); break;
     default: SS_LAUNCH(SS_BMUF); break;
   }
 #undef SS_LAUNCH

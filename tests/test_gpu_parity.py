@@ -16,7 +16,7 @@ def _torch():
 
 # ----------------------------------------------------------------------------- sync rules
 @pytest.mark.parametrize("K", [1, 2, 3, 4, 8])
-@pytest.mark.parametrize("algo", ["easgd", "easgd_literal", "ma", "bmuf"])
+@pytest.mark.parametrize("algo", ["easgd", "easgd_literal", "ma", "bmuf", "bmuf_nesterov"])
 def test_sync_round_matches_oracle(K, algo):
     torch = _torch()
     P, stride = 4 * 12345, 4 * 12345 + 256      # several blocks, a ragged last block, padded stride
@@ -33,6 +33,8 @@ def test_sync_round_matches_oracle(K, algo):
             osync.easgd_round_literal(oW, ops, 0.3)
         elif algo == "ma":
             osync.ma_round(oW, owg, 0.3)
+        elif algo == "bmuf_nesterov":
+            osync.bmuf_nesterov_round(oW, owg, ov, 0.3, 0.7, 0.9)
         else:
             osync.bmuf_round(oW, owg, ov, 0.3, 0.7, 0.9)
     torch.cuda.synchronize()
@@ -91,6 +93,7 @@ def test_tiny_config_deterministic_schedule():
 
 @pytest.mark.parametrize("algo,alpha,eta,mu,gap", [("easgd", 0.1, 1.0, 0.0, 2),
                                                    ("bmuf", 0.5, 1.0, 0.9, 1),
+                                                   ("bmuf_nesterov", 0.5, 0.8, 0.7, 2),
                                                    ("easgd_literal", 0.2, 1.0, 0.0, 3)])
 def test_fp32_other_rules_and_ragged_shapes(algo, alpha, eta, mu, gap):
     """d=64, 3 unequal tables, batch not a multiple of anything, several sort passes."""
