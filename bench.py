@@ -32,10 +32,12 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X datasheet
 
 # HBM bytes per launch measured with `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` on the
-# Mid workload (KiB per dispatch * 1024; FETCH_SIZE reads 0.50x and WRITE_SIZE 1.00x the known size
-# of a plain streaming kernel, so fetches are scaled by 2.00).  Source: profiles/mid_hbm_traffic.txt.  None = not measured.
+# Mid and Large workloads (KiB per dispatch * 1024; FETCH_SIZE reads 0.50x and WRITE_SIZE 1.00x the
+# known size of a plain streaming kernel, so fetches are scaled by 2.00).  Sources:
+# profiles/mid_hbm_traffic.txt, profiles/large_hbm_traffic.txt.  None = not measured.
 MEASURED_TRAFFIC = {
     "mid": {"gather": 52.9e6, "row_update_chunk": 125.2e6},
+    "large": {"gather": 601e6, "row_update_chunk": 1357e6},
 }
 
 
