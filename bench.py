@@ -39,6 +39,12 @@ MEASURED_TRAFFIC = {
     "mid": {"gather": 52.9e6, "row_update_chunk": 125.2e6},
     "large": {"gather": 601e6, "row_update_chunk": 1357e6},
 }
+# Average kernel duration (us) reported by `rocprofv3 --kernel-trace --stats` with ONE stream
+# active (profiles/mid_single_stream_kernel_stats.txt): the event brackets of the same run read
+# about 5.5 us more per launch.  Quoted next to the live event figures, never instead of them.
+PROFILER_ALONE_US = {
+    "mid": {"gather": 14.73, "row_update_chunk": 32.42},
+}
 
 
 def parse():
@@ -314,9 +320,16 @@ def main():
                         "alone_avg_launch_us": kd.get("alone_avg_us"),
                         "alone_achieved": kd.get("alone_GBps"),
                         "alone_frac": kd.get("alone_frac_of_hbm_peak"),
+                        "profiler_alone_avg_launch_us": PROFILER_ALONE_US.get(wl.name, {}).get(dom),
+                        "profiler_alone_frac": (
+                            kd["algorithmic_bytes_per_launch"] /
+                            (PROFILER_ALONE_US[wl.name][dom] * 1e-6) / 1e9 / HBM_PEAK_GBS
+                            if dom in PROFILER_ALONE_US.get(wl.name, {}) else None),
                         "note": "achieved/frac: HIP events inside the timed region, where "
                                 f"{NS + 1} streams share the GPU (includes queueing and shared "
-                                "bandwidth); alone_*: the same kernel with one stream active"}
+                                "bandwidth); alone_*: the same kernel with one stream active; "
+                                "profiler_alone_*: rocprofv3's duration of that kernel in a "
+                                "one-stream run (committed profile, not measured in this run)"}
 
     if args.continuous_shadow and not args.no_shadow:
         gpu.ss_shadow_stop()
