@@ -656,9 +656,11 @@ void launch_mlp_prep(const PrepArgs& a, hipStream_t s) {
 }
 
 void launch_mlp_wgrad_grouped(const WgradArgs& a, int n_tiles, hipStream_t s) {
-  // batch slices of 64 to 256 samples per wave; about two blocks per CU
-  int gy = 1;
-  while (gy < 8 && n_tiles * gy < 512 && a.B / (4 * gy * 2) >= 64) gy *= 2;
+  // batch slices of about 256 samples per wave: fewer, longer slices cost less in atomics
+  // and LDS folds than they lose in parallelism once several streams share the chip
+  int gy = a.B / (4 * 256);
+  if (gy < 1) gy = 1;
+  if (gy > 8) gy = 8;
   const size_t lds = (size_t)(4 * WG_T * WG_LD + 4 * WG_T) * sizeof(float);
   hipLaunchKernelGGL(mlp_wgrad_grouped_kernel, dim3(n_tiles, gy), dim3(256), lds, s, a);
 }
