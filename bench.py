@@ -63,7 +63,7 @@ def parse():
                          "after all of them and all of them wait for it (FR-MA / FR-BMUF)")
     ap.add_argument("--continuous-shadow", action="store_true",
                     help="loop shadow rounds back to back (ss_shadow_start) instead of pacing them")
-    ap.add_argument("--workers-per-replica", type=int, default=4,
+    ap.add_argument("--workers-per-replica", type=int, default=6,
                     help="Hogwild worker streams per replica")
     ap.add_argument("--replicas", type=int, default=0, metavar="K",
                     help="number of dense replicas (default: the workload's)")
