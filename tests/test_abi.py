@@ -71,3 +71,43 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libshadowsync.so")
     with pytest.raises(RuntimeError):
         binding.load()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: `bench.py --gpus N` with N > 1 exits with a message."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
+
+
+def test_workspace_layout_covers_all_three_bf16_mlp_paths(monkeypatch):
+    """Host-side layout only (no GPU): the fused, wide-layer and generic bf16 configurations
+    all produce a workspace size, and the wide-layer path needs more than the generic one
+    (bf16 weight snapshots, transposed copies, weight-gradient slices)."""
+    from paper_2003_03477_amd import binding, synth
+    import ctypes as C
+    lib = binding.load()
+
+    def size(wl, **env):
+        for k in ("SS_NO_FUSED_MLP", "SS_NO_WIDE_GEMM"):
+            monkeypatch.delenv(k, raising=False)
+        for k, v in env.items():
+            monkeypatch.setenv(k, v)
+        rows = (C.c_int64 * len(wl.rows))(*wl.rows)
+        bot = (C.c_int32 * len(wl.bot_dims))(*wl.bot_dims)
+        top = (C.c_int32 * len(wl.top_dims))(*wl.top_dims)
+        cfg = binding.ss_config(len(wl.rows), rows, wl.emb_dim, wl.bot_dims[0], len(wl.bot_dims), bot,
+                                len(wl.top_dims), top, wl.num_replicas, wl.batch, 400000, 2,
+                                binding.SS_BF16, 0.01, 0.01, 1e-8, 1, 0)
+        return lib.ss_workspace_bytes(C.byref(cfg))
+
+    mid = synth.mid()
+    fused = size(mid)
+    wide = size(mid, SS_NO_FUSED_MLP="1")
+    generic = size(mid, SS_NO_FUSED_MLP="1", SS_NO_WIDE_GEMM="1")
+    assert fused > 0 and wide > 0 and generic > 0
+    assert wide > generic and fused > generic
