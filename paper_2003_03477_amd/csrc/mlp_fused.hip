@@ -65,8 +65,9 @@ __device__ __forceinline__ Frag load_frag(const uint16_t* __restrict__ Wsw, int 
 // output columns of tile w (widths up to 512), so acc is one 32x32 accumulator.  A comes from
 // LDS (row stride lda bf16), B fragments from the fragment-ordered copy.  DEPTH reduction
 // steps (8 or 4) are kept in flight per wave (16 waves x 8 steps x 1 KB = 128 KB of weights
-// requested at once); steps is a multiple of DEPTH (the reduction length is zero padded) and
-// the loop body has no branches, so the loads stay in flight behind the MFMAs.  The first
+// requested at once); steps is a multiple of DEPTH (the reduction length is zero padded), the
+// loop body has no branches, so the loads stay in flight behind the MFMAs, and the last group
+// is peeled off so that no request is issued that nobody will use.  The first
 // group is loaded separately (load_group) so that the caller can issue it early -- before the
 // input tile is staged, or before the previous layer's epilogue -- and its latency is hidden.
 template <int DEPTH>
@@ -81,14 +82,19 @@ __device__ __forceinline__ void run_gemm(f32x16& acc, Frag (&q)[8],
                                          const uint16_t* __restrict__ A, int lda, int steps,
                                          int tile, int lane, const uint16_t* __restrict__ Wsw) {
   const int frow = lane & 31, fk = (lane >> 5) * 8;
-  for (int s0 = 0; s0 < steps; s0 += DEPTH) {
-    const int nx = min(s0 + DEPTH, steps - DEPTH);  // trailing refills re-read the last group
+  int s0 = 0;
+  for (; s0 + DEPTH < steps; s0 += DEPTH) {  // every group but the last refills its slots
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
       const bf16x8 a = *(const bf16x8*)(A + frow * lda + (s0 + d) * 16 + fk);
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[d].v, acc, 0, 0, 0);
-      if (steps > DEPTH) q[d] = load_frag(Wsw, tile, steps, nx + d, lane);
+      q[d] = load_frag(Wsw, tile, steps, s0 + DEPTH + d, lane);
     }
+  }
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) {  // last group: nothing left to request
+    const bf16x8 a = *(const bf16x8*)(A + frow * lda + (s0 + d) * 16 + fk);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[d].v, acc, 0, 0, 0);
   }
 }
 
