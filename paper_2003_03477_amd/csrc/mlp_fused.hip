@@ -352,38 +352,43 @@ __global__ __launch_bounds__(NT) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
     }
     __syncthreads();
     const uint16_t* aT = g.actT[nl - 1];
-    for (int k = tid; k < Wp0; k += NT) {
-      const bool kok = k < wlast;
-      const float wq = kok ? b2f(f2b(g.w_last[k])) : 0.f;
-      float acc = 0.f;
-      if (kok && full_tile) {
-        // the 32 samples of unit k are 64 contiguous bytes in both transposed arrays
-        const uint4* ap4 = (const uint4*)(aT + (size_t)k * g.ldT + b0);
-        uint4* dp4 = (uint4*)(g.dYT[nl - 1] + (size_t)k * g.ldT + b0);
-        uint4 av[4];
+    if (full_tile) {
+      // four threads per unit, eight samples each: the 32 samples of unit k are 64 contiguous
+      // bytes in both transposed arrays, 16 of them per thread
+      for (int i = tid; i < Wp0 * 4; i += NT) {
+        const int k = i >> 2, c = i & 3;
+        const bool kok = k < wlast;
+        const float wq = kok ? b2f(f2b(g.w_last[k])) : 0.f;
+        float acc = 0.f;
+        uint4 av = make_uint4(0, 0, 0, 0);
+        if (kok) av = *((const uint4*)(aT + (size_t)k * g.ldT + b0) + c);
+        const uint32_t w4[4] = {av.x, av.y, av.z, av.w};
+        uint32_t o4[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) av[c] = ap4[c];
+        for (int h2 = 0; h2 < 4; ++h2) {
+          uint32_t ow = 0;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const uint32_t w4[4] = {av[c].x, av[c].y, av[c].z, av[c].w};
-          uint32_t o4[4];
-#pragma unroll
-          for (int h2 = 0; h2 < 4; ++h2) {
-            uint32_t ow = 0;
-#pragma unroll
-            for (int q2 = 0; q2 < 2; ++q2) {
-              const int r = c * 8 + h2 * 2 + q2;
-              const uint16_t a = (uint16_t)(w4[h2] >> (16 * q2));
-              acc += dlq[r] * b2f(a);
-              const uint16_t out = ((int16_t)a > 0) ? f2b(dlq[r] * wq) : (uint16_t)0;
-              buf[0][r * ld0 + k] = out;
-              ow |= (uint32_t)out << (16 * q2);
-            }
-            o4[h2] = ow;
+          for (int q2 = 0; q2 < 2; ++q2) {
+            const int r = c * 8 + h2 * 2 + q2;
+            const uint16_t a = (uint16_t)(w4[h2] >> (16 * q2));
+            acc += dlq[r] * b2f(a);
+            const uint16_t out = (kok && (int16_t)a > 0) ? f2b(dlq[r] * wq) : (uint16_t)0;
+            buf[0][r * ld0 + k] = out;
+            ow |= (uint32_t)out << (16 * q2);
           }
-          dp4[c] = make_uint4(o4[0], o4[1], o4[2], o4[3]);
+          o4[h2] = ow;
         }
-      } else {
+        if (kok) *((uint4*)(g.dYT[nl - 1] + (size_t)k * g.ldT + b0) + c) = make_uint4(o4[0], o4[1], o4[2], o4[3]);
+        // the four threads of a unit are neighbouring lanes
+        acc += __shfl_xor(acc, 1);
+        acc += __shfl_xor(acc, 2);
+        if (kok && c == 0) atomicAdd(g.g_w_last + k, acc);
+      }
+    } else {
+      for (int k = tid; k < Wp0; k += NT) {
+        const bool kok = k < wlast;
+        const float wq = kok ? b2f(f2b(g.w_last[k])) : 0.f;
+        float acc = 0.f;
         for (int r = 0; r < TB; ++r) {
           const int b = b0 + r;
           uint16_t out = 0;
@@ -395,8 +400,8 @@ __global__ __launch_bounds__(NT) void mlp_fused_bwd_kernel(FusedBwdArgs g) {
           }
           buf[0][r * ld0 + k] = out;
         }
+        if (kok) atomicAdd(g.g_w_last + k, acc);
       }
-      if (kok) atomicAdd(g.g_w_last + k, acc);
     }
     if (tid == 0) {
       float sb = 0.f;
