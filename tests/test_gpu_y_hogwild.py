@@ -1,8 +1,10 @@
 """Hogwild mode: several lock-free worker streams on one replica plus a continuously looping
 shadow stream.  The racy run has no unique result, so the check is statistical: the
-window-averaged log-loss curve of the device run must stay within 1 % of the oracle's curve on
-the serialised schedule (worker 0's batch, worker 1's batch, ...; sync rounds spread evenly
-at the device run's measured rate of rounds per step) over the same batches."""
+window-averaged log-loss curve of the device run must stay within 1 % of the oracle's curve over
+the same batches, sync rounds spread evenly at the device run's measured rate of rounds per
+step.  The oracle's curve is taken for the two extreme interleavings of a lock-free run (fully
+serialised workers; workers of a replica that all start a round from the same state), which
+differ by about half a percent themselves; the device run has to lie within 1 % of that band."""
 import threading
 
 import numpy as np
@@ -67,26 +69,61 @@ def test_hogwild_logloss_curve_tracks_serialised_oracle():
     got = losses.cpu().numpy().astype(np.float64)          # [worker, step]
     assert np.all(np.isfinite(got)) and np.all(got > 0)
 
-    # oracle: serialised schedule on the same batches
+    # Oracle, two interleavings of the same lock-free run on the same batches, sync rounds
+    # spread evenly at the measured rate:
+    #   serial:     worker 0's batch, worker 1's batch, ... each on the fully updated state;
+    #   concurrent: the W0 workers of replica 0 start every round from the SAME state and
+    #               their changes (dense replica, touched rows, Adagrad accumulators) are summed,
+    #               i.e. every worker computes on weights that miss its peers' current updates.
+    # A real run lies between the two: how far depends on how the streams happen to overlap.
     per_step = rounds / float(NW * S)      # sync rounds per global step (either side of 1)
-    orc = oracle.OracleTrainer(wl.bot_dims, wl.top_dims, wl.row_base, synth.full_tables_h0(wl), w0,
-                               wl.num_replicas, wl.lr_dense, wl.lr_emb, wl.adagrad_eps,
-                               bf16=wl.bf16)
-    want = np.zeros_like(got)
-    due = 0.0
-    for s in range(S):
-        for w in range(NW):
-            want[w, s] = orc.train_step(0 if w < W0 else 1, *batches[w][s].as_tuple())
-            due += per_step
-            while due >= 1.0:
-                orc.shadow_sync(wl.algo, wl.alpha)
-                due -= 1.0
-    # window-averaged curves (all workers, windows of 10 steps = 50 batches)
-    win = 10
-    gc = got.mean(axis=0).reshape(S // win, win).mean(axis=1)
-    wc = want.mean(axis=0).reshape(S // win, win).mean(axis=1)
-    rel = np.abs(gc - wc) / wc
-    print(f"hogwild windows: device {gc}, oracle {wc}, rel {rel}, rounds {rounds}")
-    assert np.all(rel < 0.01), f"log-loss curves differ: device {gc}, oracle {wc}"
-    assert wc[-1] < wc[0]                                   # the model is actually learning
+
+    def make_oracle():
+        return oracle.OracleTrainer(wl.bot_dims, wl.top_dims, wl.row_base,
+                                    synth.full_tables_h0(wl), w0, wl.num_replicas, wl.lr_dense,
+                                    wl.lr_emb, wl.adagrad_eps, bf16=wl.bf16)
+
+    def run_oracle(concurrent):
+        orc = make_oracle()
+        out = np.zeros_like(got)
+        due = 0.0
+        for s in range(S):
+            if concurrent:
+                rows = np.unique(np.concatenate([
+                    oracle.dlrm.global_rows(wl.row_base, batches[w][s].indices, batches[w][s].offsets,
+                                            wl.batch) for w in range(W0)]))
+                W_s, h_s, G_s = orc.W[0].copy(), orc.h[rows].copy(), orc.G[rows].copy()
+                dW, dh, dG = np.zeros_like(W_s), np.zeros_like(h_s), np.zeros_like(G_s)
+                for w in range(W0):
+                    orc.W[0][:] = W_s; orc.h[rows] = h_s; orc.G[rows] = G_s
+                    out[w, s] = orc.train_step(0, *batches[w][s].as_tuple())
+                    dW += orc.W[0] - W_s; dh += orc.h[rows] - h_s; dG += orc.G[rows] - G_s
+                orc.W[0][:] = W_s + dW; orc.h[rows] = h_s + dh; orc.G[rows] = G_s + dG
+                for w in range(W0, NW):
+                    out[w, s] = orc.train_step(1, *batches[w][s].as_tuple())
+            else:
+                for w in range(NW):
+                    out[w, s] = orc.train_step(0 if w < W0 else 1, *batches[w][s].as_tuple())
+            for _ in range(NW):
+                due += per_step
+                while due >= 1.0:
+                    orc.shadow_sync(wl.algo, wl.alpha)
+                    due -= 1.0
+        return out
+
+    win = 10                               # windows of 10 steps = 50 batches, all workers
+
+    def curve(x):
+        return x.mean(axis=0).reshape(S // win, win).mean(axis=1)
+
+    gc, sc, cc = curve(got), curve(run_oracle(False)), curve(run_oracle(True))
+    lo, hi = np.minimum(sc, cc), np.maximum(sc, cc)
+    print(f"hogwild windows: device {gc}, oracle serial {sc}, oracle concurrent {cc}, "
+          f"rel to serial {(gc - sc) / sc}, rounds {rounds}")
+    # within 1 % of the oracle's curve, the oracle's curve being the band between its two
+    # interleavings
+    assert np.all(gc > 0.99 * lo) and np.all(gc < 1.01 * hi), \
+        f"log-loss curves differ: device {gc}, oracle serial {sc}, concurrent {cc}"
+    assert np.all(np.abs(cc - sc) / sc < 0.01)              # the band itself is narrow
+    assert sc[-1] < sc[0] and gc[-1] < gc[0]                # the model is actually learning
     gpu.close()
