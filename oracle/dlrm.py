@@ -6,7 +6,8 @@ top MLP, backward, embedding gradients pushed to the tables (lock-free optimiser
 update with co-located Adagrad state, Section 3.2 "Embedding Tables: Hogwild
 Updates"), dense parameters updated in place (Section 3.2 "Interactions and MLPs").
 It defers the model itself to the DLRM paper, so the concrete formulas below are the
-readings recorded in the design notes: sum pooling, pairwise-dot interaction over the
+readings this implementation takes: sum pooling (mean pooling, the paper's own example, as an
+option), pairwise-dot interaction over the
 bottom output and the T pooled vectors (strictly lower triangle, row-major, appended
 after the bottom output), ReLU everywhere except the last top layer, mean binary
 cross-entropy on the logit, plain SGD on dense weights, row-wise Adagrad on tables.
