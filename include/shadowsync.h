@@ -65,6 +65,11 @@ typedef enum { SS_FP32 = 0, SS_BF16 = 1 } ss_mlp_prec;
  * carries 1 / length. */
 typedef enum { SS_POOL_SUM = 0, SS_POOL_MEAN = 1 } ss_pooling;
 
+/* Which bf16 MLP kernels run the model.  SS_MLP_AUTO picks by layer width: the per-sample-tile
+ * fused kernels when every width is <= 512, the layer-wise 128x128-tile MFMA GEMMs otherwise.
+ * SS_MLP_LAYERWISE forces the layer-wise GEMMs for any width.  Ignored under SS_FP32. */
+typedef enum { SS_MLP_AUTO = 0, SS_MLP_LAYERWISE = 1 } ss_mlp_path;
+
 typedef struct {
   int32_t num_tables;        /* T, 1..64                                                  */
   const int64_t* rows;       /* host [T] rows per table; sum < 2^32                      */
@@ -86,6 +91,7 @@ typedef struct {
   float adagrad_eps;
   uint64_t seed;             /* seed of the counter-based table initialiser             */
   int32_t pooling;           /* ss_pooling                                               */
+  int32_t mlp_path;          /* ss_mlp_path                                              */
 } ss_config;
 
 /* One mini-batch.  All pointers are DEVICE pointers owned by the caller and must stay
@@ -151,7 +157,10 @@ int ss_eval_step(ss_ctx* ctx, int32_t replica, int32_t worker_slot, const ss_bat
  *  SS_MA:    w^global = mean_i w^(i); w^(i) = (1-alpha) w^(i) + alpha w^global
  *  SS_BMUF:  m = mean_i w^(i); v = momentum v + eta (m - w^global); w^global += v;
  *            w^(i) = (1-alpha) w^(i) + alpha w^global
- * eta and momentum are ignored except by SS_BMUF.  One fused, memory-bound kernel. */
+ *  SS_BMUF_NESTEROV: v and w^global as in SS_BMUF;
+ *            w^(i) = (1-alpha) w^(i) + alpha (w^global + momentum v)
+ * eta and momentum are used by SS_BMUF and SS_BMUF_NESTEROV only.  One fused, memory-bound
+ * kernel. */
 int ss_shadow_sync(ss_ctx* ctx, int32_t algo, float alpha, float eta, float momentum,
                    void* stream);
 
@@ -170,10 +179,10 @@ int ss_sync_round(int32_t algo, int32_t K, int64_t P, int64_t stride, float* dev
                   float* dev_w_ps, float* dev_w_global, float* dev_v, float alpha, float eta,
                   float momentum, void* stream);
 
-/* Algorithm 1's shadow thread: a host thread owned by the context that enqueues rounds on
- * `stream` one after another ("looping the synchronization without any knowledge of the
- * training process") until ss_shadow_stop.  The stream must not be used by the caller
- * while the loop runs. */
+/* Algorithm 1's shadow thread (shadow loop; Section 3.2): a host thread owned by the context
+ * that enqueues rounds on `stream` one after another, with no coupling to the worker
+ * iterations, until ss_shadow_stop.  The stream must not be used by the caller while the loop
+ * runs. */
 int ss_shadow_start(ss_ctx* ctx, int32_t algo, float alpha, float eta, float momentum,
                     void* stream);
 int ss_shadow_stop(ss_ctx* ctx);

@@ -104,17 +104,28 @@ def mlp_forward(x, layers, relu_last: bool, q=_identity):
     return acts
 
 
-def mlp_backward(acts, layers, d_out, relu_last: bool, q=_identity):
+def mlp_backward(acts, layers, d_out, relu_last: bool, q=_identity, gate_flips=None):
     """Back-propagation through mlp_forward.  d_out is dL/d(a_L).  Returns
     (list of (dW, db) per layer, dL/d(a_0)).  ReLU passes gradient where its output
-    is positive."""
+    is positive.
+
+    gate_flips (optional): {layer index: (sample indices, unit indices)} of ReLU units whose
+    gate decision is to be INVERTED.  A gate is a floating-point comparison with zero; for a
+    pre-activation that is zero to within the accumulation error of the precision the product
+    was formed in, both outcomes are valid results of this definition.  The parity harness
+    uses this to take such undecidable decisions the way the device's fp32 accumulation took
+    them (it only ever lists units whose pre-activation here is that close to zero)."""
     n = len(layers)
     grads = [None] * n
     d = d_out
     for li in range(n - 1, -1, -1):
         W, _ = layers[li]
         if li < n - 1 or relu_last:
-            d = d * (acts[li + 1] > 0)
+            gate = acts[li + 1] > 0
+            if gate_flips and li in gate_flips:
+                bb, uu = gate_flips[li]
+                gate[bb, uu] = ~gate[bb, uu]
+            d = d * gate
         dW = q(d).T @ q(acts[li])
         db = d.sum(axis=0)
         grads[li] = (dW, db)
@@ -291,14 +302,20 @@ def dlrm_forward(layout: DenseLayout, w, h, row_base, x, indices, offsets, bf16=
                 bot=bot, top=top, q=q)
 
 
-def dlrm_backward(layout: DenseLayout, fw, y):
+def dlrm_backward(layout: DenseLayout, fw, y, gate_flips=None):
     """Loss and gradients.  Returns (L, dense gradient vector laid out like w,
-    de (B, T, d))."""
+    de (B, T, d)).  gate_flips: see mlp_backward; keys are layer indices counted over the
+    whole model (bottom layers first)."""
     L, dlogit = bce_with_logits(fw["logit"], y)
     q = fw["q"]
-    g_top, df = mlp_backward(fw["acts_top"], fw["top"], dlogit[:, None], False, q)
+    nb = layout.n_bot
+    flips_bot = flips_top = None
+    if gate_flips:
+        flips_bot = {l: v for l, v in gate_flips.items() if l < nb}
+        flips_top = {l - nb: v for l, v in gate_flips.items() if l >= nb}
+    g_top, df = mlp_backward(fw["acts_top"], fw["top"], dlogit[:, None], False, q, flips_top)
     dz0, de = interaction_backward(fw["z0"], fw["e"], df)
-    g_bot, _ = mlp_backward(fw["acts_bot"], fw["bot"], dz0, True, q)
+    g_bot, _ = mlp_backward(fw["acts_bot"], fw["bot"], dz0, True, q, flips_bot)
     parts = []
     for dW, db in g_bot + g_top:
         parts += [dW.ravel(), db.ravel()]

@@ -17,8 +17,8 @@ import numpy as np
 
 def easgd_round(W, w_ps, alpha):
     """Shadow EASGD (Algorithm 2), reading both assignments with the values held
-    before the exchange, i.e. the symmetric elastic move of the original EASGD that the
-    text says it is "essentially the same as":
+    before the exchange, i.e. the symmetric elastic move of the original EASGD (the
+    discussion after Algorithm 4 likens the rule to it):
         delta = alpha * (w^(i) - w^PS);  w^PS += delta;  w^(i) -= delta.
     This reading conserves sum_i w^(i) + w^PS.  Replicas exchange one after another,
     so replica i+1 meets the centre already moved by replica i."""

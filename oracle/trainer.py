@@ -41,16 +41,17 @@ class OracleTrainer:
         self.last = None
 
     # ------------------------------------------------------------------ worker thread
-    def train_step(self, replica, x, y, indices, offsets, update=True):
+    def train_step(self, replica, x, y, indices, offsets, update=True, gate_flips=None):
         """One worker iteration (Algorithm 1, worker loop; Section 3.1 "Trainer"):
         forward, loss, backward, then "update h" and "update local param w^(i)".
-        Returns the mean log-loss of the batch BEFORE the update."""
+        Returns the mean log-loss of the batch BEFORE the update.
+        gate_flips: undecidable ReLU gates to take the other way (dlrm.mlp_backward)."""
         B = x.shape[0]
         L = self.layout
         w = self.W[replica]
         fw = dlrm.dlrm_forward(L, w, self.h, self.row_base, x, indices, offsets,
                                bf16=self.bf16, pooling=self.pooling)
-        loss, g, de = dlrm.dlrm_backward(L, fw, y.astype(self.dtype))
+        loss, g, de = dlrm.dlrm_backward(L, fw, y.astype(self.dtype), gate_flips)
         keys = dlrm.global_rows(self.row_base, indices, offsets, B)
         bag = dlrm.bag_of_position(offsets, B, self.T)
         scale = None
@@ -59,6 +60,7 @@ class OracleTrainer:
         rows, g_rows, sk, perm, heads = dlrm.embedding_row_gradients(
             de.reshape(B * self.T, self.d), keys, bag, scale)
         self.last = dict(e=fw["e"], f=fw["f"], logit=fw["logit"], z0=fw["z0"], g=g,
+                         acts_bot=fw["acts_bot"], acts_top=fw["acts_top"],
                          de=de, sorted_keys=sk, sorted_pos=perm, seg_starts=heads,
                          rows=rows, g_rows=g_rows, bag_of_pos=bag)
         if update:

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libshadowsync.so")
 SS_EASGD, SS_MA, SS_BMUF, SS_EASGD_LITERAL, SS_BMUF_NESTEROV = 0, 1, 2, 3, 4
 SS_FP32, SS_BF16 = 0, 1
 POOLING = {"sum": 0, "mean": 1}
+MLP_PATHS = {"auto": 0, "layerwise": 1}
 ALGOS = {"easgd": SS_EASGD, "ma": SS_MA, "bmuf": SS_BMUF, "easgd_literal": SS_EASGD_LITERAL,
          "bmuf_nesterov": SS_BMUF_NESTEROV}
 
@@ -49,7 +50,8 @@ class ss_config(C.Structure):
                 ("num_replicas", C.c_int32), ("max_batch", C.c_int32),
                 ("max_ids", C.c_int64), ("num_worker_slots", C.c_int32),
                 ("mlp_prec", C.c_int32), ("lr_dense", C.c_float), ("lr_emb", C.c_float),
-                ("adagrad_eps", C.c_float), ("seed", C.c_uint64), ("pooling", C.c_int32)]
+                ("adagrad_eps", C.c_float), ("seed", C.c_uint64), ("pooling", C.c_int32),
+                ("mlp_path", C.c_int32)]
 
 
 class ss_batch(C.Structure):
@@ -155,7 +157,7 @@ class ShadowSync:
                  top_dims: Sequence[int], num_replicas: int, max_batch: int, max_ids: int,
                  num_worker_slots: int = 1, bf16: bool = False, lr_dense: float = 0.01,
                  lr_emb: float = 0.01, adagrad_eps: float = 1e-8, seed: int = 0,
-                 device: str = "cuda:0", pooling: str = "sum"):
+                 device: str = "cuda:0", pooling: str = "sum", mlp_path: str = "auto"):
         import torch
         self.lib = load()
         self.torch = torch
@@ -166,7 +168,8 @@ class ShadowSync:
         self.cfg = ss_config(len(rows), self._rows, emb_dim, bot_dims[0], len(bot_dims),
                              self._bot, len(top_dims), self._top, num_replicas, max_batch,
                              max_ids, num_worker_slots, SS_BF16 if bf16 else SS_FP32,
-                             lr_dense, lr_emb, adagrad_eps, seed, POOLING[pooling])
+                             lr_dense, lr_emb, adagrad_eps, seed, POOLING[pooling],
+                             MLP_PATHS[mlp_path])
         self.rows, self.emb_dim, self.K = list(rows), emb_dim, num_replicas
         self.T = len(rows)
         self.ctx = C.c_void_p()
@@ -335,7 +338,7 @@ def normalized_entropy(mean_logloss: float, ctr: float) -> float:
 
 
 def from_workload(wl, rows=None, num_worker_slots: int = 1, max_ids: Optional[int] = None,
-                  device="cuda:0") -> ShadowSync:
+                  device="cuda:0", mlp_path: str = "auto") -> ShadowSync:
     """Context sized for a synth.Workload (rows may be overridden by a compacted problem)."""
     rows = list(rows if rows is not None else wl.rows)
     if max_ids is None:
@@ -343,4 +346,4 @@ def from_workload(wl, rows=None, num_worker_slots: int = 1, max_ids: Optional[in
         max_ids = int(wl.batch * wl.num_tables * (lam + 6 * (lam ** 0.5) / (wl.batch ** 0.5)) + 4096)
     return ShadowSync(rows, wl.emb_dim, wl.bot_dims, wl.top_dims, wl.num_replicas, wl.batch,
                       max_ids, num_worker_slots, wl.bf16, wl.lr_dense, wl.lr_emb,
-                      wl.adagrad_eps, wl.seed, device, wl.pooling)
+                      wl.adagrad_eps, wl.seed, device, wl.pooling, mlp_path)

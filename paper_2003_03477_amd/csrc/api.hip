@@ -66,7 +66,8 @@ struct Slot {
   // results of the last step (for ss_read_debug)
   uint32_t* sorted_keys = nullptr;
   uint32_t* sorted_pos = nullptr;
-  uint32_t last_n = 0;
+  uint32_t last_n = 0;             // ids of the last forward pass (training or evaluation)
+  uint32_t sort_n = 0;             // ids of the last TRAINING step: length of the sorted arrays
   int last_B = 0;
   bool seg_valid = false;
   bool trained = false;
@@ -132,6 +133,7 @@ struct ss_ctx {
   float* w_mean;  // replica average, filled on request (ss_read_dense with which = -4)
   std::vector<Slot> slots;
   // state
+  std::mutex err_mu;               // guards err: concurrent callers may fail at the same time
   std::string err;
   std::atomic<int> sticky{0};
   std::vector<std::atomic<uint64_t>> steps;
@@ -155,6 +157,7 @@ struct ss_ctx {
   }
 };
 
+static std::mutex g_init_err_mu;
 static std::string g_init_err;
 
 static int fail(ss_ctx* ctx, int code, const char* fmt, ...) {
@@ -163,7 +166,13 @@ static int fail(ss_ctx* ctx, int code, const char* fmt, ...) {
   va_start(ap, fmt);
   vsnprintf(buf, sizeof buf, fmt, ap);
   va_end(ap);
-  if (ctx) ctx->err = buf; else g_init_err = buf;
+  if (ctx) {
+    std::lock_guard<std::mutex> lk(ctx->err_mu);
+    ctx->err = buf;
+  } else {
+    std::lock_guard<std::mutex> lk(g_init_err_mu);
+    g_init_err = buf;
+  }
   return code;
 }
 
@@ -212,6 +221,7 @@ static int validate(const ss_config* c, std::string& why) {
   if (c->num_worker_slots < 1 || c->num_worker_slots > 64) BAD("num_worker_slots must be 1..64");
   if (c->mlp_prec != SS_FP32 && c->mlp_prec != SS_BF16) BAD("bad mlp_prec");
   if (c->pooling != SS_POOL_SUM && c->pooling != SS_POOL_MEAN) BAD("bad pooling mode");
+  if (c->mlp_path != SS_MLP_AUTO && c->mlp_path != SS_MLP_LAYERWISE) BAD("bad mlp_path");
   const size_t shm = (size_t)4 * ((T + 1) * (c->emb_dim + 4) + (((T + 1) * (T + 1) + 3) & ~3)) * 4;
   if (shm > 64 * 1024) BAD("interaction tile (T+1) x d does not fit the LDS budget");
 #undef BAD
@@ -340,7 +350,7 @@ static ss_ctx* make_ctx(const ss_config* c) {
   {
     const int nb = x->n_bot_layers, nt = x->n_top_layers, nh = nt - 1;
     bool ok = x->prec == SS_BF16 && nh >= 1 && nb <= SS_FUSED_MAX_LAYERS &&
-              nh <= SS_FUSED_MAX_LAYERS && maxw <= 512 && !getenv("SS_NO_FUSED_MLP");
+              nh <= SS_FUSED_MAX_LAYERS && maxw <= 512 && c->mlp_path == SS_MLP_AUTO;
     if (ok) {
       // reduction lengths are zero padded to a multiple of 64; the prefetch depth of a layer is
       // the larger of 8 / 4 reduction steps that divides its step count
@@ -378,7 +388,7 @@ static ss_ctx* make_ctx(const ss_config* c) {
     // bf16 operands are multiples of 64 so that no GEMM needs edge handling along its reduction.
     const int64_t pw = (maxw + 63) / 64 * 64 + 64, pb = (x->max_batch + 63) / 64 * 64 + 64;
     x->wide = !ok && x->prec == SS_BF16 && nt >= 2 && (int)x->layers.size() <= SS_NT_MAX_LAYERS &&
-              pw * pb < (1ll << 31) && !getenv("SS_NO_WIDE_GEMM");
+              pw * pb < (1ll << 31);
     if (x->wide) {
       // row pitches: multiples of 64 elements, never a multiple of 256 (rows that are a power
       // of two apart would all fall on the same memory channel)
@@ -433,7 +443,7 @@ extern "C" {
 
 size_t ss_workspace_bytes(const ss_config* cfg) {
   std::string why;
-  if (validate(cfg, why) != SS_OK) { g_init_err = why; return 0; }
+  if (validate(cfg, why) != SS_OK) { fail(nullptr, SS_EINVAL, "%s", why.c_str()); return 0; }
   ss_ctx* x = make_ctx(cfg);
   size_t bytes = layout(x, nullptr);
   delete x;
@@ -493,7 +503,19 @@ void ss_destroy(ss_ctx* ctx) {
   delete ctx;
 }
 
-const char* ss_last_error(const ss_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_err.c_str(); }
+const char* ss_last_error(const ss_ctx* ctx) {
+  // the text is copied under the lock into storage owned by the calling thread, so the pointer
+  // stays valid while other threads fail
+  static thread_local std::string copy;
+  if (ctx) {
+    std::lock_guard<std::mutex> lk(const_cast<ss_ctx*>(ctx)->err_mu);
+    copy = ctx->err;
+  } else {
+    std::lock_guard<std::mutex> lk(g_init_err_mu);
+    copy = g_init_err;
+  }
+  return copy.c_str();
+}
 
 int64_t ss_num_params(const ss_ctx* ctx) { return ctx ? ctx->P : -1; }
 
@@ -1090,6 +1112,7 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
   s.last_B = B;
   s.last_n = n;
   if (train) {
+    s.sort_n = n;
     if (x->fused) backward_fused(x, s, w, bt, st);
     else if (x->wide) backward_wide(x, s, w, bt, st);
     else backward_dense(x, s, w, bt, st);
@@ -1191,7 +1214,7 @@ int ss_shadow_start(ss_ctx* ctx, int32_t algo, float alpha, float eta, float mom
   hipStream_t st = (hipStream_t)stream;
   ctx->shadow = std::thread([ctx, algo, alpha, eta, momentum, st]() {
     if (hipSetDevice(ctx->device) != hipSuccess) { ctx->sticky = 1; return; }
-    // "simply looping the synchronization without any knowledge of the training process"
+    // Algorithm 1, shadow loop (Section 3.2): rounds follow one another, uncoupled from the workers
     while (ctx->shadow_run.load()) {
       if (sync_once(ctx, algo, alpha, eta, momentum, st) != SS_OK) break;
       if (hipStreamSynchronize(st) != hipSuccess) { ctx->sticky = 1; break; }
@@ -1217,7 +1240,7 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
   if (worker_slot < 0 || worker_slot >= ctx->num_slots) return fail(ctx, SS_EINVAL, "bad slot");
   Slot& s = ctx->slots[worker_slot];
   HIP_TRY(ctx, hipDeviceSynchronize());
-  const size_t B = (size_t)s.last_B, n = s.last_n;
+  const size_t B = (size_t)s.last_B, n = s.last_n, ns = s.sort_n;
   const void* src = nullptr; size_t size = 0; size_t pitch_src = 0, width = 0, rows = 0;
   uint32_t U = 0;
   if (item == SS_DBG_SEG_STARTS || item == SS_DBG_NUM_UNIQUE) {
@@ -1225,7 +1248,7 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
     if (!s.seg_valid) {
       // the row update works on the runs of equal keys directly; the compacted list of run
       // starts is derived from the same sorted keys when somebody asks for it
-      launch_segment_starts(s.sorted_keys, s.last_n, s.seg, nullptr);
+      launch_segment_starts(s.sorted_keys, s.sort_n, s.seg, nullptr);
       HIP_TRY(ctx, hipDeviceSynchronize());
       s.seg_valid = true;
     }
@@ -1237,8 +1260,8 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
     case SS_DBG_LOGITS: src = s.logits; size = B * 4; break;
     case SS_DBG_DENSE_GRAD: src = s.grads; size = (size_t)ctx->P * 4; break;
     case SS_DBG_POOLED_GRAD: src = s.de; size = B * ctx->T * ctx->d * 4; break;
-    case SS_DBG_SORTED_ROWS: src = s.sorted_keys; size = n * 4; break;
-    case SS_DBG_SORTED_POS: src = s.sorted_pos; size = n * 4; break;
+    case SS_DBG_SORTED_ROWS: src = s.sorted_keys; size = ns * 4; break;
+    case SS_DBG_SORTED_POS: src = s.sorted_pos; size = ns * 4; break;
     case SS_DBG_SEG_STARTS: src = s.seg.seg_starts; size = (size_t)U * 4; break;
     case SS_DBG_NUM_UNIQUE: src = s.seg.num_unique; size = 4; break;
     case SS_DBG_BAG_OF_POS: src = s.bag_of_pos; size = n * 4; break;

@@ -16,8 +16,10 @@
 //              mean log-loss and dL/dlogit);
 //   backward : dL/da_L -> ... -> dL/da_0 (data gradients only), ReLU-gated;
 //   wgrad    : all weight and bias gradients of all layers in one grouped launch,
-//              dW_l = dY_l^T X_l as wave-sized 32x32 tiles over batch slices, accumulated
-//              with atomics.
+//              dW_l = dY_l^T X_l as 64x64 tiles, one block of four waves per tile; each wave
+//              keeps the whole tile in registers over its quarter of the batch, the four
+//              partial tiles are folded through LDS and stored once (added atomically only
+//              when the batch is also split over blocks, one slice per ~1024 samples).
 // Activations and gradients that cross kernels are stored TRANSPOSED ([unit][sample], bf16):
 // an MFMA accumulator holds 4 consecutive samples of one unit per lane, so this is the cheap
 // direction to store, it is the layout the ReLU gate wants to read, and it makes the batch

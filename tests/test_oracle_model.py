@@ -109,6 +109,59 @@ def test_matches_torch_autograd(seed):
     np.testing.assert_allclose(h.grad.numpy(), dh, rtol=1e-10, atol=1e-13)
 
 
+def test_gate_flips_equal_autograd_with_the_other_gate_decision():
+    """mlp_backward's gate_flips: inverting the ReLU decision of listed units equals autograd
+    through the same model in which each activation is its forward value times a CONSTANT
+    0/1 gate, that gate being (pre-activation > 0) inverted at the listed units."""
+    rng = np.random.default_rng(11)
+    p = random_problem(rng, B=5, T=2, d=4, rows=(9, 4), bot=(3, 6, 4), top_hidden=(7, 5), max_len=3)
+    L = dlrm.DenseLayout(p["bot"], p["top"])
+    flips = {0: (np.array([0, 3]), np.array([2, 5])),      # bottom hidden layer
+             1: (np.array([1]), np.array([3])),            # bottom output (z0)
+             2: (np.array([4, 2]), np.array([0, 6])),      # top hidden layers
+             3: (np.array([0]), np.array([1]))}
+    fw = dlrm.dlrm_forward(L, p["w"], p["h"], p["row_base"], p["x"], p["indices"], p["offsets"],
+                           fast=False)
+    loss0, g0, de0 = dlrm.dlrm_backward(L, fw, p["y"])
+    loss, g, de = dlrm.dlrm_backward(L, fw, p["y"], gate_flips=flips)
+    assert loss == loss0 and not np.allclose(g, g0)
+    B, T, d = p["B"], p["T"], p["d"]
+    w = torch.tensor(p["w"], requires_grad=True)
+    layers, pos = [], 0
+    for o, i in L.layer_shapes():
+        W = w[pos:pos + o * i].view(o, i); pos += o * i
+        b = w[pos:pos + o]; pos += o
+        layers.append((W, b))
+    e_t = torch.tensor(fw["e"], requires_grad=True)
+
+    def gated(pre, li):
+        gate = (pre.detach() > 0)
+        if li in flips:
+            bb, uu = flips[li]
+            gate[torch.tensor(bb), torch.tensor(uu)] ^= True
+        # forward value unchanged (the oracle keeps its forward pass), gradient through the gate
+        return (torch.relu(pre) - pre * gate.double()).detach() + pre * gate.double()
+
+    z = torch.tensor(p["x"])
+    for li in range(L.n_bot):
+        W, b = layers[li]
+        z = gated(torch.nn.functional.linear(z, W, b), li)
+    V = torch.cat([z[:, None, :], e_t], dim=1)
+    Gm = V @ V.transpose(1, 2)
+    rr, cc = torch.tril_indices(T + 1, T + 1, offset=-1)
+    a = torch.cat([z, Gm[:, rr, cc]], dim=1)
+    n_layers = len(layers)
+    for li in range(L.n_bot, n_layers):
+        W, b = layers[li]
+        a = torch.nn.functional.linear(a, W, b)
+        if li < n_layers - 1:
+            a = gated(a, li)
+    tl = torch.nn.functional.binary_cross_entropy_with_logits(a[:, 0], torch.tensor(p["y"]))
+    tl.backward()
+    np.testing.assert_allclose(w.grad.numpy(), g, rtol=1e-10, atol=1e-13)
+    np.testing.assert_allclose(e_t.grad.numpy(), de, rtol=1e-10, atol=1e-13)
+
+
 # ----------------------------------------------------------------------------- embedding
 def _multiplicity(p):
     B, T = p["B"], p["T"]
