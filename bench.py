@@ -1,27 +1,39 @@
 #!/usr/bin/env python3
 """Throughput of the ShadowSync hot path on one MI355X.
 
-Workload (default): the Mid CTR model -- 13 dense features, 8 tables x 1e6 rows x dim 64
-fp32, ids Zipf(1.05), bag length Poisson(20)+1, bottom MLP 13-256-128-64, top MLP
-100-512-256-1 with bf16 MFMA GEMMs over fp32 master weights, batch 2048, K=4 replicas each
-fed by 2 lock-free worker streams (one host thread per stream), Shadow EASGD (alpha 0.1) enqueued
-on a separate stream once per 5 trainer iterations of a replica.  One bench "step" = one
-ss_train_step on one batch (forward, loss, backward, SGD on the replica, sort + segmented
-reduction + row-wise Adagrad on the tables); steps go round-robin over the K replicas.
-Inputs are seeded synthetic batches already resident in HBM when the clock starts.
+Headline workload (default): the Large CTR model -- 13 dense features, 26 tables of about
+1.8e8 rows x dim 64 fp32 (46 GB) filled on the device, ids Zipf(1.1), bag length Poisson(30)+1,
+bottom MLP 13-512-256-64, top MLP 415-1024-1024-512-256-1 with bf16 MFMA GEMMs over fp32 master
+weights, batch 8192, K=4 dense replicas, Shadow BMUF (block momentum 0.9, block lr 1.0) looping
+on its own stream beside the worker streams.  `--workload mid|hogwild|tiny` selects the others.
 
-Prints ONE JSON line.  Besides the contract fields it carries
-  roofline      the dominant single memory-bound kernel (largest summed time of the gather
-                and the row-update chunk pass), timed with HIP events inside the timed region
-  kernels       the same event timing for every kernel class
-  sync_isolation  the three shadow rules on K=8 x 50M-parameter replicas (GB/s vs HBM peak)
-  cpu_baseline  the numpy oracle on the host cores, on a bounded sample of the same workload
+One bench STEP = one SWEEP: every worker stream runs one ss_train_step (forward, loss,
+backward, SGD on its replica, sort + segmented reduction + row-wise Adagrad on the tables) on
+a batch of its own, so a step trains (worker streams x batch) examples; `--steps K` times
+exactly K sweeps.  Worker threads exist and every stream is warm before the clock starts.
+Inputs are seeded synthetic batches (>= 64 distinct ones, each owned by one stream) resident in
+HBM before the clock starts.
+
+Prints ONE JSON line.  Besides the contract fields:
+  no_shadow       the same K sweeps with the shadow stream off, and value / that (Section 3.2:
+                  training is not stalled by the synchronisation)
+  roofline        the kernel with the largest summed time over the timed region (all classes,
+                  MLP kernels against the bf16 MFMA peak, memory-bound ones against HBM peak),
+                  HIP events on the launching streams inside the timed region
+  kernels         event timing of every kernel class
+  sync_isolation  the three shadow rules on K=8 x 50M-parameter replicas, GB/s vs HBM peak
+  cpu_baseline    the numpy oracle on the host cores, on a bounded sample of the same workload
+  secondary       the Mid workload's throughput measured the same way (when the headline is Large)
+`--sweep widths|gap` adds the Hogwild width sweep (Section 4.4) / the sync gap against the
+number of replicas (Section 4.2) as a table inside the JSON.
 """
 from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
+import re
 import sys
 import threading
 import time
@@ -29,88 +41,355 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0  # MI355X datasheet
+HBM_PEAK_GBS = 8000.0        # MI355X datasheet
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
-# HBM bytes per launch measured with `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` on the
-# Mid and Large workloads (KiB per dispatch * 1024; FETCH_SIZE reads 0.50x and WRITE_SIZE 1.00x the
-# known size of a plain streaming kernel, so fetches are scaled by 2.00).  Sources:
-# profiles/mid_hbm_traffic.txt, profiles/large_hbm_traffic.txt.  None = not measured.
-MEASURED_TRAFFIC = {
-    "mid": {"gather": 52.9e6, "row_update_chunk": 125.2e6},
-    "large": {"gather": 601e6, "row_update_chunk": 1357e6},
-}
-# Average kernel duration (us) reported by `rocprofv3 --kernel-trace --stats` with ONE stream
-# active (profiles/mid_single_stream_kernel_stats.txt): the event brackets of the same run read
-# about 5.5 us more per launch.  Quoted next to the live event figures, never instead of them.
-PROFILER_ALONE_US = {
-    "mid": {"gather": 14.73, "row_update_chunk": 32.42},
-}
+# worker streams per replica when --workers-per-replica is not given
+DEFAULT_WORKERS = {"large": "2", "mid": "6", "tiny": "2", "hogwild": "8,1,1,1"}
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="mid", choices=["mid", "tiny", "hogwild", "large"])
-    ap.add_argument("--batches", type=int, default=16, help="distinct batches cycled through")
-    ap.add_argument("--foreground", type=int, default=0, metavar="K",
-                    help="foreground variant (FR-EASGD-k): every worker stream exchanges its "
-                         "replica with the centre copy on ITS OWN stream every k of its steps")
-    ap.add_argument("--foreground-rule", default="easgd", choices=["easgd", "ma", "bmuf"],
-                    help="with --foreground: easgd = per-worker exchange (FR-EASGD-k); ma / bmuf "
-                         "= every k steps all worker streams meet, one S-MA / S-BMUF round runs "
-                         "after all of them and all of them wait for it (FR-MA / FR-BMUF)")
-    ap.add_argument("--continuous-shadow", action="store_true",
-                    help="loop shadow rounds back to back (ss_shadow_start) instead of pacing them")
-    ap.add_argument("--workers-per-replica", type=int, default=6,
-                    help="Hogwild worker streams per replica")
-    ap.add_argument("--replicas", type=int, default=0, metavar="K",
-                    help="number of dense replicas (default: the workload's)")
-    ap.add_argument("--no-shadow", action="store_true", help="run without the shadow stream")
+    ap.add_argument("--steps", type=int, default=30, help="timed sweeps over all worker streams")
+    ap.add_argument("--warmup", type=int, default=5, help="untimed sweeps")
+    ap.add_argument("--workload", default="large", choices=["large", "mid", "tiny", "hogwild"])
+    ap.add_argument("--batches", type=int, default=64, help="distinct batches (at least)")
+    ap.add_argument("--workers-per-replica", default=None, metavar="W | W0,W1,..",
+                    help="Hogwild worker streams per replica (one number, or one per replica)")
+    ap.add_argument("--replicas", type=int, default=0, metavar="K")
+    ap.add_argument("--shadow", default="auto", choices=["auto", "paced", "continuous", "off"],
+                    help="paced: one round per sync_gap iterations of a replica, enqueued by its "
+                         "workers; continuous: the library's shadow thread loops rounds; auto: "
+                         "the workload's own (Large, Hogwild: continuous; Mid, Tiny: paced)")
+    ap.add_argument("--shadow-period-us", type=int, default=0,
+                    help="continuous shadow loop: rounds start at least this far apart")
+    ap.add_argument("--foreground", type=int, default=0, metavar="k",
+                    help="foreground variant: every k iterations a worker syncs on ITS OWN "
+                         "stream (FR-EASGD-k), or all workers stop for a round (ma / bmuf)")
+    ap.add_argument("--foreground-rule", default="easgd", choices=["easgd", "ma", "bmuf"])
+    ap.add_argument("--sweep", default="none", choices=["none", "widths", "gap"])
+    ap.add_argument("--no-shadow-off", action="store_true", help="skip the shadow-off region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sync-isolation", action="store_true")
-    ap.add_argument("--no-kernel-events", action="store_true",
-                    help="do not bracket kernels with events in the timed region")
-    ap.add_argument("--single-thread", action="store_true",
-                    help="enqueue all streams from one host thread")
+    ap.add_argument("--no-secondary", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true")
     return ap.parse_args()
 
 
-def algorithmic_bytes(kernel, wl, batch_np, n_unique):
-    """Bytes the method itself must move per launch of `kernel` on this batch."""
-    n = int(batch_np.offsets[-1])
+# ------------------------------------------------------------------------------------------
+# inputs
+def _gen_one(args):
+    gen, s = args
+    return gen.batch(s)
+
+
+def make_batches(wl, n, fork=True):
+    """n seeded batches; large jobs are generated in forked worker processes (the generator's
+    Zipf tables are built once, before the fork), which must happen before anything
+    initialises the GPU: pass fork=False afterwards."""
+    from paper_2003_03477_amd import synth
+    gen = synth.BatchGenerator(wl)
+    if not fork or wl.mean_ids * n < 5e6:
+        return gen, [gen.batch(s) for s in range(n)]
+    import multiprocessing as mp
+    procs = min(16, n, max(1, (os.cpu_count() or 1)))
+    with mp.get_context("fork").Pool(procs) as pool:
+        out = pool.map(_gen_one, [(gen, s) for s in range(n)], chunksize=1)
+    return gen, out
+
+
+# ------------------------------------------------------------------------------------------
+# algorithmic work per launch
+def mlp_flops(wl):
+    """Multiply-add flops per step of the MFMA kernel classes (the one-unit output layer runs
+    outside them and is left out: 2*B*256 flops)."""
+    layers = [(wl.bot_dims[i], wl.bot_dims[i + 1]) for i in range(len(wl.bot_dims) - 1)]
+    first_top = len(layers)
+    layers += [(wl.top_dims[i], wl.top_dims[i + 1]) for i in range(len(wl.top_dims) - 2)]
+    B = wl.batch
+    fwd = sum(2.0 * B * i * o for i, o in layers)
+    dgrad = sum(2.0 * B * i * o for k, (i, o) in enumerate(layers) if k != 0)
+    return {"mlp_fwd": fwd, "mlp_dgrad": dgrad, "mlp_wgrad": fwd}, first_top
+
+
+def hbm_bytes(kernel, wl, n_ids, n_unique):
+    """Bytes the method itself must move per launch (per id / per bag / per distinct row)."""
     B, T, d = wl.batch, wl.num_tables, wl.emb_dim
-    if kernel == "gather":
-        # per id: one row (4d) + its index (4) + sort key and pooled-vector id written (8);
-        # per bag: pooled vector written (4d) + its offset (4)
-        return n * (4 * d + 4 + 8) + B * T * (4 * d + 4)
-    if kernel == "row_update_chunk":
-        # per occurrence: gradient row (4d) + sorted key and bag id (8); per distinct row:
-        # row read + written (8d) + accumulator read + written (8)
-        return n * (4 * d + 8) + n_unique * (8 * d + 8)
+    if kernel == "gather":            # per id: row + index; per bag: pooled vector + offset
+        return n_ids * (4 * d + 4) + B * T * (4 * d + 4)
+    if kernel == "row_update_chunk":  # per occurrence: gradient row + sorted pair;
+        return n_ids * (4 * d + 8) + n_unique * (8 * d + 8)   # per row: row r/w + state r/w
+    if kernel == "interaction_bwd":   # per sample: df row, V tile read, dV tile written
+        F = d + T * (T + 1) // 2
+        return B * (4 * F + 2 * (T + 1) * d * 4)
     raise KeyError(kernel)
 
 
-def cpu_baseline(wl, gen, seconds=20.0):
-    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary (a line
+    `traffic_bytes_per_launch <kernel> <bytes>` in profiles/<workload>_hbm_traffic.txt), or None."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            m = re.match(r"\s*traffic_bytes_per_launch\s+(\S+)\s+([0-9.eE+]+)", line)
+            if m and m.group(1) == kernel:
+                return float(m.group(2))
+    except OSError:
+        pass
+    return None
+
+
+# ------------------------------------------------------------------------------------------
+def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, events=True,
+                 shadow_off=True, tag=""):
+    """Build a context, run warm-up + timed sweeps (shadow on, then shadow off), return the
+    measurements as a dict.  `workers` = worker streams per replica (list of K ints)."""
+    import numpy as np
+    import torch
+    from paper_2003_03477_amd import binding, synth
+
+    K = wl.num_replicas
+    replica_of = [r for r in range(K) for _ in range(workers[r])]
+    NS = len(replica_of)
+    assert len(host_batches) >= NS
+    max_ids = max(int(b.offsets[-1]) for b in host_batches) + 4096
+    gpu = binding.from_workload(wl, num_worker_slots=NS, max_ids=max_ids)
+    gpu.ss_init_tables_hash()
+    gpu.ss_init_dense(synth.dense_w0(wl))
+    dev_batches = [binding.upload_batch(b) for b in host_batches]
+    # every stream owns a disjoint set of batches: no two streams ever hold the same one
+    own = [list(range(w, len(dev_batches), NS)) for w in range(NS)]
+    streams = [torch.cuda.Stream() for _ in range(NS)]
+    shadow = torch.cuda.Stream()
+    total_sweeps = warmup + steps * (2 if shadow_off else 1) + 64
+    losses = torch.zeros(NS, total_sweeps, dtype=torch.float32, device="cuda")
+    done = [0] * NS                       # sweeps each worker has run so far
+    torch.cuda.synchronize()
+
+    fg = args.foreground
+    fg_collective = fg and args.foreground_rule != "easgd"
+    state = {"shadow_on": shadow_mode != "off" and not fg}
+    r_lock = threading.Lock()
+    r_steps = [0]
+    meet = threading.Barrier(NS)
+    arrive = [torch.cuda.Event() for _ in range(NS)]
+    release = [torch.cuda.Event()]
+
+    def foreground_collective(w):
+        """All worker streams stop, one averaging round runs, all resume (foreground form of
+        Algorithms 3 and 4): stream order through events, host threads meet to enqueue them."""
+        arrive[w].record(streams[w])
+        meet.wait()
+        if w == 0:
+            for e in arrive:
+                shadow.wait_event(e)
+            mu = wl.mu if args.foreground_rule == "bmuf" else 0.0
+            gpu.ss_shadow_sync(args.foreground_rule, wl.alpha, wl.eta, mu, shadow)
+            release[0] = torch.cuda.Event()
+            release[0].record(shadow)
+        meet.wait()
+        streams[w].wait_event(release[0])
+
+    def worker(w, sweeps, gate):
+        gate.wait()
+        r = replica_of[w]
+        for _ in range(sweeps):
+            j = done[w]
+            gpu.ss_train_step(r, w, dev_batches[own[w][j % len(own[w])]], streams[w],
+                              losses[w, j:j + 1])
+            done[w] = j + 1
+            if fg:
+                if (j + 1) % fg == 0:
+                    if fg_collective:
+                        foreground_collective(w)
+                    else:
+                        gpu.ss_easgd_exchange(r, wl.alpha, streams[w])
+            elif shadow_mode == "paced" and state["shadow_on"] and r == 0:
+                # one round per sync_gap iterations of replica 0 (all its workers together)
+                with r_lock:
+                    r_steps[0] += 1
+                    due = r_steps[0] % wl.sync_gap == 0
+                if due:
+                    gpu.ss_shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
+
+    def region(sweeps):
+        """Run `sweeps` sweeps on all streams; threads are created and parked at a barrier
+        before the clock starts.  Returns seconds."""
+        gate = threading.Barrier(NS + 1)
+        ts = [threading.Thread(target=worker, args=(w, sweeps, gate)) for w in range(NS)]
+        for t in ts:
+            t.start()
+        torch.cuda.synchronize()
+        gate.wait()
+        t0 = time.perf_counter()
+        for t in ts:
+            t.join()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    def shadow_loop(on):
+        if shadow_mode != "continuous" or fg:
+            state["shadow_on"] = on and shadow_mode != "off" and not fg
+            return
+        if on:
+            gpu.ss_shadow_pace(args.shadow_period_us)
+            gpu.ss_shadow_start(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
+        else:
+            gpu.ss_shadow_stop()
+        state["shadow_on"] = on
+
+    one = {"gather": binding.K_GATHER, "row_update_chunk": binding.K_ROW_UPDATE_CHUNK,
+           "mlp_fwd": binding.K_MLP_FWD, "mlp_dgrad": binding.K_MLP_DGRAD,
+           "mlp_wgrad": binding.K_MLP_WGRAD, "interaction_bwd": binding.K_INTERACT_BWD}
+    groups = {"row_update_all": binding.K_ROW_UPDATE, "sort_all_passes": binding.K_SORT,
+              "mlp_all_kernels_of_a_stage": binding.K_MLP,
+              "interaction_fwd": binding.K_INTERACT_FWD, "sync_round": binding.K_SYNC}
+
+    # ---- warm-up: every stream, every kernel, the shadow loop
+    shadow_loop(True)
+    region(warmup)
+    # ---- timed region, shadow on
+    every = max(1, (steps * NS) // 96)
+    if events:
+        gpu.ss_profile_sample(every)
+        gpu.ss_profile_arm(*one.values())
+    steps0, rounds0, _ = gpu.ss_get_counters()
+    dt_on = region(steps)
+    steps1, rounds1, _ = gpu.ss_get_counters()
+    kernels = {}
+    if events:
+        for name, kid in one.items():
+            n, ms = gpu.ss_profile_read(kid)
+            if n:
+                kernels[name] = {"brackets": n, "avg_us": ms / n * 1e3,
+                                 "where": f"timed region, 1 launch in {every} bracketed"}
+    shadow_loop(False)
+    train_ne = gpu.ss_metrics_read(0)
+    # ---- the same sweeps with the shadow stream off
+    dt_off = None
+    if shadow_off and not fg and shadow_mode != "off":
+        dt_off = region(steps)
+    rounds = rounds1 - rounds0
+    per_replica = (steps1 - steps0).astype(float)
+
+    # ---- structure of a step (launches per class) and the remaining classes, after the clock
+    if events:
+        gpu.ss_profile_sample(1)
+        gpu.ss_profile_arm(*one.values())
+        gpu.ss_train_step(0, 0, dev_batches[own[0][0]], streams[0], losses[0, -1:])
+        per_step = {name: gpu.ss_profile_read(kid)[0] for name, kid in one.items()}
+        gpu.ss_profile_arm(*groups.values())
+        state["shadow_on"] = shadow_mode != "off"
+        saved_mode = shadow_mode
+        if shadow_mode == "continuous":
+            for _ in range(8):
+                gpu.ss_shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
+        region(min(steps, 8))
+        for name, kid in groups.items():
+            n, ms = gpu.ss_profile_read(kid)
+            if n:
+                kernels[name] = {"brackets": n, "avg_us": ms / n * 1e3,
+                                 "where": "extra sweeps after the timed regions"}
+        flops, _ = mlp_flops(wl)
+        n_ids = float(np.mean([int(b.offsets[-1]) for b in host_batches]))
+        sample = host_batches[:8]
+        n_uniq = float(np.mean([sum(len(np.unique(b.indices[b.offsets[t * wl.batch]:b.offsets[(t + 1) * wl.batch]]))
+                                    for t in range(wl.num_tables)) for b in sample]))
+        train_steps = steps * NS
+        for name, kd in kernels.items():
+            if name not in one:
+                continue
+            lps = max(per_step.get(name, 1), 1)
+            kd["launches_per_step"] = lps
+            kd["total_ms_in_timed_region"] = kd["avg_us"] * lps * train_steps * 1e-3
+            if name in flops:
+                work = flops[name] / lps
+                ach = work / (kd["avg_us"] * 1e-6) / 1e12
+                kd.update({"bound": "mfma", "algorithmic_flops_per_launch": work, "TFLOPps": ach,
+                           "frac_of_bf16_mfma_peak": ach / MFMA_BF16_PEAK_TFLOPS})
+            else:
+                work = hbm_bytes(name, wl, n_ids, n_uniq)
+                ach = work / (kd["avg_us"] * 1e-6) / 1e9
+                tr = measured_traffic(wl.name, name)
+                kd.update({"bound": "hbm", "algorithmic_bytes_per_launch": work, "GBps": ach,
+                           "frac_of_hbm_peak": ach / HBM_PEAK_GBS,
+                           "counter_bytes_per_launch": tr,
+                           "counter_frac_of_hbm_peak":
+                               (tr / (kd["avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS) if tr else None})
+
+    # ---- loss windows
+    host_losses = losses.cpu().numpy().astype(float)
+    last_j = warmup + steps
+    first_win = float(host_losses[:, :max(1, min(warmup, 2))].mean()) if warmup else float(host_losses[:, 0].mean())
+    last_win = float(host_losses[:, max(0, last_j - 2):last_j].mean())
+    diverged = (not math.isfinite(last_win)) or last_win > 1.5 * max(first_win, math.log(2.0))
+
+    examples = wl.batch * NS * steps
+    res = {
+        "value": examples / dt_on, "ms_per_step": dt_on / steps * 1e3, "seconds": dt_on,
+        "worker_streams": NS, "workers_per_replica": workers, "examples_per_step": wl.batch * NS,
+        "shadow_rounds": int(rounds),
+        "avg_sync_gap": (float(per_replica.mean()) / rounds) if rounds else None,
+        "no_shadow_value": (examples / dt_off) if dt_off else None,
+        "shadow_on_over_off": (dt_off / dt_on) if dt_off else None,
+        "first_window_logloss": first_win, "last_window_logloss": last_win,
+        "diverged": bool(diverged),
+        "train_ne": {"examples": train_ne[0], "logloss": train_ne[1], "ctr": train_ne[2],
+                     "ne": train_ne[3]},
+        "kernels": kernels,
+    }
+    gpu.close()
+    del gpu, dev_batches, losses
+    torch.cuda.empty_cache()
+    return res
+
+
+def pick_roofline(kernels, NS):
+    cand = {k: v for k, v in kernels.items() if "total_ms_in_timed_region" in v}
+    if not cand:
+        return None
+    dom = max(cand, key=lambda k: cand[k]["total_ms_in_timed_region"])
+    kd = cand[dom]
+    mfma = kd["bound"] == "mfma"
+    return {"bound": kd["bound"], "kernel": dom,
+            "achieved": kd["TFLOPps"] if mfma else kd["GBps"],
+            "peak": MFMA_BF16_PEAK_TFLOPS if mfma else HBM_PEAK_GBS,
+            "unit": "TFLOP/s" if mfma else "GB/s",
+            "frac": kd["frac_of_bf16_mfma_peak"] if mfma else kd["frac_of_hbm_peak"],
+            "traffic": kd.get("counter_bytes_per_launch"),
+            "avg_launch_us": kd["avg_us"], "launches": kd["brackets"],
+            "launches_per_step": kd["launches_per_step"],
+            "work_per_launch": kd["algorithmic_flops_per_launch"] if mfma else kd["algorithmic_bytes_per_launch"],
+            "note": "largest summed time of all one-kernel classes over the timed region; HIP "
+                    f"events on the launching streams while {NS} worker streams (+ shadow) share "
+                    "the GPU, so queueing and shared bandwidth are included; MFMA classes "
+                    "average over the layers' GEMM shapes (total flops / total time)"}
+
+
+# ------------------------------------------------------------------------------------------
+def cpu_baseline(wl, seconds=20.0):
+    """The oracle as it stands on the host cores, on a bounded sample of the same workload."""
     import numpy as np
     import oracle
     from paper_2003_03477_amd import synth
-    batches = [gen.batch(10_000 + s) for s in range(3)]
-    cp = synth.compact_problem(wl, batches)
+    B = min(wl.batch, 2048)
+    swl = wl.scaled(batch=B)
+    gen = synth.BatchGenerator(swl)
+    batches = [gen.batch(20_000 + s) for s in range(2)]
+    cp = synth.compact_problem(swl, batches)
     row_base = np.concatenate(([0], np.cumsum(cp.rows)))
     orc = oracle.OracleTrainer(wl.bot_dims, wl.top_dims, row_base, cp.h0, synth.dense_w0(wl),
                                wl.num_replicas, wl.lr_dense, wl.lr_emb, wl.adagrad_eps,
                                bf16=wl.bf16)
     t0 = time.perf_counter()
-    steps = 0
+    n = 0
     while True:
-        orc.train_step(steps % wl.num_replicas, *cp.batches[steps % len(cp.batches)].as_tuple())
-        steps += 1
-        if steps % (wl.sync_gap * wl.num_replicas) == 0:
+        orc.train_step(n % wl.num_replicas, *cp.batches[n % len(cp.batches)].as_tuple())
+        n += 1
+        if n % (wl.sync_gap * wl.num_replicas) == 0:
             orc.shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu)
-        if time.perf_counter() - t0 > seconds or steps >= 64:
+        if time.perf_counter() - t0 > seconds or n >= 64:
             break
     dt = time.perf_counter() - t0
     try:
@@ -118,15 +397,36 @@ def cpu_baseline(wl, gen, seconds=20.0):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = 1
-    return {"value": wl.batch * steps / dt, "unit": "examples/s", "cores": cores,
-            "kind": "oracle",
-            "sample": f"{steps} train steps of batch {wl.batch} (+ sync rounds) of the fp64 "
-                      f"numpy oracle, tables compacted to the {sum(cp.rows)} touched rows, "
-                      f"{dt:.1f} s; BLAS may use up to `cores` threads, the rest is one thread"}
+    out = {"value": B * n / dt, "unit": "examples/s", "cores": cores, "kind": "oracle",
+           "sample": f"{n} train steps of batch {B} (the workload's batch is {wl.batch}) + sync "
+                     f"rounds of the fp64 numpy oracle, tables compacted to the {sum(cp.rows)} "
+                     f"touched rows, {dt:.1f} s; BLAS uses up to `cores` threads, the rest one"}
+    # the three sync rules on the host: K=8 replicas of 5M parameters (a tenth of the isolation
+    # workload), one round each after a warm-up round, algorithmic bytes as counted for the GPU
+    from oracle import sync as osync
+    Kh, Ph = 8, 5_000_000
+    rng = np.random.default_rng(4)
+    W = rng.standard_normal((Kh, Ph)) * 0.02
+    ps, wg, v = W[0].copy(), W[1].copy(), np.zeros(Ph)
+    rules = {"easgd": (lambda: osync.easgd_round(W, ps, 0.05), 8 * (Kh + 1)),
+             "ma": (lambda: osync.ma_round(W, wg, 0.5), 8 * Kh),
+             "bmuf": (lambda: osync.bmuf_round(W, wg, v, 0.5, 1.0, 0.9), 8 * Kh + 16)}
+    host = {}
+    for name, (fn, per_param) in rules.items():
+        fn()
+        t0 = time.perf_counter()
+        fn()
+        d = time.perf_counter() - t0
+        host[name] = {"ms_per_round": d * 1e3, "GBps_algorithmic": per_param * Ph / d / 1e9}
+    out["sync_rules_on_host"] = {"config": f"K={Kh} x {Ph} parameters, fp64 numpy, one thread",
+                                 **host}
+    return out
 
 
-def sync_isolation(binding, torch, rounds=20):
+def sync_isolation(rounds=50):
     """K=8 replicas of 50M fp32 parameters + centre copy: rounds of each rule back to back."""
+    import torch
+    from paper_2003_03477_amd import binding
     K, P = 8, 50_000_000
     g = torch.Generator(device="cuda").manual_seed(4)
     W = torch.randn(K * P, device="cuda", generator=g) * 0.02
@@ -135,16 +435,17 @@ def sync_isolation(binding, torch, rounds=20):
     v = torch.zeros(P, device="cuda")
     st = torch.cuda.Stream()
     out = {}
-    per_param = {"easgd": 8 * (K + 1), "ma": 8 * K + 4, "bmuf": 8 * K + 16}
-    args = {"easgd": dict(alpha=0.05), "ma": dict(alpha=0.5), "bmuf": dict(alpha=0.5, eta=1.0, momentum=0.9)}
+    per_param = {"easgd": 8 * (K + 1), "ma": 8 * K, "bmuf": 8 * K + 16}
+    kw = {"easgd": dict(alpha=0.05), "ma": dict(alpha=0.5),
+          "bmuf": dict(alpha=0.5, eta=1.0, momentum=0.9)}
     for algo in ("easgd", "ma", "bmuf"):
         with torch.cuda.stream(st):
             for _ in range(3):
-                binding.ss_sync_round(algo, K, P, P, W, ps, wg, v, stream=st, **args[algo])
+                binding.ss_sync_round(algo, K, P, P, W, ps, wg, v, stream=st, **kw[algo])
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(st)
             for _ in range(rounds):
-                binding.ss_sync_round(algo, K, P, P, W, ps, wg, v, stream=st, **args[algo])
+                binding.ss_sync_round(algo, K, P, P, W, ps, wg, v, stream=st, **kw[algo])
             e1.record(st)
         e1.synchronize()
         us = e0.elapsed_time(e1) * 1e3 / rounds
@@ -152,7 +453,40 @@ def sync_isolation(binding, torch, rounds=20):
         out[algo] = {"us_per_round": us, "algorithmic_bytes": per_param[algo] * P,
                      "GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
     out["config"] = f"K={K} replicas x {P} fp32 parameters, {rounds} rounds per rule back to back"
+    del W, ps, wg, v
+    torch.cuda.empty_cache()
     return out
+
+
+def parse_workers(text, K):
+    parts = [int(p) for p in str(text).split(",")]
+    if len(parts) == 1:
+        parts = parts * K
+    if len(parts) != K or min(parts) < 0 or sum(parts) < 1:
+        raise SystemExit(f"--workers-per-replica needs one number or {K} comma-separated ones")
+    return parts
+
+
+def shadow_mode_of(args, wl):
+    if args.shadow != "auto":
+        return args.shadow
+    return "continuous" if wl.name in ("large", "hogwild") else "paced"
+
+
+def shadow_text(args, wl, mode):
+    if args.foreground and args.foreground_rule != "easgd":
+        return (f"FOREGROUND {args.foreground_rule.upper()} alpha={wl.alpha}: all worker streams "
+                f"stop for one averaging round every {args.foreground} of their steps")
+    if args.foreground:
+        return (f"FOREGROUND EASGD alpha={wl.alpha}: every worker exchanges with the centre copy "
+                f"on its own stream every {args.foreground} of its steps")
+    if mode == "off":
+        return "no shadow sync"
+    rule = f"S-{wl.algo.upper()} alpha={wl.alpha}" + (f" eta={wl.eta} mu={wl.mu}" if wl.algo == "bmuf" else "")
+    if mode == "continuous":
+        pace = f", rounds at least {args.shadow_period_us} us apart" if args.shadow_period_us else " back to back"
+        return f"{rule} looping on the library's shadow thread and stream{pace}"
+    return f"{rule} on a shadow stream, one round per {wl.sync_gap} iterations of a replica"
 
 
 def main():
@@ -161,216 +495,106 @@ def main():
         print("bench.py: this build runs on ONE GPU (K replicas share its HBM); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
-    import numpy as np
-    import torch
-    from paper_2003_03477_amd import binding, synth
+    from paper_2003_03477_amd import synth
 
     wl = synth.WORKLOADS[args.workload]()
     if args.replicas:
         wl = wl.scaled(num_replicas=args.replicas)
     K = wl.num_replicas
-    WPR = args.workers_per_replica
-    NS = K * WPR                           # worker streams = worker slots
-    gen = synth.BatchGenerator(wl)
-    host_batches = [gen.batch(s) for s in range(args.batches)]
-    max_ids = max(int(b.offsets[-1]) for b in host_batches) + 4096
-    gpu = binding.from_workload(wl, num_worker_slots=NS, max_ids=max_ids)
-    gpu.ss_init_tables_hash()
-    gpu.ss_init_dense(synth.dense_w0(wl))
-    dev_batches = [binding.upload_batch(b) for b in host_batches]
-    streams = [torch.cuda.Stream() for _ in range(NS)]
-    shadow = torch.cuda.Stream()
-    losses = torch.zeros(NS, dtype=torch.float32, device="cuda")
-    torch.cuda.synchronize()
+    workers = parse_workers(args.workers_per_replica or DEFAULT_WORKERS[wl.name], K)
+    NS = sum(workers)
+    mode = shadow_mode_of(args, wl)
+    n_batches = max(args.batches, NS)
+    n_batches = (n_batches + NS - 1) // NS * NS
+    # inputs first: batch generation forks worker processes, which must precede any GPU use
+    t_gen = time.perf_counter()
+    _, host_batches = make_batches(wl, n_batches)
+    mid_batches = None
+    secondary = wl.name == "large" and not args.no_secondary and args.sweep == "none"
+    if secondary:
+        mid_wl = synth.mid()
+        mid_workers = parse_workers(DEFAULT_WORKERS["mid"], mid_wl.num_replicas)
+        _, mid_batches = make_batches(mid_wl, max(64, 3 * sum(mid_workers)))
+    t_gen = time.perf_counter() - t_gen
 
-    def run(total_steps, first_step):
-        """Step s runs on worker stream s % NS, which trains replica (s % NS) % K."""
-        def one(s):
-            w = s % NS
-            gpu.ss_train_step(w % K, w, dev_batches[s % len(dev_batches)], streams[w],
-                              losses[w:w + 1])
-
-        r0_steps = [0]
-        r0_lock = threading.Lock()
-
-        fg_collective = args.foreground and args.foreground_rule != "easgd"
-        meet = threading.Barrier(NS)
-        arrive = [torch.cuda.Event() for _ in range(NS)]
-        done = [torch.cuda.Event()]
-
-        def foreground_collective(w):
-            """All worker streams stop, one averaging round runs, all resume (the foreground
-            form of Algorithms 3 and 4): stream order is enforced with events, host threads
-            only meet to enqueue them."""
-            arrive[w].record(streams[w])
-            meet.wait()
-            if w == 0:
-                for e in arrive:
-                    shadow.wait_event(e)
-                mu = wl.mu if args.foreground_rule == "bmuf" else 0.0
-                gpu.ss_shadow_sync(args.foreground_rule, wl.alpha, wl.eta, mu, shadow)
-                done[0] = torch.cuda.Event()
-                done[0].record(shadow)
-            meet.wait()
-            streams[w].wait_event(done[0])
-
-        def worker(w):
-            for j, s in enumerate(range(first_step + w, first_step + total_steps, NS)):
-                one(s)
-                if args.foreground and (j + 1) % args.foreground == 0:
-                    if fg_collective:
-                        # every worker must come to every meeting: none after the step count
-                        # that all workers reach
-                        if j + 1 <= total_steps // NS:
-                            foreground_collective(w)
-                    else:
-                        gpu.ss_easgd_exchange(w % K, wl.alpha, streams[w])
-                    continue
-                # one shadow round per sync_gap iterations of replica 0 (all its workers)
-                if w % K == 0 and not args.no_shadow and not args.continuous_shadow \
-                        and not args.foreground:
-                    with r0_lock:
-                        r0_steps[0] += 1
-                        due = r0_steps[0] % wl.sync_gap == 0
-                    if due:
-                        gpu.ss_shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
-        if args.single_thread:
-            for s in range(first_step, first_step + total_steps):
-                one(s)
-                if not args.no_shadow and not args.continuous_shadow and \
-                        (s + 1 - first_step) % (wl.sync_gap * K) == 0:
-                    gpu.ss_shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
-            return
-        ts = [threading.Thread(target=worker, args=(w,)) for w in range(NS)]
-        for t in ts:
-            t.start()
-        for t in ts:
-            t.join()
-
-    if args.continuous_shadow and not args.no_shadow:
-        gpu.ss_shadow_start(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
-    run(args.warmup, 0)
-    torch.cuda.synchronize()
-    # Inside the timed region only the two roofline candidates are bracketed (two event pairs
-    # per step); the other classes are timed in a short extra pass after the clock stops.
-    classes = {"gather": binding.K_GATHER, "row_update_chunk": binding.K_ROW_UPDATE_CHUNK}
-    extra = {"row_update_all": binding.K_ROW_UPDATE, "sort_and_segments": binding.K_SORT,
-             "mlp_groups": binding.K_MLP, "interaction_fwd": binding.K_INTERACT_FWD,
-             "interaction_bwd": binding.K_INTERACT_BWD, "sync_round": binding.K_SYNC}
-    if not args.no_kernel_events:
-        # every 8th launch of each class is bracketed: enough samples for the average, and the
-        # cost of recording events stays out of the throughput being measured
-        gpu.ss_profile_sample(8)
-        gpu.ss_profile_arm(*classes.values())
-    steps0, rounds0, _ = gpu.ss_get_counters()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(args.steps, args.warmup)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    steps1, rounds1, _ = gpu.ss_get_counters()
-    last_losses = losses.cpu().numpy().astype(float)   # mean log-loss of each stream's last batch
-
-    kernels, roofline = {}, None
-    if not args.no_kernel_events:
-        for name, kid in classes.items():
-            n, ms = gpu.ss_profile_read(kid)
-            if n:
-                kernels[name] = {"brackets": n, "avg_us": ms / n * 1e3, "total_ms": ms,
-                                 "where": "timed region, every 8th launch bracketed"}
-        # the two roofline candidates once more with ONE stream active (no queueing behind, and
-        # no bandwidth shared with, other streams' kernels): comparable with a profiler's figure
-        gpu.ss_profile_sample(1)
-        gpu.ss_profile_arm(*classes.values())
-        for s in range(24):
-            gpu.ss_train_step(0, 0, dev_batches[s % len(dev_batches)], streams[0], losses[0:1])
-        alone = {name: gpu.ss_profile_read(kid) for name, kid in classes.items()}
-        gpu.ss_profile_arm(*extra.values())
-        run(min(args.steps, 10 * wl.sync_gap * K), args.warmup + args.steps)
-        for name, kid in extra.items():
-            n, ms = gpu.ss_profile_read(kid)
-            if n:
-                kernels[name] = {"brackets": n, "avg_us": ms / n * 1e3, "total_ms": ms,
-                                 "where": "extra pass after the timed region"}
-        uniq = [sum(len(np.unique(b.indices[b.offsets[t * wl.batch]:b.offsets[(t + 1) * wl.batch]]))
-                    for t in range(wl.num_tables)) for b in host_batches]
-        for name in ("gather", "row_update_chunk"):
-            if name not in kernels:
-                continue
-            per = [algorithmic_bytes(name, wl, b, uniq[k]) for k, b in enumerate(host_batches)]
-            bpl = float(np.mean(per))
-            ach = bpl / (kernels[name]["avg_us"] * 1e-6) / 1e9
-            kernels[name].update({"algorithmic_bytes_per_launch": bpl, "GBps": ach,
-                                  "frac_of_hbm_peak": ach / HBM_PEAK_GBS})
-            n1, ms1 = alone[name]
-            if n1:
-                us1 = ms1 / n1 * 1e3
-                kernels[name].update({"alone_avg_us": us1, "alone_GBps": bpl / us1 / 1e3,
-                                      "alone_frac_of_hbm_peak": bpl / us1 / 1e3 / HBM_PEAK_GBS})
-        cand = [k for k in ("gather", "row_update_chunk") if k in kernels]
-        if cand:
-            dom = max(cand, key=lambda k: kernels[k]["total_ms"])
-            kd = kernels[dom]
-            traffic = MEASURED_TRAFFIC.get(wl.name, {}).get(dom)
-            roofline = {"bound": "hbm", "kernel": dom, "achieved": kd["GBps"],
-                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kd["frac_of_hbm_peak"],
-                        "traffic": traffic, "avg_launch_us": kd["avg_us"],
-                        "launches": kd["brackets"],
-                        "algorithmic_bytes_per_launch": kd["algorithmic_bytes_per_launch"],
-                        "alone_avg_launch_us": kd.get("alone_avg_us"),
-                        "alone_achieved": kd.get("alone_GBps"),
-                        "alone_frac": kd.get("alone_frac_of_hbm_peak"),
-                        "profiler_alone_avg_launch_us": PROFILER_ALONE_US.get(wl.name, {}).get(dom),
-                        "profiler_alone_frac": (
-                            kd["algorithmic_bytes_per_launch"] /
-                            (PROFILER_ALONE_US[wl.name][dom] * 1e-6) / 1e9 / HBM_PEAK_GBS
-                            if dom in PROFILER_ALONE_US.get(wl.name, {}) else None),
-                        "note": "achieved/frac: HIP events inside the timed region, where "
-                                f"{NS + 1} streams share the GPU (includes queueing and shared "
-                                "bandwidth); alone_*: the same kernel with one stream active; "
-                                "profiler_alone_*: rocprofv3's duration of that kernel in a "
-                                "one-stream run (committed profile, not measured in this run)"}
-
-    if args.continuous_shadow and not args.no_shadow:
-        gpu.ss_shadow_stop()
-    rounds = rounds1 - rounds0
-    shadow_txt = (f"FOREGROUND {args.foreground_rule.upper()} alpha={wl.alpha}: all worker "
-                  f"streams stop for one averaging round every {args.foreground} of their steps"
-                  if args.foreground and args.foreground_rule != "easgd" else
-                  f"FOREGROUND EASGD alpha={wl.alpha}: every worker stream exchanges with the "
-                  f"centre copy on its own stream every {args.foreground} of its steps"
-                  if args.foreground else
-                  "no shadow sync" if args.no_shadow else
-                  f"S-{wl.algo.upper()} alpha={wl.alpha} looping continuously on a shadow stream"
-                  if args.continuous_shadow else
-                  f"S-{wl.algo.upper()} alpha={wl.alpha} on a shadow stream every {wl.sync_gap} "
-                  f"trainer steps")
+    res = run_workload(args, wl, workers, mode, args.steps, args.warmup, host_batches,
+                       events=not args.no_kernel_events, shadow_off=not args.no_shadow_off)
     out = {
         "metric": "train examples/s on 1 GPU with background sync",
-        "value": wl.batch * args.steps / dt,
-        "unit": "examples/s",
+        "value": res["value"], "unit": "examples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": dt / args.steps * 1e3,
+        "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: B={wl.batch}, {wl.num_tables} tables, {sum(wl.rows)} "
-                               f"rows x d{wl.emb_dim} fp32, Zipf({wl.zipf_s}), bag Poisson("
-                               f"{wl.bag_lambda:g})+1, K={K} replicas x {WPR} worker stream(s), "
-                               f"{shadow_txt}",
-                   "shadow_rounds": int(rounds),
-                   "last_batch_logloss": float(last_losses.mean()),
-                   "avg_sync_gap": (float((steps1 - steps0).mean()) / rounds) if rounds else None,
-                   "host_threads": 1 if args.single_thread else NS},
-        "roofline": roofline,
-        "kernels": kernels,
+        "config": {
+            "workload": f"{wl.name}: B={wl.batch}, {wl.num_tables} tables, {sum(wl.rows)} rows x "
+                        f"d{wl.emb_dim} fp32, Zipf({wl.zipf_s}), bag Poisson({wl.bag_lambda:g})+1, "
+                        f"MLP {'-'.join(map(str, wl.bot_dims))} / {'-'.join(map(str, wl.top_dims))}, "
+                        f"K={K} replicas, worker streams per replica {workers}, "
+                        f"{shadow_text(args, wl, mode)}",
+            "step": f"one sweep = one ss_train_step on each of the {NS} worker streams = "
+                    f"{res['examples_per_step']} examples",
+            "global_batch": res["examples_per_step"], "worker_streams": NS,
+            "host_threads": NS, "distinct_batches": n_batches,
+            "timed_seconds": res["seconds"],
+            "shadow_rounds": res["shadow_rounds"], "avg_sync_gap": res["avg_sync_gap"],
+            "first_window_logloss": res["first_window_logloss"],
+            "last_window_logloss": res["last_window_logloss"], "diverged": res["diverged"],
+            "train_ne": res["train_ne"], "input_generation_seconds": t_gen,
+        },
+        "no_shadow": {"value": res["no_shadow_value"], "shadow_on_over_off": res["shadow_on_over_off"],
+                      "note": "the same sweeps with the shadow stream idle; Section 3.2 claims "
+                              "background sync leaves training throughput unchanged"},
+        "roofline": pick_roofline(res["kernels"], NS),
+        "kernels": res["kernels"],
     }
-    gpu.close()
-    del gpu
-    torch.cuda.empty_cache()
+    if args.sweep == "widths":
+        table = []
+        for w in (1, 2, 4, 6, 8, 12, 16):
+            ws = [w] * K
+            need = sum(ws)
+            hb = host_batches if len(host_batches) >= need else None
+            if hb is None:
+                _, hb = make_batches(wl, need, fork=False)
+            r = run_workload(args, wl, ws, mode, args.steps, args.warmup, hb, events=False,
+                             shadow_off=False)
+            table.append({"workers_per_replica": w, "worker_streams": need,
+                          "examples_per_s": r["value"], "avg_sync_gap": r["avg_sync_gap"],
+                          "first_window_logloss": r["first_window_logloss"],
+                          "last_window_logloss": r["last_window_logloss"],
+                          "train_ne": r["train_ne"]["ne"]})
+        out["width_sweep"] = {"what": "Hogwild width (Section 4.4): lock-free worker streams per "
+                                      "replica against throughput and the loss reached over the "
+                                      "same number of sweeps", "rows": table}
+    if args.sweep == "gap":
+        table = []
+        for k in (2, 4, 8):
+            wk = wl.scaled(num_replicas=k)
+            ws = parse_workers(args.workers_per_replica or "4", k)
+            for period in (0, 200, 1000):
+                args.shadow_period_us = period
+                r = run_workload(args, wk, ws, "continuous", args.steps, args.warmup, host_batches,
+                                 events=False, shadow_off=False)
+                table.append({"replicas": k, "shadow_period_us": period,
+                              "examples_per_s": r["value"], "shadow_rounds": r["shadow_rounds"],
+                              "avg_sync_gap": r["avg_sync_gap"]})
+        out["sync_gap_table"] = {"what": "average sync gap (Section 4.2: trainer iterations per "
+                                         "sync) against the number of replicas, shadow loop back "
+                                         "to back and paced", "rows": table}
+    if secondary:
+        r = run_workload(args, mid_wl, mid_workers, "paced", args.steps, args.warmup, mid_batches,
+                         events=not args.no_kernel_events, shadow_off=not args.no_shadow_off)
+        out["secondary"] = {"mid": {
+            "value": r["value"], "unit": "examples/s", "ms_per_step": r["ms_per_step"],
+            "worker_streams": r["worker_streams"], "examples_per_step": r["examples_per_step"],
+            "no_shadow_value": r["no_shadow_value"], "shadow_on_over_off": r["shadow_on_over_off"],
+            "avg_sync_gap": r["avg_sync_gap"], "first_window_logloss": r["first_window_logloss"],
+            "last_window_logloss": r["last_window_logloss"], "diverged": r["diverged"],
+            "roofline": pick_roofline(r["kernels"], r["worker_streams"]), "kernels": r["kernels"]}}
     if not args.no_sync_isolation:
-        out["sync_isolation"] = sync_isolation(binding, torch)
+        out["sync_isolation"] = sync_isolation()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, gen)
+        out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
 
 

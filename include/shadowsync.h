@@ -186,6 +186,11 @@ int ss_sync_round(int32_t algo, int32_t K, int64_t P, int64_t stride, float* dev
 int ss_shadow_start(ss_ctx* ctx, int32_t algo, float alpha, float eta, float momentum,
                     void* stream);
 int ss_shadow_stop(ss_ctx* ctx);
+/* Pace of the shadow loop: the thread starts rounds at least min_period_us apart (0, the
+ * default: back to back).  The paper's loop is paced by its network (Section 4.2 reports one
+ * round per 5-12 trainer iterations); inside one HBM a round is a single short kernel, and
+ * this is the knob that sets the average sync gap.  May be changed while the loop runs. */
+int ss_shadow_pace(ss_ctx* ctx, int64_t min_period_us);
 
 /* Read-back (synchronises the device first).  which: 0..K-1 = w^(which), -1 = w^PS,
  * -2 = w^global, -3 = v, -4 = the mean of the K replicas, computed on the device at the time
@@ -200,7 +205,9 @@ int ss_read_rows(ss_ctx* ctx, int32_t table, const int64_t* rows, int64_t n,
                  float* host_rows_out, float* host_adagrad_out);
 
 /* Intermediates of the LAST step run on a worker slot, for element-wise checks
- * (synchronises first).  Copies min(bytes, size) bytes; returns the full size in bytes
+ * (synchronises first).  Forward results (pooled vectors, interaction, logits, activations)
+ * are those of the last ss_train_step OR ss_eval_step; the index work (sorted rows and
+ * positions, segment starts, bag ids) and the gradients are those of the last ss_train_step.  Copies min(bytes, size) bytes; returns the full size in bytes
  * through *size_out (may be NULL). */
 typedef enum {
   SS_DBG_POOLED = 0,       /* float  [B, T, d]   pooled embeddings e                       */
@@ -212,7 +219,12 @@ typedef enum {
   SS_DBG_SORTED_POS = 6,   /* uint32 [n]         flat position of each sorted entry         */
   SS_DBG_SEG_STARTS = 7,   /* uint32 [U]         sorted index where each distinct row starts */
   SS_DBG_NUM_UNIQUE = 8,   /* uint32 [1]         U                                          */
-  SS_DBG_BAG_OF_POS = 9    /* int32  [n]         b*T + t of each flat position              */
+  SS_DBG_BAG_OF_POS = 9,   /* int32  [n]         b*T + t of each flat position              */
+  SS_DBG_Z0 = 10,          /* float  [B, d]      output of the bottom MLP (after its ReLU)  */
+  SS_DBG_HIDDEN_ACT = 32   /* SS_DBG_HIDDEN_ACT + l: float [B, out_l], output of hidden layer l
+                              (layers counted over the whole model, bottom first; not the
+                              bottom output, not the logit) as the device stores it, i.e.
+                              after ReLU and, under SS_BF16, after rounding to bfloat16      */
 } ss_debug_item;
 int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out, size_t bytes,
                   size_t* size_out);
@@ -221,6 +233,17 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
  * steps_per_replica: host [K]; any pointer may be NULL. */
 int ss_get_counters(ss_ctx* ctx, uint64_t* steps_per_replica, uint64_t* rounds,
                     uint64_t* examples);
+
+/* Normalised entropy (Section 4, "Evaluation Metrics"): NE = mean log-loss / entropy of the
+ * empirical click rate of the same examples.  The library keeps two running accumulators on
+ * the device: which = 0, TRAIN -- every ss_train_step adds its batch's log-loss BEFORE the update
+ * (each example is predicted by a model that has not yet trained on it: the paper's
+ * progressive Train NE); which = 1, EVAL -- every ss_eval_step adds its batch.
+ * ss_metrics_read synchronises the device and fills out[0..3] = number of examples, mean
+ * log-loss, click rate, NE (NaN while the click rate is 0 or 1, or no example was seen).
+ * ss_metrics_reset zeroes one accumulator (synchronous). */
+int ss_metrics_read(ss_ctx* ctx, int32_t which, double* host_out4);
+int ss_metrics_reset(ss_ctx* ctx, int32_t which);
 
 /* Kernel timing with HIP events recorded on the launching stream.  ss_profile_arm takes a bit
  * mask (bit i = ss_kernel_id i); from then on every launch of an armed class is bracketed by
@@ -240,7 +263,11 @@ typedef enum {
   SS_K_INTERACT_FWD = 6,      /* one kernel                                                  */
   SS_K_INTERACT_BWD = 7,      /* one kernel                                                  */
   SS_K_ROW_UPDATE = 8,        /* group: chunk + stitch + long-run passes                     */
-  SS_K_COUNT = 9
+  SS_K_MLP_FWD = 9,           /* one kernel: each forward MFMA launch of the bf16 fused and
+                                 layer-wise paths (a layer's GEMM, or a fused stack)         */
+  SS_K_MLP_DGRAD = 10,        /* one kernel: each data-gradient MFMA launch                  */
+  SS_K_MLP_WGRAD = 11,        /* one kernel: each weight-gradient MFMA launch                */
+  SS_K_COUNT = 12
 } ss_kernel_id;
 int ss_profile_arm(ss_ctx* ctx, uint32_t kernel_mask);
 int ss_profile_sample(ss_ctx* ctx, int32_t every);

@@ -39,6 +39,9 @@ class OracleTrainer:
         self.steps = np.zeros(num_replicas, dtype=np.int64)
         self.rounds = 0
         self.last = None
+        # running sums behind the normalised entropy (Section 4, "Evaluation Metrics"):
+        # [sum of per-example log-loss, positive labels, examples] for training and evaluation
+        self.metrics = {"train": np.zeros(3), "eval": np.zeros(3)}
 
     # ------------------------------------------------------------------ worker thread
     def train_step(self, replica, x, y, indices, offsets, update=True, gate_flips=None):
@@ -64,6 +67,9 @@ class OracleTrainer:
                          de=de, sorted_keys=sk, sorted_pos=perm, seg_starts=heads,
                          rows=rows, g_rows=g_rows, bag_of_pos=bag)
         if update:
+            # the loss is the one BEFORE the update: every example is scored by a model that
+            # has not trained on it yet (the progressive Train NE of Section 4)
+            self.metrics["train"] += (loss * B, float(np.sum(y)), B)
             self.W[replica] = w - self.lr_dense * g
             dlrm.rowwise_adagrad_update(self.h, self.G, rows, g_rows, self.lr_emb,
                                         self.eps)
@@ -73,7 +79,16 @@ class OracleTrainer:
     def eval_logloss(self, replica, x, y, indices, offsets):
         fw = dlrm.dlrm_forward(self.layout, self.W[replica], self.h, self.row_base, x,
                                indices, offsets, bf16=self.bf16, pooling=self.pooling)
-        return dlrm.bce_with_logits(fw["logit"], y.astype(self.dtype))[0]
+        loss = dlrm.bce_with_logits(fw["logit"], y.astype(self.dtype))[0]
+        self.metrics["eval"] += (loss * x.shape[0], float(np.sum(y)), x.shape[0])
+        return loss
+
+    def ne(self, which):
+        """(examples, mean log-loss, click rate, NE) of the "train" or "eval" accumulator:
+        NE = mean log-loss / entropy of the click rate of the same examples (Section 4)."""
+        s, pos, n = self.metrics[which]
+        mean, p = s / n, pos / n
+        return n, mean, p, mean / -(p * np.log(p) + (1 - p) * np.log(1 - p))
 
     # ------------------------------------------------------------------ shadow thread
     def shadow_sync(self, algo, alpha, eta=1.0, mu=0.0):

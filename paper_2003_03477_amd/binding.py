@@ -29,16 +29,18 @@ _DBG_DTYPE = {DBG_POOLED: np.float32, DBG_INTERACT: np.float32, DBG_LOGITS: np.f
               DBG_DENSE_GRAD: np.float32, DBG_POOLED_GRAD: np.float32,
               DBG_SORTED_ROWS: np.uint32, DBG_SORTED_POS: np.uint32,
               DBG_SEG_STARTS: np.uint32, DBG_NUM_UNIQUE: np.uint32, DBG_BAG_OF_POS: np.int32}
+DBG_Z0, DBG_HIDDEN_ACT = 10, 32
 
 (K_NONE, K_GATHER, K_SORT, K_ROW_UPDATE_CHUNK, K_SYNC, K_MLP, K_INTERACT_FWD, K_INTERACT_BWD,
- K_ROW_UPDATE) = range(9)
+ K_ROW_UPDATE, K_MLP_FWD, K_MLP_DGRAD, K_MLP_WGRAD) = range(12)
 
 EXPORTS = [
     "ss_workspace_bytes", "ss_init", "ss_destroy", "ss_last_error", "ss_init_tables_hash",
     "ss_write_rows", "ss_write_adagrad", "ss_init_dense", "ss_num_params", "ss_train_step", "ss_eval_step",
     "ss_shadow_sync", "ss_easgd_exchange", "ss_sync_round", "ss_shadow_start", "ss_shadow_stop", "ss_read_dense",
     "ss_write_dense", "ss_read_rows", "ss_read_debug", "ss_get_counters", "ss_profile_arm",
-    "ss_profile_sample", "ss_profile_read",
+    "ss_profile_sample", "ss_profile_read", "ss_shadow_pace", "ss_metrics_read",
+    "ss_metrics_reset",
 ]
 
 
@@ -93,6 +95,9 @@ def load() -> C.CDLL:
     lib.ss_sync_round.argtypes = [i32, i32, i64, i64, vp, vp, vp, vp, f32, f32, f32, vp]
     lib.ss_shadow_start.argtypes = [vp, i32, f32, f32, f32, vp]
     lib.ss_shadow_stop.argtypes = [vp]
+    lib.ss_shadow_pace.argtypes = [vp, i64]
+    lib.ss_metrics_read.argtypes = [vp, i32, vp]
+    lib.ss_metrics_reset.argtypes = [vp, i32]
     lib.ss_read_dense.argtypes = [vp, i32, vp, i64]
     lib.ss_write_dense.argtypes = [vp, i32, vp, i64]
     lib.ss_read_rows.argtypes = [vp, i32, vp, i64, vp, vp]
@@ -265,6 +270,18 @@ class ShadowSync:
     def ss_shadow_stop(self):
         self._check(self.lib.ss_shadow_stop(self.ctx), "ss_shadow_stop")
 
+    def ss_shadow_pace(self, min_period_us: int):
+        self._check(self.lib.ss_shadow_pace(self.ctx, int(min_period_us)), "ss_shadow_pace")
+
+    def ss_metrics_read(self, which: int):
+        """(examples, mean log-loss, click rate, NE) of the train (0) or eval (1) accumulator."""
+        out = np.zeros(4, dtype=np.float64)
+        self._check(self.lib.ss_metrics_read(self.ctx, which, _np_ptr(out)), "ss_metrics_read")
+        return tuple(float(v) for v in out)
+
+    def ss_metrics_reset(self, which: int):
+        self._check(self.lib.ss_metrics_reset(self.ctx, which), "ss_metrics_reset")
+
     # ------------------------------------------------------------------ read-back
     def ss_read_dense(self, which: int) -> np.ndarray:
         out = np.empty(self.P, dtype=np.float32)
@@ -288,7 +305,7 @@ class ShadowSync:
         size = C.c_size_t(0)
         self._check(self.lib.ss_read_debug(self.ctx, slot, item, None, 0, C.byref(size)),
                     "ss_read_debug")
-        out = np.empty(size.value // 4, dtype=_DBG_DTYPE[item])
+        out = np.empty(size.value // 4, dtype=_DBG_DTYPE.get(item, np.float32))
         if size.value:
             self._check(self.lib.ss_read_debug(self.ctx, slot, item, _np_ptr(out), size.value,
                                                None), "ss_read_debug")
@@ -328,13 +345,6 @@ def ss_sync_round(algo, K: int, P: int, stride: int, replicas, w_ps=None, w_glob
                            alpha, eta, momentum, _stream_handle(stream))
     if rc != 0:
         raise ShadowSyncError(f"ss_sync_round failed ({rc})")
-
-
-def normalized_entropy(mean_logloss: float, ctr: float) -> float:
-    """NE (Section 4, "Evaluation Metrics"): mean log-loss of the predictions divided by the
-    entropy of the empirical click rate `ctr` of the same examples."""
-    import math
-    return mean_logloss / -(ctr * math.log(ctr) + (1.0 - ctr) * math.log(1.0 - ctr))
 
 
 def from_workload(wl, rows=None, num_worker_slots: int = 1, max_ids: Optional[int] = None,

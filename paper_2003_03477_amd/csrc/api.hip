@@ -2,6 +2,8 @@
 // worker iteration and one shadow round (Algorithm 1).  No device memory is allocated here:
 // everything is carved out of the caller's workspace.
 #include <atomic>
+#include <chrono>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -131,6 +133,7 @@ struct ss_ctx {
   float* w_global;
   float* v;
   float* w_mean;  // replica average, filled on request (ss_read_dense with which = -4)
+  double* metrics;  // [2][4]: (sum of log-loss, positive labels, examples, unused) train / eval
   std::vector<Slot> slots;
   // state
   std::mutex err_mu;               // guards err: concurrent callers may fail at the same time
@@ -141,6 +144,7 @@ struct ss_ctx {
   // shadow loop
   std::thread shadow;
   std::atomic<bool> shadow_run{false};
+  std::atomic<int64_t> shadow_period_us{0};
   // profiling
   std::mutex prof_mu;
   std::atomic<uint32_t> prof_mask{0};
@@ -239,6 +243,7 @@ static size_t layout(ss_ctx* x, void* base) {
   x->w_global = cv.take<float>(x->Pstride);
   x->v = cv.take<float>(x->Pstride);
   x->w_mean = cv.take<float>(x->Pstride);
+  x->metrics = cv.take<double>(8);
   const int L = (int)x->layers.size();
   x->wgrad_tiles_dev = x->wgrad_tiles.empty() ? nullptr : cv.take<int4>(x->wgrad_tiles.size());
   const int sort_blocks = sort_max_blocks((uint32_t)n);
@@ -474,6 +479,7 @@ int ss_init(const ss_config* cfg, void* dev_workspace, size_t bytes, ss_ctx** ou
   launch_fill_f32(x->W, (uint64_t)x->K * x->Pstride, 0.f, nullptr);
   launch_fill_f32(x->w_ps, (uint64_t)x->Pstride, 0.f, nullptr);
   launch_fill_f32(x->w_global, (uint64_t)x->Pstride, 0.f, nullptr);
+  launch_fill_f32((float*)x->metrics, 16, 0.f, nullptr);
   for (Slot& s : x->slots) launch_fill_f32(s.grads, (uint64_t)x->Pstride, 0.f, nullptr);
   if (x->wide) {
     // the reduction-dimension padding of these buffers is read (against zero weights) before
@@ -636,7 +642,12 @@ struct ProfScope {
   ProfScope(ss_ctx* ctx, int id, hipStream_t st) : x(ctx), s(st) {
     if (!(x->prof_mask.load(std::memory_order_relaxed) & (1u << id))) return;
     const uint32_t every = x->prof_every.load(std::memory_order_relaxed);
-    if (every > 1 && x->prof_seen[id].fetch_add(1, std::memory_order_relaxed) % every != 0) return;
+    // launches are picked by a hash of their running number, not by its remainder: a step's
+    // launches of one class cycle through the layers, and a fixed stride would always land on
+    // the same ones
+    if (every > 1 &&
+        ((x->prof_seen[id].fetch_add(1, std::memory_order_relaxed) * 0x9E3779B1u) >> 12) % every != 0)
+      return;
     std::lock_guard<std::mutex> lk(x->prof_mu);
     auto& pool = x->prof[id];
     if (!(x->prof_mask.load() & (1u << id)) || pool.used >= pool.ev.size()) return;
@@ -711,12 +722,12 @@ static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
     a.out_f32 = s.z0; a.relu_last = 1; a.has_tail = 0;
     a.kp_tail = (x->layers[nb - 1].out + 63) / 64 * 64;
     a.lds_elems0 = (unsigned)x->e0_fwd_bot;
-    launch_mlp_fused_fwd(a, x->lds_fwd_bot, st);
+    { ProfScope pk(x, SS_K_MLP_FWD, st); launch_mlp_fused_fwd(a, x->lds_fwd_bot, st); }
   }
   {
     ProfScope ps(x, SS_K_GATHER, st);
-    launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e, s.keys,
-                             s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, st);
+    launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e,
+                             train ? s.keys : nullptr, s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -736,7 +747,7 @@ static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
     a.w_last = w + last.w_off; a.b_last = w + last.b_off; a.y = bt->labels;
     a.logits = s.logits; a.dlogit = train ? s.dlogit : nullptr; a.loss = loss;
     a.lds_elems0 = (unsigned)x->e0_fwd_top;
-    launch_mlp_fused_fwd(a, x->lds_fwd_top, st);
+    { ProfScope pk(x, SS_K_MLP_FWD, st); launch_mlp_fused_fwd(a, x->lds_fwd_top, st); }
   }
 }
 
@@ -753,7 +764,7 @@ static void backward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
     for (int l = 0; l < nh; ++l) { a.actT[l] = s.actT[nb + l]; a.dYT[l] = s.dYT[nb + l]; }
     a.d_out_f32 = s.df; a.ld_d_out = x->ldf;
     a.lds_elems0 = (unsigned)x->e0_bwd_top;
-    launch_mlp_fused_bwd(a, x->lds_bwd_top, st);
+    { ProfScope pk(x, SS_K_MLP_DGRAD, st); launch_mlp_fused_bwd(a, x->lds_bwd_top, st); }
   }
   {
     ProfScope ps(x, SS_K_INTERACT_BWD, st);
@@ -768,7 +779,7 @@ static void backward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
     for (int l = 0; l < nb; ++l) { a.actT[l] = s.actT[l]; a.dYT[l] = s.dYT[l]; }
     a.d_out_f32 = nullptr;
     a.lds_elems0 = (unsigned)x->e0_bwd_bot;
-    launch_mlp_fused_bwd(a, x->lds_bwd_bot, st);
+    { ProfScope pk(x, SS_K_MLP_DGRAD, st); launch_mlp_fused_bwd(a, x->lds_bwd_bot, st); }
     WgradArgs g{};
     for (int l = 0; l < nb + nh; ++l) {
       const Layer& ly = x->layers[l];
@@ -778,7 +789,7 @@ static void backward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
       g.L[l].in = ly.in; g.L[l].out = ly.out;
     }
     g.tiles = x->wgrad_tiles_dev; g.B = B; g.ldT = x->ldT;
-    launch_mlp_wgrad_grouped(g, (int)x->wgrad_tiles.size(), st);
+    { ProfScope pk(x, SS_K_MLP_WGRAD, st); launch_mlp_wgrad_grouped(g, (int)x->wgrad_tiles.size(), st); }
   }
 }
 
@@ -797,7 +808,7 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
       a.C = s.act_bf16[l]; a.ldc = x->pout[l];
       a.CT = train ? s.actT[l] : nullptr; a.ldct = x->ldT;
     }
-    launch_gemm_nt(a, st);
+    { ProfScope pk(x, SS_K_MLP_FWD, st); launch_gemm_nt(a, st); }
   };
   {
     ProfScope ps(x, SS_K_MLP, st);
@@ -822,8 +833,8 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
   }
   {
     ProfScope ps(x, SS_K_GATHER, st);
-    launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e, s.keys,
-                             s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, st);
+    launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e,
+                             train ? s.keys : nullptr, s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -871,7 +882,8 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
       g.C_f32 = s.wg_part + x->wg_off[l];
       g.split_stride = x->wg_stride[l];
     }
-    const int slices = launch_gemm_nt(g, st);
+    int slices;
+    { ProfScope pk(x, SS_K_MLP_WGRAD, st); slices = launch_gemm_nt(g, st); }
     if (split > 1) {  // (a single slice is stored to the slice area as well)
       ReduceSegment& sg = red.seg[red.n_seg++];
       sg.part = g.C_f32; sg.out = s.grads + ly.w_off; sg.n = (int64_t)ly.out * ly.in;
@@ -885,7 +897,7 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
     a.M = B; a.N = ly.in; a.K = x->kout[l]; a.split_k = 1;
     if (l == nb) {
       a.C_f32 = s.df; a.ldc32 = x->ldf; a.epi = EPI_NONE;
-      launch_gemm_nt(a, st);
+      { ProfScope pk(x, SS_K_MLP_DGRAD, st); launch_gemm_nt(a, st); }
       return nullptr;
     }
     a.C = s.dbuf16[pp]; a.ldc = x->pout[l - 1];
@@ -893,7 +905,7 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
     a.epi = EPI_MASK;
     a.mask = s.act_bf16[l - 1]; a.ldmask = x->pout[l - 1];
     a.maskT = s.actT[l - 1]; a.ldmaskT = x->ldT;
-    launch_gemm_nt(a, st);
+    { ProfScope pk(x, SS_K_MLP_DGRAD, st); launch_gemm_nt(a, st); }
     const uint16_t* out = s.dbuf16[pp];
     pp ^= 1;
     return out;
@@ -935,7 +947,7 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
         g.L[l].in = ly.in; g.L[l].out = ly.out;
       }
       g.tiles = x->wgrad_tiles_dev; g.B = B; g.ldT = x->ldT;
-      launch_mlp_wgrad_grouped(g, (int)x->wgrad_tiles.size(), st);
+      { ProfScope pk(x, SS_K_MLP_WGRAD, st); launch_mlp_wgrad_grouped(g, (int)x->wgrad_tiles.size(), st); }
     }
   }
 }
@@ -972,8 +984,8 @@ static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, floa
   // ---- look-ups (pooled where the table lives) and interaction
   {
     ProfScope ps(x, SS_K_GATHER, st);
-    launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e, s.keys,
-                             s.bag_of_pos, fused_last(x) ? loss : nullptr, x->pool_mean ? s.inv_len : nullptr, st);
+    launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e,
+                             train ? s.keys : nullptr, s.bag_of_pos, fused_last(x) ? loss : nullptr, x->pool_mean ? s.inv_len : nullptr, st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -1111,13 +1123,14 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
   if (!fused_last(x)) launch_bce_loss(s.logits, bt->labels, B, loss, train ? s.dlogit : nullptr, st);
   s.last_B = B;
   s.last_n = n;
+  if (!train) launch_metrics(loss, bt->labels, B, x->metrics + 4, st);
   if (train) {
     s.sort_n = n;
     if (x->fused) backward_fused(x, s, w, bt, st);
     else if (x->wide) backward_wide(x, s, w, bt, st);
     else backward_dense(x, s, w, bt, st);
     // "update local param w^(i)": lock-free SGD on the replica
-    launch_sgd(w, s.grads, x->P, x->lr_dense, st);
+    launch_sgd(w, s.grads, x->P, x->lr_dense, loss, bt->labels, B, x->metrics, st);
     // "update h": stable sort by row, one Adagrad update per distinct row
     {
       ProfScope ps(x, SS_K_SORT, st);
@@ -1215,11 +1228,33 @@ int ss_shadow_start(ss_ctx* ctx, int32_t algo, float alpha, float eta, float mom
   ctx->shadow = std::thread([ctx, algo, alpha, eta, momentum, st]() {
     if (hipSetDevice(ctx->device) != hipSuccess) { ctx->sticky = 1; return; }
     // Algorithm 1, shadow loop (Section 3.2): rounds follow one another, uncoupled from the workers
+    auto next = std::chrono::steady_clock::now();
     while (ctx->shadow_run.load()) {
       if (sync_once(ctx, algo, alpha, eta, momentum, st) != SS_OK) break;
       if (hipStreamSynchronize(st) != hipSuccess) { ctx->sticky = 1; break; }
+      const int64_t period = ctx->shadow_period_us.load(std::memory_order_relaxed);
+      if (period > 0) {
+        // rounds START at least `period` apart; sleep in short slices so that a stop request
+        // is seen promptly
+        next += std::chrono::microseconds(period);
+        const auto now = std::chrono::steady_clock::now();
+        if (next < now) next = now;
+        while (ctx->shadow_run.load() && std::chrono::steady_clock::now() < next) {
+          const auto left = next - std::chrono::steady_clock::now();
+          std::this_thread::sleep_for(left > std::chrono::microseconds(200)
+                                          ? std::chrono::microseconds(200)
+                                          : std::chrono::duration_cast<std::chrono::microseconds>(left));
+        }
+      }
     }
   });
+  return SS_OK;
+}
+
+int ss_shadow_pace(ss_ctx* ctx, int64_t min_period_us) {
+  if (!ctx) return SS_EINVAL;
+  if (min_period_us < 0) return fail(ctx, SS_EINVAL, "shadow period must be >= 0");
+  ctx->shadow_period_us = min_period_us;
   return SS_OK;
 }
 
@@ -1254,7 +1289,38 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
     }
     HIP_TRY(ctx, hipMemcpy(&U, s.seg.num_unique, 4, hipMemcpyDeviceToHost));
   }
+  const int L = (int)ctx->layers.size();
+  if (item >= SS_DBG_HIDDEN_ACT && item < SS_DBG_HIDDEN_ACT + L) {
+    // hidden activations live in a path-specific layout (fp32 or bf16, row-major with a padded
+    // pitch, or transposed [unit][sample]); they are brought to float [B, out] on the host
+    const int l = item - SS_DBG_HIDDEN_ACT;
+    if (l == ctx->n_bot_layers - 1 || l == L - 1)
+      return fail(ctx, SS_EINVAL, "layer %d has no hidden activation buffer", l);
+    const size_t out = (size_t)ctx->layers[l].out;
+    const size_t sz = B * out * 4;
+    if (size_out) *size_out = sz;
+    if (!host_out || bytes == 0 || sz == 0) return SS_OK;
+    if (bytes < sz) return fail(ctx, SS_EINVAL, "buffer too small for a hidden activation");
+    float* dst = (float*)host_out;
+    if (ctx->prec == SS_FP32) {
+      HIP_TRY(ctx, hipMemcpy(dst, s.act_f32[l], sz, hipMemcpyDeviceToHost));
+      return SS_OK;
+    }
+    const bool transposed = ctx->fused;
+    const size_t pitch = transposed ? (size_t)ctx->ldT : (ctx->wide ? (size_t)ctx->pout[l] : out);
+    const size_t n_rows = transposed ? out : B;
+    std::vector<uint16_t> raw(n_rows * pitch);
+    HIP_TRY(ctx, hipMemcpy(raw.data(), transposed ? s.actT[l] : s.act_bf16[l], raw.size() * 2,
+                           hipMemcpyDeviceToHost));
+    for (size_t b = 0; b < B; ++b)
+      for (size_t u = 0; u < out; ++u) {
+        const uint32_t bits = (uint32_t)(transposed ? raw[u * pitch + b] : raw[b * pitch + u]) << 16;
+        memcpy(&dst[b * out + u], &bits, 4);
+      }
+    return SS_OK;
+  }
   switch (item) {
+    case SS_DBG_Z0: src = s.z0; size = B * ctx->d * 4; break;
     case SS_DBG_POOLED: src = s.e; size = B * ctx->T * ctx->d * 4; break;
     case SS_DBG_INTERACT: src = s.f; rows = B; width = (size_t)ctx->F * 4; pitch_src = (size_t)ctx->ldf * 4; size = rows * width; break;
     case SS_DBG_LOGITS: src = s.logits; size = B * 4; break;
@@ -1264,7 +1330,7 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
     case SS_DBG_SORTED_POS: src = s.sorted_pos; size = ns * 4; break;
     case SS_DBG_SEG_STARTS: src = s.seg.seg_starts; size = (size_t)U * 4; break;
     case SS_DBG_NUM_UNIQUE: src = s.seg.num_unique; size = 4; break;
-    case SS_DBG_BAG_OF_POS: src = s.bag_of_pos; size = n * 4; break;
+    case SS_DBG_BAG_OF_POS: src = s.bag_of_pos; size = ns * 4; break;
     default: return fail(ctx, SS_EINVAL, "unknown debug item %d", item);
   }
   if (size_out) *size_out = size;
@@ -1276,6 +1342,33 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
   } else {
     HIP_TRY(ctx, hipMemcpy(host_out, src, bytes < size ? bytes : size, hipMemcpyDeviceToHost));
   }
+  return SS_OK;
+}
+
+int ss_metrics_read(ss_ctx* ctx, int32_t which, double* host_out4) {
+  if (!ctx || !host_out4) return SS_EINVAL;
+  if (which != 0 && which != 1) return fail(ctx, SS_EINVAL, "metrics selector must be 0 (train) or 1 (eval)");
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  double acc[4];
+  HIP_TRY(ctx, hipMemcpy(acc, ctx->metrics + 4 * which, sizeof acc, hipMemcpyDeviceToHost));
+  const double n = acc[2];
+  const double nan = std::nan("");
+  host_out4[0] = n;
+  host_out4[1] = n > 0 ? acc[0] / n : nan;
+  host_out4[2] = n > 0 ? acc[1] / n : nan;
+  const double p = host_out4[2];
+  host_out4[3] = (n > 0 && p > 0.0 && p < 1.0)
+                     ? host_out4[1] / -(p * std::log(p) + (1.0 - p) * std::log(1.0 - p))
+                     : nan;
+  return SS_OK;
+}
+
+int ss_metrics_reset(ss_ctx* ctx, int32_t which) {
+  if (!ctx) return SS_EINVAL;
+  if (which != 0 && which != 1) return fail(ctx, SS_EINVAL, "metrics selector must be 0 (train) or 1 (eval)");
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemset(ctx->metrics + 4 * which, 0, 4 * sizeof(double)));
+  HIP_TRY(ctx, hipDeviceSynchronize());
   return SS_OK;
 }
 

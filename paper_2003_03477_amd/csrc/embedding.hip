@@ -35,8 +35,10 @@ __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
     uint32_t grow = 0;
     if (j < hi) {
       grow = base + (uint32_t)indices[j];
-      keys[j] = grow;
-      bag_of_pos[j] = ebag;
+      if (keys) {   // (forward-only evaluation records nothing for a backward pass)
+        keys[j] = grow;
+        bag_of_pos[j] = ebag;
+      }
     }
     const int cnt = min(SS_WAVE, hi - j0);
     // trip count is wave-uniform so every lane takes part in every permute

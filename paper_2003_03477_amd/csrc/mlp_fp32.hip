@@ -128,21 +128,60 @@ void launch_bce_loss(const float* logit, const float* y, int B, float* loss, flo
   hipLaunchKernelGGL(bce_loss_kernel, dim3(1), dim3(1024), 0, s, logit, y, B, loss, dlogit);
 }
 
+// Running sums behind the normalised entropy (Section 4, "Evaluation Metrics"): one block adds
+// the batch's summed log-loss (mean * B), its number of positive labels and B to three doubles.
+__device__ __forceinline__ void metrics_block(const float* __restrict__ mean_loss,
+                                              const float* __restrict__ y, int B,
+                                              double* __restrict__ acc) {
+  __shared__ float part[4];
+  float s = 0.f;
+  for (int b = threadIdx.x; b < B; b += 256) s += y[b];
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    atomicAdd(acc + 0, (double)mean_loss[0] * (double)B);
+    atomicAdd(acc + 1, (double)((part[0] + part[1]) + (part[2] + part[3])));
+    atomicAdd(acc + 2, (double)B);
+  }
+}
+
+__global__ __launch_bounds__(256) void metrics_kernel(const float* __restrict__ mean_loss,
+                                                      const float* __restrict__ y, int B,
+                                                      double* __restrict__ acc) {
+  metrics_block(mean_loss, y, B, acc);
+}
+
+void launch_metrics(const float* mean_loss, const float* y, int B, double* acc, hipStream_t s) {
+  hipLaunchKernelGGL(metrics_kernel, dim3(1), dim3(256), 0, s, mean_loss, y, B, acc);
+}
+
 // w -= lr * g.  Plain loads and stores: concurrent steps on one replica overwrite each other
-// the way the paper's lock-free worker threads do (Section 3.2).
+// the way the paper's lock-free worker threads do (Section 3.2).  With acc != nullptr the
+// launch carries one extra block that adds the step's loss and labels to the running metrics
+// (the loss is final by the time the update runs).
 __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ w,
                                                   const float* __restrict__ g, int64_t n,
-                                                  float lr) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+                                                  float lr, const float* __restrict__ mean_loss,
+                                                  const float* __restrict__ y, int B,
+                                                  double* __restrict__ acc) {
+  const unsigned nb = acc ? gridDim.x - 1 : gridDim.x;
+  if (blockIdx.x == nb) {
+    metrics_block(mean_loss, y, B, acc);
+    return;
+  }
+  const int64_t stride = (int64_t)nb * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
     w[i] -= lr * g[i];
 }
 
-void launch_sgd(float* w, const float* g, int64_t n, float lr, hipStream_t s) {
+void launch_sgd(float* w, const float* g, int64_t n, float lr, const float* mean_loss,
+                const float* y, int B, double* acc, hipStream_t s) {
   if (n == 0) return;
   int64_t blocks = (n + 255) / 256;
   if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, g, n, lr);
+  hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)blocks + (acc ? 1u : 0u)), dim3(256), 0, s, w, g, n,
+                     lr, mean_loss, y, B, acc);
 }
 
 }  // namespace ss

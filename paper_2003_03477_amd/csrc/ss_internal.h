@@ -94,8 +94,12 @@ void launch_col_sum_f32(const float* dY, int ld, int M, int N, float* db, hipStr
 // loss = mean_b bce(logit_b, y_b) ; dlogit_b = (sigmoid(logit_b) - y_b) / B
 void launch_bce_loss(const float* logit, const float* y, int B, float* loss, float* dlogit,
                      hipStream_t s);
-// w -= lr * g   (lock-free, plain loads and stores)
-void launch_sgd(float* w, const float* g, int64_t n, float lr, hipStream_t s);
+// w -= lr * g   (lock-free, plain loads and stores); with acc != nullptr one extra block adds
+// (mean_loss * B, sum of labels, B) to the three doubles at acc
+void launch_sgd(float* w, const float* g, int64_t n, float lr, const float* mean_loss,
+                const float* y, int B, double* acc, hipStream_t s);
+// the same accumulation as a launch of its own (evaluation steps)
+void launch_metrics(const float* mean_loss, const float* y, int B, double* acc, hipStream_t s);
 
 // ---------------------------------------------------------------------------- mlp_bf16.hip
 struct GemmBf16Args {

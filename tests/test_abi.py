@@ -84,30 +84,34 @@ def test_bench_refuses_more_than_one_gpu():
     assert "ONE GPU" in r.stderr
 
 
-def test_workspace_layout_covers_all_three_bf16_mlp_paths(monkeypatch):
-    """Host-side layout only (no GPU): the fused, wide-layer and generic bf16 configurations
-    all produce a workspace size, and the wide-layer path needs more than the generic one
-    (bf16 weight snapshots, transposed copies, weight-gradient slices)."""
+def test_workspace_layout_covers_the_bf16_mlp_paths():
+    """Host-side layout only (no GPU): the fused and the layer-wise bf16 configurations and a
+    model served by the layout-agnostic GEMM all produce a workspace size; an unknown
+    mlp_path is rejected."""
     from paper_2003_03477_amd import binding, synth
     import ctypes as C
     lib = binding.load()
 
-    def size(wl, **env):
-        for k in ("SS_NO_FUSED_MLP", "SS_NO_WIDE_GEMM"):
-            monkeypatch.delenv(k, raising=False)
-        for k, v in env.items():
-            monkeypatch.setenv(k, v)
+    def size(wl, mlp_path):
         rows = (C.c_int64 * len(wl.rows))(*wl.rows)
         bot = (C.c_int32 * len(wl.bot_dims))(*wl.bot_dims)
         top = (C.c_int32 * len(wl.top_dims))(*wl.top_dims)
         cfg = binding.ss_config(len(wl.rows), rows, wl.emb_dim, wl.bot_dims[0], len(wl.bot_dims), bot,
                                 len(wl.top_dims), top, wl.num_replicas, wl.batch, 400000, 2,
-                                binding.SS_BF16, 0.01, 0.01, 1e-8, 1, 0)
+                                binding.SS_BF16, 0.01, 0.01, 1e-8, 1, 0, mlp_path)
         return lib.ss_workspace_bytes(C.byref(cfg))
 
     mid = synth.mid()
-    fused = size(mid)
-    wide = size(mid, SS_NO_FUSED_MLP="1")
-    generic = size(mid, SS_NO_FUSED_MLP="1", SS_NO_WIDE_GEMM="1")
-    assert fused > 0 and wide > 0 and generic > 0
-    assert wide > generic and fused > generic
+    fused = size(mid, 0)
+    layerwise = size(mid, 1)
+    generic = size(mid.scaled(top_dims=(100, 1)), 0)
+    assert fused > 0 and layerwise > 0 and generic > 0
+    assert layerwise != fused
+    assert size(mid, 7) == 0
+
+
+def test_metrics_and_pace_reject_bad_arguments_without_a_device():
+    lib = binding.load()
+    assert lib.ss_metrics_read(None, 0, None) == -1
+    assert lib.ss_metrics_reset(None, 0) == -1
+    assert lib.ss_shadow_pace(None, 10) == -1

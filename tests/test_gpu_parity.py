@@ -66,6 +66,37 @@ def test_sync_invariants_on_device():
     assert float((W - W[0]).abs().max()) == 0.0
 
 
+@pytest.mark.parametrize("algo", ["easgd", "easgd_literal", "ma", "bmuf", "bmuf_nesterov"])
+def test_sync_round_streaming_size_matches_oracle(algo):
+    """A working set beyond the memory-side cache (K=8 x 8.4M parameters + centre copy, 300 MB):
+    the round then runs through the kernel's streaming (non-temporal) instantiation, the one
+    the sync-isolation benchmark times.  Every element against the oracle, two rounds."""
+    torch = _torch()
+    K, P = 8, 8_400_000
+    stride = P + 1024
+    rng = np.random.default_rng(4)
+    W = (rng.standard_normal((K, stride)) * 0.02).astype(np.float32)
+    ps, wg, v = [(rng.standard_normal(P) * 0.02).astype(np.float32) for _ in range(3)]
+    dW, dps, dwg, dv = [torch.from_numpy(a.copy()).cuda() for a in (W, ps, wg, v)]
+    oW, ops, owg, ov = [a.astype(np.float64) for a in (W[:, :P], ps, wg, v)]
+    fn = {"easgd": lambda: osync.easgd_round(oW, ops, 0.05),
+          "easgd_literal": lambda: osync.easgd_round_literal(oW, ops, 0.05),
+          "ma": lambda: osync.ma_round(oW, owg, 0.5),
+          "bmuf": lambda: osync.bmuf_round(oW, owg, ov, 0.5, 1.0, 0.9),
+          "bmuf_nesterov": lambda: osync.bmuf_nesterov_round(oW, owg, ov, 0.5, 1.0, 0.9)}[algo]
+    alpha = 0.05 if algo.startswith("easgd") else 0.5
+    for r in range(2):
+        binding.ss_sync_round(algo, K, P, stride, dW, dps, dwg, dv, alpha=alpha, eta=1.0, momentum=0.9)
+        fn()
+    torch.cuda.synchronize()
+    gW = dW.cpu().numpy()
+    H.close(gW[:, :P], oW, H.FP32_RTOL, "replicas")
+    assert np.array_equal(gW[:, P:], W[:, P:]), "padding between replicas was written"
+    H.close(dps.cpu().numpy(), ops, H.FP32_RTOL, "w_ps")
+    H.close(dwg.cpu().numpy(), owg, H.FP32_RTOL, "w_global")
+    H.close(dv.cpu().numpy(), ov, H.FP32_RTOL, "v", scale=0.02)
+
+
 # ----------------------------------------------------------------------------- table init
 def test_hash_table_init_is_bit_identical():
     wl = synth.tiny().scaled(rows=(1000, 37, 4096, 5))
@@ -89,6 +120,11 @@ def test_tiny_config_deterministic_schedule():
     H.compare_state(gpu, orc, H.FP32_RTOL, "after 20 sweeps", wl.row_base)
     steps, rounds, examples = gpu.ss_get_counters()
     assert steps.tolist() == [20, 20] and rounds == 20 and examples == 40 * wl.batch
+    # progressive Train NE over the 40 batches (each scored before the model trained on it)
+    n, mean, ctr, ne = gpu.ss_metrics_read(0)
+    on, omean, octr, one = orc.ne("train")
+    assert n == on == 40 * wl.batch and abs(ctr - octr) < 1e-12
+    assert abs(mean - omean) <= H.FP32_RTOL * omean and abs(ne - one) <= H.FP32_RTOL * one
 
 
 @pytest.mark.parametrize("algo,alpha,eta,mu,gap", [("easgd", 0.1, 1.0, 0.0, 2),
@@ -184,42 +220,82 @@ def test_empty_bags_single_sample_and_hot_row():
     H.compare_state(gpu, orc, H.FP32_RTOL, "edge cases", wl.row_base)
 
 
-def _select_mlp_path(path, monkeypatch):
-    """fused: per-sample-tile kernels; wide: one 128x128-tile GEMM per layer and pass;
-    generic: the layout-agnostic GEMM that serves every remaining bf16 model."""
-    if path in ("wide", "generic"):
-        monkeypatch.setenv("SS_NO_FUSED_MLP", "1")
-    if path == "generic":
-        monkeypatch.setenv("SS_NO_WIDE_GEMM", "1")
-
-
-@pytest.mark.parametrize("path", ["fused", "wide", "generic"])
-def test_bf16_mid_scaled(path, monkeypatch):
+# The three bf16 MLP code paths: "auto" picks the per-sample-tile fused kernels for these
+# widths, "layerwise" forces one 128x128-tile GEMM per layer and pass; models without a hidden
+# top layer run the layout-agnostic GEMM (test_bf16_no_hidden_top_layer).
+@pytest.mark.parametrize("path", ["auto", "layerwise"])
+def test_bf16_mid_scaled(path):
     """Mid CTR architecture (bf16 MLP GEMMs, fp32 master weights) on a compacted table set,
-    through each of the three bf16 MLP code paths."""
-    _select_mlp_path(path, monkeypatch)
+    step by step from a common state, every element of every tensor within the bf16 bound."""
     wl = synth.mid().scaled(batch=500, num_replicas=2, sync_gap=2)
     gen = synth.BatchGenerator(wl)
     batches = [gen.batch(s) for s in range(8)]
     cp = synth.compact_problem(wl, batches)
-    gpu, orc = H.make_pair(wl, cp.batches, h0=cp.h0, rows=cp.rows)
+    gpu, orc = H.make_pair(wl, cp.batches, h0=cp.h0, rows=cp.rows, mlp_path=path)
     row_base = np.concatenate(([0], np.cumsum(cp.rows)))
     H.run_lockstep(gpu, orc, cp.batches, wl.sync_gap, wl.algo, wl.alpha, rtol=H.BF16_RTOL,
                    resync_row_base=row_base)
+    print("gates taken the other way:", H.GATE_STATS)
 
 
-@pytest.mark.parametrize("path", ["fused", "wide", "generic"])
-def test_bf16_odd_widths(path, monkeypatch):
+@pytest.mark.parametrize("path", ["auto", "layerwise"])
+def test_bf16_odd_widths(path):
     """bf16 with layer widths that are not multiples of the MFMA tile (guards, padding)."""
-    _select_mlp_path(path, monkeypatch)
     wl = synth.tiny().scaled(batch=77, rows=(3000, 17, 900), emb_dim=64, bag_lambda=4.0,
                              bot_dims=(13, 40, 64), top_dims=(64 + 6, 72, 24, 1),
                              num_replicas=1, bf16=True, algo="ma", alpha=1.0)
     gen = synth.BatchGenerator(wl)
     batches = [gen.batch(s) for s in range(4)]
-    gpu, orc = H.make_pair(wl, batches)
+    gpu, orc = H.make_pair(wl, batches, mlp_path=path)
     H.run_lockstep(gpu, orc, batches, 1, "ma", 1.0, rtol=H.BF16_RTOL,
                    resync_row_base=wl.row_base)
+
+
+def test_bf16_no_hidden_top_layer():
+    """A bf16 model whose top MLP is a single linear unit: served by the layout-agnostic GEMM
+    (neither the fused nor the layer-wise kernels apply)."""
+    wl = synth.tiny().scaled(batch=130, rows=(3000, 17, 900), emb_dim=32, bag_lambda=4.0,
+                             bot_dims=(13, 72, 40, 32), top_dims=(32 + 6, 1),
+                             num_replicas=2, bf16=True, algo="easgd", alpha=0.2, sync_gap=2)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(6)]
+    gpu, orc = H.make_pair(wl, batches)
+    H.run_lockstep(gpu, orc, batches, wl.sync_gap, wl.algo, wl.alpha, rtol=H.BF16_RTOL,
+                   resync_row_base=wl.row_base)
+
+
+def test_bf16_free_running_mid_scaled():
+    """Mid architecture, K=4, S-EASGD every 5 sweeps, 20 sweeps WITHOUT resynchronising the two
+    sides: every loss within the bf16 bound of the oracle's, and the final replicas within it
+    in the Frobenius norm.  (Element-wise bounds do not survive a free run: row-wise Adagrad
+    turns a 1 % gradient difference into a step difference of 1e-4 on rows of magnitude 0.05,
+    and undecidable ReLU gates are taken differently; the per-step tests above cover the
+    elements.)"""
+    wl = synth.mid().scaled(batch=500, num_replicas=4, sync_gap=5)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(80)]
+    cp = synth.compact_problem(wl, batches)
+    gpu, orc = H.make_pair(wl, cp.batches, h0=cp.h0, rows=cp.rows)
+    dev = [binding.upload_batch(b) for b in cp.batches]
+    K = 4
+    worst = 0.0
+    for s in range(20):
+        for i in range(K):
+            k = s * K + i
+            lg = float(gpu.ss_train_step(i, 0, dev[k]).cpu()[0])
+            lo = orc.train_step(i, *cp.batches[k].as_tuple())
+            worst = max(worst, abs(lg - lo) / lo)
+            assert abs(lg - lo) <= H.BF16_RTOL * lo, f"step {k}: loss {lg} vs {lo}"
+        if (s + 1) % wl.sync_gap == 0:
+            orc.shadow_sync(wl.algo, wl.alpha)
+            gpu.ss_shadow_sync(wl.algo, wl.alpha)
+    for i in range(K):
+        got, want = gpu.ss_read_dense(i).astype(np.float64), orc.W[i]
+        fro = np.linalg.norm(got - want) / np.linalg.norm(want)
+        assert fro <= H.BF16_RTOL, f"replica {i}: relative Frobenius error {fro}"
+    got, want = gpu.ss_read_dense(-1).astype(np.float64), orc.w_ps
+    assert np.linalg.norm(got - want) / np.linalg.norm(want) <= H.BF16_RTOL
+    print(f"free run: worst relative loss difference {worst:.2e}")
 
 
 def test_validation_errors_through_the_abi():
@@ -261,8 +337,9 @@ def _full_size_step_check(wl, n_batches, rtol):
     B = wl.batch
     for k, (b, cb) in enumerate(zip(batches, cp.batches)):
         dev = binding.upload_batch(b)
-        lo = orc.train_step(0, *cb.as_tuple())
         lg = float(gpu.ss_train_step(0, 0, dev).cpu()[0])
+        lo, flipped = H.oracle_step(gpu, orc, 0, 0, cb.as_tuple())
+        print(f"{wl.name} step {k}: undecidable ReLU gates taken the other way: {flipped}")
         assert abs(lg - lo) <= rtol * abs(lo), f"step {k}: loss {lg} vs {lo}"
         last = orc.last
         # sort order: positions bit-exact; keys equal after mapping compact ids back
@@ -276,13 +353,15 @@ def _full_size_step_check(wl, n_batches, rtol):
         H.close(gpu.ss_read_debug(0, binding.DBG_POOLED), last["e"],
                 H.FP32_RTOL if k == 0 else rtol, f"step {k}: pooled e")
         H.close(gpu.ss_read_debug(0, binding.DBG_LOGITS), last["logit"], rtol, f"step {k}: logits")
-        H.close(gpu.ss_read_debug(0, binding.DBG_DENSE_GRAD), last["g"], rtol, f"step {k}: dense grad")
+        H.close_dense(gpu.ss_read_debug(0, binding.DBG_DENSE_GRAD), last["g"], rtol,
+                      f"step {k}: dense grad", orc.layout)
         H.close(gpu.ss_read_debug(0, binding.DBG_POOLED_GRAD), last["de"], rtol, f"step {k}: de")
-        H.close(gpu.ss_read_dense(0), orc.W[0], rtol, f"step {k}: replica 0")
+        H.close_dense(gpu.ss_read_dense(0), orc.W[0], rtol, f"step {k}: replica 0", orc.layout)
         for t in range(wl.num_tables):
             vals, acc = gpu.ss_read_rows(t, cp.touched[t])
             H.close(vals, orc.h[row_base_c[t]:row_base_c[t + 1]], rtol, f"step {k}: table {t} rows")
-            H.close(acc, orc.G[row_base_c[t]:row_base_c[t + 1]], rtol, f"step {k}: table {t} G")
+            # (the accumulator is quadratic in the row gradient: twice its relative error)
+            H.close(acc, orc.G[row_base_c[t]:row_base_c[t + 1]], 2 * rtol, f"step {k}: table {t} G")
         # a sample of untouched rows is still the hash value, accumulator still zero
         rng = np.random.default_rng(k)
         for t in range(0, wl.num_tables, 3):
@@ -334,14 +413,65 @@ def test_single_trainer_easgd_exchange_and_eval_ne():
     lo = orc.eval_logloss(0, *batches[3].as_tuple())
     assert abs(lg - lo) <= H.FP32_RTOL * lo
     assert np.array_equal(before, gpu.ss_read_dense(0))
-    ctr = float(batches[3].labels.mean())
-    ne_gpu = binding.normalized_entropy(lg, ctr)
-    ent = -(ctr * np.log(ctr) + (1 - ctr) * np.log(1 - ctr))
-    assert abs(ne_gpu - lo / ent) < 1e-5
+    # NE (Section 4): the library's running accumulators against the oracle's
+    n, mean, ctr, ne = gpu.ss_metrics_read(1)
+    on, omean, octr, one = orc.ne("eval")
+    assert n == on and abs(ctr - octr) < 1e-12
+    assert abs(mean - omean) <= H.FP32_RTOL * omean and abs(ne - one) <= H.FP32_RTOL * one
+    n, mean, ctr, ne = gpu.ss_metrics_read(0)           # the three training steps above
+    on, omean, octr, one = orc.ne("train")
+    assert n == on == 3 * wl.batch and abs(ctr - octr) < 1e-12
+    assert abs(ne - one) <= H.FP32_RTOL * one
+    gpu.ss_metrics_reset(0)
+    assert gpu.ss_metrics_read(0)[0] == 0 and np.isnan(gpu.ss_metrics_read(0)[3])
+    assert gpu.ss_metrics_read(1)[0] == wl.batch            # eval accumulator untouched by the reset
+
+
+@pytest.mark.parametrize("path", ["auto", "layerwise"])
+def test_eval_step_bf16_paths(path):
+    """Forward-only evaluation through the fused and the layer-wise bf16 kernels: loss and
+    logits against the oracle's, nothing updated, and the sorted arrays of the last TRAINING
+    step stay readable afterwards although the evaluated batch has another size."""
+    wl = synth.mid().scaled(batch=300, num_replicas=2)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(3)]
+    small = synth.BatchGenerator(wl.scaled(batch=100)).batch(7)
+    cp = synth.compact_problem(wl, batches)
+    row_base = np.concatenate(([0], np.cumsum(cp.rows)))
+    gpu, orc = H.make_pair(wl, cp.batches, h0=cp.h0, rows=cp.rows, mlp_path=path)
+    dev = [binding.upload_batch(b) for b in cp.batches]
+    gpu.ss_train_step(1, 0, dev[0])
+    H.oracle_step(gpu, orc, 0, 1, cp.batches[0].as_tuple())
+    H.push_oracle_state(gpu, orc, row_base)
+    sorted_rows = gpu.ss_read_debug(0, binding.DBG_SORTED_ROWS).copy()
+    seg = gpu.ss_read_debug(0, binding.DBG_SEG_STARTS).copy()
+    before_w = gpu.ss_read_dense(1)
+    before_rows = gpu.ss_read_rows(0, np.arange(cp.rows[0]))
+    for k in (1, 2):
+        lg = float(gpu.ss_eval_step(1, 0, dev[k]).cpu()[0])
+        lo = orc.eval_logloss(1, *cp.batches[k].as_tuple())
+        assert abs(lg - lo) <= H.BF16_RTOL * lo, f"eval loss {lg} vs {lo}"
+        orc.train_step(1, *cp.batches[k].as_tuple(), update=False)
+        H.close(gpu.ss_read_debug(0, binding.DBG_LOGITS), orc.last["logit"], H.BF16_RTOL, "eval logits")
+        H.close(gpu.ss_read_debug(0, binding.DBG_POOLED), orc.last["e"], H.FP32_RTOL, "eval pooled e")
+    # a smaller batch (rows of the same compacted tables: ids folded into range)
+    idx = small.indices.copy()
+    for t in range(wl.num_tables):
+        lo_, hi_ = small.offsets[t * 100], small.offsets[(t + 1) * 100]
+        idx[lo_:hi_] %= cp.rows[t]
+    sb = synth.Batch(small.dense, small.labels, idx, small.offsets)
+    lg = float(gpu.ss_eval_step(1, 0, binding.upload_batch(sb)).cpu()[0])
+    lo = orc.eval_logloss(1, *sb.as_tuple())
+    assert abs(lg - lo) <= H.BF16_RTOL * lo
+    assert np.array_equal(before_w, gpu.ss_read_dense(1))
+    after_rows = gpu.ss_read_rows(0, np.arange(cp.rows[0]))
+    assert np.array_equal(before_rows[0], after_rows[0]) and np.array_equal(before_rows[1], after_rows[1])
+    assert np.array_equal(sorted_rows, gpu.ss_read_debug(0, binding.DBG_SORTED_ROWS))
+    assert np.array_equal(seg, gpu.ss_read_debug(0, binding.DBG_SEG_STARTS))
 
 
 def test_profile_brackets_and_sampling():
-    """Event brackets: every launch of an armed class by default, every n-th with sampling."""
+    """Event brackets: every launch of an armed class by default, about 1 in n with sampling."""
     import torch
     wl = synth.tiny()
     gen = synth.BatchGenerator(wl)
@@ -350,16 +480,17 @@ def test_profile_brackets_and_sampling():
     gpu.ss_init_tables_hash()
     gpu.ss_init_dense(synth.dense_w0(wl))
     db = binding.upload_batch(b)
-    for every, want in ((1, 16), (4, 4), (5, 4)):
+    for every, lo, hi in ((1, 64, 64), (4, 6, 32), (8, 2, 20)):
+        # sampled launches are picked by a hash of their running number: about 1 in `every`
         gpu.ss_profile_sample(every)
         gpu.ss_profile_arm(binding.K_GATHER, binding.K_ROW_UPDATE)
-        for _ in range(16):
+        for _ in range(64):
             gpu.ss_train_step(0, 0, db, None, None)
         torch.cuda.synchronize()
         n, ms = gpu.ss_profile_read(binding.K_GATHER)
-        assert n == want and ms > 0.0
+        assert lo <= n <= hi and ms > 0.0, (every, n)
         n2, ms2 = gpu.ss_profile_read(binding.K_ROW_UPDATE)
-        assert n2 == want and ms2 > 0.0
+        assert lo <= n2 <= hi and ms2 > 0.0, (every, n2)
     with pytest.raises(binding.ShadowSyncError):
         gpu.ss_profile_sample(0)
     gpu.close()

@@ -390,3 +390,33 @@ def test_fixed_gap_schedule_reports_its_gap_and_shares_tables():
     assert tr.avg_sync_gap() == 3.0
     # alpha = 1 model averaging right after the last sweep: both replicas hold the mean
     assert np.array_equal(tr.W[0], tr.W[1])
+
+
+def test_running_ne_equals_ne_of_all_predictions_together():
+    """OracleTrainer.ne: the running accumulators over several batches give the NE of the
+    concatenated predictions (normalized_entropy, itself pinned by the constant predictor),
+    for the progressive train metric (losses before each update) and for evaluation."""
+    rng = np.random.default_rng(5)
+    p = random_problem(rng, B=6, T=2, d=4, rows=(9, 4), bot=(3, 5, 4), top_hidden=(6,))
+    tr = oracle.OracleTrainer(p["bot"], p["top"], p["row_base"], p["h"], p["w"], 1, 0.1, 0.1)
+    preds, labels = [], []
+    for k in range(4):
+        q = random_problem(np.random.default_rng(50 + k), B=5 + k, T=2, d=4, rows=(9, 4),
+                           bot=(3, 5, 4), top_hidden=(6,))
+        tr.train_step(0, q["x"], q["y"], q["indices"], q["offsets"])
+        preds.append(1 / (1 + np.exp(-tr.last["logit"])))     # scored before the update
+        labels.append(q["y"])
+    n, mean, ctr, ne = tr.ne("train")
+    assert n == sum(len(y) for y in labels)
+    assert abs(ne - oracle.normalized_entropy(np.concatenate(preds), np.concatenate(labels))) < 1e-12
+    assert abs(ctr - np.concatenate(labels).mean()) < 1e-15
+    ev_p, ev_y = [], []
+    for k in range(3):
+        q = random_problem(np.random.default_rng(80 + k), B=4 + k, T=2, d=4, rows=(9, 4),
+                           bot=(3, 5, 4), top_hidden=(6,))
+        tr.eval_logloss(0, q["x"], q["y"], q["indices"], q["offsets"])
+        fw = dlrm.dlrm_forward(tr.layout, tr.W[0], tr.h, tr.row_base, q["x"], q["indices"], q["offsets"])
+        ev_p.append(1 / (1 + np.exp(-fw["logit"])))
+        ev_y.append(q["y"])
+    assert abs(tr.ne("eval")[3] - oracle.normalized_entropy(np.concatenate(ev_p), np.concatenate(ev_y))) < 1e-12
+    assert tr.ne("train")[0] == n                              # evaluation left the train sums alone
