@@ -22,7 +22,6 @@ namespace {
 
 constexpr int MAX_LAYERS = 16;
 constexpr size_t ALIGN = 256;
-constexpr int WG_MAX_SLICES = 8;  // batch slices of a weight-gradient GEMM (wide-layer path)
 
 struct Layer {
   int in, out;
@@ -54,10 +53,11 @@ struct Slot {
   uint16_t* actT[MAX_LAYERS];      // output of hidden layer l
   uint16_t* dYT[MAX_LAYERS];       // gradient w.r.t. the output of layer l
   uint16_t* wsw;                   // bf16 fragment-ordered weights of the step's replica
-  // wide-layer path: bf16 snapshot of the weights in both orientations, bf16 dense input
-  uint16_t* wb;
-  uint16_t* xb;                    // [B][p64(num_dense)]
-  float* wg_part;                  // batch slices of the big layers' weight gradients
+  // layer-wise path: bf16 dense input, row-major gradient w.r.t. every layer's output, partial
+  // weight gradients of the batch slices
+  uint16_t* xb;                    // [B][pin[0]]
+  uint16_t* dYr[MAX_LAYERS];       // [B][pout[l]]
+  float* wg_part;
   // embedding backward
   uint32_t* keys;                  // [max_ids]
   int32_t* bag_of_pos;             // [max_ids]
@@ -109,15 +109,10 @@ struct ss_ctx {
   std::vector<int> kp_f, kp_r, depth_f, depth_r;  // per layer: padded reduction lengths, prefetch depths
   int64_t wsw_elems = 0;
   bool wide = false;               // wide-layer regime: one 128x128-tile GEMM per layer and pass
-  std::vector<int> kin, kout;      // per layer: in / out rounded up to 64 (reduction lengths)
   std::vector<int> pin, pout;      // per layer: row pitches of bf16 matrices with in / out columns
-  std::vector<int64_t> wb_off, wbt_off;  // per layer: offsets of W and W^T inside Slot::wb
-  std::vector<int> wb_tile_base;
-  std::vector<char> wgrad_grouped;  // per layer: weight gradient through the grouped 64x64-tile kernel
-  std::vector<int64_t> wg_off, wg_stride;  // per layer: its slices inside Slot::wg_part (-1: none)
+  std::vector<int64_t> wg_off, wg_stride;  // per layer: its batch slices inside Slot::wg_part
   int64_t wg_elems = 0;
-  int64_t wb_elems = 0;
-  int wb_tiles = 0;
+  int wg_slices = 1, wg_slice_len = 0;     // batch slices of the grouped weight-gradient launch
   std::vector<int4> wgrad_tiles;   // host copy of the tile table
   int4* wgrad_tiles_dev = nullptr;
   float lr_dense, lr_emb, eps;
@@ -276,17 +271,17 @@ static size_t layout(ss_ctx* x, void* base) {
     s.dz0 = cv.take<float>((size_t)B * x->d);
     s.de = cv.take<float>((size_t)B * x->T * x->d);
     s.xT = s.fT = nullptr;
-    for (int l = 0; l < L; ++l) s.actT[l] = s.dYT[l] = nullptr;
+    for (int l = 0; l < L; ++l) { s.actT[l] = s.dYT[l] = nullptr; s.dYr[l] = nullptr; }
     s.wsw = nullptr;
-    s.wb = s.xb = nullptr;
+    s.xb = nullptr;
     s.wg_part = nullptr;
+    if (x->fused || x->wide) s.wsw = cv.take<uint16_t>((size_t)x->wsw_elems);
     if (x->wide) {
       s.wg_part = cv.take<float>((size_t)x->wg_elems);
-      s.wb = cv.take<uint16_t>((size_t)x->wb_elems);
       s.xb = cv.take<uint16_t>((size_t)B * x->pin[0]);
+      for (int l = 0; l < L - 1; ++l) s.dYr[l] = cv.take<uint16_t>((size_t)B * x->pout[l]);
     }
-    if (x->fused || x->wide) {
-      if (x->fused) s.wsw = cv.take<uint16_t>((size_t)x->wsw_elems);
+    if (x->fused) {
       s.xT = cv.take<uint16_t>((size_t)x->num_dense * x->ldT);
       s.fT = cv.take<uint16_t>((size_t)x->F * x->ldT);
       for (int l = 0; l < L - 1; ++l) {
@@ -356,10 +351,11 @@ static ss_ctx* make_ctx(const ss_config* c) {
     const int nb = x->n_bot_layers, nt = x->n_top_layers, nh = nt - 1;
     bool ok = x->prec == SS_BF16 && nh >= 1 && nb <= SS_FUSED_MAX_LAYERS &&
               nh <= SS_FUSED_MAX_LAYERS && maxw <= 512 && c->mlp_path == SS_MLP_AUTO;
-    if (ok) {
-      // reduction lengths are zero padded to a multiple of 64; the prefetch depth of a layer is
-      // the larger of 8 / 4 reduction steps that divides its step count
-      auto round_up = [](int v, int m) { return (v + m - 1) / m * m; };
+    auto round_up = [](int v, int m) { return (v + m - 1) / m * m; };
+    // Both MFMA paths read the step's weights from fragment-ordered bf16 copies whose reduction
+    // lengths are zero padded to a multiple of 64; the fused kernels' prefetch depth of a layer
+    // is the larger of 8 / 4 reduction steps that divides its step count.
+    if (x->prec == SS_BF16 && nh >= 1) {
       auto depth_for = [](int kp) {
         const int steps = kp / 16;
         return steps % 8 == 0 ? 8 : 4;
@@ -370,7 +366,13 @@ static ss_ctx* make_ctx(const ss_config* c) {
         x->depth_f.push_back(depth_for(x->kp_f.back()));
         x->kp_r.push_back(round_up(ly.out, 64));
         x->depth_r.push_back(depth_for(x->kp_r.back()));
+        x->wsw_f.push_back(x->wsw_elems);
+        x->wsw_elems += (int64_t)((ly.out + 31) / 32 * 32) * x->kp_f[l];
+        x->wsw_r.push_back(x->wsw_elems);
+        x->wsw_elems += (int64_t)((ly.in + 31) / 32 * 32) * x->kp_r[l];
       }
+    }
+    if (ok) {
       // LDS tiles of each launch, in the order they are produced (tile i -> buffer i & 1)
       std::vector<int> fb, ft, rb, rt;
       for (int l = 0; l < nb; ++l) fb.push_back(x->kp_f[l]);
@@ -389,8 +391,9 @@ static ss_ctx* make_ctx(const ss_config* c) {
     }
     x->fused = ok;
     x->ldT = (x->max_batch + 7) / 8 * 8;
-    // Wide-layer regime: every other bf16 model with a hidden top layer.  Row pitches of all
-    // bf16 operands are multiples of 64 so that no GEMM needs edge handling along its reduction.
+    // Layer-wise regime: every other bf16 model with a hidden top layer.  Activations and their
+    // gradients are row-major bf16 whose pitch is a multiple of 64 elements (zero padded, so no
+    // GEMM handles an edge along its reduction).
     const int64_t pw = (maxw + 63) / 64 * 64 + 64, pb = (x->max_batch + 63) / 64 * 64 + 64;
     x->wide = !ok && x->prec == SS_BF16 && nt >= 2 && (int)x->layers.size() <= SS_NT_MAX_LAYERS &&
               pw * pb < (1ll << 31);
@@ -398,41 +401,37 @@ static ss_ctx* make_ctx(const ss_config* c) {
       // row pitches: multiples of 64 elements, never a multiple of 256 (rows that are a power
       // of two apart would all fall on the same memory channel)
       auto pitch = [](int v) { const int p = (v + 63) / 64 * 64; return (p % 256 == 0) ? p + 64 : p; };
-      x->ldT = pitch(x->max_batch);
       x->ldf16 = pitch(x->F);
+      int total_tiles = 0;
       for (size_t l = 0; l + 1 < x->layers.size(); ++l) {
         const Layer& ly = x->layers[l];
-        const int pi = pitch(ly.in), po = pitch(ly.out);
-        x->kin.push_back((ly.in + 63) / 64 * 64); x->kout.push_back((ly.out + 63) / 64 * 64);
-        x->pin.push_back(pi); x->pout.push_back(po);
-        x->wb_off.push_back(x->wb_elems); x->wb_elems += (int64_t)ly.out * pi;
-        x->wbt_off.push_back(x->wb_elems); x->wb_elems += (int64_t)ly.in * po;
-        x->wb_tile_base.push_back(x->wb_tiles);
-        x->wb_tiles += ((ly.out + 63) / 64) * (pi / 64);
-        // layers whose weight matrix has fewer than sixteen 128x128 tiles cannot fill the chip
-        // with one GEMM; their weight gradients share one launch of the grouped kernel
-        const bool small = ceil_div(ly.out, 128) * ceil_div(ly.in, 128) < 16;
-        x->wgrad_grouped.push_back(small ? 1 : 0);
-        // the other layers split the batch into up to WG_MAX_SLICES slices, each stored to its
-        // own copy and summed by one reduction launch at the end of the backward pass
-        const int64_t stride = ((int64_t)ly.out * ly.in + 3) / 4 * 4;
-        x->wg_off.push_back(small ? -1 : x->wg_elems);
-        x->wg_stride.push_back(stride);
-        if (!small) x->wg_elems += stride * WG_MAX_SLICES;
-        if (small)
-          for (int n0 = 0; n0 < ly.out; n0 += 64)
-            for (int k0 = 0; k0 < ly.in; k0 += 64)
-              x->wgrad_tiles.push_back(make_int4((int)l, n0, k0, 0));
+        x->pin.push_back(pitch(ly.in)); x->pout.push_back(pitch(ly.out));
+        total_tiles += ceil_div(ly.out, 128) * ceil_div(ly.in, 128);
       }
+      // Weight gradients: ONE launch over (layer, 128x128 tile, batch slice).  The batch is cut
+      // into as many slices as keep about two blocks per CU busy (each at least 256 samples
+      // long); a slice stores its partial [out][in] + [out] sums, one reduction launch adds them.
+      const int Bp = round_up(x->max_batch, 64);
+      int slices = 512 / total_tiles;
+      if (slices > Bp / 256) slices = Bp / 256;
+      if (slices > 32) slices = 32;
+      if (slices < 1) slices = 1;
+      x->wg_slice_len = round_up(ceil_div(Bp, slices), 64);
+      x->wg_slices = ceil_div(Bp, x->wg_slice_len);
+      for (size_t l = 0; l + 1 < x->layers.size(); ++l) {
+        const Layer& ly = x->layers[l];
+        const int64_t stride = ((int64_t)ly.out * ly.in + ly.out + 3) / 4 * 4;
+        x->wg_off.push_back(x->wg_elems);
+        x->wg_stride.push_back(stride);
+        x->wg_elems += stride * x->wg_slices;
+        for (int z = 0; z < x->wg_slices; ++z)
+          for (int m0 = 0; m0 < ly.out; m0 += 128)
+            for (int n0 = 0; n0 < ly.in; n0 += 128)
+              x->wgrad_tiles.push_back(make_int4((int)l, m0, n0, z));
+      }
+      while (x->wgrad_tiles.size() % 8) x->wgrad_tiles.push_back(make_int4(-1, 0, 0, 0));
     }
     if (ok) {
-      for (int l = 0; l < nb + nh; ++l) {
-        const Layer& ly = x->layers[l];
-        x->wsw_f.push_back(x->wsw_elems);
-        x->wsw_elems += (int64_t)((ly.out + 31) / 32 * 32) * x->kp_f[l];
-        x->wsw_r.push_back(x->wsw_elems);
-        x->wsw_elems += (int64_t)((ly.in + 31) / 32 * 32) * x->kp_r[l];
-      }
       // weight-gradient tiles of every layer except the one-unit output layer
       for (int l = 0; l < nb + nh; ++l)
         for (int n0 = 0; n0 < x->layers[l].out; n0 += 64)
@@ -482,11 +481,19 @@ int ss_init(const ss_config* cfg, void* dev_workspace, size_t bytes, ss_ctx** ou
   launch_fill_f32((float*)x->metrics, 16, 0.f, nullptr);
   for (Slot& s : x->slots) launch_fill_f32(s.grads, (uint64_t)x->Pstride, 0.f, nullptr);
   if (x->wide) {
-    // the reduction-dimension padding of these buffers is read (against zero weights) before
-    // anything writes it, so it must hold finite values from the start
-    const uint64_t words = (uint64_t)x->max_batch * ((x->maxw + 63) / 64 * 64 + 64) / 2;
-    for (Slot& s : x->slots)
-      for (int i = 0; i < 2; ++i) launch_fill_f32((float*)s.dbuf16[i], words, 0.f, nullptr);
+    // the pitch padding of these row-major bf16 buffers is read as an operand (against zero
+    // weights, or as zero contributions to a weight gradient) and only partly rewritten by the
+    // kernels, so it holds zeros from the start
+    const int L = (int)x->layers.size();
+    for (Slot& s : x->slots) {
+      launch_fill_f32((float*)s.xb, (uint64_t)x->max_batch * x->pin[0] / 2, 0.f, nullptr);
+      if (s.f_bf16) launch_fill_f32((float*)s.f_bf16, (uint64_t)x->max_batch * x->ldf16 / 2, 0.f, nullptr);
+      for (int l = 0; l < L - 1; ++l) {
+        launch_fill_f32((float*)s.dYr[l], (uint64_t)x->max_batch * x->pout[l] / 2, 0.f, nullptr);
+        if (s.act_bf16[l])
+          launch_fill_f32((float*)s.act_bf16[l], (uint64_t)x->max_batch * x->pout[l] / 2, 0.f, nullptr);
+      }
+    }
   }
   if (!x->wgrad_tiles.empty())
     (void)hipMemcpy(x->wgrad_tiles_dev, x->wgrad_tiles.data(), x->wgrad_tiles.size() * sizeof(int4),
@@ -691,28 +698,14 @@ static void fill_stack(const ss_ctx* x, const Slot& s, const float* w, int l0, i
   }
 }
 
+static void launch_weight_snapshot(ss_ctx* x, Slot& s, const float* w, bool train, hipStream_t st);
+
 static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, float* loss,
                           bool train, hipStream_t st) {
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers, nh = x->n_top_layers - 1;
   {
     ProfScope ps(x, SS_K_MLP, st);
-    // this step's snapshot of the replica, bf16, in MFMA fragment order
-    PrepArgs pa{};
-    pa.n_layers = nb + nh;
-    int64_t base = 0;
-    for (int l = 0; l < nb + nh; ++l) {
-      const Layer& ly = x->layers[l];
-      PrepLayer& pl = pa.L[l];
-      pl.W = w + ly.w_off; pl.Wf = s.wsw + x->wsw_f[l]; pl.Wr = s.wsw + x->wsw_r[l];
-      pl.in = ly.in; pl.out = ly.out; pl.frag_base = base;
-      pl.kp_f = x->kp_f[l]; pl.kp_r = x->kp_r[l];
-      pl.frags_fwd = (x->wsw_r[l] - x->wsw_f[l]) / 8;
-      const int64_t end = (l + 1 < nb + nh) ? x->wsw_f[l + 1] : x->wsw_elems;
-      base += (end - x->wsw_f[l]) / 8;
-    }
-    pa.total_frags = base;
-    pa.zero = train ? s.grads : nullptr; pa.zero_n = x->P;
-    launch_mlp_prep(pa, st);
+    launch_weight_snapshot(x, s, w, train, st);
     FusedFwdArgs a{};
     a.n_layers = nb; fill_stack(x, s, w, 0, nb, a.L);
     a.B = B; a.ldT = x->ldT;
@@ -793,38 +786,46 @@ static void backward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
   }
 }
 
-// ---- wide-layer path ------------------------------------------------------------------------
+// ---- layer-wise path ------------------------------------------------------------------------
+// this step's snapshot of the replica: bf16, MFMA fragment order, both products (also clears
+// the step's gradient accumulator when training)
+static void launch_weight_snapshot(ss_ctx* x, Slot& s, const float* w, bool train, hipStream_t st) {
+  const int nl = (int)x->layers.size() - 1;
+  PrepArgs pa{};
+  pa.n_layers = nl;
+  int64_t base = 0;
+  for (int l = 0; l < nl; ++l) {
+    const Layer& ly = x->layers[l];
+    PrepLayer& pl = pa.L[l];
+    pl.W = w + ly.w_off; pl.Wf = s.wsw + x->wsw_f[l]; pl.Wr = s.wsw + x->wsw_r[l];
+    pl.in = ly.in; pl.out = ly.out; pl.frag_base = base;
+    pl.kp_f = x->kp_f[l]; pl.kp_r = x->kp_r[l];
+    pl.frags_fwd = (x->wsw_r[l] - x->wsw_f[l]) / 8;
+    const int64_t end = (l + 1 < nl) ? x->wsw_f[l + 1] : x->wsw_elems;
+    base += (end - x->wsw_f[l]) / 8;
+  }
+  pa.total_frags = base;
+  pa.zero = train ? s.grads : nullptr; pa.zero_n = x->P;
+  launch_mlp_prep(pa, st);
+}
+
 static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, float* loss,
                          bool train, hipStream_t st) {
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
   auto layer_fwd = [&](int l, const uint16_t* in, int ld_in) {
     const Layer& ly = x->layers[l];
-    GemmNtArgs a{};
-    a.A = in; a.lda = ld_in; a.B = s.wb + x->wb_off[l]; a.ldb = x->pin[l];
-    a.M = B; a.N = ly.out; a.K = x->kin[l];
-    a.epi = EPI_BIAS | EPI_RELU; a.bias = w + ly.b_off; a.split_k = 1;
+    GemmXwArgs a{};
+    a.A = in; a.lda = ld_in; a.Bf = s.wsw + x->wsw_f[l];
+    a.M = B; a.N = ly.out; a.K = x->kp_f[l];
+    a.epi = EPI_BIAS | EPI_RELU; a.bias = w + ly.b_off;
     if (l == nb - 1) { a.C_f32 = s.z0; a.ldc32 = x->d; }
-    else {
-      a.C = s.act_bf16[l]; a.ldc = x->pout[l];
-      a.CT = train ? s.actT[l] : nullptr; a.ldct = x->ldT;
-    }
-    { ProfScope pk(x, SS_K_MLP_FWD, st); launch_gemm_nt(a, st); }
+    else { a.C = s.act_bf16[l]; a.ldc = x->pout[l]; }
+    { ProfScope pk(x, SS_K_MLP_FWD, st); launch_gemm_xw(a, st); }
   };
   {
     ProfScope ps(x, SS_K_MLP, st);
-    WeightsBf16Args wa{};
-    wa.n_layers = L - 1;
-    for (int l = 0; l < L - 1; ++l) {
-      const Layer& ly = x->layers[l];
-      WeightsBf16Layer& q = wa.L[l];
-      q.W = w + ly.w_off; q.Wb = s.wb + x->wb_off[l]; q.WbT = s.wb + x->wbt_off[l];
-      q.in = ly.in; q.out = ly.out; q.ldw = x->pin[l]; q.ldwt = x->pout[l];
-      q.tile_base = x->wb_tile_base[l];
-    }
-    wa.zero = train ? s.grads : nullptr; wa.zero_n = x->P;
-    launch_weights_bf16(wa, x->wb_tiles, st);
-    launch_cast_transpose(bt->dense, 1, x->num_dense, B, x->num_dense, s.xb, x->pin[0],
-                          train ? s.xT : nullptr, x->ldT, st);
+    launch_weight_snapshot(x, s, w, train, st);
+    launch_cast_rows(bt->dense, x->num_dense, B, x->num_dense, s.xb, x->pin[0], st);
     const uint16_t* in = s.xb; int ld_in = x->pin[0];
     for (int l = 0; l < nb; ++l) {
       layer_fwd(l, in, ld_in);
@@ -842,8 +843,6 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
   }
   {
     ProfScope ps(x, SS_K_MLP, st);
-    if (train)
-      launch_cast_transpose(s.f_bf16, 0, x->ldf16, B, x->F, nullptr, 0, s.fT, x->ldT, st);
     const uint16_t* in = s.f_bf16; int ld_in = x->ldf16;
     for (int l = nb; l < L - 1; ++l) {
       layer_fwd(l, in, ld_in);
@@ -857,71 +856,27 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
 
 static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipStream_t st) {
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
-  const int Bp = (B + 63) / 64 * 64;
-  ReduceArgs red{};
-  int red_blocks = 0;
-  // weight gradient of layer l (and its bias gradient), then the gradient w.r.t. its input
-  auto layer_bwd = [&](int l, const uint16_t* dcur, int ldd, int& pp) -> const uint16_t* {
+  // gradient w.r.t. the input of layer l from the gradient w.r.t. its output (dYr[l])
+  auto layer_dgrad = [&](int l) {
     const Layer& ly = x->layers[l];
-    if (!x->wgrad_grouped[l]) {
-    GemmNtArgs g{};
-    g.A = s.dYT[l]; g.lda = x->ldT;
-    g.B = (l == 0) ? s.xT : (l == nb) ? s.fT : s.actT[l - 1]; g.ldb = x->ldT;
-    g.M = ly.out; g.N = ly.in; g.K = Bp;
-    g.C_f32 = s.grads + ly.w_off; g.ldc32 = ly.in; g.epi = EPI_NONE;
-    g.row_sum = s.grads + ly.b_off;
-    const int tiles = ceil_div(ly.out, 128) * ceil_div(ly.in, 128);
-    // enough batch slices for two blocks per CU, each at least 512 samples long; a slice is
-    // stored to its own copy (fp32 atomics from 512 blocks onto one matrix run at ~1.2 TB/s)
-    int split = ceil_div(512, tiles);
-    if (split > WG_MAX_SLICES) split = WG_MAX_SLICES;
-    if (split > Bp / 512) split = Bp / 512;
-    if (split < 1) split = 1;
-    g.split_k = split;
-    if (split > 1) {
-      g.C_f32 = s.wg_part + x->wg_off[l];
-      g.split_stride = x->wg_stride[l];
-    }
-    int slices;
-    { ProfScope pk(x, SS_K_MLP_WGRAD, st); slices = launch_gemm_nt(g, st); }
-    if (split > 1) {  // (a single slice is stored to the slice area as well)
-      ReduceSegment& sg = red.seg[red.n_seg++];
-      sg.part = g.C_f32; sg.out = s.grads + ly.w_off; sg.n = (int64_t)ly.out * ly.in;
-      sg.stride = g.split_stride; sg.slices = slices; sg.block_base = red_blocks;
-      red_blocks += ceil_div(sg.n, 1024);
-    }
-    }
-    if (l == 0) return nullptr;
-    GemmNtArgs a{};
-    a.A = dcur; a.lda = ldd; a.B = s.wb + x->wbt_off[l]; a.ldb = x->pout[l];
-    a.M = B; a.N = ly.in; a.K = x->kout[l]; a.split_k = 1;
+    GemmXwArgs a{};
+    a.A = s.dYr[l]; a.lda = x->pout[l]; a.Bf = s.wsw + x->wsw_r[l];
+    a.M = B; a.N = ly.in; a.K = x->kp_r[l];
     if (l == nb) {
       a.C_f32 = s.df; a.ldc32 = x->ldf; a.epi = EPI_NONE;
-      { ProfScope pk(x, SS_K_MLP_DGRAD, st); launch_gemm_nt(a, st); }
-      return nullptr;
+    } else {
+      a.C = s.dYr[l - 1]; a.ldc = x->pout[l - 1];
+      a.epi = EPI_MASK; a.mask = s.act_bf16[l - 1]; a.ldmask = x->pout[l - 1];
     }
-    a.C = s.dbuf16[pp]; a.ldc = x->pout[l - 1];
-    a.CT = s.dYT[l - 1]; a.ldct = x->ldT;
-    a.epi = EPI_MASK;
-    a.mask = s.act_bf16[l - 1]; a.ldmask = x->pout[l - 1];
-    a.maskT = s.actT[l - 1]; a.ldmaskT = x->ldT;
-    { ProfScope pk(x, SS_K_MLP_DGRAD, st); launch_gemm_nt(a, st); }
-    const uint16_t* out = s.dbuf16[pp];
-    pp ^= 1;
-    return out;
+    { ProfScope pk(x, SS_K_MLP_DGRAD, st); launch_gemm_xw(a, st); }
   };
   {
     ProfScope ps(x, SS_K_MLP, st);  // (the gradient accumulator was cleared by the weight snapshot)
     const Layer& last = x->layers[L - 1];
     const int ld = x->pout[L - 2];
-    launch_last_layer_bwd(s.act_bf16[L - 2], ld, w + last.w_off, s.dlogit, B, last.in, s.dbuf16[0],
+    launch_last_layer_bwd(s.act_bf16[L - 2], ld, w + last.w_off, s.dlogit, B, last.in, s.dYr[L - 2],
                           ld, s.grads + last.w_off, s.grads + last.b_off, st);
-    launch_cast_transpose(s.dbuf16[0], 0, ld, B, last.in, nullptr, 0, s.dYT[L - 2], x->ldT, st);
-    const uint16_t* dcur = s.dbuf16[0]; int ldd = ld; int pp = 1;
-    for (int l = L - 2; l >= nb; --l) {
-      dcur = layer_bwd(l, dcur, ldd, pp);
-      if (l > nb) ldd = x->pout[l - 1];
-    }
+    for (int l = L - 2; l >= nb; --l) layer_dgrad(l);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_BWD, st);
@@ -929,26 +884,31 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
   }
   {
     ProfScope ps(x, SS_K_MLP, st);
-    const int ld = x->pout[nb - 1];
-    launch_cast_transpose(s.dz0, 1, x->d, B, x->d, s.dbuf16[0], ld, s.dYT[nb - 1], x->ldT, st);
-    const uint16_t* dcur = s.dbuf16[0]; int ldd = ld; int pp = 1;
-    for (int l = nb - 1; l >= 0; --l) {
-      dcur = layer_bwd(l, dcur, ldd, pp);
-      if (l > 0) ldd = x->pout[l - 1];
+    launch_cast_rows(s.dz0, x->d, B, x->d, s.dYr[nb - 1], x->pout[nb - 1], st);
+    for (int l = nb - 1; l >= 1; --l) layer_dgrad(l);
+    // weight and bias gradients of every layer but the one-unit output layer: one grouped
+    // launch over (layer, tile, batch slice), then one launch that adds the slices up
+    WgradGroupArgs g{};
+    ReduceArgs red{};
+    int red_blocks = 0;
+    const int slices = ceil_div(B, x->wg_slice_len);   // slices that hold samples of this batch
+    for (int l = 0; l < L - 1; ++l) {
+      const Layer& ly = x->layers[l];
+      WgradGroupLayer& q = g.L[l];
+      q.dY = s.dYr[l]; q.ldy = x->pout[l];
+      if (l == 0) { q.X = s.xb; q.ldx = x->pin[0]; }
+      else if (l == nb) { q.X = s.f_bf16; q.ldx = x->ldf16; }
+      else { q.X = s.act_bf16[l - 1]; q.ldx = x->pout[l - 1]; }
+      q.part = s.wg_part + x->wg_off[l]; q.part_stride = x->wg_stride[l];
+      q.out = ly.out; q.in = ly.in; q.slice_len = x->wg_slice_len;
+      ReduceSegment& sg = red.seg[red.n_seg++];
+      sg.part = q.part; sg.out = s.grads + ly.w_off; sg.n = (int64_t)ly.out * ly.in + ly.out;
+      sg.stride = q.part_stride; sg.slices = slices; sg.block_base = red_blocks;
+      red_blocks += ceil_div(sg.n, 1024);
     }
+    g.tiles = x->wgrad_tiles_dev; g.n_tiles = (int)x->wgrad_tiles.size(); g.B = B;
+    { ProfScope pk(x, SS_K_MLP_WGRAD, st); launch_gemm_wgrad(g, st); }
     launch_reduce_slices(red, red_blocks, st);
-    if (!x->wgrad_tiles.empty()) {
-      WgradArgs g{};
-      for (int l = 0; l < L - 1; ++l) {
-        const Layer& ly = x->layers[l];
-        g.L[l].dYT = s.dYT[l];
-        g.L[l].XT = (l == 0) ? s.xT : (l == nb) ? s.fT : s.actT[l - 1];
-        g.L[l].gW = s.grads + ly.w_off; g.L[l].gb = s.grads + ly.b_off;
-        g.L[l].in = ly.in; g.L[l].out = ly.out;
-      }
-      g.tiles = x->wgrad_tiles_dev; g.B = B; g.ldT = x->ldT;
-      { ProfScope pk(x, SS_K_MLP_WGRAD, st); launch_mlp_wgrad_grouped(g, (int)x->wgrad_tiles.size(), st); }
-    }
   }
 }
 

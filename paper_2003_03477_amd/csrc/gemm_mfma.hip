@@ -1,0 +1,570 @@
+// bf16 MFMA GEMMs of the layer-wise MLP path (gfx950 / CDNA4, wave64, v_mfma_f32_32x32x16_bf16,
+// fp32 accumulation).  Activations and activation gradients live in HBM as plain row-major
+// bf16 matrices [sample][unit]; the step's weights are a bf16 snapshot laid out in MFMA
+// fragment order (see mlp_fused.hip: for every (32-unit tile, 16-deep reduction step) the 64
+// lanes' 8 values are contiguous), once for X W^T and once for dY W.
+//
+//   gemm_xw_kernel      forward  Y = act(X W^T + b)  and data gradient  dX = gate(dY W):
+//                       the activation operand is staged through LDS, the weight operand comes
+//                       straight from the fragment-ordered copy as coalesced 1 KB wave loads
+//                       (L2-resident, 8 reduction steps in flight), so LDS carries one operand
+//                       only.  Block = 2x2 waves, tile 256x128 (wave tile 128x64, one block per
+//                       CU) or 128x128 (wave tile 64x64).  bf16 results are produced with the
+//                       MFMA operands swapped (the accumulator then holds four consecutive
+//                       output units of one sample per lane), packed, laid out in LDS and
+//                       stored as full 16-byte vectors of contiguous rows.
+//   gemm_wgrad_kernel   weight gradients  dW = dY^T X  (+ bias gradients as an MFMA against
+//                       ones) of ALL layers in one grouped launch over (layer, tile, batch
+//                       slice).  Both operands are read row-major and transposed on their way
+//                       into LDS (4 samples x 8 units per thread, byte permutes, 8-byte LDS
+//                       stores), so no transposed copy of any activation exists in HBM.  Every
+//                       slice stores its partial sums; reduce_slices_kernel adds them up.
+//
+// LDS operand tiles are [rows][64] bf16 with 128-byte rows and no padding; the 16-byte chunk c
+// of row r sits at chunk c ^ ((r ^ (r >> 3)) & 7), which spreads both the 16-byte fragment
+// reads (32 consecutive rows, one chunk) and the 8-byte transposing stores (rows 8 apart) over
+// the banks.
+#include <mutex>
+
+#include "ss_internal.h"
+
+namespace ss {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+namespace {
+
+constexpr int TK = 64;        // reduction step
+constexpr int CP = 128 + 8;   // LDS row pitch of a bf16 output tile (elements)
+
+union Frag {
+  bf16x8 v;
+  u32x4 q;
+};
+
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pk2(float lo, float hi) {
+  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+__device__ __forceinline__ int swz(int r) { return (r ^ (r >> 3)) & 7; }
+// element offset of 16-byte chunk c of row r inside an operand tile
+__device__ __forceinline__ int tile_off(int r, int c) { return r * TK + ((c ^ swz(r)) << 3); }
+
+__device__ __forceinline__ uint4 gate8(uint4 x, uint4 m) {
+  const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ms[4] = {m.x, m.y, m.z, m.w};
+  uint32_t o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t lo = ((int16_t)(ms[i] & 0xFFFFu) > 0) ? 0x0000FFFFu : 0u;
+    const uint32_t hi = ((int16_t)(ms[i] >> 16) > 0) ? 0xFFFF0000u : 0u;
+    o[i] = xs[i] & (lo | hi);
+  }
+  return make_uint4(o[0], o[1], o[2], o[3]);
+}
+// zero the elements j >= valid (0..8) of a vector of 8 bf16
+__device__ __forceinline__ uint4 keep_first(uint4 x, int valid) {
+  if (valid >= 8) return x;
+  uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t lo = (2 * i < valid) ? 0x0000FFFFu : 0u;
+    const uint32_t hi = (2 * i + 1 < valid) ? 0xFFFF0000u : 0u;
+    w[i] &= (lo | hi);
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// ------------------------------------------------------------------------------------------
+struct XwDev {
+  const uint16_t* A; int lda;       // [M][lda] bf16, K (multiple of 64) finite columns
+  const uint16_t* Bf;               // fragment-ordered weights: tile = n / 32, step = k / 16
+  int M, N, K;
+  int n_tiles32;                    // 32-unit tiles in Bf (N rounded up to 32, / 32)
+  uint16_t* C; int ldc;             // bf16 [M][ldc], columns N..ldc-1 zeroed
+  float* C32; int ldc32;            // or fp32 [M][ldc32]
+  int epi; const float* bias;
+  const uint16_t* mask; int ldmask; // [M][ldmask]: keep C(m,n) where mask > 0 (EPI_MASK)
+  int tiles_m, tiles_n;
+};
+
+template <int BM, bool F32OUT>
+__device__ __forceinline__ void xw_body(const XwDev& g) {
+  constexpr int MT = BM / 64;   // 32-row tiles per wave along M
+  constexpr int NA = BM / 32;   // 16-byte pieces of the A tile per thread and step
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  uint16_t* const As0 = smem;
+  uint16_t* const As1 = smem + BM * TK;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  // consecutive tiles (same rows of A) go to the same XCD, whose L2 then serves the re-reads
+  const int total = g.tiles_m * g.tiles_n;
+  int id = blockIdx.x;
+  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+  const int tm = id / g.tiles_n, tn = id - tm * g.tiles_n;
+  const int m0 = tm * BM, n0 = tn * 128;
+  const int nk = g.K / TK;          // >= 1
+  const int steps16 = nk * 4;
+
+  // activation operand: piece i of this thread = row (tid/8 + 32 i), chunk tid%8
+  const int lrow = tid >> 3, lch = tid & 7;
+  const uint16_t* aptr[NA];
+  int lds_a[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    const int r = lrow + 32 * i;
+    aptr[i] = g.A + (size_t)min(m0 + r, g.M - 1) * g.lda + lch * 8;
+    lds_a[i] = tile_off(r, lch);
+  }
+  // weight operand: this wave's two 32-unit tiles (clamped; results of tiles beyond N are
+  // dropped at the store)
+  const uint16_t* bptr[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int t = min((n0 >> 5) + wn * 2 + j, g.n_tiles32 - 1);
+    bptr[j] = g.Bf + ((size_t)t * steps16 * 64 + lane) * 8;
+  }
+  auto load_b = [&](Frag (&dst)[2], int step16) {
+    const int s = min(step16, steps16 - 1);   // past the end: a harmless re-read
+#pragma unroll
+    for (int j = 0; j < 2; ++j) dst[j].q = *(const u32x4*)(bptr[j] + (size_t)s * 512);
+  };
+
+  f32x16 acc[MT][2];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  u32x4 ra0[NA], ra1[NA];   // two register stages of the activation tile
+  auto fetch = [&](u32x4 (&r)[NA], int step) {
+    const int ko = min(step, nk - 1) * TK;
+#pragma unroll
+    for (int i = 0; i < NA; ++i) r[i] = *(const u32x4*)(aptr[i] + ko);
+  };
+  auto stash = [&](const u32x4 (&r)[NA], uint16_t* as) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i) *(u32x4*)(as + lds_a[i]) = r[i];
+  };
+
+  Frag bq[8][2];            // weight fragments of the next 8 reduction steps of 16
+#pragma unroll
+  for (int d = 0; d < 8; ++d) load_b(bq[d], d);
+
+  const int frow = lane & 31, fh = lane >> 5;
+  int arow[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) arow[i] = wm * (BM / 2) + i * 32 + frow;
+
+  // one reduction step of 64 on LDS buffer `as`; H = which half of the weight ring it uses;
+  // base16 = index of its first step of 16 (the ring slot is refilled with step + 8)
+  auto compute = [&](const uint16_t* as, auto H, int base16) {
+    constexpr int h = decltype(H)::value;
+    Frag a[2][MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) a[0][i].q = *(const u32x4*)(as + tile_off(arow[i], fh));
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int cur = q & 1, nxt = cur ^ 1;
+      if (q + 1 < 4) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+          a[nxt][i].q = *(const u32x4*)(as + tile_off(arow[i], 2 * (q + 1) + fh));
+      }
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          if (F32OUT)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i].v, bq[4 * h + q][j].v, acc[i][j], 0, 0, 0);
+          else   // swapped: rows of the accumulator = output units, columns = samples
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[4 * h + q][j].v, a[cur][i].v, acc[i][j], 0, 0, 0);
+        }
+      load_b(bq[4 * h + q], base16 + q + 8);
+    }
+  };
+  using H0 = std::integral_constant<int, 0>;
+  using H1 = std::integral_constant<int, 1>;
+
+  fetch(ra0, 0);
+  fetch(ra1, 1);
+  stash(ra0, As0);
+  fetch(ra0, 2);
+  __syncthreads();
+  int it = 0;
+  for (; it + 2 < nk; it += 2) {
+    compute(As0, H0{}, it * 4);
+    stash(ra1, As1);
+    fetch(ra1, it + 3);
+    __syncthreads();
+    compute(As1, H1{}, it * 4 + 4);
+    stash(ra0, As0);
+    fetch(ra0, it + 4);
+    __syncthreads();
+  }
+  compute(As0, H0{}, it * 4);   // one or two steps are left
+  if (it + 1 < nk) {
+    stash(ra1, As1);
+    __syncthreads();
+    compute(As1, H1{}, it * 4 + 4);
+  }
+
+  const int l31 = lane & 31, l4 = (lane >> 5) * 4;
+  if (F32OUT) {
+    // accumulator element e of a 32x32 tile: row = (e/4)*8 + (lane/32)*4 + e%4 (sample),
+    // column = lane%32 (unit): 32 consecutive floats of a row per half wave
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int gn = n0 + wn * 64 + j * 32 + l31;
+        if (gn >= g.N) continue;
+        const float bv = (g.epi & EPI_BIAS) ? g.bias[gn] : 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int gm = m0 + wm * (BM / 2) + i * 32 + (e >> 2) * 8 + l4 + (e & 3);
+          if (gm >= g.M) continue;
+          float v = acc[i][j][e] + bv;
+          if (g.epi & EPI_RELU) v = fmaxf(v, 0.f);
+          g.C32[(size_t)gm * g.ldc32 + gn] = v;
+        }
+      }
+    return;
+  }
+
+  // bf16 output.  Swapped accumulators: element e = unit (e/4)*8 + (lane/32)*4 + e%4 of the
+  // 32-unit tile, sample = lane%32: four consecutive units per group of e -> one 8-byte LDS store
+  __syncthreads();   // every wave is done reading the operand buffers
+  uint16_t* const Cs = smem;   // [BM][CP]
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int eg = 0; eg < 4; ++eg) {
+      const int nl = wn * 64 + j * 32 + eg * 8 + l4;   // first of four units (tile-local)
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (g.epi & EPI_BIAS) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) bv[u] = (n0 + nl + u < g.N) ? g.bias[n0 + nl + u] : 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        const int ml = wm * (BM / 2) + i * 32 + l31;
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          v[u] = acc[i][j][eg * 4 + u] + bv[u];
+          if (g.epi & EPI_RELU) v[u] = fmaxf(v[u], 0.f);
+        }
+        *(uint2*)(Cs + ml * CP + nl) = make_uint2(pk2(v[0], v[1]), pk2(v[2], v[3]));
+      }
+    }
+  __syncthreads();
+  const bool gated = (g.epi & EPI_MASK) != 0;
+#pragma unroll
+  for (int q = 0; q < BM / 16; ++q) {
+    const int v = tid + 256 * q;
+    const int r = v >> 4, c = (v & 15) * 8;
+    const int gm = m0 + r, gn = n0 + c;
+    if (gm < g.M && gn < g.ldc) {
+      uint4 x = *(const uint4*)(Cs + r * CP + c);
+      if (gated) x = gate8(x, *(const uint4*)(g.mask + (size_t)gm * g.ldmask + gn));
+      x = keep_first(x, g.N - gn);
+      *(uint4*)(g.C + (size_t)gm * g.ldc + gn) = x;
+    }
+  }
+}
+
+// 256-row tiles need more than 256 registers per lane (128 accumulators, 64 weight-fragment
+// and 64 staging registers): one wave per SIMD; 128-row tiles fit two.
+template <bool F32OUT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_xw256_kernel(XwDev g) {
+  xw_body<256, F32OUT>(g);
+}
+template <bool F32OUT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_xw128_kernel(XwDev g) {
+  xw_body<128, F32OUT>(g);
+}
+
+// ------------------------------------------------------------------------------------------
+// Weight gradients, grouped.
+__device__ __forceinline__ uint32_t perm_lo(uint32_t a, uint32_t b) {  // (a.lo16, b.lo16)
+  return __builtin_amdgcn_perm(b, a, 0x05040100u);
+}
+__device__ __forceinline__ uint32_t perm_hi(uint32_t a, uint32_t b) {  // (a.hi16, b.hi16)
+  return __builtin_amdgcn_perm(b, a, 0x07060302u);
+}
+
+// one register stage: four 16-byte rows (4 consecutive samples, 8 units) of each operand
+struct WgStage {
+  u32x4 a[4], b[4];
+};
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_wgrad_kernel(WgradGroupArgs g) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  constexpr int OP = 128 * TK;
+  uint16_t* const As0 = smem;
+  uint16_t* const As1 = smem + OP;
+  uint16_t* const Bs0 = smem + 2 * OP;
+  uint16_t* const Bs1 = smem + 3 * OP;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int id = blockIdx.x;
+  if ((g.n_tiles & 7) == 0) id = (id & 7) * (g.n_tiles >> 3) + (id >> 3);
+  const int4 t = g.tiles[id];               // (layer, first unit of dY, first unit of X, slice)
+  if (t.x < 0) return;                      // padding entry
+  const WgradGroupLayer L = g.L[t.x];
+  const int m0 = t.y, n0 = t.z;
+  const int bbeg = t.w * L.slice_len;
+  const int bend = min(g.B, bbeg + L.slice_len);
+  const int nk = (bend - bbeg + TK - 1) / TK;
+  if (nk <= 0) return;                      // (an empty slice still owns a zeroed partial: see host)
+
+  // staging: thread = (unit chunk of 8: tid%16, sample group of 4: tid/16)
+  const int cidx = tid & 15, qq = tid >> 4;
+  const int ca = m0 + cidx * 8, cb = n0 + cidx * 8;
+  const bool a_ok = ca < L.ldy, b_ok = cb < L.ldx;      // inside the row pitch (padding is zero)
+  const uint16_t* const ap = L.dY + ca;
+  const uint16_t* const bp = L.X + cb;
+  auto fetch = [&](WgStage& s, int step) {
+    const int b0 = bbeg + min(step, nk - 1) * TK + qq * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int b = b0 + i;
+      const bool ok = b < bend;
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      s.a[i] = (ok && a_ok) ? *(const u32x4*)(ap + (size_t)b * L.ldy) : z;
+      s.b[i] = (ok && b_ok) ? *(const u32x4*)(bp + (size_t)b * L.ldx) : z;
+    }
+  };
+  // transposed store of a 4 (samples) x 8 (units) micro-tile: unit row 8*cidx + j receives the
+  // four samples 4*qq .. 4*qq+3 as one 8-byte store
+  int st_off[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) st_off[j] = tile_off(cidx * 8 + j, qq >> 1) + (qq & 1) * 4;
+  auto stash_one = [&](const u32x4 (&r)[4], uint16_t* dst) {
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t x0 = r[0][w], x1 = r[1][w], x2 = r[2][w], x3 = r[3][w];
+      *(uint2*)(dst + st_off[2 * w]) = make_uint2(perm_lo(x0, x1), perm_lo(x2, x3));
+      *(uint2*)(dst + st_off[2 * w + 1]) = make_uint2(perm_hi(x0, x1), perm_hi(x2, x3));
+    }
+  };
+  auto stash = [&](const WgStage& s, uint16_t* as, uint16_t* bs) {
+    stash_one(s.a, as);
+    stash_one(s.b, bs);
+  };
+
+  const bool do_bias = (n0 == 0 && wn == 0);
+  f32x16 acc[2][2], accb[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) accb[i][e] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  }
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+
+  const int frow = lane & 31, fh = lane >> 5;
+  int arow[2], brow[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    arow[i] = wm * 64 + i * 32 + frow;
+    brow[i] = wn * 64 + i * 32 + frow;
+  }
+  auto compute = [&](const uint16_t* as, const uint16_t* bs) {
+    Frag a[2][2], b[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      a[0][i].q = *(const u32x4*)(as + tile_off(arow[i], fh));
+      b[0][i].q = *(const u32x4*)(bs + tile_off(brow[i], fh));
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int cur = q & 1, nxt = cur ^ 1;
+      if (q + 1 < 4) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          a[nxt][i].q = *(const u32x4*)(as + tile_off(arow[i], 2 * (q + 1) + fh));
+          b[nxt][i].q = *(const u32x4*)(bs + tile_off(brow[i], 2 * (q + 1) + fh));
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i].v, b[cur][j].v, acc[i][j], 0, 0, 0);
+      if (do_bias) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          accb[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i].v, ones, accb[i], 0, 0, 0);
+      }
+    }
+  };
+
+  WgStage s0, s1;
+  fetch(s0, 0);
+  fetch(s1, 1);
+  stash(s0, As0, Bs0);
+  fetch(s0, 2);
+  __syncthreads();
+  int it = 0;
+  for (; it + 2 < nk; it += 2) {
+    compute(As0, Bs0);
+    stash(s1, As1, Bs1);
+    fetch(s1, it + 3);
+    __syncthreads();
+    compute(As1, Bs1);
+    stash(s0, As0, Bs0);
+    fetch(s0, it + 4);
+    __syncthreads();
+  }
+  compute(As0, Bs0);
+  if (it + 1 < nk) {
+    stash(s1, As1, Bs1);
+    __syncthreads();
+    compute(As1, Bs1);
+  }
+  // NOTE: steps past the end re-stage the last tile but are never computed on.
+
+  // this slice's partial sums: [out][in] followed by [out] bias sums
+  float* const out = L.part + (size_t)t.w * L.part_stride;
+  const int l31 = lane & 31, l4 = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int gn = n0 + wn * 64 + j * 32 + l31;
+      if (gn >= L.in) continue;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int gm = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + l4 + (e & 3);
+        if (gm < L.out) out[(size_t)gm * L.in + gn] = acc[i][j][e];
+      }
+    }
+    if (do_bias && l31 == 0) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int gm = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + l4 + (e & 3);
+        if (gm < L.out) out[(size_t)L.out * L.in + gm] = accb[i][e];
+      }
+    }
+  }
+}
+
+// out[i] = sum over the slices of part[z * stride + i]; 1024 elements per block
+__global__ __launch_bounds__(256) void reduce_slices_kernel(ReduceArgs a) {
+  int k = 0;
+  while (k + 1 < a.n_seg && (int)blockIdx.x >= a.seg[k + 1].block_base) ++k;
+  const ReduceSegment sg = a.seg[k];
+  const int64_t base = (int64_t)(blockIdx.x - sg.block_base) * 1024;
+  const bool vec = ((sg.n & 3) == 0) && ((sg.stride & 3) == 0) && ((((uintptr_t)sg.out) & 15) == 0) &&
+                   ((((uintptr_t)sg.part) & 15) == 0);
+  if (vec) {
+    const int64_t i = base + threadIdx.x * 4;
+    if (i >= sg.n) return;
+    float4 acc = *(const float4*)(sg.part + i);
+    for (int z = 1; z < sg.slices; ++z) {
+      const float4 v = *(const float4*)(sg.part + (int64_t)z * sg.stride + i);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    *(float4*)(sg.out + i) = acc;
+  } else {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = base + threadIdx.x + 256 * u;
+      if (i < sg.n) {
+        float acc = sg.part[i];
+        for (int z = 1; z < sg.slices; ++z) acc += sg.part[(int64_t)z * sg.stride + i];
+        sg.out[i] = acc;
+      }
+    }
+  }
+}
+
+// fp32 rows -> bf16 rows with a zero-padded pitch: in [M][ld_in] (N valid columns), out
+// [M][ld_out], ld_out a multiple of 8.  One thread per 8 output elements.
+__global__ __launch_bounds__(256) void cast_rows_kernel(const float* __restrict__ in, int ld_in,
+                                                        int M, int N, uint16_t* __restrict__ out,
+                                                        int ld_out) {
+  const int per_row = ld_out >> 3;
+  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= (int64_t)M * per_row) return;
+  const int m = (int)(v / per_row), c = (int)(v - (int64_t)m * per_row) * 8;
+  const float* p = in + (size_t)m * ld_in + c;
+  float e[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) e[j] = (c + j < N) ? p[j] : 0.f;
+  *(uint4*)(out + (size_t)m * ld_out + c) =
+      make_uint4(pk2(e[0], e[1]), pk2(e[2], e[3]), pk2(e[4], e[5]), pk2(e[6], e[7]));
+}
+
+}  // namespace
+
+void launch_reduce_slices(const ReduceArgs& a, int total_blocks, hipStream_t s) {
+  if (total_blocks > 0)
+    hipLaunchKernelGGL(reduce_slices_kernel, dim3(total_blocks), dim3(256), 0, s, a);
+}
+
+void launch_cast_rows(const float* in, int ld_in, int M, int N, uint16_t* out, int ld_out,
+                      hipStream_t s) {
+  if (M <= 0 || N <= 0) return;
+  const int64_t n = (int64_t)M * (ld_out >> 3);
+  hipLaunchKernelGGL(cast_rows_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, in, ld_in,
+                     M, N, out, ld_out);
+}
+
+void launch_gemm_xw(const GemmXwArgs& a, hipStream_t s) {
+  if (a.M <= 0 || a.N <= 0 || a.K <= 0) return;
+  constexpr size_t LDS256 = (size_t)256 * CP * 2 > (size_t)2 * 256 * TK * 2 ? (size_t)256 * CP * 2 : (size_t)2 * 256 * TK * 2;
+  constexpr size_t LDS128 = (size_t)128 * CP * 2 > (size_t)2 * 128 * TK * 2 ? (size_t)128 * CP * 2 : (size_t)2 * 128 * TK * 2;
+  static std::once_flag attr_once;
+  std::call_once(attr_once, [] {
+    (void)hipFuncSetAttribute((const void*)gemm_xw256_kernel<false>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS256);
+    (void)hipFuncSetAttribute((const void*)gemm_xw256_kernel<true>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS256);
+  });
+  XwDev g;
+  g.A = a.A; g.lda = a.lda; g.Bf = a.Bf; g.M = a.M; g.N = a.N; g.K = a.K;
+  g.n_tiles32 = (a.N + 31) / 32;
+  g.C = a.C; g.ldc = a.ldc; g.C32 = a.C_f32; g.ldc32 = a.ldc32;
+  g.epi = a.epi; g.bias = a.bias; g.mask = a.mask; g.ldmask = a.ldmask;
+  g.tiles_n = ceil_div(a.N, 128);
+  // 256-row tiles when they still give every CU a block; 128-row tiles otherwise
+  const bool big = (int64_t)ceil_div(a.M, 256) * g.tiles_n >= 256;
+  g.tiles_m = ceil_div(a.M, big ? 256 : 128);
+  const dim3 grid(g.tiles_m * g.tiles_n);
+  const bool f32 = a.C_f32 != nullptr;
+  if (big) {
+    if (f32) hipLaunchKernelGGL(gemm_xw256_kernel<true>, grid, dim3(256), LDS256, s, g);
+    else hipLaunchKernelGGL(gemm_xw256_kernel<false>, grid, dim3(256), LDS256, s, g);
+  } else {
+    if (f32) hipLaunchKernelGGL(gemm_xw128_kernel<true>, grid, dim3(256), LDS128, s, g);
+    else hipLaunchKernelGGL(gemm_xw128_kernel<false>, grid, dim3(256), LDS128, s, g);
+  }
+}
+
+void launch_gemm_wgrad(const WgradGroupArgs& a, hipStream_t s) {
+  if (a.n_tiles <= 0) return;
+  constexpr size_t LDS = (size_t)4 * 128 * TK * 2;
+  static std::once_flag attr_once;
+  std::call_once(attr_once, [] {
+    (void)hipFuncSetAttribute((const void*)gemm_wgrad_kernel,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+  });
+  hipLaunchKernelGGL(gemm_wgrad_kernel, dim3(a.n_tiles), dim3(256), LDS, s, a);
+}
+
+}  // namespace ss

@@ -120,52 +120,48 @@ void launch_last_layer_fwd_loss(const uint16_t* X, int ldx, const float* w, cons
 void launch_last_layer_bwd(const uint16_t* X, int ldx, const float* w, const float* dlogit, int B,
                            int in, uint16_t* dX, int lddx, float* gW, float* gb, hipStream_t s);
 
-// ---------------------------------------------------------------------------- gemm_nt.hip
-// C[M,N] = A[M,K] B[N,K]^T, bf16 operands with the reduction dimension contiguous, K a multiple
-// of 64 (zero padded in at least one operand, finite in the other), 16-byte aligned rows.
-// Outputs: bf16 row-major C and / or transposed CT (both through EPI_BIAS / EPI_RELU, then
-// gated by mask / maskT > 0 under EPI_MASK), or fp32 C_f32 (stored; with split_k > 1 either
-// atomically added, or -- split_stride > 0 -- slice z stored to C_f32 + z * split_stride for a
-// later launch_reduce_slices).  row_sum (+)= row sums of A (first column of tiles only).
-struct GemmNtArgs {
+// ---------------------------------------------------------------------------- gemm_mfma.hip
+#define SS_NT_MAX_LAYERS 16
+// C[M,N] = A[M,K] W^T (+ bias, ReLU, gate): A bf16 row-major with K (a multiple of 64) finite
+// columns per row, the weight operand a fragment-ordered bf16 copy (tile = n / 32, step =
+// k / 16, zero padded to 32 units and 64 reduction elements).  Output: bf16 C [M][ldc] (columns
+// N..ldc-1 zeroed; under EPI_MASK kept where mask > 0) or fp32 C_f32 [M][ldc32].
+struct GemmXwArgs {
   const uint16_t* A; int lda;
-  const uint16_t* B; int ldb;
+  const uint16_t* Bf;
   int M, N, K;
   uint16_t* C; int ldc;
-  uint16_t* CT; int ldct;
   float* C_f32; int ldc32;
   int epi; const float* bias;
   const uint16_t* mask; int ldmask;
-  const uint16_t* maskT; int ldmaskT;
-  float* row_sum;
-  int split_k;
-  int64_t split_stride;
 };
-// Returns the number of reduction slices actually launched (<= split_k).
-int launch_gemm_nt(const GemmNtArgs& a, hipStream_t s);
-// out[i] = sum over the slices of part[z * stride + i], for up to SS_NT_MAX_LAYERS segments in
-// one launch (n and stride multiples of 4, 16-byte aligned pointers)
+void launch_gemm_xw(const GemmXwArgs& a, hipStream_t s);
+// Weight gradients of all layers in one launch.  Layer l: part[z] (z = batch slice) receives
+// dY[slice]^T X[slice] as [out][in] fp32 followed by the [out] column sums of dY[slice]; dY
+// [B][ldy] and X [B][ldx] are row-major bf16 whose pitch padding is zero.  tiles: device table
+// of (layer, first unit of dY, first unit of X, slice), 128x128 tiles, padded to a multiple of
+// 8 entries with layer = -1.
+struct WgradGroupLayer {
+  const uint16_t* dY; int ldy;
+  const uint16_t* X; int ldx;
+  float* part; int64_t part_stride;
+  int out, in;
+  int slice_len;      // samples per slice, a multiple of 64
+};
+struct WgradGroupArgs {
+  WgradGroupLayer L[SS_NT_MAX_LAYERS];
+  const int4* tiles;
+  int n_tiles;
+  int B;
+};
+void launch_gemm_wgrad(const WgradGroupArgs& a, hipStream_t s);
+// out[i] = sum over the slices of part[z * stride + i], for up to 16 segments in one launch
 struct ReduceSegment { const float* part; float* out; int64_t n, stride; int slices; int block_base; };
 struct ReduceArgs { ReduceSegment seg[16]; int n_seg; };
 void launch_reduce_slices(const ReduceArgs& a, int total_blocks, hipStream_t s);
-// in [M][ld_in] (fp32 or bf16, N columns) -> out [M][ld_out] bf16 (optional, zero padded) and
-// outT [N][ldt] bf16 (optional, zero padded to the end of the last 64-sample tile)
-void launch_cast_transpose(const void* in, int in_is_f32, int ld_in, int M, int N, uint16_t* out,
-                           int ld_out, uint16_t* outT, int ldt, hipStream_t s);
-#define SS_NT_MAX_LAYERS 16
-struct WeightsBf16Layer {
-  const float* W;    // [out][in] fp32
-  uint16_t* Wb;      // [out][ldw] bf16, ldw = in rounded up to 64
-  uint16_t* WbT;     // [in][ldwt] bf16, ldwt = out rounded up to 64
-  int in, out, ldw, ldwt;
-  int tile_base;     // first block of this layer: ceil(out/64) * (ldw/64) blocks per layer
-};
-struct WeightsBf16Args {
-  WeightsBf16Layer L[SS_NT_MAX_LAYERS];
-  int n_layers;
-  float* zero; int64_t zero_n;   // gradient accumulator to clear (or null)
-};
-void launch_weights_bf16(const WeightsBf16Args& a, int total_tiles, hipStream_t s);
+// fp32 [M][ld_in] (N valid columns) -> bf16 [M][ld_out] (zero padded; ld_out a multiple of 8)
+void launch_cast_rows(const float* in, int ld_in, int M, int N, uint16_t* out, int ld_out,
+                      hipStream_t s);
 
 // ---------------------------------------------------------------------------- mlp_fused.hip
 #define SS_FUSED_MAX_LAYERS 8
