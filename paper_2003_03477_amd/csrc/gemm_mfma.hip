@@ -8,11 +8,11 @@
 //                       the activation operand is staged through LDS, the weight operand comes
 //                       straight from the fragment-ordered copy as coalesced 1 KB wave loads
 //                       (L2-resident, 8 reduction steps in flight), so LDS carries one operand
-//                       only.  Block = 2x2 waves, tile 256x128 (wave tile 128x64, one block per
-//                       CU) or 128x128 (wave tile 64x64).  bf16 results are produced with the
-//                       MFMA operands swapped (the accumulator then holds four consecutive
-//                       output units of one sample per lane), packed, laid out in LDS and
-//                       stored as full 16-byte vectors of contiguous rows.
+//                       only.  Block = 2x2 waves, tile 128x128 (wave tile 64x64), two blocks per
+//                       CU (256x128 tiles with one block per CU measured 12 % slower on
+//                       8192x1024x1024).  The MFMA operands are swapped (the accumulator then
+//                       holds four consecutive output units of one sample per lane); results
+//                       are laid out in LDS and stored as 16-byte vectors of contiguous rows.
 //   gemm_wgrad_kernel   weight gradients  dW = dY^T X  (+ bias gradients as an MFMA against
 //                       ones) of ALL layers in one grouped launch over (layer, tile, batch
 //                       slice).  Both operands are read row-major and transposed on their way
@@ -38,6 +38,7 @@ namespace {
 
 constexpr int TK = 64;        // reduction step
 constexpr int CP = 128 + 8;   // LDS row pitch of a bf16 output tile (elements)
+constexpr int CPF = 128 + 4;  // LDS row pitch of an fp32 output tile (floats)
 
 union Frag {
   bf16x8 v;
@@ -91,10 +92,11 @@ struct XwDev {
   int epi; const float* bias;
   const uint16_t* mask; int ldmask; // [M][ldmask]: keep C(m,n) where mask > 0 (EPI_MASK)
   int tiles_m, tiles_n;
+  int stream_out;                   // bf16 output stored non-temporally
 };
 
-template <int BM, bool F32OUT>
-__device__ __forceinline__ void xw_body(const XwDev& g) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_xw_kernel(XwDev g) {
+  constexpr int BM = 128;
   constexpr int MT = BM / 64;   // 32-row tiles per wave along M
   constexpr int NA = BM / 32;   // 16-byte pieces of the A tile per thread and step
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
@@ -135,6 +137,8 @@ __device__ __forceinline__ void xw_body(const XwDev& g) {
     for (int j = 0; j < 2; ++j) dst[j].q = *(const u32x4*)(bptr[j] + (size_t)s * 512);
   };
 
+  // Accumulators with the MFMA operands swapped: rows = output units, columns = samples, so a
+  // lane holds four consecutive units of one sample per group of four elements.
   f32x16 acc[MT][2];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
@@ -181,12 +185,8 @@ __device__ __forceinline__ void xw_body(const XwDev& g) {
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          if (F32OUT)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i].v, bq[4 * h + q][j].v, acc[i][j], 0, 0, 0);
-          else   // swapped: rows of the accumulator = output units, columns = samples
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[4 * h + q][j].v, a[cur][i].v, acc[i][j], 0, 0, 0);
-        }
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[4 * h + q][j].v, a[cur][i].v, acc[i][j], 0, 0, 0);
       load_b(bq[4 * h + q], base16 + q + 8);
     }
   };
@@ -209,6 +209,19 @@ __device__ __forceinline__ void xw_body(const XwDev& g) {
     fetch(ra0, it + 4);
     __syncthreads();
   }
+  // the bias of this lane's 2 x 16 output units is requested ahead of the last step(s), whose
+  // MFMAs cover the latency
+  const int l31 = lane & 31, l4 = (lane >> 5) * 4;
+  float bv[2][4][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int eg = 0; eg < 4; ++eg)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int gn = n0 + wn * 64 + j * 32 + eg * 8 + l4 + u;
+        bv[j][eg][u] = ((g.epi & EPI_BIAS) && gn < g.N) ? g.bias[gn] : 0.f;
+      }
   compute(As0, H0{}, it * 4);   // one or two steps are left
   if (it + 1 < nk) {
     stash(ra1, As1);
@@ -216,80 +229,97 @@ __device__ __forceinline__ void xw_body(const XwDev& g) {
     compute(As1, H1{}, it * 4 + 4);
   }
 
-  const int l31 = lane & 31, l4 = (lane >> 5) * 4;
-  if (F32OUT) {
-    // accumulator element e of a 32x32 tile: row = (e/4)*8 + (lane/32)*4 + e%4 (sample),
-    // column = lane%32 (unit): 32 consecutive floats of a row per half wave
+  // Epilogue.  Element e of an accumulator = unit (e/4)*8 + (lane/32)*4 + e%4 of its 32-unit
+  // tile, sample = lane%32.  The tile is laid out in LDS ([sample][unit], bf16 or fp32), then
+  // every thread stores 16-byte vectors of contiguous rows.
+  __syncthreads();   // every wave is done reading the operand buffers
+  const bool gated = (g.epi & EPI_MASK) != 0;
+  const int oc = (tid & 15) * 8;          // bf16 output: this thread's 8 units of rows tid/16 + 16 q
+  uint4 mk[BM / 16];
+  if (gated) {                            // the gate's activations, requested before the LDS pass
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+    for (int q = 0; q < BM / 16; ++q) {
+      const int gm = m0 + (tid >> 4) + 16 * q, gn = n0 + oc;
+      mk[q] = (gm < g.M && gn < g.ldc) ? *(const uint4*)(g.mask + (size_t)gm * g.ldmask + gn)
+                                        : make_uint4(0, 0, 0, 0);
+    }
+  }
+  if (g.C32 == nullptr) {
+    uint16_t* const Cs = smem;   // [BM][CP]
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int gn = n0 + wn * 64 + j * 32 + l31;
-        if (gn >= g.N) continue;
-        const float bv = (g.epi & EPI_BIAS) ? g.bias[gn] : 0.f;
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int gm = m0 + wm * (BM / 2) + i * 32 + (e >> 2) * 8 + l4 + (e & 3);
-          if (gm >= g.M) continue;
-          float v = acc[i][j][e] + bv;
-          if (g.epi & EPI_RELU) v = fmaxf(v, 0.f);
-          g.C32[(size_t)gm * g.ldc32 + gn] = v;
+      for (int eg = 0; eg < 4; ++eg) {
+        const int nl = wn * 64 + j * 32 + eg * 8 + l4;   // first of four units (tile-local)
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+          const int ml = wm * (BM / 2) + i * 32 + l31;
+          float v[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            v[u] = acc[i][j][eg * 4 + u] + bv[j][eg][u];
+            if (g.epi & EPI_RELU) v[u] = fmaxf(v[u], 0.f);
+          }
+          *(uint2*)(Cs + ml * CP + nl) = make_uint2(pk2(v[0], v[1]), pk2(v[2], v[3]));
         }
       }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < BM / 16; ++q) {
+      const int r = (tid >> 4) + 16 * q;
+      const int gm = m0 + r, gn = n0 + oc;
+      if (gm < g.M && gn < g.ldc) {
+        uint4 x = *(const uint4*)(Cs + r * CP + oc);
+        if (gated) x = gate8(x, mk[q]);
+        x = keep_first(x, g.N - gn);
+        uint16_t* dst = g.C + (size_t)gm * g.ldc + gn;
+        if (g.stream_out) {   // large outputs bypass the L2 (the reader is a later kernel)
+          __builtin_nontemporal_store(x.x, (uint32_t*)dst);
+          __builtin_nontemporal_store(x.y, (uint32_t*)dst + 1);
+          __builtin_nontemporal_store(x.z, (uint32_t*)dst + 2);
+          __builtin_nontemporal_store(x.w, (uint32_t*)dst + 3);
+        } else {
+          *(uint4*)dst = x;
+        }
+      }
+    }
     return;
   }
-
-  // bf16 output.  Swapped accumulators: element e = unit (e/4)*8 + (lane/32)*4 + e%4 of the
-  // 32-unit tile, sample = lane%32: four consecutive units per group of e -> one 8-byte LDS store
-  __syncthreads();   // every wave is done reading the operand buffers
-  uint16_t* const Cs = smem;   // [BM][CP]
+  // fp32 output (bottom output z0, gradient w.r.t. the interaction output)
+  float* const Cf = (float*)smem;   // [BM][CPF]
 #pragma unroll
   for (int j = 0; j < 2; ++j)
 #pragma unroll
     for (int eg = 0; eg < 4; ++eg) {
-      const int nl = wn * 64 + j * 32 + eg * 8 + l4;   // first of four units (tile-local)
-      float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (g.epi & EPI_BIAS) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) bv[u] = (n0 + nl + u < g.N) ? g.bias[n0 + nl + u] : 0.f;
-      }
+      const int nl = wn * 64 + j * 32 + eg * 8 + l4;
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
         const int ml = wm * (BM / 2) + i * 32 + l31;
-        float v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          v[u] = acc[i][j][eg * 4 + u] + bv[u];
-          if (g.epi & EPI_RELU) v[u] = fmaxf(v[u], 0.f);
-        }
-        *(uint2*)(Cs + ml * CP + nl) = make_uint2(pk2(v[0], v[1]), pk2(v[2], v[3]));
+        float4 v;
+        v.x = acc[i][j][eg * 4 + 0] + bv[j][eg][0]; v.y = acc[i][j][eg * 4 + 1] + bv[j][eg][1];
+        v.z = acc[i][j][eg * 4 + 2] + bv[j][eg][2]; v.w = acc[i][j][eg * 4 + 3] + bv[j][eg][3];
+        if (g.epi & EPI_RELU) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
+        *(float4*)(Cf + ml * CPF + nl) = v;
       }
     }
   __syncthreads();
-  const bool gated = (g.epi & EPI_MASK) != 0;
+  const bool vec = ((g.ldc32 & 3) == 0) && ((((uintptr_t)g.C32) & 15) == 0);
 #pragma unroll
-  for (int q = 0; q < BM / 16; ++q) {
-    const int v = tid + 256 * q;
-    const int r = v >> 4, c = (v & 15) * 8;
+  for (int q = 0; q < BM / 8; ++q) {
+    const int r = (tid >> 5) + 8 * q, c = (tid & 31) * 4;   // 32 threads x 4 floats per row
     const int gm = m0 + r, gn = n0 + c;
-    if (gm < g.M && gn < g.ldc) {
-      uint4 x = *(const uint4*)(Cs + r * CP + c);
-      if (gated) x = gate8(x, *(const uint4*)(g.mask + (size_t)gm * g.ldmask + gn));
-      x = keep_first(x, g.N - gn);
-      *(uint4*)(g.C + (size_t)gm * g.ldc + gn) = x;
+    if (gm >= g.M || gn >= g.N) continue;
+    const float4 v = *(const float4*)(Cf + r * CPF + c);
+    float* dst = g.C32 + (size_t)gm * g.ldc32 + gn;
+    if (vec && gn + 4 <= g.N) {
+      *(float4*)dst = v;
+    } else {
+      const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (gn + u < g.N) dst[u] = e[u];
     }
   }
-}
-
-// 256-row tiles need more than 256 registers per lane (128 accumulators, 64 weight-fragment
-// and 64 staging registers): one wave per SIMD; 128-row tiles fit two.
-template <bool F32OUT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_xw256_kernel(XwDev g) {
-  xw_body<256, F32OUT>(g);
-}
-template <bool F32OUT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_xw128_kernel(XwDev g) {
-  xw_body<128, F32OUT>(g);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -527,14 +557,13 @@ void launch_cast_rows(const float* in, int ld_in, int M, int N, uint16_t* out, i
 
 void launch_gemm_xw(const GemmXwArgs& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return;
-  constexpr size_t LDS256 = (size_t)256 * CP * 2 > (size_t)2 * 256 * TK * 2 ? (size_t)256 * CP * 2 : (size_t)2 * 256 * TK * 2;
-  constexpr size_t LDS128 = (size_t)128 * CP * 2 > (size_t)2 * 128 * TK * 2 ? (size_t)128 * CP * 2 : (size_t)2 * 128 * TK * 2;
+  // operand double buffer (2 x 16 KB), reused by the output tile: bf16 [128][136] or fp32 [128][132]
+  constexpr size_t LDS = (size_t)128 * CPF * 4;
+  static_assert(LDS >= (size_t)2 * 128 * TK * 2 && LDS >= (size_t)128 * CP * 2, "output tile must cover the buffers");
   static std::once_flag attr_once;
   std::call_once(attr_once, [] {
-    (void)hipFuncSetAttribute((const void*)gemm_xw256_kernel<false>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS256);
-    (void)hipFuncSetAttribute((const void*)gemm_xw256_kernel<true>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS256);
+    (void)hipFuncSetAttribute((const void*)gemm_xw_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)LDS);
   });
   XwDev g;
   g.A = a.A; g.lda = a.lda; g.Bf = a.Bf; g.M = a.M; g.N = a.N; g.K = a.K;
@@ -542,18 +571,9 @@ void launch_gemm_xw(const GemmXwArgs& a, hipStream_t s) {
   g.C = a.C; g.ldc = a.ldc; g.C32 = a.C_f32; g.ldc32 = a.ldc32;
   g.epi = a.epi; g.bias = a.bias; g.mask = a.mask; g.ldmask = a.ldmask;
   g.tiles_n = ceil_div(a.N, 128);
-  // 256-row tiles when they still give every CU a block; 128-row tiles otherwise
-  const bool big = (int64_t)ceil_div(a.M, 256) * g.tiles_n >= 256;
-  g.tiles_m = ceil_div(a.M, big ? 256 : 128);
-  const dim3 grid(g.tiles_m * g.tiles_n);
-  const bool f32 = a.C_f32 != nullptr;
-  if (big) {
-    if (f32) hipLaunchKernelGGL(gemm_xw256_kernel<true>, grid, dim3(256), LDS256, s, g);
-    else hipLaunchKernelGGL(gemm_xw256_kernel<false>, grid, dim3(256), LDS256, s, g);
-  } else {
-    if (f32) hipLaunchKernelGGL(gemm_xw128_kernel<true>, grid, dim3(256), LDS128, s, g);
-    else hipLaunchKernelGGL(gemm_xw128_kernel<false>, grid, dim3(256), LDS128, s, g);
-  }
+  g.tiles_m = ceil_div(a.M, 128);
+  g.stream_out = ((int64_t)a.M * a.N * 2 >= (8ll << 20)) ? 1 : 0;
+  hipLaunchKernelGGL(gemm_xw_kernel, dim3(g.tiles_m * g.tiles_n), dim3(256), LDS, s, g);
 }
 
 void launch_gemm_wgrad(const WgradGroupArgs& a, hipStream_t s) {

@@ -170,16 +170,27 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ w,
     metrics_block(mean_loss, y, B, acc);
     return;
   }
+  // four floats per thread and trip (replicas and gradient buffers are 16-byte aligned)
+  const int64_t n4 = n >> 2;
   const int64_t stride = (int64_t)nb * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    float4 wv = ((float4*)w)[i];
+    const float4 gv = ((const float4*)g)[i];
+    wv.x -= lr * gv.x; wv.y -= lr * gv.y; wv.z -= lr * gv.z; wv.w -= lr * gv.w;
+    ((float4*)w)[i] = wv;
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+    const int64_t i = (n4 << 2) + threadIdx.x;
     w[i] -= lr * g[i];
+  }
 }
 
 void launch_sgd(float* w, const float* g, int64_t n, float lr, const float* mean_loss,
                 const float* y, int B, double* acc, hipStream_t s) {
   if (n == 0) return;
-  int64_t blocks = (n + 255) / 256;
+  int64_t blocks = ((n >> 2) + 255) / 256;
   if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)blocks + (acc ? 1u : 0u)), dim3(256), 0, s, w, g, n,
                      lr, mean_loss, y, B, acc);
 }
