@@ -152,6 +152,19 @@ int ss_train_step(ss_ctx* ctx, int32_t replica, int32_t worker_slot, const ss_ba
 int ss_eval_step(ss_ctx* ctx, int32_t replica, int32_t worker_slot, const ss_batch* batch,
                  void* stream, float* dev_loss_out);
 
+/* ss_eval_step for callers that cannot allocate and hold no worker slot (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the forward pass keeps its
+ * activations in a static device array of the library (8 MiB per GPU, held until the process
+ * ends) instead of a worker slot's part of the workspace.  The call allocates nothing and uses
+ * no memset node.  dev_loss_out (device, 1 float, required) receives the batch's mean log-loss,
+ * dev_logits_out (device, [batch] floats, may be NULL) the logits; the eval NE accumulator is
+ * advanced as by ss_eval_step.  Returns SS_ENOMEM, with the sizes in ss_last_error, when the
+ * batch's activations (and the model's bf16 weight snapshot) exceed the array.  All calls on
+ * one GPU share the array: calls that overlap in time -- on different streams, contexts or
+ * host threads -- race; order them on one stream. */
+int ss_eval_step_static(ss_ctx* ctx, int32_t replica, const ss_batch* batch, void* stream,
+                        float* dev_loss_out, float* dev_logits_out);
+
 /* One shadow round over all K replicas, i ascending, element-wise (Algorithms 2-4):
  *  SS_EASGD: for each i: delta = alpha (w^(i) - w^PS); w^PS += delta; w^(i) -= delta
  *  SS_MA:    w^global = mean_i w^(i); w^(i) = (1-alpha) w^(i) + alpha w^global

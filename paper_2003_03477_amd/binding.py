@@ -40,7 +40,7 @@ EXPORTS = [
     "ss_shadow_sync", "ss_easgd_exchange", "ss_sync_round", "ss_shadow_start", "ss_shadow_stop", "ss_read_dense",
     "ss_write_dense", "ss_read_rows", "ss_read_debug", "ss_get_counters", "ss_profile_arm",
     "ss_profile_sample", "ss_profile_read", "ss_shadow_pace", "ss_metrics_read",
-    "ss_metrics_reset",
+    "ss_metrics_reset", "ss_eval_step_static",
 ]
 
 
@@ -90,6 +90,7 @@ def load() -> C.CDLL:
     lib.ss_num_params.argtypes = [vp]
     lib.ss_train_step.argtypes = [vp, i32, i32, C.POINTER(ss_batch), vp, vp]
     lib.ss_eval_step.argtypes = [vp, i32, i32, C.POINTER(ss_batch), vp, vp]
+    lib.ss_eval_step_static.argtypes = [vp, i32, C.POINTER(ss_batch), vp, vp, vp]
     lib.ss_shadow_sync.argtypes = [vp, i32, f32, f32, f32, vp]
     lib.ss_easgd_exchange.argtypes = [vp, i32, i32, f32, vp]
     lib.ss_sync_round.argtypes = [i32, i32, i64, i64, vp, vp, vp, vp, f32, f32, f32, vp]
@@ -249,6 +250,16 @@ class ShadowSync:
                                           _stream_handle(stream), out.data_ptr()),
                     "ss_eval_step")
         return out
+
+    def ss_eval_step_static(self, replica: int, batch: DeviceBatch, loss_out, logits_out=None,
+                            stream=None):
+        """Forward pass in the library's static scratch array (no worker slot, no allocation):
+        loss_out / logits_out are caller-owned device tensors (1 float / [batch] floats)."""
+        st = batch.struct()
+        self._check(self.lib.ss_eval_step_static(
+            self.ctx, replica, C.byref(st), _stream_handle(stream), loss_out.data_ptr(),
+            None if logits_out is None else logits_out.data_ptr()), "ss_eval_step_static")
+        return loss_out
 
     def ss_shadow_sync(self, algo, alpha: float, eta: float = 1.0, momentum: float = 0.0,
                        stream=None):

@@ -18,6 +18,12 @@
 
 using namespace ss;
 
+// Scratch of ss_eval_step_static: activations of one forward pass, for callers that may not
+// allocate and hold no worker slot.  One copy per GPU the library runs on, kept until the
+// process ends; the kernels reach it through the address ss_init looks up, never by this name.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int MAX_LAYERS = 16;
@@ -129,6 +135,7 @@ struct ss_ctx {
   float* v;
   float* w_mean;  // replica average, filled on request (ss_read_dense with which = -4)
   double* metrics;  // [2][4]: (sum of log-loss, positive labels, examples, unused) train / eval
+  unsigned char* static_scratch = nullptr;  // this device's copy of the file-scope array
   std::vector<Slot> slots;
   // state
   std::mutex err_mu;               // guards err: concurrent callers may fail at the same time
@@ -227,6 +234,78 @@ static int validate(const ss_config* c, std::string& why) {
   return SS_OK;
 }
 
+// Per-caller scratch of one step for a batch of up to B samples and n ids: activations,
+// gradients, sort and row-update buffers.  fwd_only leaves out everything only a training step
+// touches (the forward kernels skip outputs whose pointer is null).
+static void carve_slot(const ss_ctx* x, Carver& cv, Slot& s, int B, int64_t n, bool fwd_only) {
+  const int L = (int)x->layers.size();
+  for (int l = 0; l < L; ++l) {
+    s.act_f32[l] = nullptr;
+    s.act_bf16[l] = nullptr;
+    s.actT[l] = s.dYT[l] = nullptr;
+    s.dYr[l] = nullptr;
+    const bool is_z0 = (l == x->n_bot_layers - 1), is_logit = (l == L - 1);
+    if (is_z0 || is_logit) continue;
+    if (x->prec == SS_FP32) s.act_f32[l] = cv.take<float>((size_t)B * x->layers[l].out);
+    else if (!x->fused) s.act_bf16[l] = cv.take<uint16_t>((size_t)B * (x->wide ? x->pout[l] : x->layers[l].out));
+  }
+  s.z0 = cv.take<float>((size_t)B * x->d);
+  s.e = cv.take<float>((size_t)B * x->T * x->d);
+  s.inv_len = cv.take<float>((size_t)B * x->T);
+  s.f = cv.take<float>((size_t)B * x->ldf);
+  s.f_bf16 = (x->prec == SS_BF16) ? cv.take<uint16_t>((size_t)B * x->ldf16) : nullptr;
+  s.logits = cv.take<float>(B);
+  s.loss = cv.take<float>(64);
+  s.xT = s.fT = nullptr;
+  s.wsw = nullptr;
+  s.xb = nullptr;
+  s.wg_part = nullptr;
+  s.dlogit = s.grads = s.df = s.dz0 = s.de = nullptr;
+  s.dbuf[0] = s.dbuf[1] = nullptr;
+  s.dbuf16[0] = s.dbuf16[1] = nullptr;
+  if (x->fused || x->wide) s.wsw = cv.take<uint16_t>((size_t)x->wsw_elems);
+  if (x->wide) s.xb = cv.take<uint16_t>((size_t)B * x->pin[0]);
+  if (fwd_only) return;
+  s.dlogit = cv.take<float>(B);
+  s.grads = cv.take<float>(x->Pstride);
+  for (int i = 0; i < 2; ++i) {
+    if (x->prec == SS_FP32) s.dbuf[i] = cv.take<float>((size_t)B * x->maxw);
+    else if (!x->fused && !x->wide) s.dbuf16[i] = cv.take<uint16_t>((size_t)B * ((x->maxw + 63) / 64 * 64 + 64));
+  }
+  s.df = cv.take<float>((size_t)B * x->ldf);
+  s.dz0 = cv.take<float>((size_t)B * x->d);
+  s.de = cv.take<float>((size_t)B * x->T * x->d);
+  if (x->wide) {
+    s.wg_part = cv.take<float>((size_t)x->wg_elems);
+    for (int l = 0; l < L - 1; ++l) s.dYr[l] = cv.take<uint16_t>((size_t)B * x->pout[l]);
+  }
+  if (x->fused) {
+    s.xT = cv.take<uint16_t>((size_t)x->num_dense * x->ldT);
+    s.fT = cv.take<uint16_t>((size_t)x->F * x->ldT);
+    for (int l = 0; l < L - 1; ++l) {
+      if (l != x->n_bot_layers - 1) s.actT[l] = cv.take<uint16_t>((size_t)x->layers[l].out * x->ldT);
+      s.dYT[l] = cv.take<uint16_t>((size_t)x->layers[l].out * x->ldT);
+    }
+  }
+  const int sort_blocks = sort_max_blocks((uint32_t)n);
+  const int seg_blocks = ceil_div(n, 2048) + 1;
+  s.keys = cv.take<uint32_t>(n);
+  s.bag_of_pos = cv.take<int32_t>(n);
+  s.sorted_bag = cv.take<int32_t>(n);
+  s.sort.keys_alt = cv.take<uint32_t>(n);
+  s.sort.vals = cv.take<uint32_t>(n);
+  s.sort.vals_alt = cv.take<uint32_t>(n);
+  s.sort.block_hist = cv.take<uint32_t>((size_t)256 * sort_blocks);
+  s.sort.digit_tot = cv.take<uint32_t>(256);
+  s.seg.block_counts = cv.take<uint32_t>(seg_blocks);
+  s.seg.seg_starts = cv.take<uint32_t>(n + 1);
+  s.seg.num_unique = cv.take<uint32_t>(64);
+  s.upd.parts = cv.take<float>((size_t)row_update_chunks(n, x->d) * 2 * x->d);
+  s.upd.flags = cv.take<uint32_t>((size_t)row_update_chunks(n, x->d));
+  s.upd.long_list = cv.take<uint32_t>(2 * ((size_t)row_update_chunks(n, x->d) / 30 + 2));
+  s.upd.long_count = cv.take<uint32_t>(64);
+}
+
 static size_t layout(ss_ctx* x, void* base) {
   Carver cv(base);
   const int B = x->max_batch;
@@ -239,72 +318,8 @@ static size_t layout(ss_ctx* x, void* base) {
   x->v = cv.take<float>(x->Pstride);
   x->w_mean = cv.take<float>(x->Pstride);
   x->metrics = cv.take<double>(8);
-  const int L = (int)x->layers.size();
   x->wgrad_tiles_dev = x->wgrad_tiles.empty() ? nullptr : cv.take<int4>(x->wgrad_tiles.size());
-  const int sort_blocks = sort_max_blocks((uint32_t)n);
-  const int seg_blocks = ceil_div(n, 2048) + 1;
-  for (Slot& s : x->slots) {
-    for (int l = 0; l < L; ++l) {
-      s.act_f32[l] = nullptr;
-      s.act_bf16[l] = nullptr;
-      const bool is_z0 = (l == x->n_bot_layers - 1), is_logit = (l == L - 1);
-      if (is_z0 || is_logit) continue;
-      if (x->prec == SS_FP32) s.act_f32[l] = cv.take<float>((size_t)B * x->layers[l].out);
-      else s.act_bf16[l] = cv.take<uint16_t>((size_t)B * (x->wide ? x->pout[l] : x->layers[l].out));
-    }
-    s.z0 = cv.take<float>((size_t)B * x->d);
-    s.e = cv.take<float>((size_t)B * x->T * x->d);
-    s.inv_len = cv.take<float>((size_t)B * x->T);
-    s.f = cv.take<float>((size_t)B * x->ldf);
-    s.f_bf16 = (x->prec == SS_BF16) ? cv.take<uint16_t>((size_t)B * x->ldf16) : nullptr;
-    s.logits = cv.take<float>(B);
-    s.loss = cv.take<float>(64);
-    s.dlogit = cv.take<float>(B);
-    s.grads = cv.take<float>(x->Pstride);
-    for (int i = 0; i < 2; ++i) {
-      s.dbuf[i] = nullptr;
-      s.dbuf16[i] = nullptr;
-      if (x->prec == SS_FP32) s.dbuf[i] = cv.take<float>((size_t)B * x->maxw);
-      else s.dbuf16[i] = cv.take<uint16_t>((size_t)B * ((x->maxw + 63) / 64 * 64 + 64));
-    }
-    s.df = cv.take<float>((size_t)B * x->ldf);
-    s.dz0 = cv.take<float>((size_t)B * x->d);
-    s.de = cv.take<float>((size_t)B * x->T * x->d);
-    s.xT = s.fT = nullptr;
-    for (int l = 0; l < L; ++l) { s.actT[l] = s.dYT[l] = nullptr; s.dYr[l] = nullptr; }
-    s.wsw = nullptr;
-    s.xb = nullptr;
-    s.wg_part = nullptr;
-    if (x->fused || x->wide) s.wsw = cv.take<uint16_t>((size_t)x->wsw_elems);
-    if (x->wide) {
-      s.wg_part = cv.take<float>((size_t)x->wg_elems);
-      s.xb = cv.take<uint16_t>((size_t)B * x->pin[0]);
-      for (int l = 0; l < L - 1; ++l) s.dYr[l] = cv.take<uint16_t>((size_t)B * x->pout[l]);
-    }
-    if (x->fused) {
-      s.xT = cv.take<uint16_t>((size_t)x->num_dense * x->ldT);
-      s.fT = cv.take<uint16_t>((size_t)x->F * x->ldT);
-      for (int l = 0; l < L - 1; ++l) {
-        if (l != x->n_bot_layers - 1) s.actT[l] = cv.take<uint16_t>((size_t)x->layers[l].out * x->ldT);
-        s.dYT[l] = cv.take<uint16_t>((size_t)x->layers[l].out * x->ldT);
-      }
-    }
-    s.keys = cv.take<uint32_t>(n);
-    s.bag_of_pos = cv.take<int32_t>(n);
-    s.sorted_bag = cv.take<int32_t>(n);
-    s.sort.keys_alt = cv.take<uint32_t>(n);
-    s.sort.vals = cv.take<uint32_t>(n);
-    s.sort.vals_alt = cv.take<uint32_t>(n);
-    s.sort.block_hist = cv.take<uint32_t>((size_t)256 * sort_blocks);
-    s.sort.digit_tot = cv.take<uint32_t>(256);
-    s.seg.block_counts = cv.take<uint32_t>(seg_blocks);
-    s.seg.seg_starts = cv.take<uint32_t>(n + 1);
-    s.seg.num_unique = cv.take<uint32_t>(64);
-    s.upd.parts = cv.take<float>((size_t)row_update_chunks(n, x->d) * 2 * x->d);
-    s.upd.flags = cv.take<uint32_t>((size_t)row_update_chunks(n, x->d));
-    s.upd.long_list = cv.take<uint32_t>(2 * ((size_t)row_update_chunks(n, x->d) / 30 + 2));
-    s.upd.long_count = cv.take<uint32_t>(64);
-  }
+  for (Slot& s : x->slots) carve_slot(x, cv, s, B, n, false);
   return (cv.off + ALIGN - 1) / ALIGN * ALIGN;
 }
 
@@ -471,6 +486,12 @@ int ss_init(const ss_config* cfg, void* dev_workspace, size_t bytes, ss_ctx** ou
   if (e != hipSuccess) {
     delete x;
     return fail(nullptr, SS_EDEVICE, "hipGetDevice: %s", hipGetErrorString(e));
+  }
+  // this device's address of the static scratch array (every GPU holds its own copy)
+  e = hipGetSymbolAddress((void**)&x->static_scratch, HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !x->static_scratch) {
+    delete x;
+    return fail(nullptr, SS_EDEVICE, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
   }
   // optimiser state and momentum start at zero (Algorithm 1 initialisation)
   launch_fill_f32(x->G, x->total_rows, 0.f, nullptr);
@@ -1124,6 +1145,39 @@ int ss_train_step(ss_ctx* ctx, int32_t replica, int32_t worker_slot, const ss_ba
 int ss_eval_step(ss_ctx* ctx, int32_t replica, int32_t worker_slot, const ss_batch* batch,
                  void* stream, float* dev_loss_out) {
   return train_or_eval(ctx, replica, worker_slot, batch, stream, dev_loss_out, false);
+}
+
+int ss_eval_step_static(ss_ctx* ctx, int32_t replica, const ss_batch* batch, void* stream,
+                        float* dev_loss_out, float* dev_logits_out) {
+  if (!ctx) return SS_EINVAL;
+  int rc = check_batch(ctx, replica, 0, batch);
+  if (rc != SS_OK) return rc;
+  if (!dev_loss_out) return fail(ctx, SS_EINVAL, "ss_eval_step_static: dev_loss_out must not be NULL");
+  // forward-only scratch for exactly this batch, laid out in the static array
+  Slot s;
+  Carver sizing(nullptr);
+  carve_slot(ctx, sizing, s, batch->batch, batch->num_ids, true);
+  const size_t need = (sizing.off + ALIGN - 1) / ALIGN * ALIGN;
+  if (need > STATIC_SCRATCH_BYTES)
+    return fail(ctx, SS_ENOMEM,
+                "ss_eval_step_static: a batch of %d needs %zu bytes of scratch, the static array "
+                "holds %zu (use ss_eval_step with a worker slot)",
+                batch->batch, need, STATIC_SCRATCH_BYTES);
+  hipStream_t st = (hipStream_t)stream;
+  Carver cv(ctx->static_scratch);
+  carve_slot(ctx, cv, s, batch->batch, batch->num_ids, true);
+  // the array keeps the last call's contents, and the layer-wise kernels read the pitch padding
+  // of their operands: the part this call uses starts from zero (a fill kernel, so that the
+  // call may be captured into a graph)
+  launch_fill_f32((float*)ctx->static_scratch, (uint64_t)(need / 4), 0.f, st);
+  if (dev_logits_out) s.logits = dev_logits_out;
+  const float* w = ctx->W + (size_t)replica * ctx->Pstride;
+  if (ctx->fused) forward_fused(ctx, s, w, batch, dev_loss_out, false, st);
+  else if (ctx->wide) forward_wide(ctx, s, w, batch, dev_loss_out, false, st);
+  else forward(ctx, s, w, batch, dev_loss_out, false, st);
+  if (!fused_last(ctx)) launch_bce_loss(s.logits, batch->labels, batch->batch, dev_loss_out, nullptr, st);
+  launch_metrics(dev_loss_out, batch->labels, batch->batch, ctx->metrics + 4, st);
+  return check_hip(ctx, hipGetLastError(), "ss_eval_step_static");
 }
 
 // ------------------------------------------------------------------------------------------
