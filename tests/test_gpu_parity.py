@@ -298,6 +298,23 @@ def test_bf16_free_running_mid_scaled():
     print(f"free run: worst relative loss difference {worst:.2e}")
 
 
+def test_bf16_large_architecture_lockstep_bmuf():
+    """The Large architecture (26 tables, 1024-wide top MLP, layer-wise MFMA GEMMs) with ITS
+    schedule -- K=4 replicas, S-BMUF alpha 0.5, block lr 1, block momentum 0.9, a round after
+    every sweep -- at a reduced batch on compacted tables, two sweeps, every step and every
+    round checked element by element from a common state."""
+    wl = synth.large().scaled(batch=256)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(8)]
+    cp = synth.compact_problem(wl, batches)
+    gpu, orc = H.make_pair(wl, cp.batches, h0=cp.h0, rows=cp.rows)
+    row_base = np.concatenate(([0], np.cumsum(cp.rows)))
+    H.run_lockstep(gpu, orc, cp.batches, wl.sync_gap, wl.algo, wl.alpha, wl.eta, wl.mu,
+                   rtol=H.BF16_RTOL, resync_row_base=row_base)
+    assert gpu.ss_get_counters()[1] == 2                      # two S-BMUF rounds ran
+    print("gates taken the other way:", H.GATE_STATS)
+
+
 def test_validation_errors_through_the_abi():
     wl = synth.tiny()
     gen = synth.BatchGenerator(wl)
