@@ -62,8 +62,10 @@ def parse():
                     help="paced: one round per sync_gap iterations of a replica, enqueued by its "
                          "workers; continuous: the library's shadow thread loops rounds; auto: "
                          "the workload's own (Large, Hogwild: continuous; Mid, Tiny: paced)")
-    ap.add_argument("--shadow-period-us", type=int, default=0,
-                    help="continuous shadow loop: rounds start at least this far apart")
+    ap.add_argument("--shadow-period-us", type=int, default=-1,
+                    help="continuous shadow loop: rounds start at least this far apart "
+                         "(default: 1000 for Large -- about one round per trainer iteration of a "
+                         "replica --, 0 = back to back otherwise)")
     ap.add_argument("--foreground", type=int, default=0, metavar="k",
                     help="foreground variant: every k iterations a worker syncs on ITS OWN "
                          "stream (FR-EASGD-k), or all workers stop for a round (ma / bmuf)")
@@ -279,6 +281,12 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
         gpu.ss_profile_arm(*one.values())
         gpu.ss_train_step(0, 0, dev_batches[own[0][0]], streams[0], losses[0, -1:])
         per_step = {name: gpu.ss_profile_read(kid)[0] for name, kid in one.items()}
+        # every one-kernel class once more with ONE stream active (no queueing behind, and no
+        # bandwidth or CUs shared with, other streams' kernels)
+        gpu.ss_profile_arm(*one.values())
+        for j in range(12):
+            gpu.ss_train_step(0, 0, dev_batches[own[0][j % len(own[0])]], streams[0], losses[0, -1:])
+        alone = {name: gpu.ss_profile_read(kid) for name, kid in one.items()}
         gpu.ss_profile_arm(*groups.values())
         state["shadow_on"] = shadow_mode != "off"
         saved_mode = shadow_mode
@@ -303,11 +311,16 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
             lps = max(per_step.get(name, 1), 1)
             kd["launches_per_step"] = lps
             kd["total_ms_in_timed_region"] = kd["avg_us"] * lps * train_steps * 1e-3
+            n1, ms1 = alone.get(name, (0, 0.0))
+            kd["alone_avg_us"] = (ms1 / n1 * 1e3) if n1 else None
             if name in flops:
                 work = flops[name] / lps
                 ach = work / (kd["avg_us"] * 1e-6) / 1e12
                 kd.update({"bound": "mfma", "algorithmic_flops_per_launch": work, "TFLOPps": ach,
                            "frac_of_bf16_mfma_peak": ach / MFMA_BF16_PEAK_TFLOPS})
+                if kd["alone_avg_us"]:
+                    kd["alone_TFLOPps"] = work / (kd["alone_avg_us"] * 1e-6) / 1e12
+                    kd["alone_frac_of_bf16_mfma_peak"] = kd["alone_TFLOPps"] / MFMA_BF16_PEAK_TFLOPS
             else:
                 work = hbm_bytes(name, wl, n_ids, n_uniq)
                 ach = work / (kd["avg_us"] * 1e-6) / 1e9
@@ -317,6 +330,11 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
                            "counter_bytes_per_launch": tr,
                            "counter_frac_of_hbm_peak":
                                (tr / (kd["avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS) if tr else None})
+                if kd["alone_avg_us"]:
+                    kd["alone_GBps"] = work / (kd["alone_avg_us"] * 1e-6) / 1e9
+                    kd["alone_frac_of_hbm_peak"] = kd["alone_GBps"] / HBM_PEAK_GBS
+                    kd["alone_counter_frac_of_hbm_peak"] = \
+                        (tr / (kd["alone_avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS) if tr else None
 
     # ---- loss windows
     host_losses = losses.cpu().numpy().astype(float)
@@ -361,9 +379,13 @@ def pick_roofline(kernels, NS):
             "avg_launch_us": kd["avg_us"], "launches": kd["brackets"],
             "launches_per_step": kd["launches_per_step"],
             "work_per_launch": kd["algorithmic_flops_per_launch"] if mfma else kd["algorithmic_bytes_per_launch"],
+            "alone_avg_launch_us": kd.get("alone_avg_us"),
+            "alone_achieved": kd.get("alone_TFLOPps") if mfma else kd.get("alone_GBps"),
+            "alone_frac": kd.get("alone_frac_of_bf16_mfma_peak") if mfma else kd.get("alone_frac_of_hbm_peak"),
             "note": "largest summed time of all one-kernel classes over the timed region; HIP "
                     f"events on the launching streams while {NS} worker streams (+ shadow) share "
-                    "the GPU, so queueing and shared bandwidth are included; MFMA classes "
+                    "the GPU, so queueing and shared bandwidth are included; alone_*: the same "
+                    "class with one stream active, measured after the timed regions; MFMA classes "
                     "average over the layers' GEMM shapes (total flops / total time)"}
 
 
@@ -504,6 +526,8 @@ def main():
     workers = parse_workers(args.workers_per_replica or DEFAULT_WORKERS[wl.name], K)
     NS = sum(workers)
     mode = shadow_mode_of(args, wl)
+    if args.shadow_period_us < 0:
+        args.shadow_period_us = 1000 if wl.name == "large" else 0
     n_batches = max(args.batches, NS)
     n_batches = (n_batches + NS - 1) // NS * NS
     # inputs first: batch generation forks worker processes, which must precede any GPU use

@@ -70,6 +70,16 @@ typedef enum { SS_POOL_SUM = 0, SS_POOL_MEAN = 1 } ss_pooling;
  * SS_MLP_LAYERWISE forces the layer-wise GEMMs for any width.  Ignored under SS_FP32. */
 typedef enum { SS_MLP_AUTO = 0, SS_MLP_LAYERWISE = 1 } ss_mlp_path;
 
+/* Optimiser of the embedding tables (Section 3.2, "Embedding Tables: Hogwild Updates": lock-free
+ * updates with the optimiser's auxiliary state co-located with the rows; the section names
+ * Adagrad and Adam).  SS_OPT_ROWWISE_ADAGRAD: one accumulator per row, G += mean_c g^2,
+ * h -= lr g / (sqrt(G) + eps).  SS_OPT_ADAM: first and second moments per element, one step
+ * count per row; a row's state advances only in the steps that touch it (t_r += 1;
+ * m = b1 m + (1-b1) g; v = b2 v + (1-b2) g^2; h -= lr (m / (1-b1^t_r)) / (sqrt(v / (1-b2^t_r)) + eps)).
+ * Either way the gradients of all occurrences of a row in the batch are summed first and the
+ * row gets one update per step. */
+typedef enum { SS_OPT_ROWWISE_ADAGRAD = 0, SS_OPT_ADAM = 1 } ss_emb_optimizer;
+
 typedef struct {
   int32_t num_tables;        /* T, 1..64                                                  */
   const int64_t* rows;       /* host [T] rows per table; sum < 2^32                      */
@@ -92,6 +102,9 @@ typedef struct {
   uint64_t seed;             /* seed of the counter-based table initialiser             */
   int32_t pooling;           /* ss_pooling                                               */
   int32_t mlp_path;          /* ss_mlp_path                                              */
+  int32_t emb_optimizer;     /* ss_emb_optimizer; lr_emb and adagrad_eps serve both      */
+  float adam_beta1;          /* SS_OPT_ADAM only (0 <= beta < 1)                         */
+  float adam_beta2;
 } ss_config;
 
 /* One mini-batch.  All pointers are DEVICE pointers owned by the caller and must stay
@@ -130,6 +143,11 @@ int ss_write_rows(ss_ctx* ctx, int32_t table, int64_t first_row, int64_t n_rows,
  * optimiser state; Section 3.2 keeps this state beside the rows).  Synchronous. */
 int ss_write_adagrad(ss_ctx* ctx, int32_t table, int64_t first_row, int64_t n_rows,
                      const float* host_acc);
+
+/* SS_OPT_ADAM: moments of the same row range <- host values [n_rows, d] each (either may be
+ * NULL); the rows' step counts are written with ss_write_adagrad.  Synchronous. */
+int ss_write_adam_state(ss_ctx* ctx, int32_t table, int64_t first_row, int64_t n_rows,
+                        const float* host_m, const float* host_v);
 
 /* Algorithm 1: w^(i) <- w0 for all i, w^PS <- w0, w^global <- w0 (Algorithms 3, 4), v <- 0.
  * host_w0 holds P floats.  Synchronous. */
@@ -213,9 +231,12 @@ int ss_shadow_pace(ss_ctx* ctx, int64_t min_period_us);
 int ss_read_dense(ss_ctx* ctx, int32_t which, float* host_out, int64_t n);
 int ss_write_dense(ss_ctx* ctx, int32_t which, const float* host_in, int64_t n);
 /* rows: host [n] row ids of `table`; host_rows_out [n, d] and host_adagrad_out [n] may
- * each be NULL. */
+ * each be NULL.  Under SS_OPT_ADAM host_adagrad_out receives the rows' step counts and
+ * ss_read_adam_state the moments ([n, d] each, either may be NULL). */
 int ss_read_rows(ss_ctx* ctx, int32_t table, const int64_t* rows, int64_t n,
                  float* host_rows_out, float* host_adagrad_out);
+int ss_read_adam_state(ss_ctx* ctx, int32_t table, const int64_t* rows, int64_t n,
+                       float* host_m_out, float* host_v_out);
 
 /* Intermediates of the LAST step run on a worker slot, for element-wise checks
  * (synchronises first).  Forward results (pooled vectors, interaction, logits, activations)

@@ -17,6 +17,9 @@ Parity status of each part (what independent fact pins it):
   embedding backward segment sums    : transposed multiplicity matrix (pinned)
   stable sort order                  : Python's sorted() on (key, position) (pinned)
   row-wise Adagrad                   : closed form of the first step (pinned)
+  Adam on table rows                 : first-step closed form, torch.optim.Adam when every
+                                       row is touched every step, untouched rows keep their
+                                       state (pinned)
   S-EASGD / S-MA / S-BMUF            : conservation laws, fixed points, scalar
                                        recurrences (pinned)
   Hogwild (racy) schedules           : parity unpinned by nature; only the
@@ -26,6 +29,7 @@ Parity status of each part (what independent fact pins it):
 
 from .dlrm import (  # noqa: F401
     DenseLayout,
+    adam_update,
     bf16_round,
     bce_with_logits,
     dlrm_forward,

@@ -235,6 +235,23 @@ def rowwise_adagrad_update(h, G, rows, g, lr: float, eps: float):
     h[rows] = h[rows] - lr * g / (np.sqrt(G[rows]) + eps)[:, None]
 
 
+def adam_update(h, M, V, T, rows, g, lr: float, eps: float, beta1: float, beta2: float):
+    """Adam on the touched rows only, with its state kept beside the rows (Section 3.2 names
+    Adam next to Adagrad as a table optimiser with co-located auxiliary state): per row r in
+    `rows` (each distinct, one update per step)
+        T_r += 1;  M_r = beta1 M_r + (1-beta1) g_r;  V_r = beta2 V_r + (1-beta2) g_r^2;
+        h[r,:] -= lr * (M_r / (1-beta1^T_r)) / (sqrt(V_r / (1-beta2^T_r)) + eps).
+    M, V are per element, T is the row's own step count: a row that a batch does not touch
+    keeps all of its state.  In place."""
+    T[rows] = T[rows] + 1
+    M[rows] = beta1 * M[rows] + (1 - beta1) * g
+    V[rows] = beta2 * V[rows] + (1 - beta2) * g * g
+    t = T[rows][:, None]
+    m_hat = M[rows] / (1 - beta1 ** t)
+    v_hat = V[rows] / (1 - beta2 ** t)
+    h[rows] = h[rows] - lr * m_hat / (np.sqrt(v_hat) + eps)
+
+
 # --------------------------------------------------------------------------- interaction
 def lower_pairs(T: int):
     """(r, c) with 1 <= r <= T, 0 <= c < r, row-major: the strictly lower triangle of

@@ -17,7 +17,8 @@ from . import dlrm, sync
 class OracleTrainer:
     def __init__(self, bot_dims, top_dims, row_base, h0, w0, num_replicas,
                  lr_dense=0.01, lr_emb=0.01, adagrad_eps=1e-8, dtype=np.float64,
-                 bf16=False, pooling="sum"):
+                 bf16=False, pooling="sum", emb_optimizer="rowwise_adagrad",
+                 adam_betas=(0.9, 0.999)):
         self.layout = dlrm.DenseLayout(tuple(bot_dims), tuple(top_dims))
         self.row_base = np.asarray(row_base, dtype=np.int64)
         self.T = len(self.row_base) - 1
@@ -29,8 +30,14 @@ class OracleTrainer:
         self.bf16 = bf16
         assert pooling in ("sum", "mean")
         self.pooling = pooling
+        assert emb_optimizer in ("rowwise_adagrad", "adam")
+        self.emb_optimizer = emb_optimizer
+        self.adam_betas = adam_betas
         self.h = h0.astype(dtype).copy()
+        # per row: the Adagrad accumulator, or (Adam) the row's own step count
         self.G = np.zeros(h0.shape[0], dtype=dtype)
+        self.M = np.zeros_like(self.h) if emb_optimizer == "adam" else None
+        self.V = np.zeros_like(self.h) if emb_optimizer == "adam" else None
         self.W = np.tile(w0.astype(dtype), (num_replicas, 1))
         self.w_ps = w0.astype(dtype).copy()
         self.w_global = w0.astype(dtype).copy()
@@ -71,8 +78,12 @@ class OracleTrainer:
             # has not trained on it yet (the progressive Train NE of Section 4)
             self.metrics["train"] += (loss * B, float(np.sum(y)), B)
             self.W[replica] = w - self.lr_dense * g
-            dlrm.rowwise_adagrad_update(self.h, self.G, rows, g_rows, self.lr_emb,
-                                        self.eps)
+            if self.emb_optimizer == "adam":
+                dlrm.adam_update(self.h, self.M, self.V, self.G, rows, g_rows, self.lr_emb,
+                                 self.eps, *self.adam_betas)
+            else:
+                dlrm.rowwise_adagrad_update(self.h, self.G, rows, g_rows, self.lr_emb,
+                                            self.eps)
             self.steps[replica] += 1
         return loss
 

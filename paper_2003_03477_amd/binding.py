@@ -20,6 +20,7 @@ SS_EASGD, SS_MA, SS_BMUF, SS_EASGD_LITERAL, SS_BMUF_NESTEROV = 0, 1, 2, 3, 4
 SS_FP32, SS_BF16 = 0, 1
 POOLING = {"sum": 0, "mean": 1}
 MLP_PATHS = {"auto": 0, "layerwise": 1}
+EMB_OPTIMIZERS = {"rowwise_adagrad": 0, "adam": 1}
 ALGOS = {"easgd": SS_EASGD, "ma": SS_MA, "bmuf": SS_BMUF, "easgd_literal": SS_EASGD_LITERAL,
          "bmuf_nesterov": SS_BMUF_NESTEROV}
 
@@ -40,7 +41,7 @@ EXPORTS = [
     "ss_shadow_sync", "ss_easgd_exchange", "ss_sync_round", "ss_shadow_start", "ss_shadow_stop", "ss_read_dense",
     "ss_write_dense", "ss_read_rows", "ss_read_debug", "ss_get_counters", "ss_profile_arm",
     "ss_profile_sample", "ss_profile_read", "ss_shadow_pace", "ss_metrics_read",
-    "ss_metrics_reset", "ss_eval_step_static",
+    "ss_metrics_reset", "ss_eval_step_static", "ss_write_adam_state", "ss_read_adam_state",
 ]
 
 
@@ -53,7 +54,8 @@ class ss_config(C.Structure):
                 ("max_ids", C.c_int64), ("num_worker_slots", C.c_int32),
                 ("mlp_prec", C.c_int32), ("lr_dense", C.c_float), ("lr_emb", C.c_float),
                 ("adagrad_eps", C.c_float), ("seed", C.c_uint64), ("pooling", C.c_int32),
-                ("mlp_path", C.c_int32)]
+                ("mlp_path", C.c_int32), ("emb_optimizer", C.c_int32),
+                ("adam_beta1", C.c_float), ("adam_beta2", C.c_float)]
 
 
 class ss_batch(C.Structure):
@@ -85,6 +87,8 @@ def load() -> C.CDLL:
     lib.ss_init_tables_hash.argtypes = [vp, vp]
     lib.ss_write_rows.argtypes = [vp, i32, i64, i64, vp]
     lib.ss_write_adagrad.argtypes = [vp, i32, i64, i64, vp]
+    lib.ss_write_adam_state.argtypes = [vp, i32, i64, i64, vp, vp]
+    lib.ss_read_adam_state.argtypes = [vp, i32, vp, i64, vp, vp]
     lib.ss_init_dense.argtypes = [vp, vp]
     lib.ss_num_params.restype = i64
     lib.ss_num_params.argtypes = [vp]
@@ -163,7 +167,8 @@ class ShadowSync:
                  top_dims: Sequence[int], num_replicas: int, max_batch: int, max_ids: int,
                  num_worker_slots: int = 1, bf16: bool = False, lr_dense: float = 0.01,
                  lr_emb: float = 0.01, adagrad_eps: float = 1e-8, seed: int = 0,
-                 device: str = "cuda:0", pooling: str = "sum", mlp_path: str = "auto"):
+                 device: str = "cuda:0", pooling: str = "sum", mlp_path: str = "auto",
+                 emb_optimizer: str = "rowwise_adagrad", adam_betas=(0.9, 0.999)):
         import torch
         self.lib = load()
         self.torch = torch
@@ -175,7 +180,8 @@ class ShadowSync:
                              self._bot, len(top_dims), self._top, num_replicas, max_batch,
                              max_ids, num_worker_slots, SS_BF16 if bf16 else SS_FP32,
                              lr_dense, lr_emb, adagrad_eps, seed, POOLING[pooling],
-                             MLP_PATHS[mlp_path])
+                             MLP_PATHS[mlp_path], EMB_OPTIMIZERS[emb_optimizer],
+                             adam_betas[0], adam_betas[1])
         self.rows, self.emb_dim, self.K = list(rows), emb_dim, num_replicas
         self.T = len(rows)
         self.ctx = C.c_void_p()
@@ -224,6 +230,20 @@ class ShadowSync:
         v = np.ascontiguousarray(values, dtype=np.float32)
         self._check(self.lib.ss_write_adagrad(self.ctx, table, first_row, v.shape[0], _np_ptr(v)),
                     "ss_write_adagrad")
+
+    def ss_write_adam_state(self, table: int, first_row: int, m: np.ndarray, v: np.ndarray):
+        m = np.ascontiguousarray(m, dtype=np.float32)
+        v = np.ascontiguousarray(v, dtype=np.float32)
+        self._check(self.lib.ss_write_adam_state(self.ctx, table, first_row, m.shape[0], _np_ptr(m),
+                                                 _np_ptr(v)), "ss_write_adam_state")
+
+    def ss_read_adam_state(self, table: int, rows: np.ndarray):
+        r = np.ascontiguousarray(rows, dtype=np.int64)
+        m = np.empty((len(r), self.emb_dim), dtype=np.float32)
+        v = np.empty((len(r), self.emb_dim), dtype=np.float32)
+        self._check(self.lib.ss_read_adam_state(self.ctx, table, _np_ptr(r), len(r), _np_ptr(m),
+                                                _np_ptr(v)), "ss_read_adam_state")
+        return m, v
 
     def ss_init_dense(self, w0: np.ndarray):
         w = np.ascontiguousarray(w0, dtype=np.float32)
@@ -367,4 +387,6 @@ def from_workload(wl, rows=None, num_worker_slots: int = 1, max_ids: Optional[in
         max_ids = int(wl.batch * wl.num_tables * (lam + 6 * (lam ** 0.5) / (wl.batch ** 0.5)) + 4096)
     return ShadowSync(rows, wl.emb_dim, wl.bot_dims, wl.top_dims, wl.num_replicas, wl.batch,
                       max_ids, num_worker_slots, wl.bf16, wl.lr_dense, wl.lr_emb,
-                      wl.adagrad_eps, wl.seed, device, wl.pooling, mlp_path)
+                      wl.adagrad_eps, wl.seed, device, wl.pooling, mlp_path,
+                      getattr(wl, "emb_optimizer", "rowwise_adagrad"),
+                      getattr(wl, "adam_betas", (0.9, 0.999)))

@@ -122,6 +122,8 @@ struct ss_ctx {
   std::vector<int4> wgrad_tiles;   // host copy of the tile table
   int4* wgrad_tiles_dev = nullptr;
   float lr_dense, lr_emb, eps;
+  bool adam = false;               // table optimiser: Adam instead of row-wise Adagrad
+  float beta1 = 0.9f, beta2 = 0.999f;
   uint64_t seed;
   int device;
   TableMeta meta;
@@ -129,6 +131,8 @@ struct ss_ctx {
   // device memory
   float* h;
   float* G;
+  float* M = nullptr;  // Adam: first / second moments, [total_rows, d] each
+  float* V = nullptr;
   float* W;  // K replicas, stride Pstride
   float* w_ps;
   float* w_global;
@@ -228,6 +232,11 @@ static int validate(const ss_config* c, std::string& why) {
   if (c->mlp_prec != SS_FP32 && c->mlp_prec != SS_BF16) BAD("bad mlp_prec");
   if (c->pooling != SS_POOL_SUM && c->pooling != SS_POOL_MEAN) BAD("bad pooling mode");
   if (c->mlp_path != SS_MLP_AUTO && c->mlp_path != SS_MLP_LAYERWISE) BAD("bad mlp_path");
+  if (c->emb_optimizer != SS_OPT_ROWWISE_ADAGRAD && c->emb_optimizer != SS_OPT_ADAM)
+    BAD("bad emb_optimizer");
+  if (c->emb_optimizer == SS_OPT_ADAM &&
+      !(c->adam_beta1 >= 0.f && c->adam_beta1 < 1.f && c->adam_beta2 >= 0.f && c->adam_beta2 < 1.f))
+    BAD("Adam betas must lie in [0, 1)");
   const size_t shm = (size_t)4 * ((T + 1) * (c->emb_dim + 4) + (((T + 1) * (T + 1) + 3) & ~3)) * 4;
   if (shm > 64 * 1024) BAD("interaction tile (T+1) x d does not fit the LDS budget");
 #undef BAD
@@ -312,6 +321,10 @@ static size_t layout(ss_ctx* x, void* base) {
   const int64_t n = x->max_ids;
   x->h = cv.take<float>(x->total_rows * (uint64_t)x->d);
   x->G = cv.take<float>(x->total_rows);
+  if (x->adam) {
+    x->M = cv.take<float>(x->total_rows * (uint64_t)x->d);
+    x->V = cv.take<float>(x->total_rows * (uint64_t)x->d);
+  }
   x->W = cv.take<float>((size_t)x->K * x->Pstride);
   x->w_ps = cv.take<float>(x->Pstride);
   x->w_global = cv.take<float>(x->Pstride);
@@ -330,6 +343,8 @@ static ss_ctx* make_ctx(const ss_config* c) {
   x->num_slots = c->num_worker_slots; x->prec = c->mlp_prec;
   x->pool_mean = (c->pooling == SS_POOL_MEAN);
   x->lr_dense = c->lr_dense; x->lr_emb = c->lr_emb; x->eps = c->adagrad_eps; x->seed = c->seed;
+  x->adam = (c->emb_optimizer == SS_OPT_ADAM);
+  x->beta1 = c->adam_beta1; x->beta2 = c->adam_beta2;
   x->rows.assign(c->rows, c->rows + c->num_tables);
   uint64_t base = 0;
   memset(&x->meta, 0, sizeof x->meta);
@@ -495,6 +510,10 @@ int ss_init(const ss_config* cfg, void* dev_workspace, size_t bytes, ss_ctx** ou
   }
   // optimiser state and momentum start at zero (Algorithm 1 initialisation)
   launch_fill_f32(x->G, x->total_rows, 0.f, nullptr);
+  if (x->adam) {
+    launch_fill_f32(x->M, x->total_rows * (uint64_t)x->d, 0.f, nullptr);
+    launch_fill_f32(x->V, x->total_rows * (uint64_t)x->d, 0.f, nullptr);
+  }
   launch_fill_f32(x->v, (uint64_t)x->Pstride, 0.f, nullptr);
   launch_fill_f32(x->W, (uint64_t)x->K * x->Pstride, 0.f, nullptr);
   launch_fill_f32(x->w_ps, (uint64_t)x->Pstride, 0.f, nullptr);
@@ -560,6 +579,10 @@ int ss_init_tables_hash(ss_ctx* ctx, void* stream) {
     launch_table_hash_init(ctx->h + (size_t)ctx->meta.row_base[t] * ctx->d,
                            (uint64_t)ctx->rows[t] * ctx->d, ctx->seed, t, s);
   launch_fill_f32(ctx->G, ctx->total_rows, 0.f, s);
+  if (ctx->adam) {
+    launch_fill_f32(ctx->M, ctx->total_rows * (uint64_t)ctx->d, 0.f, s);
+    launch_fill_f32(ctx->V, ctx->total_rows * (uint64_t)ctx->d, 0.f, s);
+  }
   return check_hip(ctx, hipGetLastError(), "table init");
 }
 
@@ -575,7 +598,27 @@ int ss_write_rows(ss_ctx* ctx, int32_t table, int64_t first_row, int64_t n_rows,
   HIP_TRY(ctx, hipMemcpy(ctx->h + r0 * ctx->d, host_rows, (size_t)n_rows * ctx->d * sizeof(float),
                          hipMemcpyHostToDevice));
   launch_fill_f32(ctx->G + r0, (uint64_t)n_rows, 0.f, nullptr);
+  if (ctx->adam) {
+    launch_fill_f32(ctx->M + r0 * ctx->d, (uint64_t)n_rows * ctx->d, 0.f, nullptr);
+    launch_fill_f32(ctx->V + r0 * ctx->d, (uint64_t)n_rows * ctx->d, 0.f, nullptr);
+  }
   HIP_TRY(ctx, hipDeviceSynchronize());
+  return SS_OK;
+}
+
+int ss_write_adam_state(ss_ctx* ctx, int32_t table, int64_t first_row, int64_t n_rows,
+                        const float* host_m, const float* host_v) {
+  if (!ctx) return SS_EINVAL;
+  if (!ctx->adam) return fail(ctx, SS_ESTATE, "the table optimiser is not Adam");
+  if (table < 0 || table >= ctx->T || first_row < 0 || n_rows < 0 ||
+      first_row + n_rows > ctx->rows[table])
+    return fail(ctx, SS_EINVAL, "ss_write_adam_state: bad table/row range");
+  if (n_rows == 0) return SS_OK;
+  const size_t r0 = (size_t)ctx->meta.row_base[table] + first_row;
+  const size_t bytes = (size_t)n_rows * ctx->d * sizeof(float);
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  if (host_m) HIP_TRY(ctx, hipMemcpy(ctx->M + r0 * ctx->d, host_m, bytes, hipMemcpyHostToDevice));
+  if (host_v) HIP_TRY(ctx, hipMemcpy(ctx->V + r0 * ctx->d, host_v, bytes, hipMemcpyHostToDevice));
   return SS_OK;
 }
 
@@ -655,6 +698,31 @@ int ss_read_rows(ss_ctx* ctx, int32_t table, const int64_t* rows, int64_t n, flo
     if (host_adagrad_out)
       HIP_TRY(ctx, hipMemcpy(host_adagrad_out + i, ctx->G + r, (size_t)(j - i) * sizeof(float),
                              hipMemcpyDeviceToHost));
+    i = j;
+  }
+  return SS_OK;
+}
+
+int ss_read_adam_state(ss_ctx* ctx, int32_t table, const int64_t* rows, int64_t n,
+                       float* host_m_out, float* host_v_out) {
+  if (!ctx || (!rows && n)) return SS_EINVAL;
+  if (!ctx->adam) return fail(ctx, SS_ESTATE, "the table optimiser is not Adam");
+  if (table < 0 || table >= ctx->T || n < 0) return fail(ctx, SS_EINVAL, "ss_read_adam_state: bad table");
+  for (int64_t i = 0; i < n; ++i)
+    if (rows[i] < 0 || rows[i] >= ctx->rows[table])
+      return fail(ctx, SS_EINVAL, "ss_read_adam_state: row %lld out of range", (long long)rows[i]);
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  const size_t base = ctx->meta.row_base[table];
+  int64_t i = 0;
+  while (i < n) {   // contiguous runs are copied in one piece
+    int64_t j = i + 1;
+    while (j < n && rows[j] == rows[j - 1] + 1) ++j;
+    const size_t r = base + (size_t)rows[i];
+    const size_t bytes = (size_t)(j - i) * ctx->d * sizeof(float);
+    if (host_m_out)
+      HIP_TRY(ctx, hipMemcpy(host_m_out + (size_t)i * ctx->d, ctx->M + r * ctx->d, bytes, hipMemcpyDeviceToHost));
+    if (host_v_out)
+      HIP_TRY(ctx, hipMemcpy(host_v_out + (size_t)i * ctx->d, ctx->V + r * ctx->d, bytes, hipMemcpyDeviceToHost));
     i = j;
   }
   return SS_OK;
@@ -1119,14 +1187,15 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
                         s.bag_of_pos, s.sorted_bag, st);
       s.seg_valid = false;  // compacted segment starts are produced on demand (ss_read_debug)
     }
+    const EmbOpt opt{x->h, x->G, x->M, x->V, x->lr_emb, x->eps, x->beta1, x->beta2, x->adam ? 1 : 0};
     {
       ProfScope all(x, SS_K_ROW_UPDATE, st);
       {
         ProfScope ps(x, SS_K_ROW_UPDATE_CHUNK, st);
-        launch_row_update_chunk(s.sorted_keys, s.sorted_bag, s.de, n, s.upd, x->d, x->h, x->G,
-                                x->lr_emb, x->eps, x->pool_mean ? s.inv_len : nullptr, st);
+        launch_row_update_chunk(s.sorted_keys, s.sorted_bag, s.de, n, s.upd, x->d, opt,
+                                x->pool_mean ? s.inv_len : nullptr, st);
       }
-      launch_row_update_finish(s.sorted_keys, n, s.upd, x->d, x->h, x->G, x->lr_emb, x->eps, st);
+      launch_row_update_finish(s.sorted_keys, n, s.upd, x->d, opt, st);
     }
     s.trained = true;
     x->steps[replica].fetch_add(1);

@@ -1,8 +1,12 @@
 // Embedding backward, second half (gfx950): per distinct row, the sum of the pooled-vector
-// gradients of all its occurrences, then one row-wise Adagrad update
-//   G_r += mean_c g_r[c]^2 ;  h[r,:] -= lr * g_r / (sqrt(G_r) + eps)
-// (Section 3.2: lock-free optimiser updates on the single shared copy of the tables, with the
-// Adagrad accumulator kept beside each row).
+// gradients of all its occurrences, then ONE optimiser update of that row (Section 3.2:
+// lock-free optimiser updates on the single shared copy of the tables, the optimiser's state
+// kept beside each row; the section names Adagrad and Adam):
+//   row-wise Adagrad   G_r += mean_c g_r[c]^2 ;  h[r,:] -= lr * g_r / (sqrt(G_r) + eps)
+//   Adam (lazy)        t_r += 1 ; m = b1 m + (1-b1) g ; v = b2 v + (1-b2) g^2 ;
+//                      h[r,:] -= lr * (m / (1-b1^t_r)) / (sqrt(v / (1-b2^t_r)) + eps)
+//                      with m, v per element and the step count t_r per row (kept in G[r]):
+//                      a row's state only moves in the steps that touch the row.
 //
 // Input: the (row, position) pairs sorted by row, as `sorted_keys` and the pooled-vector id
 // `sorted_bag` of every sorted entry.  With Zipf-distributed ids the run lengths range from 1
@@ -28,27 +32,48 @@ int64_t row_update_chunks(int64_t max_ids, int d) {
   return (max_ids + C - 1) / C + 1;
 }
 
-template <int LPR>
-__device__ __forceinline__ void adagrad_store(float4 g, float4 hv, float Gv, uint32_t row, int c4,
-                                              float* __restrict__ h, float* __restrict__ G,
-                                              float lr, float eps) {
+template <int LPR, bool ADAM>
+__device__ __forceinline__ void apply_update(float4 g, float4 hv, float Gv, uint32_t row, int c4,
+                                             const EmbOpt& o) {
   constexpr int D = LPR * 4;
+  float* __restrict__ h = o.h;
+  if (ADAM) {
+    const size_t at = (size_t)row * D + c4 * 4;
+    float4 m = *(const float4*)(o.M + at), v = *(const float4*)(o.V + at);
+    const float t = Gv + 1.0f;
+    const float b1 = o.beta1, b2 = o.beta2;
+    m.x = b1 * m.x + (1.f - b1) * g.x; m.y = b1 * m.y + (1.f - b1) * g.y;
+    m.z = b1 * m.z + (1.f - b1) * g.z; m.w = b1 * m.w + (1.f - b1) * g.w;
+    v.x = b2 * v.x + (1.f - b2) * g.x * g.x; v.y = b2 * v.y + (1.f - b2) * g.y * g.y;
+    v.z = b2 * v.z + (1.f - b2) * g.z * g.z; v.w = b2 * v.w + (1.f - b2) * g.w * g.w;
+    const float c1 = 1.f - powf(b1, t), c2 = 1.f - powf(b2, t);
+    const float s1 = o.lr / c1, s2 = 1.f / sqrtf(c2);
+    hv.x -= s1 * m.x / (sqrtf(v.x) * s2 + o.eps); hv.y -= s1 * m.y / (sqrtf(v.y) * s2 + o.eps);
+    hv.z -= s1 * m.z / (sqrtf(v.z) * s2 + o.eps); hv.w -= s1 * m.w / (sqrtf(v.w) * s2 + o.eps);
+    *(float4*)(o.M + at) = m;
+    *(float4*)(o.V + at) = v;
+    *(float4*)(h + at) = hv;
+    if (c4 == 0) o.G[row] = t;
+    return;
+  }
   float ss = g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
 #pragma unroll
   for (int off = 1; off < LPR; off <<= 1) ss += __shfl_xor(ss, off);
   const float Gn = Gv + ss * (1.0f / (float)D);
-  const float scale = lr / (sqrtf(Gn) + eps);
+  const float scale = o.lr / (sqrtf(Gn) + o.eps);
   hv.x -= scale * g.x; hv.y -= scale * g.y; hv.z -= scale * g.z; hv.w -= scale * g.w;
   *(float4*)(h + (size_t)row * D + c4 * 4) = hv;
-  if (c4 == 0) G[row] = Gn;
+  if (c4 == 0) o.G[row] = Gn;
 }
 
-template <int LPR>
+template <int LPR, bool ADAM>
 __global__ __launch_bounds__(256) void row_update_chunk_kernel(
     const uint32_t* __restrict__ keys, const int32_t* __restrict__ bags,
-    const float* __restrict__ de, uint32_t n, float* __restrict__ h, float* __restrict__ G,
-    float lr, float eps, float* __restrict__ parts, uint32_t* __restrict__ flags,
-    uint32_t* __restrict__ long_count, const float* __restrict__ inv_len) {
+    const float* __restrict__ de, uint32_t n, EmbOpt o, float* __restrict__ parts,
+    uint32_t* __restrict__ flags, uint32_t* __restrict__ long_count,
+    const float* __restrict__ inv_len) {
+  const float* __restrict__ h = o.h;
+  const float* __restrict__ G = o.G;
   constexpr int D = LPR * 4, C = LPR, SUB = (C < 8 ? C : 8);
   if (blockIdx.x == 0 && threadIdx.x == 0) *long_count = 0;  // consumed by the later passes
   const int lane = threadIdx.x & 63, c = lane % LPR, gw = lane / LPR;
@@ -108,7 +133,7 @@ __global__ __launch_bounds__(256) void row_update_chunk_kernel(
         acc.x += v[i].x; acc.y += v[i].y; acc.z += v[i].z; acc.w += v[i].w;
         if ((tm >> p) & 1u) {
           if (started) {
-            adagrad_store<LPR>(acc, hv[i], Gv[i], rw[i], c, h, G, lr, eps);
+            apply_update<LPR, ADAM>(acc, hv[i], Gv[i], rw[i], c, o);
           } else {
             *part0 = acc;  // end of a run that came in from the previous chunk
             fl |= 1u;
@@ -126,11 +151,13 @@ __global__ __launch_bounds__(256) void row_update_chunk_kernel(
   if (c == 0) flags[g] = fl;
 }
 
-template <int LPR>
+template <int LPR, bool ADAM>
 __global__ __launch_bounds__(256) void row_update_stitch_kernel(
     const uint32_t* __restrict__ keys, uint32_t n, float* __restrict__ parts,
-    const uint32_t* __restrict__ flags, float* __restrict__ h, float* __restrict__ G, float lr,
-    float eps, uint32_t* __restrict__ long_list, uint32_t* __restrict__ long_count) {
+    const uint32_t* __restrict__ flags, EmbOpt o, uint32_t* __restrict__ long_list,
+    uint32_t* __restrict__ long_count) {
+  const float* __restrict__ h = o.h;
+  const float* __restrict__ G = o.G;
   constexpr int D = LPR * 4, C = LPR, MAXB = 16;
   const int c = threadIdx.x % LPR;
   const uint32_t nchunks = (n + C - 1) / C;
@@ -170,7 +197,7 @@ __global__ __launch_bounds__(256) void row_update_stitch_kernel(
     batch = min(MAXB, batch * 2);
   }
   if (done) {
-    adagrad_store<LPR>(acc, hv, Gv, row, c, h, G, lr, eps);
+    apply_update<LPR, ADAM>(acc, hv, Gv, row, c, o);
   } else {
     *mine = acc;  // sum so far; the long-run kernel continues from chunk g2
     if (c == 0) {
@@ -181,11 +208,13 @@ __global__ __launch_bounds__(256) void row_update_stitch_kernel(
   }
 }
 
-template <int LPR>
+template <int LPR, bool ADAM>
 __global__ __launch_bounds__(1024) void row_update_long_kernel(
     const uint32_t* __restrict__ keys, uint32_t n, const float* __restrict__ parts,
-    const uint32_t* __restrict__ flags, float* __restrict__ h, float* __restrict__ G, float lr,
-    float eps, const uint32_t* __restrict__ long_list, const uint32_t* __restrict__ long_count) {
+    const uint32_t* __restrict__ flags, EmbOpt o, const uint32_t* __restrict__ long_list,
+    const uint32_t* __restrict__ long_count) {
+  const float* __restrict__ h = o.h;
+  const float* __restrict__ G = o.G;
   constexpr int D = LPR * 4, C = LPR, NG = 1024 / LPR;
   __shared__ float4 red[1024];
   __shared__ uint32_t last_chunk;
@@ -242,7 +271,7 @@ __global__ __launch_bounds__(1024) void row_update_long_kernel(
       acc.x += first.x; acc.y += first.y; acc.z += first.z; acc.w += first.w;
       const uint32_t row = keys[(g + 1) * C - 1];
       const float4 hv = *(const float4*)(h + (size_t)row * D + c * 4);
-      adagrad_store<LPR>(acc, hv, G[row], row, c, h, G, lr, eps);
+      apply_update<LPR, ADAM>(acc, hv, G[row], row, c, o);
     }
     __syncthreads();
   }
@@ -250,26 +279,27 @@ __global__ __launch_bounds__(1024) void row_update_long_kernel(
 
 void launch_row_update_chunk(const uint32_t* sorted_keys, const int32_t* sorted_bag,
                              const float* de, uint32_t n, const RowUpdateScratch& sc, int d,
-                             float* h, float* G, float lr, float eps, const float* inv_len,
-                             hipStream_t s) {
+                             const EmbOpt& o, const float* inv_len, hipStream_t s) {
   if (n == 0) return;
   const int lpr = d / 4;
   const int64_t nchunks = ((int64_t)n + lpr - 1) / lpr;
   const int blocks = ceil_div(nchunks, 256 / lpr);
-#define L(LPR)                                                                                   \
-  hipLaunchKernelGGL((row_update_chunk_kernel<LPR>), dim3(blocks), dim3(256), 0, s, sorted_keys, \
-                     sorted_bag, de, n, h, G, lr, eps, sc.parts, sc.flags, sc.long_count, inv_len)
+#define L(LPR, A)                                                                                    \
+  hipLaunchKernelGGL((row_update_chunk_kernel<LPR, A>), dim3(blocks), dim3(256), 0, s, sorted_keys, \
+                     sorted_bag, de, n, o, sc.parts, sc.flags, sc.long_count, inv_len)
+#define LA(LPR) do { if (o.adam) { L(LPR, true); } else { L(LPR, false); } } while (0)
   switch (d) {
-    case 16: L(4); break;
-    case 32: L(8); break;
-    case 64: L(16); break;
-    default: L(32); break;
+    case 16: LA(4); break;
+    case 32: LA(8); break;
+    case 64: LA(16); break;
+    default: LA(32); break;
   }
+#undef LA
 #undef L
 }
 
 void launch_row_update_finish(const uint32_t* sorted_keys, uint32_t n, const RowUpdateScratch& sc,
-                              int d, float* h, float* G, float lr, float eps, hipStream_t s) {
+                              int d, const EmbOpt& o, hipStream_t s) {
   if (n == 0) return;
   const int lpr = d / 4;
   const int64_t nchunks = ((int64_t)n + lpr - 1) / lpr;
@@ -278,17 +308,19 @@ void launch_row_update_finish(const uint32_t* sorted_keys, uint32_t n, const Row
   // for the worst case that matters (a run is long from about 30 chunks on) and capped
   const int64_t lb = nchunks / 512 + 16;
   const int long_blocks = (int)(lb > 512 ? 512 : lb);
-#define L(LPR)                                                                                    \
-  hipLaunchKernelGGL((row_update_stitch_kernel<LPR>), dim3(blocks), dim3(256), 0, s, sorted_keys, \
-                     n, sc.parts, sc.flags, h, G, lr, eps, sc.long_list, sc.long_count);          \
-  hipLaunchKernelGGL((row_update_long_kernel<LPR>), dim3(long_blocks), dim3(1024), 0, s, sorted_keys, n, \
-                     sc.parts, sc.flags, h, G, lr, eps, sc.long_list, sc.long_count)
+#define L(LPR, A)                                                                                      \
+  hipLaunchKernelGGL((row_update_stitch_kernel<LPR, A>), dim3(blocks), dim3(256), 0, s, sorted_keys,  \
+                     n, sc.parts, sc.flags, o, sc.long_list, sc.long_count);                           \
+  hipLaunchKernelGGL((row_update_long_kernel<LPR, A>), dim3(long_blocks), dim3(1024), 0, s,           \
+                     sorted_keys, n, sc.parts, sc.flags, o, sc.long_list, sc.long_count)
+#define LA(LPR) do { if (o.adam) { L(LPR, true); } else { L(LPR, false); } } while (0)
   switch (d) {
-    case 16: L(4); break;
-    case 32: L(8); break;
-    case 64: L(16); break;
-    default: L(32); break;
+    case 16: LA(4); break;
+    case 32: LA(8); break;
+    case 64: LA(16); break;
+    default: LA(32); break;
   }
+#undef LA
 #undef L
 }
 

@@ -46,14 +46,21 @@ struct RowUpdateScratch {
   uint32_t* long_count;  // [1]
 };
 int64_t row_update_chunks(int64_t max_ids, int d);
-// Per distinct row: g = sum of de over its occurrences (all of them first), then row-wise
-// Adagrad on h and G.  Input: keys sorted ascending with the pooled-vector id of each entry.
+// Table optimiser of the row update: h and its state beside the rows.  adam = 0: row-wise
+// Adagrad, G = one accumulator per row.  adam = 1: Adam, M / V = first / second moments per
+// element, G = the row's own step count.
+struct EmbOpt {
+  float* h; float* G; float* M; float* V;
+  float lr, eps, beta1, beta2;
+  int adam;
+};
+// Per distinct row: g = sum of de over its occurrences (all of them first), then one optimiser
+// update of that row.  Input: keys sorted ascending with the pooled-vector id of each entry.
 void launch_row_update_chunk(const uint32_t* sorted_keys, const int32_t* sorted_bag,
                              const float* de, uint32_t n, const RowUpdateScratch& sc, int d,
-                             float* h, float* G, float lr, float eps, const float* inv_len,
-                             hipStream_t s);
+                             const EmbOpt& o, const float* inv_len, hipStream_t s);
 void launch_row_update_finish(const uint32_t* sorted_keys, uint32_t n, const RowUpdateScratch& sc,
-                              int d, float* h, float* G, float lr, float eps, hipStream_t s);
+                              int d, const EmbOpt& o, hipStream_t s);
 
 // ---------------------------------------------------------------------------- sort.hip
 struct SortScratch {

@@ -84,6 +84,8 @@ class Workload:
     lr_emb: float = 0.01
     adagrad_eps: float = 1e-8
     pooling: str = "sum"           # "sum" | "mean"
+    emb_optimizer: str = "rowwise_adagrad"   # | "adam"
+    adam_betas: Tuple[float, float] = (0.9, 0.999)
 
     @property
     def num_tables(self) -> int:

@@ -127,13 +127,15 @@ def make_pair(wl, batches, h0=None, rows=None, slots=1, dtype=np.float64, mlp_pa
     gpu = binding.ShadowSync(rows, wl.emb_dim, wl.bot_dims, wl.top_dims, wl.num_replicas,
                              max(b.dense.shape[0] for b in batches), max_ids, slots, wl.bf16,
                              wl.lr_dense, wl.lr_emb, wl.adagrad_eps, wl.seed, pooling=wl.pooling,
-                             mlp_path=mlp_path)
+                             mlp_path=mlp_path, emb_optimizer=wl.emb_optimizer,
+                             adam_betas=wl.adam_betas)
     for t in range(len(rows)):
         gpu.ss_write_rows(t, 0, h0[row_base[t]:row_base[t + 1]])
     gpu.ss_init_dense(w0)
     orc = oracle.OracleTrainer(wl.bot_dims, wl.top_dims, row_base, h0, w0, wl.num_replicas,
                                wl.lr_dense, wl.lr_emb, wl.adagrad_eps, dtype=dtype,
-                               bf16=wl.bf16, pooling=wl.pooling)
+                               bf16=wl.bf16, pooling=wl.pooling, emb_optimizer=wl.emb_optimizer,
+                               adam_betas=wl.adam_betas)
     return gpu, orc
 
 
@@ -171,6 +173,14 @@ def compare_state(gpu, orc, rtol, name, row_base):
         vals, acc = gpu.ss_read_rows(t, np.arange(n))
         close(vals, orc.h[row_base[t]:row_base[t + 1]], rtol, f"{name}: table {t}")
         # the accumulator is quadratic in the row gradient: twice its relative error
+        if orc.emb_optimizer == "adam":
+            assert np.array_equal(acc, orc.G[row_base[t]:row_base[t + 1]]), f"{name}: step counts {t}"
+            m, v = gpu.ss_read_adam_state(t, np.arange(n))
+            close(m, orc.M[row_base[t]:row_base[t + 1]], rtol, f"{name}: Adam m {t}")
+            # (the second moment is quadratic in the row gradient: twice its relative error)
+            close(v, orc.V[row_base[t]:row_base[t + 1]], 2 * rtol if rtol > FP32_RTOL else rtol,
+                  f"{name}: Adam v {t}")
+            continue
         close(acc, orc.G[row_base[t]:row_base[t + 1]], 2 * rtol if rtol > FP32_RTOL else rtol,
               f"{name}: adagrad state {t}")
 
@@ -185,6 +195,9 @@ def push_oracle_state(gpu, orc, row_base):
     for t in range(len(row_base) - 1):
         gpu.ss_write_rows(t, 0, orc.h[row_base[t]:row_base[t + 1]])
         gpu.ss_write_adagrad(t, 0, orc.G[row_base[t]:row_base[t + 1]])
+        if orc.emb_optimizer == "adam":
+            gpu.ss_write_adam_state(t, 0, orc.M[row_base[t]:row_base[t + 1]],
+                                    orc.V[row_base[t]:row_base[t + 1]])
 
 
 def push_oracle_state_sparse(gpu, orc, cp, row_base_c):

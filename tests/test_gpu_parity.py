@@ -188,6 +188,28 @@ def test_mean_pooling(bf16):
         H.compare_state(gpu, orc, H.FP32_RTOL, "mean pooling", wl.row_base)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_adam_on_the_tables(bf16):
+    """Adam as the table optimiser (Section 3.2 names it beside Adagrad): moments per element
+    and a step count per row kept beside the rows, rows updated only in the steps that touch
+    them; hot rows (Zipf 1.3) take the chunk, stitch and long-run passes.  Every step is checked
+    from a common state, in both precisions: m / (sqrt(v) + eps) turns the RELATIVE error of a
+    gradient element into an absolute error of the row, however small the element, so free-
+    running trajectories separate beyond any bound relative to the table's scale.  eps = 1e-4
+    (the gradients here are 1e-4 .. 1e-3) keeps a single step well conditioned."""
+    wl = synth.tiny().scaled(batch=160, rows=(5000, 9, 700), emb_dim=32, bag_lambda=7.0,
+                             bot_dims=(13, 48, 32), top_dims=(32 + 6, 64, 24, 1),
+                             num_replicas=2, algo="ma", alpha=0.5, sync_gap=2, zipf_s=1.3,
+                             bf16=bf16, emb_optimizer="adam", adam_betas=(0.9, 0.99),
+                             lr_emb=0.003, adagrad_eps=1e-4)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(10)]
+    gpu, orc = H.make_pair(wl, batches, h0=synth.full_tables_h0(wl))
+    H.run_lockstep(gpu, orc, batches, wl.sync_gap, wl.algo, wl.alpha,
+                   rtol=H.BF16_RTOL if bf16 else H.FP32_RTOL, resync_row_base=wl.row_base)
+    assert orc.G.max() >= 5                      # some row was updated in many steps
+
+
 def test_empty_bags_single_sample_and_hot_row():
     """Edge cases: empty bags, batch of one, one row owning a very long segment."""
     wl = synth.tiny().scaled(batch=64, rows=(50, 1000), emb_dim=16, bot_dims=(13, 16),

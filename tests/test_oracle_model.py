@@ -291,6 +291,57 @@ def test_duplicate_rows_get_one_update_with_summed_gradient():
     assert tr.last["seg_starts"].tolist() == [0, 3]
 
 
+def test_adam_first_step_closed_form_and_untouched_rows():
+    """First Adam step from zero state: m_hat = g and v_hat = g^2 exactly, so the row moves by
+    lr * g / (|g| + eps) -- about lr * sign(g) -- whatever the betas; rows that are not listed
+    keep their values, moments and step counts bit for bit."""
+    rng = np.random.default_rng(0)
+    h = rng.standard_normal((9, 4)); h0 = h.copy()
+    M, V, T = np.zeros_like(h), np.zeros_like(h), np.zeros(9)
+    rows = np.array([1, 4, 7])
+    g = rng.standard_normal((3, 4))
+    dlrm.adam_update(h, M, V, T, rows, g, 0.05, 1e-8, 0.9, 0.999)
+    np.testing.assert_allclose(h[rows], h0[rows] - 0.05 * g / (np.abs(g) + 1e-8), rtol=1e-12)
+    np.testing.assert_allclose(M[rows], 0.1 * g, rtol=1e-12)
+    np.testing.assert_allclose(V[rows], 0.001 * g * g, rtol=1e-12)
+    others = np.setdiff1d(np.arange(9), rows)
+    assert np.array_equal(h[others], h0[others]) and not M[others].any() and not V[others].any()
+    assert T.tolist() == [0, 1, 0, 0, 1, 0, 0, 1, 0]
+
+
+def test_adam_equals_torch_adam_when_every_row_is_touched_every_step():
+    """With all rows listed in every step the lazy per-row step count equals the global one and
+    the update is plain Adam: compared with torch.optim.Adam over 7 steps of random gradients."""
+    rng = np.random.default_rng(1)
+    h = rng.standard_normal((5, 3))
+    p = torch.tensor(h.copy(), requires_grad=True)
+    opt = torch.optim.Adam([p], lr=0.02, betas=(0.8, 0.95), eps=1e-6)
+    M, V, T = np.zeros_like(h), np.zeros_like(h), np.zeros(5)
+    for _ in range(7):
+        g = rng.standard_normal((5, 3))
+        dlrm.adam_update(h, M, V, T, np.arange(5), g, 0.02, 1e-6, 0.8, 0.95)
+        p.grad = torch.tensor(g.copy())
+        opt.step()
+    np.testing.assert_allclose(h, p.detach().numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_adam_is_lazy_per_row():
+    """A row touched in steps 1 and 3 only sees two updates with step counts 1 and 2 -- the same
+    as a one-row Adam run on those two gradients alone."""
+    rng = np.random.default_rng(2)
+    h = rng.standard_normal((3, 2)); ref = h[1:2].copy()
+    M, V, T = np.zeros_like(h), np.zeros_like(h), np.zeros(3)
+    Mr, Vr, Tr = np.zeros((1, 2)), np.zeros((1, 2)), np.zeros(1)
+    gs = [rng.standard_normal((1, 2)) for _ in range(3)]
+    dlrm.adam_update(h, M, V, T, np.array([1]), gs[0], 0.1, 1e-8, 0.9, 0.999)
+    dlrm.adam_update(h, M, V, T, np.array([0]), gs[1], 0.1, 1e-8, 0.9, 0.999)
+    dlrm.adam_update(h, M, V, T, np.array([1]), gs[2], 0.1, 1e-8, 0.9, 0.999)
+    for g in (gs[0], gs[2]):
+        dlrm.adam_update(ref, Mr, Vr, Tr, np.array([0]), g, 0.1, 1e-8, 0.9, 0.999)
+    np.testing.assert_allclose(h[1], ref[0], rtol=1e-14)
+    assert T.tolist() == [1, 2, 0]
+
+
 # ----------------------------------------------------------------------------- interaction
 def _golden_lines(name):
     with open(os.path.join(GOLDEN, name)) as fh:
