@@ -105,6 +105,12 @@ typedef struct {
   int32_t emb_optimizer;     /* ss_emb_optimizer; lr_emb and adagrad_eps serve both      */
   float adam_beta1;          /* SS_OPT_ADAM only (0 <= beta < 1)                         */
   float adam_beta2;
+  int32_t emb_row_shards;    /* 0 or 1: tables are not split.  S > 1 (Section 3.1, "Embedding
+                                PS": a table too large for one server is split by rows, each
+                                part pools what it owns, the trainer adds the partial results):
+                                every table is cut into S equal row ranges, the look-up pools
+                                per range and a second kernel adds the S partial vectors in
+                                range order                                              */
 } ss_config;
 
 /* One mini-batch.  All pointers are DEVICE pointers owned by the caller and must stay
@@ -118,6 +124,26 @@ typedef struct {
   const int32_t* indices;  /* dev [n], row within its table                             */
   const int32_t* offsets;  /* dev [T*B + 1]                                             */
 } ss_batch;
+
+/* Placement of the tables on embedding parameter servers (host only, no device work; Section
+ * 3.1, "Embedding PS": every table's look-up cost is profiled and the tables are bin-packed so
+ * that the servers carry similar costs; tables too large for one server are partitioned).
+ * Tables with more than max_rows_per_shard rows (> 0) are cut into ceil(rows / limit) equal row
+ * ranges whose cost is their share of the table's; the parts are packed by the
+ * longest-processing-time rule (decreasing cost, each to the least loaded server, ties to the
+ * lower index).  out_shards (host, capacity entries) receives the parts in (table, first row)
+ * order, *out_num_shards their number (also when capacity is too small: SS_ENOMEM),
+ * out_ps_cost (host [num_ps], may be NULL) the cost per server. */
+typedef struct {
+  int32_t table;
+  int64_t first_row;
+  int64_t rows;
+  double cost;
+  int32_t ps;
+} ss_shard;
+int ss_plan_placement(int32_t num_tables, const int64_t* rows, const double* cost, int32_t num_ps,
+                      int64_t max_rows_per_shard, ss_shard* out_shards, int32_t capacity,
+                      int32_t* out_num_shards, double* out_ps_cost);
 
 /* Device bytes ss_init needs for this configuration (0 on an invalid configuration). */
 size_t ss_workspace_bytes(const ss_config* cfg);
@@ -255,6 +281,8 @@ typedef enum {
   SS_DBG_NUM_UNIQUE = 8,   /* uint32 [1]         U                                          */
   SS_DBG_BAG_OF_POS = 9,   /* int32  [n]         b*T + t of each flat position              */
   SS_DBG_Z0 = 10,          /* float  [B, d]      output of the bottom MLP (after its ReLU)  */
+  SS_DBG_POOLED_PARTIALS = 11, /* float [S, B, T, d] partial pooling results per row shard
+                                  (sums, before any 1/length factor); emb_row_shards > 1   */
   SS_DBG_HIDDEN_ACT = 32   /* SS_DBG_HIDDEN_ACT + l: float [B, out_l], output of hidden layer l
                               (layers counted over the whole model, bottom first; not the
                               bottom output, not the logit) as the device stores it, i.e.

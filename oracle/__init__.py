@@ -14,7 +14,11 @@ names the passage of the paper it follows and which independent fact pins it
 Parity status of each part (what independent fact pins it):
   mlp / interaction / loss gradients : finite differences + torch autograd (pinned)
   embedding_bag_forward              : dense multiplicity-matrix product (pinned)
+  partial pooling over row shards    : multiplicity matrix restricted to each shard's
+                                       rows; partials add up to the unsharded result (pinned)
   embedding backward segment sums    : transposed multiplicity matrix (pinned)
+  table placement (LPT bin packing)  : brute-force optimum on small cases within the
+                                       4/3 - 1/(3m) bound; every shard placed once (pinned)
   stable sort order                  : Python's sorted() on (key, position) (pinned)
   row-wise Adagrad                   : closed form of the first step (pinned)
   Adam on table rows                 : first-step closed form, torch.optim.Adam when every
@@ -35,6 +39,7 @@ from .dlrm import (  # noqa: F401
     dlrm_forward,
     dlrm_backward,
     embedding_bag_forward,
+    embedding_bag_forward_sharded,
     bag_lengths,
     embedding_row_gradients,
     interaction_backward,

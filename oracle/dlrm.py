@@ -172,6 +172,33 @@ def embedding_bag_forward_fast(h, row_base, indices, offsets, B: int, pooling: s
     return e
 
 
+def embedding_bag_forward_sharded(h, row_base, indices, offsets, B: int, n_shards: int,
+                                  pooling: str = "sum"):
+    """Partial pooling (Section 3.1, "Embedding PS"): table t is split into n_shards equal row
+    ranges of ceil(rows_t / n_shards) rows; every range pools, in bag order, the rows of a bag
+    that it owns; the trainer adds the partial vectors in range order (and divides by the bag
+    length under mean pooling).  Returns (e (B, T, d), partials (n_shards, B, T, d))."""
+    assert pooling in ("sum", "mean")
+    T = len(row_base) - 1
+    d = h.shape[1]
+    parts = np.zeros((n_shards, B, T, d), dtype=h.dtype)
+    for t in range(T):
+        rows_t = int(row_base[t + 1] - row_base[t])
+        per = -(-rows_t // n_shards)
+        for b in range(B):
+            lo, hi = offsets[t * B + b], offsets[t * B + b + 1]
+            for j in range(lo, hi):
+                s = int(indices[j]) // per
+                parts[s, b, t, :] += h[row_base[t] + indices[j], :]
+    e = parts[0].copy()
+    for s in range(1, n_shards):
+        e += parts[s]
+    if pooling == "mean":
+        lens = np.maximum(bag_lengths(offsets, B, T), 1).reshape(B, T)
+        e = e / lens[:, :, None]
+    return e, parts
+
+
 def bag_lengths(offsets, B: int, T: int):
     """Length of the bag behind pooled vector b*T + t."""
     off = np.asarray(offsets, dtype=np.int64)
@@ -300,7 +327,7 @@ def bce_with_logits(logit, y):
 
 # --------------------------------------------------------------------------- whole model
 def dlrm_forward(layout: DenseLayout, w, h, row_base, x, indices, offsets, bf16=False,
-                 fast=True, pooling="sum"):
+                 fast=True, pooling="sum", row_shards=1):
     """Forward pass in the paper's order (Section 3.1 "Trainer").  Returns a dict of
     every intermediate the backward pass needs."""
     dtype = w.dtype
@@ -310,13 +337,18 @@ def dlrm_forward(layout: DenseLayout, w, h, row_base, x, indices, offsets, bf16=
     B = x.shape[0]
     acts_bot = mlp_forward(x.astype(dtype), bot, relu_last=True, q=q)
     z0 = acts_bot[-1]
-    bag = embedding_bag_forward_fast if fast else embedding_bag_forward
-    e = bag(h, row_base, indices, offsets, B, pooling)
+    e_parts = None
+    if row_shards > 1:
+        e, e_parts = embedding_bag_forward_sharded(h, row_base, indices, offsets, B, row_shards,
+                                                   pooling)
+    else:
+        bag = embedding_bag_forward_fast if fast else embedding_bag_forward
+        e = bag(h, row_base, indices, offsets, B, pooling)
     f = interaction_forward(z0, e)
     acts_top = mlp_forward(f, top, relu_last=False, q=q)
     logit = acts_top[-1][:, 0]
     return dict(acts_bot=acts_bot, z0=z0, e=e, f=f, acts_top=acts_top, logit=logit,
-                bot=bot, top=top, q=q)
+                bot=bot, top=top, q=q, e_parts=e_parts)
 
 
 def dlrm_backward(layout: DenseLayout, fw, y, gate_flips=None):

@@ -18,7 +18,7 @@ class OracleTrainer:
     def __init__(self, bot_dims, top_dims, row_base, h0, w0, num_replicas,
                  lr_dense=0.01, lr_emb=0.01, adagrad_eps=1e-8, dtype=np.float64,
                  bf16=False, pooling="sum", emb_optimizer="rowwise_adagrad",
-                 adam_betas=(0.9, 0.999)):
+                 adam_betas=(0.9, 0.999), emb_row_shards=1):
         self.layout = dlrm.DenseLayout(tuple(bot_dims), tuple(top_dims))
         self.row_base = np.asarray(row_base, dtype=np.int64)
         self.T = len(self.row_base) - 1
@@ -30,6 +30,7 @@ class OracleTrainer:
         self.bf16 = bf16
         assert pooling in ("sum", "mean")
         self.pooling = pooling
+        self.row_shards = max(1, int(emb_row_shards))
         assert emb_optimizer in ("rowwise_adagrad", "adam")
         self.emb_optimizer = emb_optimizer
         self.adam_betas = adam_betas
@@ -60,7 +61,7 @@ class OracleTrainer:
         L = self.layout
         w = self.W[replica]
         fw = dlrm.dlrm_forward(L, w, self.h, self.row_base, x, indices, offsets,
-                               bf16=self.bf16, pooling=self.pooling)
+                               bf16=self.bf16, pooling=self.pooling, row_shards=self.row_shards)
         loss, g, de = dlrm.dlrm_backward(L, fw, y.astype(self.dtype), gate_flips)
         keys = dlrm.global_rows(self.row_base, indices, offsets, B)
         bag = dlrm.bag_of_position(offsets, B, self.T)
@@ -70,7 +71,7 @@ class OracleTrainer:
         rows, g_rows, sk, perm, heads = dlrm.embedding_row_gradients(
             de.reshape(B * self.T, self.d), keys, bag, scale)
         self.last = dict(e=fw["e"], f=fw["f"], logit=fw["logit"], z0=fw["z0"], g=g,
-                         acts_bot=fw["acts_bot"], acts_top=fw["acts_top"],
+                         acts_bot=fw["acts_bot"], acts_top=fw["acts_top"], e_parts=fw["e_parts"],
                          de=de, sorted_keys=sk, sorted_pos=perm, seg_starts=heads,
                          rows=rows, g_rows=g_rows, bag_of_pos=bag)
         if update:
@@ -89,7 +90,8 @@ class OracleTrainer:
 
     def eval_logloss(self, replica, x, y, indices, offsets):
         fw = dlrm.dlrm_forward(self.layout, self.W[replica], self.h, self.row_base, x,
-                               indices, offsets, bf16=self.bf16, pooling=self.pooling)
+                               indices, offsets, bf16=self.bf16, pooling=self.pooling,
+                               row_shards=self.row_shards)
         loss = dlrm.bce_with_logits(fw["logit"], y.astype(self.dtype))[0]
         self.metrics["eval"] += (loss * x.shape[0], float(np.sum(y)), x.shape[0])
         return loss

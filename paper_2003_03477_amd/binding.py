@@ -30,7 +30,7 @@ _DBG_DTYPE = {DBG_POOLED: np.float32, DBG_INTERACT: np.float32, DBG_LOGITS: np.f
               DBG_DENSE_GRAD: np.float32, DBG_POOLED_GRAD: np.float32,
               DBG_SORTED_ROWS: np.uint32, DBG_SORTED_POS: np.uint32,
               DBG_SEG_STARTS: np.uint32, DBG_NUM_UNIQUE: np.uint32, DBG_BAG_OF_POS: np.int32}
-DBG_Z0, DBG_HIDDEN_ACT = 10, 32
+DBG_Z0, DBG_POOLED_PARTIALS, DBG_HIDDEN_ACT = 10, 11, 32
 
 (K_NONE, K_GATHER, K_SORT, K_ROW_UPDATE_CHUNK, K_SYNC, K_MLP, K_INTERACT_FWD, K_INTERACT_BWD,
  K_ROW_UPDATE, K_MLP_FWD, K_MLP_DGRAD, K_MLP_WGRAD) = range(12)
@@ -42,6 +42,7 @@ EXPORTS = [
     "ss_write_dense", "ss_read_rows", "ss_read_debug", "ss_get_counters", "ss_profile_arm",
     "ss_profile_sample", "ss_profile_read", "ss_shadow_pace", "ss_metrics_read",
     "ss_metrics_reset", "ss_eval_step_static", "ss_write_adam_state", "ss_read_adam_state",
+    "ss_plan_placement",
 ]
 
 
@@ -55,7 +56,13 @@ class ss_config(C.Structure):
                 ("mlp_prec", C.c_int32), ("lr_dense", C.c_float), ("lr_emb", C.c_float),
                 ("adagrad_eps", C.c_float), ("seed", C.c_uint64), ("pooling", C.c_int32),
                 ("mlp_path", C.c_int32), ("emb_optimizer", C.c_int32),
-                ("adam_beta1", C.c_float), ("adam_beta2", C.c_float)]
+                ("adam_beta1", C.c_float), ("adam_beta2", C.c_float),
+                ("emb_row_shards", C.c_int32)]
+
+
+class ss_shard(C.Structure):
+    _fields_ = [("table", C.c_int32), ("first_row", C.c_int64), ("rows", C.c_int64),
+                ("cost", C.c_double), ("ps", C.c_int32)]
 
 
 class ss_batch(C.Structure):
@@ -89,6 +96,7 @@ def load() -> C.CDLL:
     lib.ss_write_adagrad.argtypes = [vp, i32, i64, i64, vp]
     lib.ss_write_adam_state.argtypes = [vp, i32, i64, i64, vp, vp]
     lib.ss_read_adam_state.argtypes = [vp, i32, vp, i64, vp, vp]
+    lib.ss_plan_placement.argtypes = [i32, vp, vp, i32, i64, vp, i32, vp, vp]
     lib.ss_init_dense.argtypes = [vp, vp]
     lib.ss_num_params.restype = i64
     lib.ss_num_params.argtypes = [vp]
@@ -168,7 +176,8 @@ class ShadowSync:
                  num_worker_slots: int = 1, bf16: bool = False, lr_dense: float = 0.01,
                  lr_emb: float = 0.01, adagrad_eps: float = 1e-8, seed: int = 0,
                  device: str = "cuda:0", pooling: str = "sum", mlp_path: str = "auto",
-                 emb_optimizer: str = "rowwise_adagrad", adam_betas=(0.9, 0.999)):
+                 emb_optimizer: str = "rowwise_adagrad", adam_betas=(0.9, 0.999),
+                 emb_row_shards: int = 1):
         import torch
         self.lib = load()
         self.torch = torch
@@ -181,7 +190,7 @@ class ShadowSync:
                              max_ids, num_worker_slots, SS_BF16 if bf16 else SS_FP32,
                              lr_dense, lr_emb, adagrad_eps, seed, POOLING[pooling],
                              MLP_PATHS[mlp_path], EMB_OPTIMIZERS[emb_optimizer],
-                             adam_betas[0], adam_betas[1])
+                             adam_betas[0], adam_betas[1], emb_row_shards)
         self.rows, self.emb_dim, self.K = list(rows), emb_dim, num_replicas
         self.T = len(rows)
         self.ctx = C.c_void_p()
@@ -378,6 +387,23 @@ def ss_sync_round(algo, K: int, P: int, stride: int, replicas, w_ps=None, w_glob
         raise ShadowSyncError(f"ss_sync_round failed ({rc})")
 
 
+def ss_plan_placement(rows, cost, num_ps: int, max_rows_per_shard: int = 0):
+    """Host-side placement plan: ([(table, first_row, rows, cost, ps)], cost per PS)."""
+    lib = load()
+    r = np.ascontiguousarray(rows, dtype=np.int64)
+    c = np.ascontiguousarray(cost, dtype=np.float64)
+    n = C.c_int32(0)
+    load_out = np.zeros(num_ps, dtype=np.float64)
+    lib.ss_plan_placement(len(r), _np_ptr(r), _np_ptr(c), num_ps, max_rows_per_shard, None, 0,
+                          C.byref(n), None)
+    buf = (ss_shard * max(n.value, 1))()
+    rc = lib.ss_plan_placement(len(r), _np_ptr(r), _np_ptr(c), num_ps, max_rows_per_shard, buf,
+                               n.value, C.byref(n), _np_ptr(load_out))
+    if rc != 0:
+        raise ShadowSyncError(f"ss_plan_placement failed ({rc})")
+    return [(s.table, s.first_row, s.rows, s.cost, s.ps) for s in buf[:n.value]], load_out.tolist()
+
+
 def from_workload(wl, rows=None, num_worker_slots: int = 1, max_ids: Optional[int] = None,
                   device="cuda:0", mlp_path: str = "auto") -> ShadowSync:
     """Context sized for a synth.Workload (rows may be overridden by a compacted problem)."""
@@ -389,4 +415,4 @@ def from_workload(wl, rows=None, num_worker_slots: int = 1, max_ids: Optional[in
                       max_ids, num_worker_slots, wl.bf16, wl.lr_dense, wl.lr_emb,
                       wl.adagrad_eps, wl.seed, device, wl.pooling, mlp_path,
                       getattr(wl, "emb_optimizer", "rowwise_adagrad"),
-                      getattr(wl, "adam_betas", (0.9, 0.999)))
+                      getattr(wl, "adam_betas", (0.9, 0.999)), getattr(wl, "emb_row_shards", 1))

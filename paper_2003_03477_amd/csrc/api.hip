@@ -40,6 +40,7 @@ struct Slot {
   uint16_t* act_bf16[MAX_LAYERS];  // bf16 path: output of hidden layers
   float* z0;                       // output of the last bottom layer (fp32 in both paths)
   float* e;                        // [B,T,d]
+  float* e_part = nullptr;         // [shards][B,T,d] partial pooling results (row-sharded tables)
   float* inv_len;                  // [B,T] 1 / bag length (mean pooling)
   float* f;                        // [B,ldf]
   uint16_t* f_bf16;                // [B,ldf16]
@@ -100,6 +101,7 @@ struct ss_ctx {
   // configuration
   int T, d, num_dense, K, max_batch, num_slots, prec;
   bool pool_mean = false;          // mean instead of sum pooling
+  int row_shards = 1;              // row shards per table (partial pooling); 1 = not split
   int64_t max_ids;
   std::vector<int64_t> rows;
   std::vector<Layer> layers;
@@ -232,6 +234,7 @@ static int validate(const ss_config* c, std::string& why) {
   if (c->mlp_prec != SS_FP32 && c->mlp_prec != SS_BF16) BAD("bad mlp_prec");
   if (c->pooling != SS_POOL_SUM && c->pooling != SS_POOL_MEAN) BAD("bad pooling mode");
   if (c->mlp_path != SS_MLP_AUTO && c->mlp_path != SS_MLP_LAYERWISE) BAD("bad mlp_path");
+  if (c->emb_row_shards < 0 || c->emb_row_shards > 64) BAD("emb_row_shards must be 0..64");
   if (c->emb_optimizer != SS_OPT_ROWWISE_ADAGRAD && c->emb_optimizer != SS_OPT_ADAM)
     BAD("bad emb_optimizer");
   if (c->emb_optimizer == SS_OPT_ADAM &&
@@ -260,6 +263,7 @@ static void carve_slot(const ss_ctx* x, Carver& cv, Slot& s, int B, int64_t n, b
   }
   s.z0 = cv.take<float>((size_t)B * x->d);
   s.e = cv.take<float>((size_t)B * x->T * x->d);
+  s.e_part = x->row_shards > 1 ? cv.take<float>((size_t)x->row_shards * B * x->T * x->d) : nullptr;
   s.inv_len = cv.take<float>((size_t)B * x->T);
   s.f = cv.take<float>((size_t)B * x->ldf);
   s.f_bf16 = (x->prec == SS_BF16) ? cv.take<uint16_t>((size_t)B * x->ldf16) : nullptr;
@@ -342,6 +346,7 @@ static ss_ctx* make_ctx(const ss_config* c) {
   x->K = c->num_replicas; x->max_batch = c->max_batch; x->max_ids = c->max_ids;
   x->num_slots = c->num_worker_slots; x->prec = c->mlp_prec;
   x->pool_mean = (c->pooling == SS_POOL_MEAN);
+  x->row_shards = c->emb_row_shards < 1 ? 1 : c->emb_row_shards;
   x->lr_dense = c->lr_dense; x->lr_emb = c->lr_emb; x->eps = c->adagrad_eps; x->seed = c->seed;
   x->adam = (c->emb_optimizer == SS_OPT_ADAM);
   x->beta1 = c->adam_beta1; x->beta2 = c->adam_beta2;
@@ -809,7 +814,8 @@ static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
   {
     ProfScope ps(x, SS_K_GATHER, st);
     launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e,
-                             train ? s.keys : nullptr, s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, st);
+                             train ? s.keys : nullptr, s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, x->row_shards,
+                             s.e_part, st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -924,7 +930,8 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
   {
     ProfScope ps(x, SS_K_GATHER, st);
     launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e,
-                             train ? s.keys : nullptr, s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, st);
+                             train ? s.keys : nullptr, s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, x->row_shards,
+                             s.e_part, st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -1034,7 +1041,8 @@ static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, floa
   {
     ProfScope ps(x, SS_K_GATHER, st);
     launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e,
-                             train ? s.keys : nullptr, s.bag_of_pos, fused_last(x) ? loss : nullptr, x->pool_mean ? s.inv_len : nullptr, st);
+                             train ? s.keys : nullptr, s.bag_of_pos, fused_last(x) ? loss : nullptr,
+                             x->pool_mean ? s.inv_len : nullptr, x->row_shards, s.e_part, st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -1404,6 +1412,9 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
   }
   switch (item) {
     case SS_DBG_Z0: src = s.z0; size = B * ctx->d * 4; break;
+    case SS_DBG_POOLED_PARTIALS:
+      if (ctx->row_shards <= 1) return fail(ctx, SS_ESTATE, "the tables are not row-sharded");
+      src = s.e_part; size = (size_t)ctx->row_shards * B * ctx->T * ctx->d * 4; break;
     case SS_DBG_POOLED: src = s.e; size = B * ctx->T * ctx->d * 4; break;
     case SS_DBG_INTERACT: src = s.f; rows = B; width = (size_t)ctx->F * 4; pitch_src = (size_t)ctx->ldf * 4; size = rows * width; break;
     case SS_DBG_LOGITS: src = s.logits; size = B * 4; break;

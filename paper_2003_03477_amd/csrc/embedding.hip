@@ -11,44 +11,66 @@ namespace ss {
 // index list is read once, coalesced, 64 ids at a time, and handed between lanes with
 // cross-lane permutes; every lane owns fixed columns, partial sums of the 64/LPR row slots
 // are folded with xor-shuffles at the end.
-template <int LPR>
+// With row shards (Section 3.1, "Embedding PS": a table too large for one parameter server is
+// split by rows, every shard pools the rows it owns and the trainer adds the partial results)
+// blockIdx.y is the shard: the wave walks the whole bag but only fetches and adds the rows
+// inside its shard's range, and writes the bag's PARTIAL sum to its shard's slice of `e`
+// ([shard][B*T][d]); embedding_combine_kernel adds the slices in shard order.
+template <int LPR, bool SHARDED>
 __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
     const float* __restrict__ h, const int32_t* __restrict__ indices,
     const int32_t* __restrict__ offsets, TableMeta meta, int B, int T, float* __restrict__ e,
     uint32_t* __restrict__ keys, int32_t* __restrict__ bag_of_pos,
-    float* __restrict__ zero_scalar, float* __restrict__ inv_len) {
+    float* __restrict__ zero_scalar, float* __restrict__ inv_len, int n_shards) {
   constexpr int D = LPR * 4;
   constexpr int RPW = SS_WAVE / LPR;  // rows per wave-wide load
+  const int shard = SHARDED ? blockIdx.y : 0;
   // the step's loss accumulator is cleared here, ahead of the kernel that adds into it
-  if (zero_scalar && blockIdx.x == 0 && threadIdx.x == 0) *zero_scalar = 0.f;
+  if (zero_scalar && blockIdx.x == 0 && shard == 0 && threadIdx.x == 0) *zero_scalar = 0.f;
   const int lane = threadIdx.x & 63;
   const int bag = (int)((blockIdx.x * (uint64_t)blockDim.x + threadIdx.x) >> 6);  // t*B + b
   if (bag >= T * B) return;
   const int t = bag / B, b = bag - t * B;
   const int lo = offsets[bag], hi = offsets[bag + 1];
   const uint32_t base = meta.row_base[t];
+  // this shard's rows of table t: [s_lo, s_hi) (everything when the tables are not split)
+  uint32_t s_lo = 0, s_hi = 0xFFFFFFFFu;
+  if (SHARDED) {
+    const uint32_t rows_t = meta.row_base[t + 1] - base;
+    const uint32_t per = (rows_t + n_shards - 1) / n_shards;
+    s_lo = (uint32_t)shard * per;
+    s_hi = s_lo + per;
+    e += (size_t)shard * B * T * D;
+  }
   const int sub = lane / LPR, c4 = lane % LPR;
   const int ebag = b * T + t;
   float4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
   for (int j0 = lo; j0 < hi; j0 += SS_WAVE) {
     const int j = j0 + lane;
-    uint32_t grow = 0;
+    uint32_t grow = 0, lrow = 0xFFFFFFFFu;
     if (j < hi) {
-      grow = base + (uint32_t)indices[j];
-      if (keys) {   // (forward-only evaluation records nothing for a backward pass)
+      lrow = (uint32_t)indices[j];
+      grow = base + lrow;
+      if (keys && shard == 0) {   // (forward-only evaluation records nothing for a backward pass)
         keys[j] = grow;
         bag_of_pos[j] = ebag;
       }
     }
+    const bool mine = !SHARDED || (lrow >= s_lo && lrow < s_hi);
     const int cnt = min(SS_WAVE, hi - j0);
     // trip count is wave-uniform so every lane takes part in every permute
     for (int it = 0; it < cnt; it += 2 * RPW) {
       const int ja = it + sub, jb = it + RPW + sub;
       const uint32_t ra = (uint32_t)__shfl((int)grow, ja & 63);
       const uint32_t rb = (uint32_t)__shfl((int)grow, jb & 63);
+      bool ma = true, mb = true;
+      if (SHARDED) {
+        ma = __shfl((int)mine, ja & 63) != 0;
+        mb = __shfl((int)mine, jb & 63) != 0;
+      }
       float4 va = {0.f, 0.f, 0.f, 0.f}, vb = {0.f, 0.f, 0.f, 0.f};
-      if (ja < cnt) va = *(const float4*)(h + (size_t)ra * D + c4 * 4);
-      if (jb < cnt) vb = *(const float4*)(h + (size_t)rb * D + c4 * 4);
+      if (ja < cnt && ma) va = *(const float4*)(h + (size_t)ra * D + c4 * 4);
+      if (jb < cnt && mb) vb = *(const float4*)(h + (size_t)rb * D + c4 * 4);
       acc0.x += va.x; acc0.y += va.y; acc0.z += va.z; acc0.w += va.w;
       acc1.x += vb.x; acc1.y += vb.y; acc1.z += vb.z; acc1.w += vb.w;
     }
@@ -63,24 +85,54 @@ __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
   }
   if (inv_len) {
     // mean pooling: the sum over the bag divided by its length; 1/length is kept per pooled
-    // vector because every member's gradient carries the same factor
+    // vector because every member's gradient carries the same factor.  With row shards the
+    // partial sums stay sums; the combining kernel applies the factor.
     const float sc = (hi > lo) ? 1.0f / (float)(hi - lo) : 0.f;
-    acc.x *= sc; acc.y *= sc; acc.z *= sc; acc.w *= sc;
-    if (lane == 0) inv_len[ebag] = sc;
+    if (!SHARDED) { acc.x *= sc; acc.y *= sc; acc.z *= sc; acc.w *= sc; }
+    if (lane == 0 && shard == 0) inv_len[ebag] = sc;
   }
   if (sub == 0) *(float4*)(e + (size_t)ebag * D + c4 * 4) = acc;
+}
+
+// Trainer side of partial pooling: e[v] = (sum over the shards, ascending, of part[s][v]) (times
+// 1 / bag length under mean pooling).  One thread per float4.
+__global__ __launch_bounds__(256) void embedding_combine_kernel(const float* __restrict__ part,
+                                                                int n_shards, int64_t n_vec4,
+                                                                int d4, const float* __restrict__ inv_len,
+                                                                float* __restrict__ e) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_vec4) return;
+  float4 acc = ((const float4*)part)[i];
+  for (int s = 1; s < n_shards; ++s) {
+    const float4 v = ((const float4*)part)[(int64_t)s * n_vec4 + i];
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  if (inv_len) {
+    const float sc = inv_len[i / d4];
+    acc.x *= sc; acc.y *= sc; acc.z *= sc; acc.w *= sc;
+  }
+  ((float4*)e)[i] = acc;
 }
 
 void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int32_t* offsets,
                               const TableMeta& meta, int B, int T, int d, float* e,
                               uint32_t* keys, int32_t* bag_of_pos, float* zero_scalar,
-                              float* inv_len, hipStream_t s) {
+                              float* inv_len, int n_shards, float* e_part, hipStream_t s) {
   const int64_t bags = (int64_t)B * T;
   if (bags == 0) return;
-  dim3 grid((unsigned)ceil_div(bags, 4)), block(256);
-#define L(LPR)                                                                               \
-  hipLaunchKernelGGL((embedding_bag_fwd_kernel<LPR>), grid, block, 0, s, h, indices, offsets, \
-                     meta, B, T, e, keys, bag_of_pos, zero_scalar, inv_len)
+  const bool split = n_shards > 1;
+  dim3 grid((unsigned)ceil_div(bags, 4), split ? n_shards : 1), block(256);
+  float* out = split ? e_part : e;
+#define L(LPR)                                                                                  \
+  do {                                                                                          \
+    if (split)                                                                                  \
+      hipLaunchKernelGGL((embedding_bag_fwd_kernel<LPR, true>), grid, block, 0, s, h, indices,  \
+                         offsets, meta, B, T, out, keys, bag_of_pos, zero_scalar, inv_len,      \
+                         n_shards);                                                             \
+    else                                                                                        \
+      hipLaunchKernelGGL((embedding_bag_fwd_kernel<LPR, false>), grid, block, 0, s, h, indices, \
+                         offsets, meta, B, T, out, keys, bag_of_pos, zero_scalar, inv_len, 1);  \
+  } while (0)
   switch (d) {
     case 16: L(4); break;
     case 32: L(8); break;
@@ -88,6 +140,11 @@ void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int3
     default: L(32); break;  // 128
   }
 #undef L
+  if (split) {
+    const int64_t n_vec4 = bags * (d / 4);
+    hipLaunchKernelGGL(embedding_combine_kernel, dim3((unsigned)ceil_div(n_vec4, 256)), dim3(256), 0,
+                       s, e_part, n_shards, n_vec4, d / 4, inv_len, e);
+  }
 }
 
 // ------------------------------------------------------------------------------------------

@@ -25,10 +25,13 @@ void launch_fill_u32(uint32_t* p, uint64_t n, uint32_t v, hipStream_t s);
 // Sum-pooled gather: e[b,t,:] = sum_j h[row_base[t] + indices[j], :].  Also records, for the
 // backward pass, the sort key (global row) and the pooled-vector index b*T+t of every flat
 // position.
+// n_shards > 1: every table is split into n_shards equal row ranges, each range pools the rows
+// it owns into e_part[shard][b*T+t][d] and a second launch adds the partial results in shard
+// order into e (partial pooling).
 void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int32_t* offsets,
                               const TableMeta& meta, int B, int T, int d, float* e,
                               uint32_t* keys, int32_t* bag_of_pos, float* zero_scalar,
-                              float* inv_len, hipStream_t s);
+                              float* inv_len, int n_shards, float* e_part, hipStream_t s);
 
 struct SegScratch {
   uint32_t* block_counts;  // [seg_blocks]

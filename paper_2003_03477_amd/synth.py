@@ -86,6 +86,7 @@ class Workload:
     pooling: str = "sum"           # "sum" | "mean"
     emb_optimizer: str = "rowwise_adagrad"   # | "adam"
     adam_betas: Tuple[float, float] = (0.9, 0.999)
+    emb_row_shards: int = 1        # > 1: every table split into that many row ranges
 
     @property
     def num_tables(self) -> int:

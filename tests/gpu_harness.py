@@ -128,14 +128,14 @@ def make_pair(wl, batches, h0=None, rows=None, slots=1, dtype=np.float64, mlp_pa
                              max(b.dense.shape[0] for b in batches), max_ids, slots, wl.bf16,
                              wl.lr_dense, wl.lr_emb, wl.adagrad_eps, wl.seed, pooling=wl.pooling,
                              mlp_path=mlp_path, emb_optimizer=wl.emb_optimizer,
-                             adam_betas=wl.adam_betas)
+                             adam_betas=wl.adam_betas, emb_row_shards=wl.emb_row_shards)
     for t in range(len(rows)):
         gpu.ss_write_rows(t, 0, h0[row_base[t]:row_base[t + 1]])
     gpu.ss_init_dense(w0)
     orc = oracle.OracleTrainer(wl.bot_dims, wl.top_dims, row_base, h0, w0, wl.num_replicas,
                                wl.lr_dense, wl.lr_emb, wl.adagrad_eps, dtype=dtype,
                                bf16=wl.bf16, pooling=wl.pooling, emb_optimizer=wl.emb_optimizer,
-                               adam_betas=wl.adam_betas)
+                               adam_betas=wl.adam_betas, emb_row_shards=wl.emb_row_shards)
     return gpu, orc
 
 
@@ -153,6 +153,10 @@ def compare_step(gpu, orc, slot, rtol, step_name, tables_exact=False):
     assert int(gpu.ss_read_debug(slot, binding.DBG_NUM_UNIQUE)[0]) == len(last["seg_starts"])
     close(gpu.ss_read_debug(slot, binding.DBG_POOLED), last["e"],
           FP32_RTOL if (tables_exact or rtol <= FP32_RTOL) else rtol, f"{step_name}: pooled e")
+    if last.get("e_parts") is not None:
+        close(gpu.ss_read_debug(slot, binding.DBG_POOLED_PARTIALS), last["e_parts"],
+              FP32_RTOL if (tables_exact or rtol <= FP32_RTOL) else rtol,
+              f"{step_name}: partial pooling results per row shard")
     close(gpu.ss_read_debug(slot, binding.DBG_INTERACT), last["f"], rtol, f"{step_name}: interaction f")
     close(gpu.ss_read_debug(slot, binding.DBG_LOGITS), last["logit"], rtol, f"{step_name}: logits")
     close_dense(gpu.ss_read_debug(slot, binding.DBG_DENSE_GRAD), last["g"], rtol,

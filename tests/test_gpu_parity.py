@@ -210,6 +210,23 @@ def test_adam_on_the_tables(bf16):
     assert orc.G.max() >= 5                      # some row was updated in many steps
 
 
+@pytest.mark.parametrize("pooling,d", [("sum", 64), ("mean", 16)])
+def test_partial_pooling_over_row_shards(pooling, d):
+    """Tables split into three row ranges (Section 3.1, "Embedding PS"): every range pools the
+    rows it owns, the partial vectors are compared one by one with the oracle's, and their sum
+    feeds the rest of the step as usual."""
+    T = 3
+    wl = synth.tiny().scaled(batch=120, rows=(4001, 5, 700), emb_dim=d, bag_lambda=6.0,
+                             bot_dims=(13, 32, d), top_dims=(d + T * (T + 1) // 2, 24, 1),
+                             num_replicas=2, algo="ma", alpha=0.5, sync_gap=2, zipf_s=1.2,
+                             pooling=pooling, emb_row_shards=3)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(6)]
+    gpu, orc = H.make_pair(wl, batches, h0=synth.full_tables_h0(wl))
+    H.run_lockstep(gpu, orc, batches, wl.sync_gap, wl.algo, wl.alpha)
+    H.compare_state(gpu, orc, H.FP32_RTOL, "partial pooling", wl.row_base)
+
+
 def test_empty_bags_single_sample_and_hot_row():
     """Edge cases: empty bags, batch of one, one row owning a very long segment."""
     wl = synth.tiny().scaled(batch=64, rows=(50, 1000), emb_dim=16, bot_dims=(13, 16),

@@ -291,6 +291,30 @@ def test_duplicate_rows_get_one_update_with_summed_gradient():
     assert tr.last["seg_starts"].tolist() == [0, 3]
 
 
+@pytest.mark.parametrize("pooling", ["sum", "mean"])
+def test_partial_pooling_over_row_shards(pooling):
+    """Each shard's partial vector is the multiplicity matrix restricted to the rows the shard
+    owns times those rows; the partials add up to the unsharded pooling (then divided by the bag
+    length under mean pooling)."""
+    rng = np.random.default_rng(9)
+    p = random_problem(rng, B=5, T=3, d=4, rows=(10, 3, 7), bot=(3, 5, 4), top_hidden=(6,),
+                       max_len=4, allow_empty=True)
+    S = 3
+    e, parts = dlrm.embedding_bag_forward_sharded(p["h"], p["row_base"], p["indices"], p["offsets"],
+                                                  p["B"], S, pooling)
+    Cm = _multiplicity(p)
+    for s in range(S):
+        own = np.zeros(p["row_base"][-1], dtype=bool)
+        for t in range(p["T"]):
+            rows_t = p["row_base"][t + 1] - p["row_base"][t]
+            per = -(-rows_t // S)
+            own[p["row_base"][t] + s * per: p["row_base"][t] + min(rows_t, (s + 1) * per)] = True
+        want = (Cm[:, own] @ p["h"][own]).reshape(p["B"], p["T"], p["d"])
+        np.testing.assert_allclose(parts[s], want, rtol=1e-12, atol=1e-14)
+    ref = dlrm.embedding_bag_forward(p["h"], p["row_base"], p["indices"], p["offsets"], p["B"], pooling)
+    np.testing.assert_allclose(e, ref, rtol=1e-12, atol=1e-14)
+
+
 def test_adam_first_step_closed_form_and_untouched_rows():
     """First Adam step from zero state: m_hat = g and v_hat = g^2 exactly, so the row moves by
     lr * g / (|g| + eps) -- about lr * sign(g) -- whatever the betas; rows that are not listed
