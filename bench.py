@@ -70,7 +70,7 @@ def parse():
                     help="foreground variant: every k iterations a worker syncs on ITS OWN "
                          "stream (FR-EASGD-k), or all workers stop for a round (ma / bmuf)")
     ap.add_argument("--foreground-rule", default="easgd", choices=["easgd", "ma", "bmuf"])
-    ap.add_argument("--sweep", default="none", choices=["none", "widths", "gap"])
+    ap.add_argument("--sweep", default="none", choices=["none", "widths", "gap", "foreground"])
     ap.add_argument("--no-shadow-off", action="store_true", help="skip the shadow-off region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sync-isolation", action="store_true")
@@ -529,6 +529,11 @@ def main():
     if args.shadow_period_us < 0:
         args.shadow_period_us = 1000 if wl.name == "large" else 0
     n_batches = max(args.batches, NS)
+    if args.sweep != "none":
+        # sweeps compare the loss reached, so no stream may see a batch twice: enough distinct
+        # batches for the widest configuration (16 workers on each replica, or 8 replicas x 4)
+        widest = {"widths": 16 * K, "gap": 32, "foreground": NS}[args.sweep]
+        n_batches = max(n_batches, widest * (args.warmup + args.steps))
     n_batches = (n_batches + NS - 1) // NS * NS
     # inputs first: batch generation forks worker processes, which must precede any GPU use
     t_gen = time.perf_counter()
@@ -605,6 +610,26 @@ def main():
         out["sync_gap_table"] = {"what": "average sync gap (Section 4.2: trainer iterations per "
                                          "sync) against the number of replicas, shadow loop back "
                                          "to back and paced", "rows": table}
+    if args.sweep == "foreground":
+        table = []
+        variants = [("shadow", 0, "easgd"), ("no sync", 0, "easgd"), ("FR-EASGD", 1, "easgd"),
+                    ("FR-EASGD", 5, "easgd"), ("FR-EASGD", 30, "easgd"), ("FR-MA", 5, "ma"),
+                    ("FR-MA", 1, "ma"), ("FR-BMUF", 5, "bmuf")]
+        for name, k, rule in variants:
+            args.foreground, args.foreground_rule = k, rule
+            m = "off" if name == "no sync" else mode
+            r = run_workload(args, wl, workers, m, args.steps, args.warmup, host_batches,
+                             events=False, shadow_off=False)
+            table.append({"variant": name if not k else f"{name}-{k}", "examples_per_s": r["value"],
+                          "shadow_rounds": r["shadow_rounds"], "avg_sync_gap": r["avg_sync_gap"],
+                          "last_window_logloss": r["last_window_logloss"],
+                          "train_ne": r["train_ne"]["ne"]})
+        args.foreground = 0
+        out["foreground_table"] = {
+            "what": "background (shadow) synchronisation against the foreground variants of "
+                    "Section 4 (FR-EASGD-k: every worker exchanges with the centre copy on its own "
+                    "stream every k iterations; FR-MA / FR-BMUF: all workers stop for one averaging "
+                    "round every k iterations) and against no synchronisation", "rows": table}
     if secondary:
         r = run_workload(args, mid_wl, mid_workers, "paced", args.steps, args.warmup, mid_batches,
                          events=not args.no_kernel_events, shadow_off=not args.no_shadow_off)
