@@ -71,6 +71,8 @@ def parse():
                          "stream (FR-EASGD-k), or all workers stop for a round (ma / bmuf)")
     ap.add_argument("--foreground-rule", default="easgd", choices=["easgd", "ma", "bmuf"])
     ap.add_argument("--sweep", default="none", choices=["none", "widths", "gap", "foreground"])
+    ap.add_argument("--mlp-path", default="auto", choices=["auto", "layerwise"],
+                    help="bf16 MLP kernels: auto = fused per-sample-tile kernels for widths <= 512")
     ap.add_argument("--no-shadow-off", action="store_true", help="skip the shadow-off region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sync-isolation", action="store_true")
@@ -156,7 +158,7 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
     NS = len(replica_of)
     assert len(host_batches) >= NS
     max_ids = max(int(b.offsets[-1]) for b in host_batches) + 4096
-    gpu = binding.from_workload(wl, num_worker_slots=NS, max_ids=max_ids)
+    gpu = binding.from_workload(wl, num_worker_slots=NS, max_ids=max_ids, mlp_path=args.mlp_path)
     gpu.ss_init_tables_hash()
     gpu.ss_init_dense(synth.dense_w0(wl))
     dev_batches = [binding.upload_batch(b) for b in host_batches]

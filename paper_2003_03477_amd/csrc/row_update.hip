@@ -11,7 +11,8 @@
 // Input: the (row, position) pairs sorted by row, as `sorted_keys` and the pooled-vector id
 // `sorted_bag` of every sorted entry.  With Zipf-distributed ids the run lengths range from 1
 // to thousands, so work is split by POSITION, not by row: a group of LPR = d/4 lanes owns a
-// chunk of C = LPR consecutive sorted entries, whatever runs they belong to.
+// chunk of C = S * LPR consecutive sorted entries (S = 1, 2 or 4 slices of LPR, one entry per
+// lane and slice, by problem size), whatever runs they belong to.
 //   pass 1 (chunk kernel): walk the chunk; a run that begins and ends inside the chunk is
 //     finished on the spot (gradient rows and table rows of a sub-block of 8 entries are all
 //     in flight together).  A run cut by the chunk's edges leaves a partial sum: slot 0 for
@@ -26,6 +27,13 @@
 #include "ss_internal.h"
 
 namespace ss {
+
+// A chunk is CHUNK_SLICES wave-slices of LPR entries: short enough for tens of thousands of
+// chunks per step, long enough that few runs are cut by a chunk's edges (with Zipf-distributed
+// ids almost every second pair of neighbours in the sorted order shares its row).
+// Slices per chunk by problem size: long chunks pay off once there are enough of them to keep
+// every CU busy (sized for the shortest chunk, which needs the most scratch).
+static int chunk_slices(uint32_t n) { return n >= (1u << 21) ? 4 : (n >= (1u << 18) ? 2 : 1); }
 
 int64_t row_update_chunks(int64_t max_ids, int d) {
   const int C = d / 4;
@@ -66,7 +74,7 @@ __device__ __forceinline__ void apply_update(float4 g, float4 hv, float Gv, uint
   if (c4 == 0) o.G[row] = Gn;
 }
 
-template <int LPR, bool ADAM>
+template <int LPR, bool ADAM, int CHUNK_SLICES>
 __global__ __launch_bounds__(256) void row_update_chunk_kernel(
     const uint32_t* __restrict__ keys, const int32_t* __restrict__ bags,
     const float* __restrict__ de, uint32_t n, EmbOpt o, float* __restrict__ parts,
@@ -74,91 +82,105 @@ __global__ __launch_bounds__(256) void row_update_chunk_kernel(
     const float* __restrict__ inv_len) {
   const float* __restrict__ h = o.h;
   const float* __restrict__ G = o.G;
-  constexpr int D = LPR * 4, C = LPR, SUB = (C < 8 ? C : 8);
+  constexpr int D = LPR * 4, C = CHUNK_SLICES * LPR, SUB = (LPR < 8 ? LPR : 8);
   if (blockIdx.x == 0 && threadIdx.x == 0) *long_count = 0;  // consumed by the later passes
   const int lane = threadIdx.x & 63, c = lane % LPR, gw = lane / LPR;
   const uint32_t nchunks = (n + C - 1) / C;
   const uint32_t g = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
   const bool live = g < nchunks;
-  const uint32_t j = g * C + c;
-  const bool valid = live && j < n;
-  const uint32_t key = valid ? keys[j] : 0u;
-  const int bag = valid ? bags[j] : 0;
-  const bool head = valid && (j == 0 || keys[j - 1] != key);
-  const bool tail = valid && (j + 1 == n || keys[j + 1] != key);
-  const uint64_t hb = __ballot(head), tb = __ballot(tail), vb = __ballot(valid);
-  if (!live) return;
-  const uint32_t gmask = (C == 32) ? 0xFFFFFFFFu : ((1u << C) - 1u);
-  const uint32_t hm = (uint32_t)(hb >> (gw * C)) & gmask;
-  const uint32_t tm = (uint32_t)(tb >> (gw * C)) & gmask;
-  const uint32_t vm = (uint32_t)(vb >> (gw * C)) & gmask;
-  const int nv = __popc(vm);  // valid entries form a prefix of the chunk
+  const uint32_t gmask = (LPR == 32) ? 0xFFFFFFFFu : ((1u << LPR) - 1u);
   float4 acc = {0.f, 0.f, 0.f, 0.f};
   bool started = false;  // the current run began at a head inside this chunk
+  bool open = false;     // the last entry seen so far did not end its run
   uint32_t fl = 0;
   float4* part0 = (float4*)(parts + ((size_t)g * 2 + 0) * D) + c;
   float4* part1 = (float4*)(parts + ((size_t)g * 2 + 1) * D) + c;
-  for (int s0 = 0; s0 < nv; s0 += SUB) {
-    float4 v[SUB], hv[SUB];
-    float Gv[SUB];
-    uint32_t rw[SUB];
+  // every slice's index work first (one entry per lane and slice; every lane of the wave
+  // takes part in all ballots), so that all index loads are in flight together
+  uint32_t key_s[CHUNK_SLICES], hm_s[CHUNK_SLICES], tm_s[CHUNK_SLICES];
+  int bag_s[CHUNK_SLICES], nv_s[CHUNK_SLICES];
 #pragma unroll
-    for (int i = 0; i < SUB; ++i) {
-      const int p = s0 + i;
-      const int bg = __shfl(bag, p, LPR);
-      rw[i] = (uint32_t)__shfl((int)key, p, LPR);
-      v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-      hv[i] = v[i];
-      Gv[i] = 0.f;
-      if (p < nv) {
-        v[i] = *(const float4*)(de + (size_t)bg * D + c * 4);
-        if (inv_len) {  // mean pooling: d(mean)/d(member) = 1 / bag length
-          const float sc = inv_len[bg];
-          v[i].x *= sc; v[i].y *= sc; v[i].z *= sc; v[i].w *= sc;
-        }
-        if ((tm >> p) & 1u) {
-          hv[i] = *(const float4*)(h + (size_t)rw[i] * D + c * 4);
-          Gv[i] = G[rw[i]];
+  for (int sl = 0; sl < CHUNK_SLICES; ++sl) {
+    const uint32_t j = g * C + sl * LPR + c;
+    const bool valid = live && j < n;
+    key_s[sl] = valid ? keys[j] : 0u;
+    bag_s[sl] = valid ? bags[j] : 0;
+    const bool head = valid && (j == 0 || keys[j - 1] != key_s[sl]);
+    const bool tail = valid && (j + 1 == n || keys[j + 1] != key_s[sl]);
+    const uint64_t hb = __ballot(head), tb = __ballot(tail), vb = __ballot(valid);
+    hm_s[sl] = (uint32_t)(hb >> (gw * LPR)) & gmask;
+    tm_s[sl] = (uint32_t)(tb >> (gw * LPR)) & gmask;
+    nv_s[sl] = __popc((uint32_t)(vb >> (gw * LPR)) & gmask);  // valid entries form a prefix
+  }
+#pragma unroll
+  for (int sl = 0; sl < CHUNK_SLICES; ++sl) {
+    const uint32_t key = key_s[sl], hm = hm_s[sl], tm = tm_s[sl];
+    const int bag = bag_s[sl], nv = nv_s[sl];
+    for (int s0 = 0; s0 < nv; s0 += SUB) {
+      float4 v[SUB], hv[SUB];
+      float Gv[SUB];
+      uint32_t rw[SUB];
+#pragma unroll
+      for (int i = 0; i < SUB; ++i) {
+        const int p = s0 + i;
+        const int bg = __shfl(bag, p, LPR);
+        rw[i] = (uint32_t)__shfl((int)key, p, LPR);
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        hv[i] = v[i];
+        Gv[i] = 0.f;
+        if (p < nv) {
+          v[i] = *(const float4*)(de + (size_t)bg * D + c * 4);
+          if (inv_len) {  // mean pooling: d(mean)/d(member) = 1 / bag length
+            const float sc = inv_len[bg];
+            v[i].x *= sc; v[i].y *= sc; v[i].z *= sc; v[i].w *= sc;
+          }
+          if ((tm >> p) & 1u) {
+            hv[i] = *(const float4*)(h + (size_t)rw[i] * D + c * 4);
+            Gv[i] = G[rw[i]];
+          }
         }
       }
-    }
 #pragma unroll
-    for (int i = 0; i < SUB; ++i) {
-      const int p = s0 + i;
-      if (p < nv) {
-        if ((hm >> p) & 1u) {
-          acc = make_float4(0.f, 0.f, 0.f, 0.f);
-          started = true;
-        }
-        acc.x += v[i].x; acc.y += v[i].y; acc.z += v[i].z; acc.w += v[i].w;
-        if ((tm >> p) & 1u) {
-          if (started) {
-            apply_update<LPR, ADAM>(acc, hv[i], Gv[i], rw[i], c, o);
-          } else {
-            *part0 = acc;  // end of a run that came in from the previous chunk
-            fl |= 1u;
+      for (int i = 0; i < SUB; ++i) {
+        const int p = s0 + i;
+        if (p < nv) {
+          if ((hm >> p) & 1u) {
+            acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            started = true;
           }
-          acc = make_float4(0.f, 0.f, 0.f, 0.f);
-          started = false;
+          acc.x += v[i].x; acc.y += v[i].y; acc.z += v[i].z; acc.w += v[i].w;
+          open = true;
+          if ((tm >> p) & 1u) {
+            if (started) {
+              apply_update<LPR, ADAM>(acc, hv[i], Gv[i], rw[i], c, o);
+            } else {
+              *part0 = acc;  // end of a run that came in from the previous chunk
+              fl |= 1u;
+            }
+            acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            started = false;
+            open = false;
+          }
         }
       }
     }
   }
-  if (nv > 0 && !((tm >> (nv - 1)) & 1u)) {  // the last run goes on into the next chunk
+  if (!live) return;
+  if (open) {  // the last run goes on into the next chunk
     if (started) { *part1 = acc; fl |= 2u; }
     else { *part0 = acc; fl |= 4u; }
   }
   if (c == 0) flags[g] = fl;
 }
 
-template <int LPR, bool ADAM>
+template <int LPR, bool ADAM, int CHUNK_SLICES>
 __global__ __launch_bounds__(256) void row_update_stitch_kernel(
     const uint32_t* __restrict__ keys, uint32_t n, float* __restrict__ parts,
     const uint32_t* __restrict__ flags, EmbOpt o, uint32_t* __restrict__ long_list,
     uint32_t* __restrict__ long_count) {
   const float* __restrict__ h = o.h;
   const float* __restrict__ G = o.G;
-  constexpr int D = LPR * 4, C = LPR, MAXB = 16;
+  constexpr int D = LPR * 4, C = CHUNK_SLICES * LPR, MAXB = 16;
   const int c = threadIdx.x % LPR;
   const uint32_t nchunks = (n + C - 1) / C;
   const uint32_t g = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
@@ -208,14 +230,14 @@ __global__ __launch_bounds__(256) void row_update_stitch_kernel(
   }
 }
 
-template <int LPR, bool ADAM>
+template <int LPR, bool ADAM, int CHUNK_SLICES>
 __global__ __launch_bounds__(1024) void row_update_long_kernel(
     const uint32_t* __restrict__ keys, uint32_t n, const float* __restrict__ parts,
     const uint32_t* __restrict__ flags, EmbOpt o, const uint32_t* __restrict__ long_list,
     const uint32_t* __restrict__ long_count) {
   const float* __restrict__ h = o.h;
   const float* __restrict__ G = o.G;
-  constexpr int D = LPR * 4, C = LPR, NG = 1024 / LPR;
+  constexpr int D = LPR * 4, C = CHUNK_SLICES * LPR, NG = 1024 / LPR;
   __shared__ float4 red[1024];
   __shared__ uint32_t last_chunk;
   const uint32_t nchunks = (n + C - 1) / C;
@@ -281,13 +303,14 @@ void launch_row_update_chunk(const uint32_t* sorted_keys, const int32_t* sorted_
                              const float* de, uint32_t n, const RowUpdateScratch& sc, int d,
                              const EmbOpt& o, const float* inv_len, hipStream_t s) {
   if (n == 0) return;
-  const int lpr = d / 4;
-  const int64_t nchunks = ((int64_t)n + lpr - 1) / lpr;
+  const int lpr = d / 4, ch = chunk_slices(n), C = ch * lpr;
+  const int64_t nchunks = ((int64_t)n + C - 1) / C;
   const int blocks = ceil_div(nchunks, 256 / lpr);
-#define L(LPR, A)                                                                                    \
-  hipLaunchKernelGGL((row_update_chunk_kernel<LPR, A>), dim3(blocks), dim3(256), 0, s, sorted_keys, \
-                     sorted_bag, de, n, o, sc.parts, sc.flags, sc.long_count, inv_len)
-#define LA(LPR) do { if (o.adam) { L(LPR, true); } else { L(LPR, false); } } while (0)
+#define L(LPR, A, CH)                                                                          \
+  hipLaunchKernelGGL((row_update_chunk_kernel<LPR, A, CH>), dim3(blocks), dim3(256), 0, s,    \
+                     sorted_keys, sorted_bag, de, n, o, sc.parts, sc.flags, sc.long_count, inv_len)
+#define LC(LPR, A) do { if (ch == 4) { L(LPR, A, 4); } else if (ch == 2) { L(LPR, A, 2); } else { L(LPR, A, 1); } } while (0)
+#define LA(LPR) do { if (o.adam) LC(LPR, true); else LC(LPR, false); } while (0)
   switch (d) {
     case 16: LA(4); break;
     case 32: LA(8); break;
@@ -295,25 +318,27 @@ void launch_row_update_chunk(const uint32_t* sorted_keys, const int32_t* sorted_
     default: LA(32); break;
   }
 #undef LA
+#undef LC
 #undef L
 }
 
 void launch_row_update_finish(const uint32_t* sorted_keys, uint32_t n, const RowUpdateScratch& sc,
                               int d, const EmbOpt& o, hipStream_t s) {
   if (n == 0) return;
-  const int lpr = d / 4;
-  const int64_t nchunks = ((int64_t)n + lpr - 1) / lpr;
+  const int lpr = d / 4, ch = chunk_slices(n), C = ch * lpr;
+  const int64_t nchunks = ((int64_t)n + C - 1) / C;
   const int blocks = ceil_div(nchunks, 256 / lpr);
   // one block per long run; their number is only known on the device, so the grid is sized
   // for the worst case that matters (a run is long from about 30 chunks on) and capped
   const int64_t lb = nchunks / 512 + 16;
   const int long_blocks = (int)(lb > 512 ? 512 : lb);
-#define L(LPR, A)                                                                                      \
-  hipLaunchKernelGGL((row_update_stitch_kernel<LPR, A>), dim3(blocks), dim3(256), 0, s, sorted_keys,  \
-                     n, sc.parts, sc.flags, o, sc.long_list, sc.long_count);                           \
-  hipLaunchKernelGGL((row_update_long_kernel<LPR, A>), dim3(long_blocks), dim3(1024), 0, s,           \
+#define L(LPR, A, CH)                                                                             \
+  hipLaunchKernelGGL((row_update_stitch_kernel<LPR, A, CH>), dim3(blocks), dim3(256), 0, s,      \
+                     sorted_keys, n, sc.parts, sc.flags, o, sc.long_list, sc.long_count);         \
+  hipLaunchKernelGGL((row_update_long_kernel<LPR, A, CH>), dim3(long_blocks), dim3(1024), 0, s,  \
                      sorted_keys, n, sc.parts, sc.flags, o, sc.long_list, sc.long_count)
-#define LA(LPR) do { if (o.adam) { L(LPR, true); } else { L(LPR, false); } } while (0)
+#define LC(LPR, A) do { if (ch == 4) { L(LPR, A, 4); } else if (ch == 2) { L(LPR, A, 2); } else { L(LPR, A, 1); } } while (0)
+#define LA(LPR) do { if (o.adam) LC(LPR, true); else LC(LPR, false); } while (0)
   switch (d) {
     case 16: LA(4); break;
     case 32: LA(8); break;
@@ -321,6 +346,7 @@ void launch_row_update_finish(const uint32_t* sorted_keys, uint32_t n, const Row
     default: LA(32); break;
   }
 #undef LA
+#undef LC
 #undef L
 }
 
