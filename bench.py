@@ -226,11 +226,16 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
             t.start()
         torch.cuda.synchronize()
         gate.wait()
+        clk = [time.clock_gettime_ns(time.CLOCK_MONOTONIC), time.clock_gettime_ns(time.CLOCK_BOOTTIME)]
         t0 = time.perf_counter()
         for t in ts:
             t.join()
         torch.cuda.synchronize()
-        return time.perf_counter() - t0
+        dt = time.perf_counter() - t0
+        # host clocks at both ends (a profiler's kernel time stamps can be cut to this window)
+        state["clock_ns"] = {"monotonic": [clk[0], time.clock_gettime_ns(time.CLOCK_MONOTONIC)],
+                             "boottime": [clk[1], time.clock_gettime_ns(time.CLOCK_BOOTTIME)]}
+        return dt
 
     def shadow_loop(on):
         if shadow_mode != "continuous" or fg:
@@ -260,6 +265,7 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
         gpu.ss_profile_arm(*one.values())
     steps0, rounds0, _ = gpu.ss_get_counters()
     dt_on = region(steps)
+    clock_on = state.get("clock_ns")
     steps1, rounds1, _ = gpu.ss_get_counters()
     kernels = {}
     if events:
@@ -357,7 +363,7 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
         "diverged": bool(diverged),
         "train_ne": {"examples": train_ne[0], "logloss": train_ne[1], "ctr": train_ne[2],
                      "ne": train_ne[3]},
-        "kernels": kernels,
+        "kernels": kernels, "timed_region_host_clock_ns": clock_on,
     }
     gpu.close()
     del gpu, dev_batches, losses
@@ -572,6 +578,7 @@ def main():
             "first_window_logloss": res["first_window_logloss"],
             "last_window_logloss": res["last_window_logloss"], "diverged": res["diverged"],
             "train_ne": res["train_ne"], "input_generation_seconds": t_gen,
+            "timed_region_host_clock_ns": res["timed_region_host_clock_ns"],
         },
         "no_shadow": {"value": res["no_shadow_value"], "shadow_on_over_off": res["shadow_on_over_off"],
                       "note": "the same sweeps with the shadow stream idle; Section 3.2 claims "

@@ -276,13 +276,18 @@ typedef enum {
   SS_DBG_DENSE_GRAD = 3,   /* float  [P]         gradient of the mean loss w.r.t. w         */
   SS_DBG_POOLED_GRAD = 4,  /* float  [B, T, d]   de                                         */
   SS_DBG_SORTED_ROWS = 5,  /* uint32 [n]         global row (row_base[t]+row), ascending    */
-  SS_DBG_SORTED_POS = 6,   /* uint32 [n]         flat position of each sorted entry         */
+  SS_DBG_SORTED_POS = 6,   /* uint32 [n]         flat position of each sorted entry (made on
+                              demand: the step's keys sorted once more with positions as
+                              the values; the step itself carries SS_DBG_SORTED_BAG)      */
   SS_DBG_SEG_STARTS = 7,   /* uint32 [U]         sorted index where each distinct row starts */
   SS_DBG_NUM_UNIQUE = 8,   /* uint32 [1]         U                                          */
   SS_DBG_BAG_OF_POS = 9,   /* int32  [n]         b*T + t of each flat position              */
   SS_DBG_Z0 = 10,          /* float  [B, d]      output of the bottom MLP (after its ReLU)  */
   SS_DBG_POOLED_PARTIALS = 11, /* float [S, B, T, d] partial pooling results per row shard
                                   (sums, before any 1/length factor); emb_row_shards > 1   */
+  SS_DBG_SORTED_BAG = 12,  /* int32  [n]         b*T + t of each sorted entry: the values the
+                              step's sort carries (the update sums de[b, t, :] of a row's
+                              entries in this order)                                       */
   SS_DBG_HIDDEN_ACT = 32   /* SS_DBG_HIDDEN_ACT + l: float [B, out_l], output of hidden layer l
                               (layers counted over the whole model, bottom first; not the
                               bottom output, not the logit) as the device stores it, i.e.

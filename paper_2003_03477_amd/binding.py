@@ -30,7 +30,8 @@ _DBG_DTYPE = {DBG_POOLED: np.float32, DBG_INTERACT: np.float32, DBG_LOGITS: np.f
               DBG_DENSE_GRAD: np.float32, DBG_POOLED_GRAD: np.float32,
               DBG_SORTED_ROWS: np.uint32, DBG_SORTED_POS: np.uint32,
               DBG_SEG_STARTS: np.uint32, DBG_NUM_UNIQUE: np.uint32, DBG_BAG_OF_POS: np.int32}
-DBG_Z0, DBG_POOLED_PARTIALS, DBG_HIDDEN_ACT = 10, 11, 32
+DBG_Z0, DBG_POOLED_PARTIALS, DBG_SORTED_BAG, DBG_HIDDEN_ACT = 10, 11, 12, 32
+_DBG_DTYPE[DBG_SORTED_BAG] = np.int32
 
 (K_NONE, K_GATHER, K_SORT, K_ROW_UPDATE_CHUNK, K_SYNC, K_MLP, K_INTERACT_FWD, K_INTERACT_BWD,
  K_ROW_UPDATE, K_MLP_FWD, K_MLP_DGRAD, K_MLP_WGRAD) = range(12)

@@ -66,15 +66,14 @@ struct Slot {
   uint16_t* dYr[MAX_LAYERS];       // [B][pout[l]]
   float* wg_part;
   // embedding backward
-  uint32_t* keys;                  // [max_ids]
-  int32_t* bag_of_pos;             // [max_ids]
-  int32_t* sorted_bag;             // [max_ids] bag_of_pos in sorted order
+  uint32_t* keys;                  // [max_ids] global row of every position (the sort's input, kept)
+  int32_t* bag_of_pos;             // [max_ids] pooled-vector id of every position (the sort's values)
   SortScratch sort;
   SegScratch seg;
   RowUpdateScratch upd;
   // results of the last step (for ss_read_debug)
   uint32_t* sorted_keys = nullptr;
-  uint32_t* sorted_pos = nullptr;
+  uint32_t* sorted_bag = nullptr;  // pooled-vector id of every sorted entry
   uint32_t last_n = 0;             // ids of the last forward pass (training or evaluation)
   uint32_t sort_n = 0;             // ids of the last TRAINING step: length of the sorted arrays
   int last_B = 0;
@@ -304,8 +303,8 @@ static void carve_slot(const ss_ctx* x, Carver& cv, Slot& s, int B, int64_t n, b
   const int seg_blocks = ceil_div(n, 2048) + 1;
   s.keys = cv.take<uint32_t>(n);
   s.bag_of_pos = cv.take<int32_t>(n);
-  s.sorted_bag = cv.take<int32_t>(n);
-  s.sort.keys_alt = cv.take<uint32_t>(n);
+  s.sort.keys_a = cv.take<uint32_t>(n);
+  s.sort.keys_b = cv.take<uint32_t>(n);
   s.sort.vals = cv.take<uint32_t>(n);
   s.sort.vals_alt = cv.take<uint32_t>(n);
   s.sort.block_hist = cv.take<uint32_t>((size_t)256 * sort_blocks);
@@ -1191,8 +1190,10 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
     // "update h": stable sort by row, one Adagrad update per distinct row
     {
       ProfScope ps(x, SS_K_SORT, st);
-      launch_sort_pairs(s.keys, n, x->key_bits, s.sort, &s.sorted_keys, &s.sorted_pos,
-                        s.bag_of_pos, s.sorted_bag, st);
+      // the value carried through the passes is the pooled-vector id of the position: equal
+      // rows keep the order of their positions (stable), and the update needs nothing else
+      launch_sort_pairs(s.keys, (const uint32_t*)s.bag_of_pos, n, x->key_bits, s.sort,
+                        &s.sorted_keys, &s.sorted_bag, st);
       s.seg_valid = false;  // compacted segment starts are produced on demand (ss_read_debug)
     }
     const EmbOpt opt{x->h, x->G, x->M, x->V, x->lr_emb, x->eps, x->beta1, x->beta2, x->adam ? 1 : 0};
@@ -1200,7 +1201,7 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
       ProfScope all(x, SS_K_ROW_UPDATE, st);
       {
         ProfScope ps(x, SS_K_ROW_UPDATE_CHUNK, st);
-        launch_row_update_chunk(s.sorted_keys, s.sorted_bag, s.de, n, s.upd, x->d, opt,
+        launch_row_update_chunk(s.sorted_keys, (const int32_t*)s.sorted_bag, s.de, n, s.upd, x->d, opt,
                                 x->pool_mean ? s.inv_len : nullptr, st);
       }
       launch_row_update_finish(s.sorted_keys, n, s.upd, x->d, opt, st);
@@ -1380,6 +1381,23 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
     }
     HIP_TRY(ctx, hipMemcpy(&U, s.seg.num_unique, 4, hipMemcpyDeviceToHost));
   }
+  if (item == SS_DBG_SORTED_POS) {
+    // The step's sort carries pooled-vector ids, not positions.  The positions come from
+    // sorting the step's keys (kept) once more with each element's own position as its value:
+    // the same stable passes, so the same permutation.  The step's sorted arrays are rebuilt
+    // afterwards (the passes share their buffers).
+    if (!s.trained) return fail(ctx, SS_ESTATE, "no training step has run on this slot yet");
+    if (size_out) *size_out = ns * 4;
+    if (!host_out || bytes == 0 || ns == 0) return SS_OK;
+    uint32_t *k = nullptr, *v = nullptr;
+    launch_sort_pairs(s.keys, nullptr, s.sort_n, ctx->key_bits, s.sort, &k, &v, nullptr);
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    HIP_TRY(ctx, hipMemcpy(host_out, v, bytes < ns * 4 ? bytes : ns * 4, hipMemcpyDeviceToHost));
+    launch_sort_pairs(s.keys, (const uint32_t*)s.bag_of_pos, s.sort_n, ctx->key_bits, s.sort,
+                      &s.sorted_keys, &s.sorted_bag, nullptr);
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    return SS_OK;
+  }
   const int L = (int)ctx->layers.size();
   if (item >= SS_DBG_HIDDEN_ACT && item < SS_DBG_HIDDEN_ACT + L) {
     // hidden activations live in a path-specific layout (fp32 or bf16, row-major with a padded
@@ -1421,7 +1439,7 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
     case SS_DBG_DENSE_GRAD: src = s.grads; size = (size_t)ctx->P * 4; break;
     case SS_DBG_POOLED_GRAD: src = s.de; size = B * ctx->T * ctx->d * 4; break;
     case SS_DBG_SORTED_ROWS: src = s.sorted_keys; size = ns * 4; break;
-    case SS_DBG_SORTED_POS: src = s.sorted_pos; size = ns * 4; break;
+    case SS_DBG_SORTED_BAG: src = s.sorted_bag; size = ns * 4; break;
     case SS_DBG_SEG_STARTS: src = s.seg.seg_starts; size = (size_t)U * 4; break;
     case SS_DBG_NUM_UNIQUE: src = s.seg.num_unique; size = 4; break;
     case SS_DBG_BAG_OF_POS: src = s.bag_of_pos; size = ns * 4; break;

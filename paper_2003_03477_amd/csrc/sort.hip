@@ -119,8 +119,7 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
     const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in, uint32_t n,
     int shift, int rounds, int nblocks, const uint32_t* __restrict__ block_hist,
     const uint32_t* __restrict__ digit_tot, uint32_t* __restrict__ keys_out,
-    uint32_t* __restrict__ vals_out, const int32_t* __restrict__ lookup,
-    int32_t* __restrict__ lookup_out) {
+    uint32_t* __restrict__ vals_out) {
   // per-wave running digit counts; volatile: lanes of one wave hand values to each other
   // through it between rounds without a barrier
   __shared__ volatile uint32_t wrun[SORT_WAVES][RADIX];
@@ -217,27 +216,25 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
     const uint32_t dst = gbase[dg] + (i - lbase[dg]);
     keys_out[dst] = k;
     vals_out[dst] = v;
-    if (lookup) lookup_out[dst] = lookup[v];
   }
 }
 
-void launch_sort_pairs(uint32_t* keys, uint32_t n, int key_bits, const SortScratch& sc,
-                       uint32_t** sorted_keys, uint32_t** sorted_vals, const int32_t* lookup,
-                       int32_t* lookup_out, hipStream_t s) {
-  uint32_t* kin = keys;
-  uint32_t* kout = sc.keys_alt;
-  const uint32_t* vin = nullptr;  // first pass: the value is the element's own position
+void launch_sort_pairs(const uint32_t* keys, const uint32_t* vals, uint32_t n, int key_bits,
+                       const SortScratch& sc, uint32_t** sorted_keys, uint32_t** sorted_vals,
+                       hipStream_t s) {
+  const uint32_t* kin = keys;
+  const uint32_t* vin = vals;     // null: the value is the element's own position
+  uint32_t* kout = sc.keys_a;
+  uint32_t* kother = sc.keys_b;
   uint32_t* vout = sc.vals;
   uint32_t* vother = sc.vals_alt;
   int passes = (key_bits + RADIX_BITS - 1) / RADIX_BITS;
   if (passes < 1) passes = 1;
   int rounds = 1;
   const int nblocks = sort_num_blocks(n, &rounds);
-  if (n == 0) {
-    *sorted_keys = kin;
-    *sorted_vals = sc.vals;
-    return;
-  }
+  *sorted_keys = sc.keys_a;
+  *sorted_vals = sc.vals;
+  if (n == 0) return;
   for (int p = 0; p < passes; ++p) {
     const int shift = p * RADIX_BITS;
     hipLaunchKernelGGL(radix_hist_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, n, shift,
@@ -245,14 +242,13 @@ void launch_sort_pairs(uint32_t* keys, uint32_t n, int key_bits, const SortScrat
     hipLaunchKernelGGL(radix_scan_kernel, dim3(RADIX), dim3(256), 0, s, sc.block_hist, nblocks,
                        sc.digit_tot);
     hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, vin, n,
-                       shift, rounds, nblocks, sc.block_hist, sc.digit_tot, kout, vout,
-                       (p == passes - 1) ? lookup : nullptr, lookup_out);
-    uint32_t* t = kin; kin = kout; kout = t;
-    vin = vout;
-    uint32_t* tv = vout; vout = vother; vother = tv;
+                       shift, rounds, nblocks, sc.block_hist, sc.digit_tot, kout, vout);
+    *sorted_keys = kout;
+    *sorted_vals = vout;
+    kin = kout; vin = vout;
+    uint32_t* t = kout; kout = kother; kother = t;
+    t = vout; vout = vother; vother = t;
   }
-  *sorted_keys = kin;
-  *sorted_vals = (uint32_t*)vin;
 }
 
 }  // namespace ss

@@ -67,7 +67,8 @@ void launch_row_update_finish(const uint32_t* sorted_keys, uint32_t n, const Row
 
 // ---------------------------------------------------------------------------- sort.hip
 struct SortScratch {
-  uint32_t* keys_alt;   // [max_ids]
+  uint32_t* keys_a;     // [max_ids] ping-pong buffers of the passes
+  uint32_t* keys_b;     // [max_ids]
   uint32_t* vals;       // [max_ids]
   uint32_t* vals_alt;   // [max_ids]
   uint32_t* block_hist; // [256 * max_sort_blocks]
@@ -75,13 +76,12 @@ struct SortScratch {
 };
 int sort_num_blocks(uint32_t n, int* rounds_out);
 int sort_max_blocks(uint32_t max_n);
-// Stable LSD radix sort of (key, position) pairs on key_bits bits.  keys is overwritten or
-// left as is depending on the pass count; the sorted arrays are returned through the out
-// pointers (each one of the two ping-pong buffers).
-// If lookup != nullptr the last pass also writes lookup_out[j] = lookup[sorted_vals[j]].
-void launch_sort_pairs(uint32_t* keys, uint32_t n, int key_bits, const SortScratch& sc,
-                       uint32_t** sorted_keys, uint32_t** sorted_vals, const int32_t* lookup,
-                       int32_t* lookup_out, hipStream_t s);
+// Stable LSD radix sort of (key, value) pairs on key_bits bits; vals == nullptr sorts
+// (key, position).  The inputs are left as they are; the sorted arrays are returned through
+// the out pointers (one of the ping-pong buffers each).
+void launch_sort_pairs(const uint32_t* keys, const uint32_t* vals, uint32_t n, int key_bits,
+                       const SortScratch& sc, uint32_t** sorted_keys, uint32_t** sorted_vals,
+                       hipStream_t s);
 
 // ---------------------------------------------------------------------------- interaction.hip
 // f[b] = [z0[b], <V_r, V_c> for r>c], V = [z0[b]; e[b,0..T-1]].  Writes fp32 f (ldf floats per

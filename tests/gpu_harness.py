@@ -150,6 +150,10 @@ def compare_step(gpu, orc, slot, rtol, step_name, tables_exact=False):
                       (binding.DBG_SEG_STARTS, "seg_starts"), (binding.DBG_BAG_OF_POS, "bag_of_pos")):
         got = gpu.ss_read_debug(slot, item).astype(np.int64)
         assert np.array_equal(got, np.asarray(last[key], dtype=np.int64)), f"{step_name}: {key} differs"
+    # the values the step's sort carries: the pooled-vector id of every sorted entry
+    want_bag = np.asarray(last["bag_of_pos"], dtype=np.int64)[np.asarray(last["sorted_pos"], dtype=np.int64)]
+    assert np.array_equal(gpu.ss_read_debug(slot, binding.DBG_SORTED_BAG).astype(np.int64), want_bag), \
+        f"{step_name}: sorted pooled-vector ids differ"
     assert int(gpu.ss_read_debug(slot, binding.DBG_NUM_UNIQUE)[0]) == len(last["seg_starts"])
     close(gpu.ss_read_debug(slot, binding.DBG_POOLED), last["e"],
           FP32_RTOL if (tables_exact or rtol <= FP32_RTOL) else rtol, f"{step_name}: pooled e")

@@ -401,6 +401,8 @@ def _full_size_step_check(wl, n_batches, rtol):
         # sort order: positions bit-exact; keys equal after mapping compact ids back
         assert np.array_equal(gpu.ss_read_debug(0, binding.DBG_SORTED_POS).astype(np.int64),
                               last["sorted_pos"])
+        assert np.array_equal(gpu.ss_read_debug(0, binding.DBG_SORTED_BAG).astype(np.int64),
+                              np.asarray(last["bag_of_pos"], dtype=np.int64)[last["sorted_pos"]])
         glob = np.concatenate([wl.row_base[t] + cp.touched[t] for t in range(wl.num_tables)])
         assert np.array_equal(gpu.ss_read_debug(0, binding.DBG_SORTED_ROWS).astype(np.int64),
                               glob[last["sorted_keys"]])
