@@ -78,6 +78,8 @@ def parse():
     ap.add_argument("--no-sync-isolation", action="store_true")
     ap.add_argument("--no-secondary", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--no-fork", action="store_true",
+                    help="generate the batches in this process (for runs under a profiler)")
     return ap.parse_args()
 
 
@@ -86,6 +88,11 @@ def parse():
 def _gen_one(args):
     gen, s = args
     return gen.batch(s)
+
+
+def progress(msg):
+    """One line on stderr per finished stage of the run."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
 def make_batches(wl, n, fork=True):
@@ -98,8 +105,14 @@ def make_batches(wl, n, fork=True):
         return gen, [gen.batch(s) for s in range(n)]
     import multiprocessing as mp
     procs = min(16, n, max(1, (os.cpu_count() or 1)))
-    with mp.get_context("fork").Pool(procs) as pool:
+    # close + join: the workers leave through their normal exit (terminating them by signal
+    # runs whatever handler a profiler preloaded into the process, which can block)
+    pool = mp.get_context("fork").Pool(procs)
+    try:
         out = pool.map(_gen_one, [(gen, s) for s in range(n)], chunksize=1)
+    finally:
+        pool.close()
+        pool.join()
     return gen, out
 
 
@@ -161,6 +174,7 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
     gpu = binding.from_workload(wl, num_worker_slots=NS, max_ids=max_ids, mlp_path=args.mlp_path)
     gpu.ss_init_tables_hash()
     gpu.ss_init_dense(synth.dense_w0(wl))
+    progress(f"{wl.name}{tag}: context ready, {NS} worker streams")
     dev_batches = [binding.upload_batch(b) for b in host_batches]
     # every stream owns a disjoint set of batches: no two streams ever hold the same one
     own = [list(range(w, len(dev_batches), NS)) for w in range(NS)]
@@ -258,6 +272,7 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
     # ---- warm-up: every stream, every kernel, the shadow loop
     shadow_loop(True)
     region(warmup)
+    progress(f"{wl.name}{tag}: warm-up done")
     # ---- timed region, shadow on
     every = max(1, (steps * NS) // 96)
     if events:
@@ -266,6 +281,7 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
     steps0, rounds0, _ = gpu.ss_get_counters()
     dt_on = region(steps)
     clock_on = state.get("clock_ns")
+    progress(f"{wl.name}{tag}: timed region done, {wl.batch * NS * steps / dt_on:.4g} examples/s")
     steps1, rounds1, _ = gpu.ss_get_counters()
     kernels = {}
     if events:
@@ -545,14 +561,15 @@ def main():
     n_batches = (n_batches + NS - 1) // NS * NS
     # inputs first: batch generation forks worker processes, which must precede any GPU use
     t_gen = time.perf_counter()
-    _, host_batches = make_batches(wl, n_batches)
+    _, host_batches = make_batches(wl, n_batches, fork=not args.no_fork)
     mid_batches = None
     secondary = wl.name == "large" and not args.no_secondary and args.sweep == "none"
     if secondary:
         mid_wl = synth.mid()
         mid_workers = parse_workers(DEFAULT_WORKERS["mid"], mid_wl.num_replicas)
-        _, mid_batches = make_batches(mid_wl, max(64, 3 * sum(mid_workers)))
+        _, mid_batches = make_batches(mid_wl, max(64, 3 * sum(mid_workers)), fork=not args.no_fork)
     t_gen = time.perf_counter() - t_gen
+    progress(f"inputs generated in {t_gen:.1f} s")
 
     res = run_workload(args, wl, workers, mode, args.steps, args.warmup, host_batches,
                        events=not args.no_kernel_events, shadow_off=not args.no_shadow_off)
@@ -651,6 +668,7 @@ def main():
             "roofline": pick_roofline(r["kernels"], r["worker_streams"]), "kernels": r["kernels"]}}
     if not args.no_sync_isolation:
         out["sync_isolation"] = sync_isolation()
+        progress("sync isolation done")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

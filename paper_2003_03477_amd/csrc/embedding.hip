@@ -28,8 +28,15 @@ __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
   // the step's loss accumulator is cleared here, ahead of the kernel that adds into it
   if (zero_scalar && blockIdx.x == 0 && shard == 0 && threadIdx.x == 0) *zero_scalar = 0.f;
   const int lane = threadIdx.x & 63;
-  const int bag = (int)((blockIdx.x * (uint64_t)blockDim.x + threadIdx.x) >> 6);  // t*B + b
-  if (bag >= T * B) return;
+  // Workgroups go to the chip's eight dies (each with its own L2) in turn; the grid is a
+  // multiple of 8 and die x takes the x-th eighth of the bags (table-major), so that every L2
+  // holds the hot rows of the one or two tables its die is working on instead of all eight
+  // holding the same table's.
+  const uint32_t per_die = gridDim.x >> 3;
+  const uint32_t lb = (blockIdx.x & 7u) * per_die + (blockIdx.x >> 3);
+  const int64_t bag64 = (int64_t)lb * (blockDim.x >> 6) + (threadIdx.x >> 6);  // t*B + b
+  if (bag64 >= (int64_t)T * B) return;
+  const int bag = (int)bag64;
   const int t = bag / B, b = bag - t * B;
   const int lo = offsets[bag], hi = offsets[bag + 1];
   const uint32_t base = meta.row_base[t];
@@ -121,7 +128,7 @@ void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int3
   const int64_t bags = (int64_t)B * T;
   if (bags == 0) return;
   const bool split = n_shards > 1;
-  dim3 grid((unsigned)ceil_div(bags, 4), split ? n_shards : 1), block(256);
+  dim3 grid((unsigned)(ceil_div(ceil_div(bags, 4), 8) * 8), split ? n_shards : 1), block(256);
   float* out = split ? e_part : e;
 #define L(LPR)                                                                                  \
   do {                                                                                          \
