@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libshadowsync.so")
 SOURCES = ["api.hip", "init.hip", "embedding.hip", "row_update.hip", "sort.hip", "interaction.hip",
-           "mlp_fp32.hip", "mlp_bf16.hip", "mlp_fused.hip", "gemm_mfma.hip", "sync.hip", "placement.hip"]
+           "mlp_fp32.hip", "mlp_last.hip", "mlp_fused.hip", "gemm_mfma.hip", "sync.hip", "placement.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result"]
 

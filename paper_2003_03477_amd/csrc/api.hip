@@ -50,7 +50,6 @@ struct Slot {
   float* dlogit;                   // [B]
   float* grads;                    // [P]
   float* dbuf[2];                  // fp32 path ping-pong [B, maxw]
-  uint16_t* dbuf16[2];             // bf16 path ping-pong
   float* df;                       // [B,ldf]
   float* dz0;                      // [B,d]
   float* de;                       // [B,T,d]
@@ -219,6 +218,14 @@ static int validate(const ss_config* c, std::string& why) {
   if (c->top_dims[c->n_top - 1] != 1) BAD("last top width must be 1");
   for (int i = 0; i < c->n_bot; ++i) if (c->bot_dims[i] < 1) BAD("bad bottom width");
   for (int i = 0; i < c->n_top; ++i) if (c->top_dims[i] < 1) BAD("bad top width");
+  if (c->mlp_prec == SS_BF16) {
+    // the bf16 kernels index padded [batch][width] operands with 32 bits
+    int maxw = 0;
+    for (int i = 0; i < c->n_bot; ++i) maxw = c->bot_dims[i] > maxw ? c->bot_dims[i] : maxw;
+    for (int i = 0; i < c->n_top; ++i) maxw = c->top_dims[i] > maxw ? c->top_dims[i] : maxw;
+    if (((int64_t)maxw + 128) * ((int64_t)c->max_batch + 128) >= (1ll << 31))
+      BAD("max_batch x widest layer too large for the bf16 MLP kernels");
+  }
   uint64_t tot = 0;
   for (int t = 0; t < T; ++t) {
     if (c->rows[t] < 1) BAD("table %d has no rows", t);
@@ -274,7 +281,6 @@ static void carve_slot(const ss_ctx* x, Carver& cv, Slot& s, int B, int64_t n, b
   s.wg_part = nullptr;
   s.dlogit = s.grads = s.df = s.dz0 = s.de = nullptr;
   s.dbuf[0] = s.dbuf[1] = nullptr;
-  s.dbuf16[0] = s.dbuf16[1] = nullptr;
   if (x->fused || x->wide) s.wsw = cv.take<uint16_t>((size_t)x->wsw_elems);
   if (x->wide) s.xb = cv.take<uint16_t>((size_t)B * x->pin[0]);
   if (fwd_only) return;
@@ -282,7 +288,6 @@ static void carve_slot(const ss_ctx* x, Carver& cv, Slot& s, int B, int64_t n, b
   s.grads = cv.take<float>(x->Pstride);
   for (int i = 0; i < 2; ++i) {
     if (x->prec == SS_FP32) s.dbuf[i] = cv.take<float>((size_t)B * x->maxw);
-    else if (!x->fused && !x->wide) s.dbuf16[i] = cv.take<uint16_t>((size_t)B * ((x->maxw + 63) / 64 * 64 + 64));
   }
   s.df = cv.take<float>((size_t)B * x->ldf);
   s.dz0 = cv.take<float>((size_t)B * x->d);
@@ -389,7 +394,7 @@ static ss_ctx* make_ctx(const ss_config* c) {
     // Both MFMA paths read the step's weights from fragment-ordered bf16 copies whose reduction
     // lengths are zero padded to a multiple of 64; the fused kernels' prefetch depth of a layer
     // is the larger of 8 / 4 reduction steps that divides its step count.
-    if (x->prec == SS_BF16 && nh >= 1) {
+    if (x->prec == SS_BF16) {
       auto depth_for = [](int kp) {
         const int steps = kp / 16;
         return steps % 8 == 0 ? 8 : 4;
@@ -425,12 +430,10 @@ static ss_ctx* make_ctx(const ss_config* c) {
     }
     x->fused = ok;
     x->ldT = (x->max_batch + 7) / 8 * 8;
-    // Layer-wise regime: every other bf16 model with a hidden top layer.  Activations and their
-    // gradients are row-major bf16 whose pitch is a multiple of 64 elements (zero padded, so no
-    // GEMM handles an edge along its reduction).
-    const int64_t pw = (maxw + 63) / 64 * 64 + 64, pb = (x->max_batch + 63) / 64 * 64 + 64;
-    x->wide = !ok && x->prec == SS_BF16 && nt >= 2 && (int)x->layers.size() <= SS_NT_MAX_LAYERS &&
-              pw * pb < (1ll << 31);
+    // Layer-wise regime: every other bf16 model.  Activations and their gradients are
+    // row-major bf16 whose pitch is a multiple of 64 elements (zero padded, so no GEMM handles
+    // an edge along its reduction).
+    x->wide = !ok && x->prec == SS_BF16;
     if (x->wide) {
       // row pitches: multiples of 64 elements, never a multiple of 256 (rows that are a power
       // of two apart would all fall on the same memory channel)
@@ -777,7 +780,8 @@ static int check_batch(ss_ctx* x, int replica, int slot, const ss_batch* b) {
 
 // bf16 models with at least one hidden top layer run the one-unit output layer and the loss
 // (and that layer's backward) as fused kernels instead of GEMMs with a single column.
-static bool fused_last(const ss_ctx* x) { return x->prec == SS_BF16 && x->n_top_layers >= 2; }
+// bf16 models run the one-unit output layer, the loss and dL/dlogit in one kernel
+static bool fused_last(const ss_ctx* x) { return x->prec == SS_BF16; }
 
 // ---- fused-MLP path -------------------------------------------------------------------------
 static void fill_stack(const ss_ctx* x, const Slot& s, const float* w, int l0, int n,
@@ -968,9 +972,17 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
   {
     ProfScope ps(x, SS_K_MLP, st);  // (the gradient accumulator was cleared by the weight snapshot)
     const Layer& last = x->layers[L - 1];
-    const int ld = x->pout[L - 2];
-    launch_last_layer_bwd(s.act_bf16[L - 2], ld, w + last.w_off, s.dlogit, B, last.in, s.dYr[L - 2],
-                          ld, s.grads + last.w_off, s.grads + last.b_off, st);
+    if (L - 1 == nb) {
+      // no hidden top layer: the output unit reads the interaction output, its data gradient
+      // is the fp32 gradient w.r.t. that output (no gate: f is no ReLU output)
+      launch_last_layer_bwd(s.f_bf16, x->ldf16, w + last.w_off, s.dlogit, B, last.in, nullptr, 0,
+                            s.df, x->ldf, s.grads + last.w_off, s.grads + last.b_off, st);
+    } else {
+      const int ld = x->pout[L - 2];
+      launch_last_layer_bwd(s.act_bf16[L - 2], ld, w + last.w_off, s.dlogit, B, last.in,
+                            s.dYr[L - 2], ld, nullptr, 0, s.grads + last.w_off,
+                            s.grads + last.b_off, st);
+    }
     for (int l = L - 2; l >= nb; --l) layer_dgrad(l);
   }
   {
@@ -1007,150 +1019,74 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
   }
 }
 
-static void forward(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, float* loss,
-                    bool train, hipStream_t st) {
+// ---- fp32 path: every layer one GEMM on the vector units -------------------------------------
+static void forward_f32(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, float* loss,
+                        bool train, hipStream_t st) {
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
-  const bool bf = x->prec == SS_BF16;
-  // ---- bottom MLP
+  (void)loss;
   {
     ProfScope ps(x, SS_K_MLP, st);
-    const void* in = bt->dense; int ld_in = x->num_dense; bool in_f32 = true;
+    const float* in = bt->dense; int ld_in = x->num_dense;
     for (int l = 0; l < nb; ++l) {
       const Layer& ly = x->layers[l];
-      const bool last = (l == nb - 1);
-      if (!bf) {
-        float* out = last ? s.z0 : s.act_f32[l];
-        launch_gemm_f32((const float*)in, ld_in, 1, w + ly.w_off, 1, ly.in, out, ly.out, B, ly.out,
-                        ly.in, EPI_BIAS | EPI_RELU, w + ly.b_off, nullptr, 0, st);
-        in = out; ld_in = ly.out;
-      } else {
-        GemmBf16Args a{};
-        a.A = in; a.a_is_f32 = in_f32; a.lda = ld_in; a.a_kcontig = 1;
-        a.B = w + ly.w_off; a.b_is_f32 = 1; a.ldb = ly.in; a.b_kcontig = 1;
-        a.M = B; a.N = ly.out; a.K = ly.in; a.ldc = ly.out;
-        a.epi = EPI_BIAS | EPI_RELU; a.bias = w + ly.b_off; a.split_k = 1;
-        if (last) a.C_f32 = s.z0; else a.C_bf16 = s.act_bf16[l];
-        launch_gemm_bf16(a, st);
-        in = last ? (const void*)s.z0 : (const void*)s.act_bf16[l];
-        ld_in = ly.out; in_f32 = last;
-      }
+      float* out = (l == nb - 1) ? s.z0 : s.act_f32[l];
+      launch_gemm_f32(in, ld_in, 1, w + ly.w_off, 1, ly.in, out, ly.out, B, ly.out, ly.in,
+                      EPI_BIAS | EPI_RELU, w + ly.b_off, nullptr, 0, st);
+      in = out; ld_in = ly.out;
     }
   }
-  // ---- look-ups (pooled where the table lives) and interaction
+  // look-ups (pooled where the table lives) and interaction
   {
     ProfScope ps(x, SS_K_GATHER, st);
     launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e,
-                             train ? s.keys : nullptr, s.bag_of_pos, fused_last(x) ? loss : nullptr,
+                             train ? s.keys : nullptr, s.bag_of_pos, nullptr,
                              x->pool_mean ? s.inv_len : nullptr, x->row_shards, s.e_part, st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
-    launch_interaction_fwd(s.z0, s.e, B, x->T, x->d, s.f, x->ldf, s.f_bf16, x->ldf16, st);
+    launch_interaction_fwd(s.z0, s.e, B, x->T, x->d, s.f, x->ldf, nullptr, 0, st);
   }
-  // ---- top MLP
   {
     ProfScope ps(x, SS_K_MLP, st);
-    const void* in = bf ? (const void*)s.f_bf16 : (const void*)s.f;
-    int ld_in = bf ? x->ldf16 : x->ldf;
+    const float* in = s.f; int ld_in = x->ldf;
     for (int l = nb; l < L; ++l) {
       const Layer& ly = x->layers[l];
       const bool last = (l == L - 1);
-      const int epi = last ? EPI_BIAS : (EPI_BIAS | EPI_RELU);
-      if (!bf) {
-        float* out = last ? s.logits : s.act_f32[l];
-        launch_gemm_f32((const float*)in, ld_in, 1, w + ly.w_off, 1, ly.in, out, ly.out, B, ly.out,
-                        ly.in, epi, w + ly.b_off, nullptr, 0, st);
-        in = out; ld_in = ly.out;
-      } else if (last && fused_last(x)) {
-        launch_last_layer_fwd_loss((const uint16_t*)in, ld_in, w + ly.w_off, w + ly.b_off,
-                                   bt->labels, B, ly.in, s.logits, train ? s.dlogit : nullptr,
-                                   loss, st);
-      } else {
-        GemmBf16Args a{};
-        a.A = in; a.a_is_f32 = 0; a.lda = ld_in; a.a_kcontig = 1;
-        a.B = w + ly.w_off; a.b_is_f32 = 1; a.ldb = ly.in; a.b_kcontig = 1;
-        a.M = B; a.N = ly.out; a.K = ly.in; a.ldc = ly.out;
-        a.epi = epi; a.bias = w + ly.b_off; a.split_k = 1;
-        if (last) a.C_f32 = s.logits; else a.C_bf16 = s.act_bf16[l];
-        launch_gemm_bf16(a, st);
-        in = s.act_bf16[l]; ld_in = ly.out;
-      }
+      float* out = last ? s.logits : s.act_f32[l];
+      launch_gemm_f32(in, ld_in, 1, w + ly.w_off, 1, ly.in, out, ly.out, B, ly.out, ly.in,
+                      last ? EPI_BIAS : (EPI_BIAS | EPI_RELU), w + ly.b_off, nullptr, 0, st);
+      in = out; ld_in = ly.out;
     }
   }
 }
 
-static int choose_split(int M, int N, int K) {
-  const int tiles = ceil_div(M, 64) * ceil_div(N, 64);
-  if (tiles >= 128 || K < 512) return 1;
-  int split = ceil_div(256, tiles);
-  const int max_split = K / 128;
-  if (split > max_split) split = max_split;
-  return split < 1 ? 1 : split;
-}
-
-static void backward_dense(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipStream_t st) {
+static void backward_f32(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipStream_t st) {
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
-  const bool bf = x->prec == SS_BF16;
-  // input activation of layer l and its layout
-  auto layer_in = [&](int l, const void*& p, int& ld, bool& f32) {
-    if (l == 0) { p = bt->dense; ld = x->num_dense; f32 = true; }
-    else if (l == nb) { p = bf ? (const void*)s.f_bf16 : (const void*)s.f; ld = bf ? x->ldf16 : x->ldf; f32 = !bf; }
-    else { p = bf ? (const void*)s.act_bf16[l - 1] : (const void*)s.act_f32[l - 1]; ld = x->layers[l - 1].out; f32 = !bf; }
-  };
-  auto run_layers = [&](int l_hi, int l_lo, const void* d0, int ldd0, bool d0_f32) {
-    const void* dcur = d0; int ldd = ldd0; bool d_f32 = d0_f32; int pp = 0;
+  // layers l_hi .. l_lo from the gradient d0 w.r.t. the output of layer l_hi
+  auto run_layers = [&](int l_hi, int l_lo, const float* d0, int ldd0) {
+    const float* dcur = d0; int ldd = ldd0; int pp = 0;
     for (int l = l_hi; l >= l_lo; --l) {
       const Layer& ly = x->layers[l];
-      const void* xin; int ldx; bool x_f32;
-      layer_in(l, xin, ldx, x_f32);
-      float* gW = s.grads + ly.w_off; float* gb = s.grads + ly.b_off;
-      const bool need_dx = (l != 0);
-      const bool to_df = (l == nb);            // gradient w.r.t. the interaction output
-      if (!bf) {
-        launch_gemm_f32((const float*)dcur, 1, ldd, (const float*)xin, ldx, 1, gW, ly.in, ly.out,
-                        ly.in, B, EPI_NONE, nullptr, nullptr, 0, st);
-        launch_col_sum_f32((const float*)dcur, ldd, B, ly.out, gb, st);
-        if (need_dx) {
-          float* out = to_df ? s.df : s.dbuf[pp];
-          const int ldo = to_df ? x->ldf : ly.in;
-          launch_gemm_f32((const float*)dcur, ldd, 1, w + ly.w_off, ly.in, 1, out, ldo, B, ly.in,
-                          ly.out, to_df ? EPI_NONE : EPI_MASK, nullptr,
-                          to_df ? nullptr : (const float*)xin, ldx, st);
-          dcur = out; ldd = ldo; pp ^= 1;
-        }
-      } else if (l == L - 1 && fused_last(x)) {
-        launch_last_layer_bwd((const uint16_t*)xin, ldx, w + ly.w_off, (const float*)dcur, B,
-                              ly.in, s.dbuf16[pp], ly.in, gW, gb, st);
-        dcur = s.dbuf16[pp]; ldd = ly.in; d_f32 = false; pp ^= 1;
-      } else {
-        GemmBf16Args a{};
-        a.A = dcur; a.a_is_f32 = d_f32; a.lda = ldd; a.a_kcontig = 0;
-        a.B = xin; a.b_is_f32 = x_f32; a.ldb = ldx; a.b_kcontig = 0;
-        a.M = ly.out; a.N = ly.in; a.K = B; a.C_f32 = gW; a.ldc = ly.in; a.epi = EPI_NONE;
-        a.split_k = choose_split(ly.out, ly.in, B);
-        a.row_sum = gb;  // bias gradient = row sums of dY^T
-        launch_gemm_bf16(a, st);
-        if (need_dx) {
-          GemmBf16Args g{};
-          g.A = dcur; g.a_is_f32 = d_f32; g.lda = ldd; g.a_kcontig = 1;
-          g.B = w + ly.w_off; g.b_is_f32 = 1; g.ldb = ly.in; g.b_kcontig = 0;
-          g.M = B; g.N = ly.in; g.K = ly.out; g.split_k = 1;
-          if (to_df) { g.C_f32 = s.df; g.ldc = x->ldf; g.epi = EPI_NONE; }
-          else {
-            g.C_bf16 = s.dbuf16[pp]; g.ldc = ly.in; g.epi = EPI_MASK;
-            g.mask = (const uint16_t*)xin; g.ldmask = ldx;
-          }
-          launch_gemm_bf16(g, st);
-          if (to_df) { dcur = s.df; ldd = x->ldf; d_f32 = true; }
-          else { dcur = s.dbuf16[pp]; ldd = ly.in; d_f32 = false; pp ^= 1; }
-        }
+      const float* xin; int ldx;
+      if (l == 0) { xin = bt->dense; ldx = x->num_dense; }
+      else if (l == nb) { xin = s.f; ldx = x->ldf; }
+      else { xin = s.act_f32[l - 1]; ldx = x->layers[l - 1].out; }
+      launch_gemm_f32(dcur, 1, ldd, xin, ldx, 1, s.grads + ly.w_off, ly.in, ly.out, ly.in, B,
+                      EPI_NONE, nullptr, nullptr, 0, st);
+      launch_col_sum_f32(dcur, ldd, B, ly.out, s.grads + ly.b_off, st);
+      if (l != 0) {
+        const bool to_df = (l == nb);            // gradient w.r.t. the interaction output
+        float* out = to_df ? s.df : s.dbuf[pp];
+        const int ldo = to_df ? x->ldf : ly.in;
+        launch_gemm_f32(dcur, ldd, 1, w + ly.w_off, ly.in, 1, out, ldo, B, ly.in, ly.out,
+                        to_df ? EPI_NONE : EPI_MASK, nullptr, to_df ? nullptr : xin, ldx, st);
+        dcur = out; ldd = ldo; pp ^= 1;
       }
     }
   };
   {
     ProfScope ps(x, SS_K_MLP, st);
-    if (bf) launch_fill_f32(s.grads, (uint64_t)x->P, 0.f, st);  // split-K accumulates atomically
-    run_layers(L - 1, nb, s.dlogit, 1, true);
+    run_layers(L - 1, nb, s.dlogit, 1);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_BWD, st);
@@ -1158,7 +1094,7 @@ static void backward_dense(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
   }
   {
     ProfScope ps(x, SS_K_MLP, st);
-    run_layers(nb - 1, 0, s.dz0, x->d, true);
+    run_layers(nb - 1, 0, s.dz0, x->d);
   }
 }
 
@@ -1175,7 +1111,7 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
   float* loss = dev_loss_out ? dev_loss_out : s.loss;
   if (x->fused) forward_fused(x, s, w, bt, loss, train, st);
   else if (x->wide) forward_wide(x, s, w, bt, loss, train, st);
-  else forward(x, s, w, bt, loss, train, st);
+  else forward_f32(x, s, w, bt, loss, train, st);
   if (!fused_last(x)) launch_bce_loss(s.logits, bt->labels, B, loss, train ? s.dlogit : nullptr, st);
   s.last_B = B;
   s.last_n = n;
@@ -1184,7 +1120,7 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
     s.sort_n = n;
     if (x->fused) backward_fused(x, s, w, bt, st);
     else if (x->wide) backward_wide(x, s, w, bt, st);
-    else backward_dense(x, s, w, bt, st);
+    else backward_f32(x, s, w, bt, st);
     // "update local param w^(i)": lock-free SGD on the replica
     launch_sgd(w, s.grads, x->P, x->lr_dense, loss, bt->labels, B, x->metrics, st);
     // "update h": stable sort by row, one Adagrad update per distinct row
@@ -1252,7 +1188,7 @@ int ss_eval_step_static(ss_ctx* ctx, int32_t replica, const ss_batch* batch, voi
   const float* w = ctx->W + (size_t)replica * ctx->Pstride;
   if (ctx->fused) forward_fused(ctx, s, w, batch, dev_loss_out, false, st);
   else if (ctx->wide) forward_wide(ctx, s, w, batch, dev_loss_out, false, st);
-  else forward(ctx, s, w, batch, dev_loss_out, false, st);
+  else forward_f32(ctx, s, w, batch, dev_loss_out, false, st);
   if (!fused_last(ctx)) launch_bce_loss(s.logits, batch->labels, batch->batch, dev_loss_out, nullptr, st);
   launch_metrics(dev_loss_out, batch->labels, batch->batch, ctx->metrics + 4, st);
   return check_hip(ctx, hipGetLastError(), "ss_eval_step_static");

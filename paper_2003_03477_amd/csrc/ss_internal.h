@@ -111,24 +111,16 @@ void launch_sgd(float* w, const float* g, int64_t n, float lr, const float* mean
 // the same accumulation as a launch of its own (evaluation steps)
 void launch_metrics(const float* mean_loss, const float* y, int B, double* acc, hipStream_t s);
 
-// ---------------------------------------------------------------------------- mlp_bf16.hip
-struct GemmBf16Args {
-  const void* A; int a_is_f32; int64_t lda; int a_kcontig;   // A(m,k)
-  const void* B; int b_is_f32; int64_t ldb; int b_kcontig;   // B(n,k)
-  int M, N, K;
-  float* C_f32; uint16_t* C_bf16; int ldc;                   // one of the two outputs
-  int epi; const float* bias; const uint16_t* mask; int ldmask;
-  int split_k;                                               // >1: atomicAdd into C_f32
-  float* row_sum;                                            // [M] (+)= sum_k A(m,k), or null
-};
-void launch_gemm_bf16(const GemmBf16Args& a, hipStream_t s);
+// ---------------------------------------------------------------------------- mlp_last.hip
 // Last top layer (one output unit) fused with the mean log-loss (accumulated into *loss,
 // which must be zero) and its gradient; and the whole backward of that layer.
 void launch_last_layer_fwd_loss(const uint16_t* X, int ldx, const float* w, const float* bias,
                                 const float* y, int B, int in, float* logits, float* dlogit,
                                 float* loss, hipStream_t s);
+// (data gradient either bf16, gated by X > 0, to dX, or fp32 without a gate to dX32)
 void launch_last_layer_bwd(const uint16_t* X, int ldx, const float* w, const float* dlogit, int B,
-                           int in, uint16_t* dX, int lddx, float* gW, float* gb, hipStream_t s);
+                           int in, uint16_t* dX, int lddx, float* dX32, int lddx32, float* gW,
+                           float* gb, hipStream_t s);
 
 // ---------------------------------------------------------------------------- gemm_mfma.hip
 #define SS_NT_MAX_LAYERS 16

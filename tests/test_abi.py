@@ -86,8 +86,8 @@ def test_bench_refuses_more_than_one_gpu():
 
 def test_workspace_layout_covers_the_bf16_mlp_paths():
     """Host-side layout only (no GPU): the fused and the layer-wise bf16 configurations and a
-    model served by the layout-agnostic GEMM all produce a workspace size; an unknown
-    mlp_path is rejected."""
+    model without hidden top layer all produce a workspace size; an unknown mlp_path and a
+    bf16 model too large for 32-bit operand indexing are rejected."""
     from paper_2003_03477_amd import binding, synth
     import ctypes as C
     lib = binding.load()
@@ -104,10 +104,11 @@ def test_workspace_layout_covers_the_bf16_mlp_paths():
     mid = synth.mid()
     fused = size(mid, 0)
     layerwise = size(mid, 1)
-    generic = size(mid.scaled(top_dims=(100, 1)), 0)
-    assert fused > 0 and layerwise > 0 and generic > 0
+    no_hidden = size(mid.scaled(top_dims=(100, 1)), 0)
+    assert fused > 0 and layerwise > 0 and no_hidden > 0
     assert layerwise != fused
     assert size(mid, 7) == 0
+    assert size(mid.scaled(batch=1 << 20, top_dims=(100, 4096, 1)), 0) == 0
 
 
 def test_metrics_and_pace_reject_bad_arguments_without_a_device():

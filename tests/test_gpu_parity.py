@@ -259,9 +259,9 @@ def test_empty_bags_single_sample_and_hot_row():
     H.compare_state(gpu, orc, H.FP32_RTOL, "edge cases", wl.row_base)
 
 
-# The three bf16 MLP code paths: "auto" picks the per-sample-tile fused kernels for these
-# widths, "layerwise" forces one 128x128-tile GEMM per layer and pass; models without a hidden
-# top layer run the layout-agnostic GEMM (test_bf16_no_hidden_top_layer).
+# The two bf16 MLP code paths: "auto" picks the per-sample-tile fused kernels for these
+# widths, "layerwise" forces one 128x128-tile GEMM per layer and pass (also what models
+# outside the fused kernels' limits get: test_bf16_no_hidden_top_layer, the Large architecture).
 @pytest.mark.parametrize("path", ["auto", "layerwise"])
 def test_bf16_mid_scaled(path):
     """Mid CTR architecture (bf16 MLP GEMMs, fp32 master weights) on a compacted table set,
@@ -291,8 +291,9 @@ def test_bf16_odd_widths(path):
 
 
 def test_bf16_no_hidden_top_layer():
-    """A bf16 model whose top MLP is a single linear unit: served by the layout-agnostic GEMM
-    (neither the fused nor the layer-wise kernels apply)."""
+    """A bf16 model whose top MLP is a single linear unit: layer-wise kernels for the bottom
+    stack; the output unit reads the interaction output and hands back an fp32, ungated
+    gradient w.r.t. it."""
     wl = synth.tiny().scaled(batch=130, rows=(3000, 17, 900), emb_dim=32, bag_lambda=4.0,
                              bot_dims=(13, 72, 40, 32), top_dims=(32 + 6, 1),
                              num_replicas=2, bf16=True, algo="easgd", alpha=0.2, sync_gap=2)
