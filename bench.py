@@ -45,6 +45,10 @@ HBM_PEAK_GBS = 8000.0        # MI355X datasheet
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # worker streams per replica when --workers-per-replica is not given
+# worker streams per replica tried by --sweep widths (a Large batch is 50 MB, and no stream
+# may see a batch twice: fewer widths there)
+WIDTHS = {"large": (1, 2, 3, 4, 6), "mid": (1, 2, 4, 6, 8, 12, 16), "tiny": (1, 2, 4, 8),
+          "hogwild": (1, 2, 4, 6, 8, 12, 16)}
 DEFAULT_WORKERS = {"large": "2", "mid": "6", "tiny": "2", "hogwild": "8,1,1,1"}
 
 
@@ -109,7 +113,11 @@ def make_batches(wl, n, fork=True):
     # runs whatever handler a profiler preloaded into the process, which can block)
     pool = mp.get_context("fork").Pool(procs)
     try:
-        out = pool.map(_gen_one, [(gen, s) for s in range(n)], chunksize=1)
+        out = []
+        for k, bt in enumerate(pool.imap(_gen_one, [(gen, s) for s in range(n)], chunksize=1)):
+            out.append(bt)
+            if (k + 1) % 32 == 0:
+                progress(f"{k + 1} of {n} batches generated")
     finally:
         pool.close()
         pool.join()
@@ -161,7 +169,13 @@ def measured_traffic(workload, kernel):
 def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, events=True,
                  shadow_off=True, tag=""):
     """Build a context, run warm-up + timed sweeps (shadow on, then shadow off), return the
-    measurements as a dict.  `workers` = worker streams per replica (list of K ints)."""
+    measurements as a dict.  `workers` = worker streams per replica (list of K ints).
+    With more than one lock-free worker per replica the first two warm-up sweeps run stream
+    after stream: row-wise Adagrad starts from empty accumulators, where every update moves a
+    row by about lr whatever the gradient, and several stale workers doing that to the same hot
+    rows at once is the one moment a lock-free run can blow up (it did in the oracle's
+    max-staleness schedule too).  A trainer spends a vanishing share of its life there; the
+    remaining warm-up sweeps and everything timed run fully concurrent."""
     import numpy as np
     import torch
     from paper_2003_03477_amd import binding, synth
@@ -209,13 +223,25 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
         meet.wait()
         streams[w].wait_event(release[0])
 
-    def worker(w, sweeps, gate):
+    turn = threading.Condition()
+    turn_of = [0]
+
+    def worker(w, sweeps, gate, serial=0):
         gate.wait()
         r = replica_of[w]
-        for _ in range(sweeps):
+        for i in range(sweeps):
             j = done[w]
+            if i < serial:
+                # cold start: the first sweeps run stream after stream (see run_workload's doc)
+                with turn:
+                    turn.wait_for(lambda: turn_of[0] == i * NS + w)
             gpu.ss_train_step(r, w, dev_batches[own[w][j % len(own[w])]], streams[w],
                               losses[w, j:j + 1])
+            if i < serial:
+                streams[w].synchronize()
+                with turn:
+                    turn_of[0] += 1
+                    turn.notify_all()
             done[w] = j + 1
             if fg:
                 if (j + 1) % fg == 0:
@@ -231,11 +257,12 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
                 if due:
                     gpu.ss_shadow_sync(wl.algo, wl.alpha, wl.eta, wl.mu, shadow)
 
-    def region(sweeps):
-        """Run `sweeps` sweeps on all streams; threads are created and parked at a barrier
-        before the clock starts.  Returns seconds."""
+    def region(sweeps, serial=0):
+        """Run `sweeps` sweeps on all streams (the first `serial` of them one stream at a time);
+        threads are created and parked at a barrier before the clock starts.  Returns seconds."""
         gate = threading.Barrier(NS + 1)
-        ts = [threading.Thread(target=worker, args=(w, sweeps, gate)) for w in range(NS)]
+        turn_of[0] = 0
+        ts = [threading.Thread(target=worker, args=(w, sweeps, gate, serial)) for w in range(NS)]
         for t in ts:
             t.start()
         torch.cuda.synchronize()
@@ -271,7 +298,7 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
 
     # ---- warm-up: every stream, every kernel, the shadow loop
     shadow_loop(True)
-    region(warmup)
+    region(warmup, serial=min(2, max(warmup - 1, 0)) if NS > K else 0)
     progress(f"{wl.name}{tag}: warm-up done")
     # ---- timed region, shadow on
     every = max(1, (steps * NS) // 96)
@@ -377,6 +404,7 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
         "shadow_on_over_off": (dt_off / dt_on) if dt_off else None,
         "first_window_logloss": first_win, "last_window_logloss": last_win,
         "diverged": bool(diverged),
+        "logloss_per_sweep": [float(v) for v in host_losses[:, :last_j].mean(axis=0)],
         "train_ne": {"examples": train_ne[0], "logloss": train_ne[1], "ctr": train_ne[2],
                      "ne": train_ne[3]},
         "kernels": kernels, "timed_region_host_clock_ns": clock_on,
@@ -556,7 +584,8 @@ def main():
     if args.sweep != "none":
         # sweeps compare the loss reached, so no stream may see a batch twice: enough distinct
         # batches for the widest configuration (16 workers on each replica, or 8 replicas x 4)
-        widest = {"widths": 16 * K, "gap": 32, "foreground": NS}[args.sweep]
+        gap_w = int(args.workers_per_replica) if (args.workers_per_replica or "").isdigit() else 4
+        widest = {"widths": max(WIDTHS[wl.name]) * K, "gap": 8 * gap_w, "foreground": NS}[args.sweep]
         n_batches = max(n_batches, widest * (args.warmup + args.steps))
     n_batches = (n_batches + NS - 1) // NS * NS
     # inputs first: batch generation forks worker processes, which must precede any GPU use
@@ -594,6 +623,7 @@ def main():
             "shadow_rounds": res["shadow_rounds"], "avg_sync_gap": res["avg_sync_gap"],
             "first_window_logloss": res["first_window_logloss"],
             "last_window_logloss": res["last_window_logloss"], "diverged": res["diverged"],
+            "logloss_per_sweep": res["logloss_per_sweep"],
             "train_ne": res["train_ne"], "input_generation_seconds": t_gen,
             "timed_region_host_clock_ns": res["timed_region_host_clock_ns"],
         },
@@ -605,7 +635,7 @@ def main():
     }
     if args.sweep == "widths":
         table = []
-        for w in (1, 2, 4, 6, 8, 12, 16):
+        for w in WIDTHS[wl.name]:
             ws = [w] * K
             need = sum(ws)
             hb = host_batches if len(host_batches) >= need else None
@@ -625,7 +655,7 @@ def main():
         table = []
         for k in (2, 4, 8):
             wk = wl.scaled(num_replicas=k)
-            ws = parse_workers(args.workers_per_replica or "4", k)
+            ws = parse_workers(str(gap_w), k)
             for period in (0, 200, 1000):
                 args.shadow_period_us = period
                 r = run_workload(args, wk, ws, "continuous", args.steps, args.warmup, host_batches,
