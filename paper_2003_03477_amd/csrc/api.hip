@@ -795,14 +795,15 @@ static void fill_stack(const ss_ctx* x, const Slot& s, const float* w, int l0, i
   }
 }
 
-static void launch_weight_snapshot(ss_ctx* x, Slot& s, const float* w, bool train, hipStream_t st);
+static void launch_weight_snapshot(ss_ctx* x, Slot& s, const float* w, bool train,
+                                   const ss_batch* cast_dense, hipStream_t st);
 
 static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, float* loss,
                           bool train, hipStream_t st) {
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers, nh = x->n_top_layers - 1;
   {
     ProfScope ps(x, SS_K_MLP, st);
-    launch_weight_snapshot(x, s, w, train, st);
+    launch_weight_snapshot(x, s, w, train, nullptr, st);
     FusedFwdArgs a{};
     a.n_layers = nb; fill_stack(x, s, w, 0, nb, a.L);
     a.B = B; a.ldT = x->ldT;
@@ -859,7 +860,7 @@ static void backward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
   }
   {
     ProfScope ps(x, SS_K_INTERACT_BWD, st);
-    launch_interaction_bwd(s.z0, s.e, s.df, x->ldf, B, x->T, x->d, s.dz0, s.de, st);
+    launch_interaction_bwd(s.z0, s.e, s.df, x->ldf, B, x->T, x->d, s.dz0, s.de, nullptr, 0, st);
   }
   {
     ProfScope ps(x, SS_K_MLP, st);
@@ -887,7 +888,8 @@ static void backward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* b
 // ---- layer-wise path ------------------------------------------------------------------------
 // this step's snapshot of the replica: bf16, MFMA fragment order, both products (also clears
 // the step's gradient accumulator when training)
-static void launch_weight_snapshot(ss_ctx* x, Slot& s, const float* w, bool train, hipStream_t st) {
+static void launch_weight_snapshot(ss_ctx* x, Slot& s, const float* w, bool train,
+                                   const ss_batch* cast_dense, hipStream_t st) {
   const int nl = (int)x->layers.size() - 1;
   PrepArgs pa{};
   pa.n_layers = nl;
@@ -904,6 +906,10 @@ static void launch_weight_snapshot(ss_ctx* x, Slot& s, const float* w, bool trai
   }
   pa.total_frags = base;
   pa.zero = train ? s.grads : nullptr; pa.zero_n = x->P;
+  if (cast_dense) {   // layer-wise path: the dense input as bf16 rows of the first GEMM's pitch
+    pa.cast_src = cast_dense->dense; pa.cast_dst = s.xb;
+    pa.cast_rows = cast_dense->batch; pa.cast_cols = x->num_dense; pa.cast_ld = x->pin[0];
+  }
   launch_mlp_prep(pa, st);
 }
 
@@ -922,8 +928,7 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
   };
   {
     ProfScope ps(x, SS_K_MLP, st);
-    launch_weight_snapshot(x, s, w, train, st);
-    launch_cast_rows(bt->dense, x->num_dense, B, x->num_dense, s.xb, x->pin[0], st);
+    launch_weight_snapshot(x, s, w, train, bt, st);
     const uint16_t* in = s.xb; int ld_in = x->pin[0];
     for (int l = 0; l < nb; ++l) {
       layer_fwd(l, in, ld_in);
@@ -948,8 +953,21 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
       in = s.act_bf16[l]; ld_in = x->pout[l];
     }
     const Layer& last = x->layers[L - 1];
-    launch_last_layer_fwd_loss(in, ld_in, w + last.w_off, w + last.b_off, bt->labels, B, last.in,
-                               s.logits, train ? s.dlogit : nullptr, loss, st);
+    if (!train) {
+      launch_last_layer_fwd_loss(in, ld_in, w + last.w_off, w + last.b_off, bt->labels, B, last.in,
+                                 s.logits, nullptr, loss, st);
+    } else if (L - 1 == nb) {
+      // training: the output unit's forward, loss and backward are one launch.  Without a
+      // hidden top layer it reads the interaction output and its data gradient is the fp32
+      // gradient w.r.t. that output (no gate: f is no ReLU output)
+      launch_last_layer_train(in, ld_in, w + last.w_off, w + last.b_off, bt->labels, B, last.in,
+                              s.logits, s.dlogit, loss, nullptr, 0, s.df, x->ldf,
+                              s.grads + last.w_off, s.grads + last.b_off, st);
+    } else {
+      launch_last_layer_train(in, ld_in, w + last.w_off, w + last.b_off, bt->labels, B, last.in,
+                              s.logits, s.dlogit, loss, s.dYr[L - 2], x->pout[L - 2], nullptr, 0,
+                              s.grads + last.w_off, s.grads + last.b_off, st);
+    }
   }
 }
 
@@ -971,27 +989,16 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
   };
   {
     ProfScope ps(x, SS_K_MLP, st);  // (the gradient accumulator was cleared by the weight snapshot)
-    const Layer& last = x->layers[L - 1];
-    if (L - 1 == nb) {
-      // no hidden top layer: the output unit reads the interaction output, its data gradient
-      // is the fp32 gradient w.r.t. that output (no gate: f is no ReLU output)
-      launch_last_layer_bwd(s.f_bf16, x->ldf16, w + last.w_off, s.dlogit, B, last.in, nullptr, 0,
-                            s.df, x->ldf, s.grads + last.w_off, s.grads + last.b_off, st);
-    } else {
-      const int ld = x->pout[L - 2];
-      launch_last_layer_bwd(s.act_bf16[L - 2], ld, w + last.w_off, s.dlogit, B, last.in,
-                            s.dYr[L - 2], ld, nullptr, 0, s.grads + last.w_off,
-                            s.grads + last.b_off, st);
-    }
+    // (the output unit's backward ran with its forward: launch_last_layer_train)
     for (int l = L - 2; l >= nb; --l) layer_dgrad(l);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_BWD, st);
-    launch_interaction_bwd(s.z0, s.e, s.df, x->ldf, B, x->T, x->d, s.dz0, s.de, st);
+    launch_interaction_bwd(s.z0, s.e, s.df, x->ldf, B, x->T, x->d, s.dz0, s.de,
+                           s.dYr[nb - 1], x->pout[nb - 1], st);
   }
   {
     ProfScope ps(x, SS_K_MLP, st);
-    launch_cast_rows(s.dz0, x->d, B, x->d, s.dYr[nb - 1], x->pout[nb - 1], st);
     for (int l = nb - 1; l >= 1; --l) layer_dgrad(l);
     // weight and bias gradients of every layer but the one-unit output layer: one grouped
     // launch over (layer, tile, batch slice), then one launch that adds the slices up
@@ -1090,7 +1097,7 @@ static void backward_f32(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
   }
   {
     ProfScope ps(x, SS_K_INTERACT_BWD, st);
-    launch_interaction_bwd(s.z0, s.e, s.df, x->ldf, B, x->T, x->d, s.dz0, s.de, st);
+    launch_interaction_bwd(s.z0, s.e, s.df, x->ldf, B, x->T, x->d, s.dz0, s.de, nullptr, 0, st);
   }
   {
     ProfScope ps(x, SS_K_MLP, st);

@@ -24,6 +24,7 @@ __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
     float* __restrict__ zero_scalar, float* __restrict__ inv_len, int n_shards) {
   constexpr int D = LPR * 4;
   constexpr int RPW = SS_WAVE / LPR;  // rows per wave-wide load
+  constexpr int NIF = 8;              // row loads in flight per lane
   const int shard = SHARDED ? blockIdx.y : 0;
   // the step's loss accumulator is cleared here, ahead of the kernel that adds into it
   if (zero_scalar && blockIdx.x == 0 && shard == 0 && threadIdx.x == 0) *zero_scalar = 0.f;
@@ -65,21 +66,25 @@ __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
     }
     const bool mine = !SHARDED || (lrow >= s_lo && lrow < s_hi);
     const int cnt = min(SS_WAVE, hi - j0);
-    // trip count is wave-uniform so every lane takes part in every permute
-    for (int it = 0; it < cnt; it += 2 * RPW) {
-      const int ja = it + sub, jb = it + RPW + sub;
-      const uint32_t ra = (uint32_t)__shfl((int)grow, ja & 63);
-      const uint32_t rb = (uint32_t)__shfl((int)grow, jb & 63);
-      bool ma = true, mb = true;
-      if (SHARDED) {
-        ma = __shfl((int)mine, ja & 63) != 0;
-        mb = __shfl((int)mine, jb & 63) != 0;
+    // trip count is wave-uniform so every lane takes part in every permute; NIF row loads per
+    // lane are issued before the first is consumed (a bag of up to NIF * RPW ids is one round
+    // trip to memory instead of one per pair of loads)
+    for (int it = 0; it < cnt; it += NIF * RPW) {
+      float4 v[NIF];
+#pragma unroll
+      for (int u = 0; u < NIF; ++u) {
+        const int ju = it + u * RPW + sub;
+        const uint32_t ru = (uint32_t)__shfl((int)grow, ju & 63);
+        bool mu = true;
+        if (SHARDED) mu = __shfl((int)mine, ju & 63) != 0;
+        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ju < cnt && mu) v[u] = *(const float4*)(h + (size_t)ru * D + c4 * 4);
       }
-      float4 va = {0.f, 0.f, 0.f, 0.f}, vb = {0.f, 0.f, 0.f, 0.f};
-      if (ja < cnt && ma) va = *(const float4*)(h + (size_t)ra * D + c4 * 4);
-      if (jb < cnt && mb) vb = *(const float4*)(h + (size_t)rb * D + c4 * 4);
-      acc0.x += va.x; acc0.y += va.y; acc0.z += va.z; acc0.w += va.w;
-      acc1.x += vb.x; acc1.y += vb.y; acc1.z += vb.z; acc1.w += vb.w;
+#pragma unroll
+      for (int u = 0; u < NIF; u += 2) {
+        acc0.x += v[u].x; acc0.y += v[u].y; acc0.z += v[u].z; acc0.w += v[u].w;
+        acc1.x += v[u + 1].x; acc1.y += v[u + 1].y; acc1.z += v[u + 1].z; acc1.w += v[u + 1].w;
+      }
     }
   }
   float4 acc = {acc0.x + acc1.x, acc0.y + acc1.y, acc0.z + acc1.z, acc0.w + acc1.w};

@@ -523,36 +523,11 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(ReduceArgs a) {
   }
 }
 
-// fp32 rows -> bf16 rows with a zero-padded pitch: in [M][ld_in] (N valid columns), out
-// [M][ld_out], ld_out a multiple of 8.  One thread per 8 output elements.
-__global__ __launch_bounds__(256) void cast_rows_kernel(const float* __restrict__ in, int ld_in,
-                                                        int M, int N, uint16_t* __restrict__ out,
-                                                        int ld_out) {
-  const int per_row = ld_out >> 3;
-  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (v >= (int64_t)M * per_row) return;
-  const int m = (int)(v / per_row), c = (int)(v - (int64_t)m * per_row) * 8;
-  const float* p = in + (size_t)m * ld_in + c;
-  float e[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) e[j] = (c + j < N) ? p[j] : 0.f;
-  *(uint4*)(out + (size_t)m * ld_out + c) =
-      make_uint4(pk2(e[0], e[1]), pk2(e[2], e[3]), pk2(e[4], e[5]), pk2(e[6], e[7]));
-}
-
 }  // namespace
 
 void launch_reduce_slices(const ReduceArgs& a, int total_blocks, hipStream_t s) {
   if (total_blocks > 0)
     hipLaunchKernelGGL(reduce_slices_kernel, dim3(total_blocks), dim3(256), 0, s, a);
-}
-
-void launch_cast_rows(const float* in, int ld_in, int M, int N, uint16_t* out, int ld_out,
-                      hipStream_t s) {
-  if (M <= 0 || N <= 0) return;
-  const int64_t n = (int64_t)M * (ld_out >> 3);
-  hipLaunchKernelGGL(cast_rows_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, in, ld_in,
-                     M, N, out, ld_out);
 }
 
 void launch_gemm_xw(const GemmXwArgs& a, hipStream_t s) {

@@ -82,7 +82,8 @@ __global__ __launch_bounds__(256) void interaction_fwd_kernel(
 
 __global__ __launch_bounds__(256) void interaction_bwd_kernel(
     const float* __restrict__ z0, const float* __restrict__ e, const float* __restrict__ df,
-    int lddf, int B, int T, int d, float* __restrict__ dz0, float* __restrict__ de) {
+    int lddf, int B, int T, int d, float* __restrict__ dz0, float* __restrict__ de,
+    uint16_t* __restrict__ dz0_bf16, int ld16) {
   extern __shared__ float smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ld = d + IPAD;
@@ -123,10 +124,17 @@ __global__ __launch_bounds__(256) void interaction_bwd_kernel(
           o.z = z.z > 0.f ? acc.z + pass.z : 0.f;
           o.w = z.w > 0.f ? acc.w + pass.w : 0.f;
           *(float4*)(dz0 + (size_t)b * d + 4 * k4) = o;
+          if (dz0_bf16) {  // the same values as the bottom stack's bf16 GEMM operand
+            uint16_t* q = dz0_bf16 + (size_t)b * ld16 + 4 * k4;
+            *(uint2*)q = make_uint2((uint32_t)f32_to_bf16(o.x) | ((uint32_t)f32_to_bf16(o.y) << 16),
+                                    (uint32_t)f32_to_bf16(o.z) | ((uint32_t)f32_to_bf16(o.w) << 16));
+          }
         } else {
           *(float4*)(de + ((size_t)b * T + (r - 1)) * d + 4 * k4) = acc;
         }
       }
+      if (dz0_bf16)   // zero padding of the operand row
+        for (int k = d + lane; k < ld16; k += SS_WAVE) dz0_bf16[(size_t)b * ld16 + k] = 0;
     }
     __syncthreads();
   }
@@ -143,14 +151,15 @@ void launch_interaction_fwd(const float* z0, const float* e, int B, int T, int d
 }
 
 void launch_interaction_bwd(const float* z0, const float* e, const float* df, int lddf, int B,
-                            int T, int d, float* dz0, float* de, hipStream_t s) {
+                            int T, int d, float* dz0, float* de, uint16_t* dz0_bf16, int ld16,
+                            hipStream_t s) {
   if (B == 0) return;
   const int n1 = T + 1;
   const size_t shm = (size_t)4 * (n1 * (d + IPAD) + ((n1 * n1 + 3) & ~3)) * sizeof(float);
   int blocks = ceil_div(B, 4);
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(interaction_bwd_kernel, dim3(blocks), dim3(256), shm, s, z0, e, df, lddf, B,
-                     T, d, dz0, de);
+                     T, d, dz0, de, dz0_bf16, ld16);
 }
 
 }  // namespace ss

@@ -124,6 +124,13 @@ __global__ __launch_bounds__(256) void mlp_prep_kernel(PrepArgs g) {
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t i = v; i < g.zero_n; i += stride) g.zero[i] = 0.f;
   }
+  if (g.cast_dst) {
+    const int64_t stride = (int64_t)gridDim.x * 256, n = (int64_t)g.cast_rows * g.cast_ld;
+    for (int64_t i = v; i < n; i += stride) {
+      const int r = (int)(i / g.cast_ld), c = (int)(i - (int64_t)r * g.cast_ld);
+      g.cast_dst[i] = (c < g.cast_cols) ? f2b(g.cast_src[(size_t)r * g.cast_cols + c]) : (uint16_t)0;
+    }
+  }
   if (v >= g.total_frags) return;
   int l = 0;
   while (l + 1 < g.n_layers && v >= g.L[l + 1].frag_base) ++l;

@@ -76,22 +76,63 @@ void launch_last_layer_fwd_loss(const uint16_t* X, int ldx, const float* w, cons
                      bias, y, B, in, logits, dlogit, loss);
 }
 
-// Backward of that layer in one pass over X: dX[b,k] = q(dlogit_b) q(w_k), stored as bf16 and
-// gated by X[b,k] > 0 when X is the output of a hidden layer (dX), or as fp32 without a gate
-// when X is the interaction output (dX32; a model without hidden top layer);
-// gW[k] += sum_b q(dlogit_b) X[b,k], gb += sum_b dlogit_b.  A block owns LAST_ROWS_PB samples.
+// Training step.  Forward as above plus the layer's whole backward in the same launch:
+// dX[b,k] = q(dlogit_b) q(w_k), stored as bf16 and gated by X[b,k] > 0 when X is the output of
+// a hidden layer (dX), or as fp32 without a gate when X is the interaction output (dX32; a
+// model without hidden top layer); gW[k] += sum_b q(dlogit_b) X[b,k], gb += sum_b dlogit_b.
 constexpr int LAST_ROWS_PB = 32;
-__global__ __launch_bounds__(256) void last_layer_bwd_kernel(
+// A block owns LAST_ROWS_PB samples: 8 lanes per sample compute the logit, the loss term and
+// dL/dlogit, which stay in LDS for the block's backward pass over the same (cache-resident)
+// rows of X.
+__global__ __launch_bounds__(256) void last_layer_train_kernel(
     const uint16_t* __restrict__ X, int ldx, const float* __restrict__ w,
-    const float* __restrict__ dlogit, int B, int in, uint16_t* __restrict__ dX, int lddx,
-    float* __restrict__ dX32, int lddx32, float* __restrict__ gW, float* __restrict__ gb) {
-  __shared__ float dl[LAST_ROWS_PB], dlq[LAST_ROWS_PB];
+    const float* __restrict__ bias, const float* __restrict__ y, int B, int in,
+    float* __restrict__ logits, float* __restrict__ dlogit, float* __restrict__ loss,
+    uint16_t* __restrict__ dX, int lddx, float* __restrict__ dX32, int lddx32,
+    float* __restrict__ gW, float* __restrict__ gb) {
+  static_assert(LAST_ROWS_PB * 8 == 256, "8 lanes per sample");
+  __shared__ float dl[LAST_ROWS_PB], dlq[LAST_ROWS_PB], lossv[LAST_ROWS_PB];
   const int b0 = blockIdx.x * LAST_ROWS_PB;
   const int nb = min(LAST_ROWS_PB, B - b0);
-  if (threadIdx.x < LAST_ROWS_PB) {
-    const float v = ((int)threadIdx.x < nb) ? dlogit[b0 + threadIdx.x] : 0.f;
-    dl[threadIdx.x] = v;
-    dlq[threadIdx.x] = bf16_to_f32(to_bf16(v));
+  {
+    const int sub = threadIdx.x & 7, sl = threadIdx.x >> 3;
+    const int b = b0 + sl;
+    float s = 0.f;
+    if (sl < nb) {
+      const uint16_t* xr = X + (size_t)b * ldx;
+      for (int k = sub * 8; k < in; k += 64) {
+        if (k + 8 <= in && ((((uintptr_t)(xr + k)) & 15) == 0)) {
+          const uint4 xv = *(const uint4*)(xr + k);
+          const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float xf = bf16_to_f32((uint16_t)(xw[j >> 1] >> ((j & 1) * 16)));
+            s += xf * bf16_to_f32(to_bf16(w[k + j]));
+          }
+        } else {
+          for (int j = 0; j < 8 && k + j < in; ++j)
+            s += bf16_to_f32(xr[k + j]) * bf16_to_f32(to_bf16(w[k + j]));
+        }
+      }
+    }
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) s += __shfl_xor(s, off);
+    if (sub == 0) {
+      float lv = 0.f, d = 0.f;
+      if (sl < nb) {
+        const float invB = 1.0f / (float)B;
+        const float l = s + bias[0], t = y[b];
+        const float ex = expf(-fabsf(l));
+        lv = fmaxf(l, 0.f) - l * t + log1pf(ex);
+        const float p = (l >= 0.f) ? 1.0f / (1.0f + ex) : ex / (1.0f + ex);
+        d = (p - t) * invB;
+        logits[b] = l;
+        dlogit[b] = d;
+      }
+      lossv[sl] = lv;
+      dl[sl] = d;
+      dlq[sl] = bf16_to_f32(to_bf16(d));
+    }
   }
   __syncthreads();
   for (int k = threadIdx.x; k < in; k += 256) {
@@ -107,17 +148,19 @@ __global__ __launch_bounds__(256) void last_layer_bwd_kernel(
     atomicAdd(gW + k, acc);
   }
   if (threadIdx.x == 0) {
-    float sb = 0.f;
-    for (int r = 0; r < nb; ++r) sb += dl[r];
+    float sb = 0.f, tot = 0.f;
+    for (int r = 0; r < nb; ++r) { sb += dl[r]; tot += lossv[r]; }
     atomicAdd(gb, sb);
+    atomicAdd(loss, tot * (1.0f / (float)B));
   }
 }
 
-void launch_last_layer_bwd(const uint16_t* X, int ldx, const float* w, const float* dlogit, int B,
-                           int in, uint16_t* dX, int lddx, float* dX32, int lddx32, float* gW,
-                           float* gb, hipStream_t s) {
-  hipLaunchKernelGGL(last_layer_bwd_kernel, dim3(ceil_div(B, LAST_ROWS_PB)), dim3(256), 0, s, X,
-                     ldx, w, dlogit, B, in, dX, lddx, dX32, lddx32, gW, gb);
+void launch_last_layer_train(const uint16_t* X, int ldx, const float* w, const float* bias,
+                             const float* y, int B, int in, float* logits, float* dlogit,
+                             float* loss, uint16_t* dX, int lddx, float* dX32, int lddx32,
+                             float* gW, float* gb, hipStream_t s) {
+  hipLaunchKernelGGL(last_layer_train_kernel, dim3(ceil_div(B, LAST_ROWS_PB)), dim3(256), 0, s, X,
+                     ldx, w, bias, y, B, in, logits, dlogit, loss, dX, lddx, dX32, lddx32, gW, gb);
 }
 
 }  // namespace ss

@@ -88,9 +88,11 @@ void launch_sort_pairs(const uint32_t* keys, const uint32_t* vals, uint32_t n, i
 // row) and, if f_bf16 != nullptr, a bf16 copy with row stride ldf_bf16 (zero padded).
 void launch_interaction_fwd(const float* z0, const float* e, int B, int T, int d, float* f,
                             int ldf, uint16_t* f_bf16, int ldf_bf16, hipStream_t s);
-// dz0 (masked by z0 > 0) and de from df.
+// dz0 (masked by z0 > 0) and de from df; dz0_bf16 (optional): dz0 once more as bf16 rows of
+// pitch ld16 (a multiple of 4, zero padded).
 void launch_interaction_bwd(const float* z0, const float* e, const float* df, int lddf, int B,
-                            int T, int d, float* dz0, float* de, hipStream_t s);
+                            int T, int d, float* dz0, float* de, uint16_t* dz0_bf16, int ld16,
+                            hipStream_t s);
 
 // ---------------------------------------------------------------------------- mlp_fp32.hip
 enum : int { EPI_NONE = 0, EPI_BIAS = 1, EPI_RELU = 2, EPI_MASK = 4 };
@@ -113,15 +115,16 @@ void launch_metrics(const float* mean_loss, const float* y, int B, double* acc, 
 
 // ---------------------------------------------------------------------------- mlp_last.hip
 // Last top layer (one output unit) fused with the mean log-loss (accumulated into *loss,
-// which must be zero) and its gradient; and the whole backward of that layer.
+// which must be zero) and its gradient.
 void launch_last_layer_fwd_loss(const uint16_t* X, int ldx, const float* w, const float* bias,
                                 const float* y, int B, int in, float* logits, float* dlogit,
                                 float* loss, hipStream_t s);
-// (data gradient either bf16, gated by X > 0, to dX, or fp32 without a gate to dX32)
-void launch_last_layer_bwd(const uint16_t* X, int ldx, const float* w, const float* dlogit, int B,
-                           int in, uint16_t* dX, int lddx, float* dX32, int lddx32, float* gW,
-                           float* gb, hipStream_t s);
-
+// forward, loss and the layer's whole backward in one launch (training steps); the data
+// gradient goes either as bf16, gated by X > 0, to dX, or as fp32 without a gate to dX32
+void launch_last_layer_train(const uint16_t* X, int ldx, const float* w, const float* bias,
+                             const float* y, int B, int in, float* logits, float* dlogit,
+                             float* loss, uint16_t* dX, int lddx, float* dX32, int lddx32,
+                             float* gW, float* gb, hipStream_t s);
 // ---------------------------------------------------------------------------- gemm_mfma.hip
 #define SS_NT_MAX_LAYERS 16
 // C[M,N] = A[M,K] W^T (+ bias, ReLU, gate): A bf16 row-major with K (a multiple of 64) finite
@@ -161,9 +164,6 @@ void launch_gemm_wgrad(const WgradGroupArgs& a, hipStream_t s);
 struct ReduceSegment { const float* part; float* out; int64_t n, stride; int slices; int block_base; };
 struct ReduceArgs { ReduceSegment seg[16]; int n_seg; };
 void launch_reduce_slices(const ReduceArgs& a, int total_blocks, hipStream_t s);
-// fp32 [M][ld_in] (N valid columns) -> bf16 [M][ld_out] (zero padded; ld_out a multiple of 8)
-void launch_cast_rows(const float* in, int ld_in, int M, int N, uint16_t* out, int ld_out,
-                      hipStream_t s);
 
 // ---------------------------------------------------------------------------- mlp_fused.hip
 #define SS_FUSED_MAX_LAYERS 8
@@ -190,6 +190,11 @@ struct PrepArgs {
   int64_t total_frags;
   float* zero;      // optional: zero_n floats cleared by the same launch
   int64_t zero_n;
+  // optional: fp32 rows [cast_rows][cast_cols] -> bf16 rows of pitch cast_ld, zero padded (the
+  // dense input as the first GEMM's operand)
+  const float* cast_src;
+  uint16_t* cast_dst;
+  int cast_rows, cast_cols, cast_ld;
 };
 void launch_mlp_prep(const PrepArgs& a, hipStream_t s);
 struct FusedFwdArgs {
