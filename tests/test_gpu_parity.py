@@ -553,3 +553,17 @@ def test_profile_brackets_and_sampling():
     with pytest.raises(binding.ShadowSyncError):
         gpu.ss_profile_sample(0)
     gpu.close()
+
+
+def test_many_small_tables():
+    """33 small tables of 60 rows (561 interaction pairs per sample, every row hit many times
+    per step): the fp32 lockstep on a shape far from the configured workloads."""
+    T = 33
+    wl = synth.tiny().scaled(batch=40, rows=(60,) * T, emb_dim=16, bag_lambda=2.0,
+                             bot_dims=(13, 24, 16), top_dims=(16 + T * (T + 1) // 2, 32, 1),
+                             num_replicas=1, algo="ma", alpha=1.0)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(3)]
+    gpu, orc = H.make_pair(wl, batches)
+    H.run_lockstep(gpu, orc, batches, 1, "ma", 1.0)
+    H.compare_state(gpu, orc, H.FP32_RTOL, "33 tables", wl.row_base)
