@@ -971,7 +971,9 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
   }
 }
 
-static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, hipStream_t st) {
+static void backward_wide(ss_ctx* x, Slot& s, float* w_rw, const float* loss, const ss_batch* bt,
+                          hipStream_t st) {
+  const float* w = w_rw;
   const int B = bt->batch, L = (int)x->layers.size(), nb = x->n_bot_layers;
   // gradient w.r.t. the input of layer l from the gradient w.r.t. its output (dYr[l])
   auto layer_dgrad = [&](int l) {
@@ -1022,6 +1024,16 @@ static void backward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
     }
     g.tiles = x->wgrad_tiles_dev; g.n_tiles = (int)x->wgrad_tiles.size(); g.B = B;
     { ProfScope pk(x, SS_K_MLP_WGRAD, st); launch_gemm_wgrad(g, st); }
+    // the reduction is also the step's SGD update of the replica ("update local param w^(i)":
+    // lock-free) and feeds the Train-NE accumulators; the output unit's gradients, complete
+    // since its own launch, ride along as a one-slice segment
+    const Layer& last = x->layers[L - 1];
+    ReduceSegment& lg = red.seg[red.n_seg++];
+    lg.part = s.grads + last.w_off; lg.out = s.grads + last.w_off; lg.n = (int64_t)last.in + 1;
+    lg.stride = 0; lg.slices = 1; lg.block_base = red_blocks;
+    red_blocks += ceil_div(lg.n, 1024);
+    for (int k = 0; k < red.n_seg; ++k) red.seg[k].w = w_rw + (red.seg[k].out - s.grads);
+    red.lr = x->lr_dense; red.mean_loss = loss; red.y = bt->labels; red.B = B; red.acc = x->metrics;
     launch_reduce_slices(red, red_blocks, st);
   }
 }
@@ -1126,10 +1138,11 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
   if (train) {
     s.sort_n = n;
     if (x->fused) backward_fused(x, s, w, bt, st);
-    else if (x->wide) backward_wide(x, s, w, bt, st);
+    else if (x->wide) backward_wide(x, s, w, loss, bt, st);
     else backward_f32(x, s, w, bt, st);
-    // "update local param w^(i)": lock-free SGD on the replica
-    launch_sgd(w, s.grads, x->P, x->lr_dense, loss, bt->labels, B, x->metrics, st);
+    // "update local param w^(i)": lock-free SGD on the replica (the layer-wise path's last
+    // kernel has already applied it)
+    if (!x->wide) launch_sgd(w, s.grads, x->P, x->lr_dense, loss, bt->labels, B, x->metrics, st);
     // "update h": stable sort by row, one Adagrad update per distinct row
     {
       ProfScope ps(x, SS_K_SORT, st);

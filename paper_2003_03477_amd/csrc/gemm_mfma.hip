@@ -493,14 +493,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 }
 
-// out[i] = sum over the slices of part[z * stride + i]; 1024 elements per block
-__global__ __launch_bounds__(256) void reduce_slices_kernel(ReduceArgs a) {
+// out[i] = sum over the slices of part[z * stride + i] (and the SGD step on w); 1024 elements
+// per block; the block after the last segment's feeds the metrics accumulators
+__global__ __launch_bounds__(256) void reduce_slices_kernel(ReduceArgs a, int total_blocks) {
+  if ((int)blockIdx.x == total_blocks) {
+    metrics_block(a.mean_loss, a.y, a.B, a.acc);
+    return;
+  }
   int k = 0;
   while (k + 1 < a.n_seg && (int)blockIdx.x >= a.seg[k + 1].block_base) ++k;
   const ReduceSegment sg = a.seg[k];
   const int64_t base = (int64_t)(blockIdx.x - sg.block_base) * 1024;
   const bool vec = ((sg.n & 3) == 0) && ((sg.stride & 3) == 0) && ((((uintptr_t)sg.out) & 15) == 0) &&
-                   ((((uintptr_t)sg.part) & 15) == 0);
+                   ((((uintptr_t)sg.part) & 15) == 0) && ((((uintptr_t)sg.w) & 15) == 0);
   if (vec) {
     const int64_t i = base + threadIdx.x * 4;
     if (i >= sg.n) return;
@@ -510,6 +515,11 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(ReduceArgs a) {
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
     *(float4*)(sg.out + i) = acc;
+    if (sg.w) {
+      float4 wv = *(const float4*)(sg.w + i);
+      wv.x -= a.lr * acc.x; wv.y -= a.lr * acc.y; wv.z -= a.lr * acc.z; wv.w -= a.lr * acc.w;
+      *(float4*)(sg.w + i) = wv;
+    }
   } else {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -518,6 +528,7 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(ReduceArgs a) {
         float acc = sg.part[i];
         for (int z = 1; z < sg.slices; ++z) acc += sg.part[(int64_t)z * sg.stride + i];
         sg.out[i] = acc;
+        if (sg.w) sg.w[i] -= a.lr * acc;
       }
     }
   }
@@ -527,7 +538,8 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(ReduceArgs a) {
 
 void launch_reduce_slices(const ReduceArgs& a, int total_blocks, hipStream_t s) {
   if (total_blocks > 0)
-    hipLaunchKernelGGL(reduce_slices_kernel, dim3(total_blocks), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(reduce_slices_kernel, dim3(total_blocks + (a.acc ? 1 : 0)), dim3(256), 0, s,
+                       a, total_blocks);
 }
 
 void launch_gemm_xw(const GemmXwArgs& a, hipStream_t s) {

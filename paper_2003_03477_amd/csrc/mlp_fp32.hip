@@ -128,24 +128,6 @@ void launch_bce_loss(const float* logit, const float* y, int B, float* loss, flo
   hipLaunchKernelGGL(bce_loss_kernel, dim3(1), dim3(1024), 0, s, logit, y, B, loss, dlogit);
 }
 
-// Running sums behind the normalised entropy (Section 4, "Evaluation Metrics"): one block adds
-// the batch's summed log-loss (mean * B), its number of positive labels and B to three doubles.
-__device__ __forceinline__ void metrics_block(const float* __restrict__ mean_loss,
-                                              const float* __restrict__ y, int B,
-                                              double* __restrict__ acc) {
-  __shared__ float part[4];
-  float s = 0.f;
-  for (int b = threadIdx.x; b < B; b += 256) s += y[b];
-  for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    atomicAdd(acc + 0, (double)mean_loss[0] * (double)B);
-    atomicAdd(acc + 1, (double)((part[0] + part[1]) + (part[2] + part[3])));
-    atomicAdd(acc + 2, (double)B);
-  }
-}
-
 __global__ __launch_bounds__(256) void metrics_kernel(const float* __restrict__ mean_loss,
                                                       const float* __restrict__ y, int B,
                                                       double* __restrict__ acc) {

@@ -157,10 +157,10 @@ __global__ __launch_bounds__(256) void row_update_chunk_kernel(
       for (int i = 0; i < SUB; ++i) {
         const int p = s0 + i;
         const int bg = __shfl(bag, p, LPR);
-        rw[i] = (uint32_t)__shfl((int)key, p, LPR);
         v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
         hv[i] = v[i];
         Gv[i] = 0.f;
+        rw[i] = 0;
         if (p < nv) {
           v[i] = *(const float4*)(de + (size_t)bg * D + c * 4);
           if (inv_len) {  // mean pooling: d(mean)/d(member) = 1 / bag length
@@ -168,6 +168,9 @@ __global__ __launch_bounds__(256) void row_update_chunk_kernel(
             v[i].x *= sc; v[i].y *= sc; v[i].z *= sc; v[i].w *= sc;
           }
           if ((tm >> p) & 1u) {
+            // (the row is only needed where a run ends; the condition is uniform over the
+            // group's lanes, which is all the permute reads from)
+            rw[i] = (uint32_t)__shfl((int)key, p, LPR);
             hv[i] = load_row_nt(h + (size_t)rw[i] * D + c * 4);
             Gv[i] = G[rw[i]];
           }

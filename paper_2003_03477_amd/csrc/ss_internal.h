@@ -113,6 +113,24 @@ void launch_sgd(float* w, const float* g, int64_t n, float lr, const float* mean
 // the same accumulation as a launch of its own (evaluation steps)
 void launch_metrics(const float* mean_loss, const float* y, int B, double* acc, hipStream_t s);
 
+// Running sums behind the normalised entropy (Section 4, "Evaluation Metrics"): one block adds
+// the batch's summed log-loss (mean * B), its number of positive labels and B to three doubles.
+__device__ __forceinline__ void metrics_block(const float* __restrict__ mean_loss,
+                                              const float* __restrict__ y, int B,
+                                              double* __restrict__ acc) {
+  __shared__ float part[4];
+  float s = 0.f;
+  for (int b = threadIdx.x; b < B; b += 256) s += y[b];
+  for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    atomicAdd(acc + 0, (double)mean_loss[0] * (double)B);
+    atomicAdd(acc + 1, (double)((part[0] + part[1]) + (part[2] + part[3])));
+    atomicAdd(acc + 2, (double)B);
+  }
+}
+
 // ---------------------------------------------------------------------------- mlp_last.hip
 // Last top layer (one output unit) fused with the mean log-loss (accumulated into *loss,
 // which must be zero) and its gradient.
@@ -161,8 +179,15 @@ struct WgradGroupArgs {
 };
 void launch_gemm_wgrad(const WgradGroupArgs& a, hipStream_t s);
 // out[i] = sum over the slices of part[z * stride + i], for up to 16 segments in one launch
-struct ReduceSegment { const float* part; float* out; int64_t n, stride; int slices; int block_base; };
-struct ReduceArgs { ReduceSegment seg[16]; int n_seg; };
+// out[i] = sum over the slices of part[z * stride + i]; with w != nullptr also the SGD step
+// w[i] -= lr * out[i] (plain loads and stores: lock-free, Section 3.2).  With acc != nullptr the
+// launch carries one more block that adds the step's loss and labels to the running metrics.
+struct ReduceSegment { const float* part; float* out; float* w; int64_t n, stride; int slices; int block_base; };
+struct ReduceArgs {
+  ReduceSegment seg[16]; int n_seg;
+  float lr;
+  const float* mean_loss; const float* y; int B; double* acc;
+};
 void launch_reduce_slices(const ReduceArgs& a, int total_blocks, hipStream_t s);
 
 // ---------------------------------------------------------------------------- mlp_fused.hip
