@@ -581,6 +581,11 @@ def main():
     if args.shadow_period_us < 0:
         args.shadow_period_us = 1000 if wl.name == "large" else 0
     n_batches = max(args.batches, NS)
+    if wl.mean_ids < 1e6:
+        # small batches are cheap to generate: no stream sees a batch twice, so the loss and NE
+        # columns are progressive validation on fresh data (a Large batch is 50 MB and takes
+        # 14 s to generate: there the streams cycle their 64 / NS batches)
+        n_batches = max(n_batches, NS * (args.warmup + args.steps))
     if args.sweep != "none":
         # sweeps compare the loss reached, so no stream may see a batch twice: enough distinct
         # batches for the widest configuration (16 workers on each replica, or 8 replicas x 4)
@@ -596,7 +601,8 @@ def main():
     if secondary:
         mid_wl = synth.mid()
         mid_workers = parse_workers(DEFAULT_WORKERS["mid"], mid_wl.num_replicas)
-        _, mid_batches = make_batches(mid_wl, max(64, 3 * sum(mid_workers)), fork=not args.no_fork)
+        _, mid_batches = make_batches(mid_wl, max(64, sum(mid_workers) * (args.warmup + args.steps)),
+                                      fork=not args.no_fork)
     t_gen = time.perf_counter() - t_gen
     progress(f"inputs generated in {t_gen:.1f} s")
 
