@@ -560,7 +560,12 @@ void launch_gemm_xw(const GemmXwArgs& a, hipStream_t s) {
   g.tiles_n = ceil_div(a.N, 128);
   g.tiles_m = ceil_div(a.M, 128);
   g.stream_out = ((int64_t)a.M * a.N * 2 >= (8ll << 20)) ? 1 : 0;
-  hipLaunchKernelGGL(gemm_xw_kernel, dim3(g.tiles_m * g.tiles_n), dim3(256), LDS, s, g);
+  // a launch with the bf16 output asks for half the LDS of an fp32 one: four of its
+  // workgroups fit a CU beside other streams' kernels instead of two
+  constexpr size_t LDS_BF16 = (size_t)128 * CP * 2;
+  static_assert(LDS_BF16 >= (size_t)2 * 128 * TK * 2, "bf16 output tile must cover the buffers");
+  hipLaunchKernelGGL(gemm_xw_kernel, dim3(g.tiles_m * g.tiles_n), dim3(256),
+                     a.C_f32 ? LDS : LDS_BF16, s, g);
 }
 
 void launch_gemm_wgrad(const WgradGroupArgs& a, hipStream_t s) {
