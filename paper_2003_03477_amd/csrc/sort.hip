@@ -151,10 +151,15 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
       const bool valid = j < n;
       const uint32_t dg = (key[r] >> shift) & (RADIX - 1);
       uint64_t m = __ballot(valid);
+      // a wave inside a long run of one hot row (passes after the first: equal keys are
+      // neighbours) holds a single digit: every valid lane matches every other
+      const uint32_t lead = __builtin_amdgcn_readfirstlane(dg);
+      if (__ballot(valid && dg != lead) != 0) {
 #pragma unroll
-      for (int b = 0; b < RADIX_BITS; ++b) {
-        const uint64_t bal = __ballot((dg >> b) & 1u);
-        m &= ((dg >> b) & 1u) ? bal : ~bal;
+        for (int b = 0; b < RADIX_BITS; ++b) {
+          const uint64_t bal = __ballot((dg >> b) & 1u);
+          m &= ((dg >> b) & 1u) ? bal : ~bal;
+        }
       }
       // m = valid lanes of this wave holding the same digit (includes this lane if valid)
       const uint32_t before = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
