@@ -306,14 +306,19 @@ static void carve_slot(const ss_ctx* x, Carver& cv, Slot& s, int B, int64_t n, b
   }
   const int sort_blocks = sort_max_blocks((uint32_t)n);
   const int seg_blocks = ceil_div(n, 2048) + 1;
-  s.keys = cv.take<uint32_t>(n);
-  s.bag_of_pos = cv.take<int32_t>(n);
-  s.sort.keys_a = cv.take<uint32_t>(n);
-  s.sort.keys_b = cv.take<uint32_t>(n);
-  s.sort.vals = cv.take<uint32_t>(n);
-  s.sort.vals_alt = cv.take<uint32_t>(n);
+  // (+4: the sort's histogram reads whole 16-byte vectors up to the end of the array)
+  s.keys = cv.take<uint32_t>(n + 4);
+  s.bag_of_pos = cv.take<int32_t>(n + 4);
+  s.sort.keys_a = cv.take<uint32_t>(n + 4);
+  s.sort.keys_b = cv.take<uint32_t>(n + 4);
+  s.sort.keys_f = cv.take<uint32_t>(n + 4);
+  s.sort.vals = cv.take<uint32_t>(n + 4);
+  s.sort.vals_alt = cv.take<uint32_t>(n + 4);
+  s.sort.vals_f = cv.take<uint32_t>(n + 4);
   s.sort.block_hist = cv.take<uint32_t>((size_t)256 * sort_blocks);
-  s.sort.digit_tot = cv.take<uint32_t>(256);
+  s.sort.seg_tot = cv.take<uint32_t>((size_t)SS_MAX_TABLES * 256);
+  s.sort.seg_lo = cv.take<uint32_t>(SS_MAX_TABLES + 1);
+  s.sort.tile_base = cv.take<uint32_t>(SS_MAX_TABLES + 1);
   s.seg.block_counts = cv.take<uint32_t>(seg_blocks);
   s.seg.seg_starts = cv.take<uint32_t>(n + 1);
   s.seg.num_unique = cv.take<uint32_t>(64);
@@ -795,6 +800,12 @@ static void fill_stack(const ss_ctx* x, const Slot& s, const float* w, int l0, i
   }
 }
 
+// Training steps: the gather also writes the plan of the step's sort into the slot.
+static SortPlanOut sort_plan_of(const Slot& s, const ss_batch* bt, bool train) {
+  if (!train || bt->num_ids <= 0) return SortPlanOut{nullptr, nullptr, 0};
+  return SortPlanOut{s.sort.seg_lo, s.sort.tile_base, sort_tile((uint32_t)bt->num_ids)};
+}
+
 static void launch_weight_snapshot(ss_ctx* x, Slot& s, const float* w, bool train,
                                    const ss_batch* cast_dense, hipStream_t st);
 
@@ -819,7 +830,7 @@ static void forward_fused(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt
     ProfScope ps(x, SS_K_GATHER, st);
     launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e,
                              train ? s.keys : nullptr, s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, x->row_shards,
-                             s.e_part, st);
+                             s.e_part, sort_plan_of(s, bt, train), st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -939,7 +950,7 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
     ProfScope ps(x, SS_K_GATHER, st);
     launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e,
                              train ? s.keys : nullptr, s.bag_of_pos, loss, x->pool_mean ? s.inv_len : nullptr, x->row_shards,
-                             s.e_part, st);
+                             s.e_part, sort_plan_of(s, bt, train), st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -1059,7 +1070,7 @@ static void forward_f32(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt, 
     ProfScope ps(x, SS_K_GATHER, st);
     launch_embedding_bag_fwd(x->h, bt->indices, bt->offsets, x->meta, B, x->T, x->d, s.e,
                              train ? s.keys : nullptr, s.bag_of_pos, nullptr,
-                             x->pool_mean ? s.inv_len : nullptr, x->row_shards, s.e_part, st);
+                             x->pool_mean ? s.inv_len : nullptr, x->row_shards, s.e_part, sort_plan_of(s, bt, train), st);
   }
   {
     ProfScope ps(x, SS_K_INTERACT_FWD, st);
@@ -1148,8 +1159,9 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
       ProfScope ps(x, SS_K_SORT, st);
       // the value carried through the passes is the pooled-vector id of the position: equal
       // rows keep the order of their positions (stable), and the update needs nothing else
-      launch_sort_pairs(s.keys, (const uint32_t*)s.bag_of_pos, n, x->key_bits, s.sort,
-                        &s.sorted_keys, &s.sorted_bag, st);
+      const SortSegments seg{x->T, &x->meta};   // (the tables' ranges: planned by the gather)
+      launch_sort_pairs(s.keys, (const uint32_t*)s.bag_of_pos, n, seg, s.sort, &s.sorted_keys,
+                        &s.sorted_bag, st);
       s.seg_valid = false;  // compacted segment starts are produced on demand (ss_read_debug)
     }
     const EmbOpt opt{x->h, x->G, x->M, x->V, x->lr_emb, x->eps, x->beta1, x->beta2, x->adam ? 1 : 0};
@@ -1346,10 +1358,12 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
     if (size_out) *size_out = ns * 4;
     if (!host_out || bytes == 0 || ns == 0) return SS_OK;
     uint32_t *k = nullptr, *v = nullptr;
-    launch_sort_pairs(s.keys, nullptr, s.sort_n, ctx->key_bits, s.sort, &k, &v, nullptr);
+    // (the tables' position ranges are those the step's own sort left in its plan)
+    const SortSegments seg{ctx->T, &ctx->meta};
+    launch_sort_pairs(s.keys, nullptr, s.sort_n, seg, s.sort, &k, &v, nullptr);
     HIP_TRY(ctx, hipDeviceSynchronize());
     HIP_TRY(ctx, hipMemcpy(host_out, v, bytes < ns * 4 ? bytes : ns * 4, hipMemcpyDeviceToHost));
-    launch_sort_pairs(s.keys, (const uint32_t*)s.bag_of_pos, s.sort_n, ctx->key_bits, s.sort,
+    launch_sort_pairs(s.keys, (const uint32_t*)s.bag_of_pos, s.sort_n, seg, s.sort,
                       &s.sorted_keys, &s.sorted_bag, nullptr);
     HIP_TRY(ctx, hipDeviceSynchronize());
     return SS_OK;

@@ -21,7 +21,7 @@ __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
     const float* __restrict__ h, const int32_t* __restrict__ indices,
     const int32_t* __restrict__ offsets, TableMeta meta, int B, int T, float* __restrict__ e,
     uint32_t* __restrict__ keys, int32_t* __restrict__ bag_of_pos,
-    float* __restrict__ zero_scalar, float* __restrict__ inv_len, int n_shards) {
+    float* __restrict__ zero_scalar, float* __restrict__ inv_len, int n_shards, SortPlanOut plan) {
   constexpr int D = LPR * 4;
   constexpr int RPW = SS_WAVE / LPR;  // rows per wave-wide load
   constexpr int NIF = 8;              // row loads in flight per lane
@@ -29,6 +29,30 @@ __global__ __launch_bounds__(256) void embedding_bag_fwd_kernel(
   // the step's loss accumulator is cleared here, ahead of the kernel that adds into it
   if (zero_scalar && blockIdx.x == 0 && shard == 0 && threadIdx.x == 0) *zero_scalar = 0.f;
   const int lane = threadIdx.x & 63;
+  // The last workgroup of the grid (a spare one: the launcher rounds up past the bags) leaves
+  // the plan of the backward pass's sort behind: where every table's positions begin and how
+  // many tiles of the sort precede them.
+  if (plan.seg_lo && blockIdx.x == gridDim.x - 1 && shard == 0 && threadIdx.x < 64) {
+    const uint32_t n_all = (uint32_t)offsets[(size_t)T * B];
+    const uint32_t lo = lane < T ? (uint32_t)offsets[(size_t)lane * B] : n_all;
+    uint32_t nxt = (uint32_t)__shfl_down((int)lo, 1);
+    if (lane >= T - 1) nxt = n_all;
+    const uint32_t tiles = lane < T ? (nxt - lo + plan.tile - 1) / plan.tile : 0u;
+    uint32_t incl = tiles;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t v = (uint32_t)__shfl_up((int)incl, off);
+      if (lane >= off) incl += v;
+    }
+    if (lane < T) {
+      plan.seg_lo[lane] = lo;
+      plan.tile_base[lane] = incl - tiles;
+    }
+    if (lane == T - 1) {
+      plan.seg_lo[T] = n_all;
+      plan.tile_base[T] = incl;
+    }
+  }
   // Workgroups go to the chip's eight dies (each with its own L2) in turn; the grid is a
   // multiple of 8 and die x takes the x-th eighth of the bags (table-major), so that every L2
   // holds the hot rows of the one or two tables its die is working on instead of all eight
@@ -129,21 +153,24 @@ __global__ __launch_bounds__(256) void embedding_combine_kernel(const float* __r
 void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int32_t* offsets,
                               const TableMeta& meta, int B, int T, int d, float* e,
                               uint32_t* keys, int32_t* bag_of_pos, float* zero_scalar,
-                              float* inv_len, int n_shards, float* e_part, hipStream_t s) {
+                              float* inv_len, int n_shards, float* e_part, const SortPlanOut& plan,
+                              hipStream_t s) {
   const int64_t bags = (int64_t)B * T;
   if (bags == 0) return;
   const bool split = n_shards > 1;
-  dim3 grid((unsigned)(ceil_div(ceil_div(bags, 4), 8) * 8), split ? n_shards : 1), block(256);
+  // (one workgroup more than the bags need: see the kernel)
+  dim3 grid((unsigned)(ceil_div(ceil_div(bags, 4) + 1, 8) * 8), split ? n_shards : 1), block(256);
   float* out = split ? e_part : e;
 #define L(LPR)                                                                                  \
   do {                                                                                          \
     if (split)                                                                                  \
       hipLaunchKernelGGL((embedding_bag_fwd_kernel<LPR, true>), grid, block, 0, s, h, indices,  \
                          offsets, meta, B, T, out, keys, bag_of_pos, zero_scalar, inv_len,      \
-                         n_shards);                                                             \
+                         n_shards, plan);                                                       \
     else                                                                                        \
       hipLaunchKernelGGL((embedding_bag_fwd_kernel<LPR, false>), grid, block, 0, s, h, indices, \
-                         offsets, meta, B, T, out, keys, bag_of_pos, zero_scalar, inv_len, 1);  \
+                         offsets, meta, B, T, out, keys, bag_of_pos, zero_scalar, inv_len, 1,   \
+                         plan);                                                                 \
   } while (0)
   switch (d) {
     case 16: L(4); break;

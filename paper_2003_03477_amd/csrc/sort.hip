@@ -1,10 +1,18 @@
-// Stable LSD radix sort of (global row, flat position) pairs, 8 bits per pass (gfx950).
+// Stable LSD radix sort of (global row, value) pairs, 8 bits per pass (gfx950).
 // The embedding backward needs every distinct row's occurrences side by side and in
 // ascending flat position, so equal keys must keep their input order: each pass is
 // histogram -> per-digit scan over blocks -> stable scatter.
 //
-// A block owns a contiguous tile of 256*rounds elements; wave w of the block owns the w-th
-// quarter of the tile and walks it 64 elements at a time, so "earlier in the tile" is
+// The input is table-major (all positions of table 0, then table 1, ...) and the key is
+// row_base[t] + row, so the tables' position ranges are already in key order: every table's
+// range is sorted on its own, on the digits of the LOCAL row, with as many passes as that
+// table's row count needs (a table of 60 000 rows takes two passes, one of 40 million four),
+// and a table's last pass writes into the common result buffers.  The ranges come from a
+// plan the step's gather kernel leaves in the scratch (first position and first tile of every
+// table); blocks map to (table, tile) through it.
+//
+// A block owns a contiguous tile of 256*rounds elements of one table; wave w of the block owns
+// the w-th quarter of the tile and walks it 64 elements at a time, so "earlier in the tile" is
 // (wave, round, lane) order.  Ranks among equal digits inside a wave come from 8 ballots
 // (one per digit bit); running per-wave digit counts live in LDS.  The scatter first reorders
 // its tile by digit inside LDS, so that elements with equal digits leave as contiguous runs.
@@ -18,9 +26,10 @@ constexpr int SORT_THREADS = 256;
 constexpr int SORT_WAVES = SORT_THREADS / SS_WAVE;
 constexpr int MAX_ROUNDS = 16;
 
+// Tile length for n elements in all: one block per CU once there is enough work, tiles of at
+// most 4096 elements (long tiles give the scatter longer runs of equal digits, i.e. wider
+// contiguous stores).  Returns the number of tiles of an unsegmented array.
 int sort_num_blocks(uint32_t n, int* rounds_out) {
-  // one block per CU once there is enough work, tiles of at most 4096 elements: long tiles
-  // give the scatter longer runs of equal digits, i.e. wider contiguous stores
   int rounds = (int)((n + 256u * SORT_THREADS - 1) / (256u * SORT_THREADS));
   if (rounds < 1) rounds = 1;
   if (rounds > MAX_ROUNDS) rounds = MAX_ROUNDS;
@@ -28,98 +37,137 @@ int sort_num_blocks(uint32_t n, int* rounds_out) {
   return ceil_div(n, (int64_t)SORT_THREADS * rounds);
 }
 
+uint32_t sort_tile(uint32_t n) {
+  int rounds = 1;
+  sort_num_blocks(n, &rounds);
+  return (uint32_t)(SORT_THREADS * rounds);
+}
+
 int sort_max_blocks(uint32_t max_n) {
-  // below the round cap a sort never uses more than 256 blocks; above it, tiles of 4096
+  // below the round cap a sort never uses more than 256 tiles; above it, tiles of 4096; every
+  // table's range may end in one partial tile
   int b = ceil_div(max_n, (int64_t)SORT_THREADS * MAX_ROUNDS);
-  return (b > 256 ? b : 256) + 1;
+  return (b > 256 ? b : 256) + SS_MAX_TABLES + 1;
+}
+
+struct SegDev {
+  const uint32_t* seg_lo;     // [T + 1]
+  const uint32_t* tile_base;  // [T + 1]
+  int T;
+  // 32-bit entries on purpose: with a byte array here the compiler derived the address of
+  // meta.row_base[t] from the byte address of passes[t] (base + t, plus 3 t), and a scalar load
+  // ignores the two low bits of each of its address components
+  int32_t passes[SS_MAX_TABLES];
+  TableMeta meta;
+};
+
+// (table, tile inside the table) of this block, or false when the block is beyond the last tile
+// or its table is done after `pass` passes.  Wave-uniform.
+__device__ __forceinline__ bool seg_of_block(const SegDev& g, int pass, uint32_t tile, int& t,
+                                             uint32_t& base, uint32_t& end) {
+  const int lane = threadIdx.x & 63;
+  const bool ge = lane < g.T && blockIdx.x >= g.tile_base[lane + 1];
+  t = (int)__popcll(__ballot(ge));
+  if (t >= g.T || (int)g.passes[t] <= pass) return false;
+  base = g.seg_lo[t] + (blockIdx.x - g.tile_base[t]) * tile;
+  end = min(g.seg_lo[t + 1], base + tile);
+  return true;
 }
 
 __global__ __launch_bounds__(SORT_THREADS) void radix_hist_kernel(
-    const uint32_t* __restrict__ keys, uint32_t n, int shift, int rounds, int nblocks,
+    const uint32_t* __restrict__ keys, SegDev g, int pass, int rounds, int pitch,
     uint32_t* __restrict__ block_hist) {
   __shared__ uint32_t hist[RADIX];
+  const uint32_t tile = (uint32_t)(SORT_THREADS * rounds);
+  int t;
+  uint32_t base, end;
+  if (!seg_of_block(g, pass, tile, t, base, end)) return;
+  const uint32_t rb = g.meta.row_base[t];
+  const int shift = pass * RADIX_BITS;
   hist[threadIdx.x] = 0;
   __syncthreads();
-  const uint32_t base = blockIdx.x * (uint32_t)(SORT_THREADS * rounds);
-  // the order inside the tile does not matter here: 16-byte loads, all issued up front
-  const uint32_t end = min(n, base + (uint32_t)(SORT_THREADS * rounds));
-  const uint32_t cnt = end > base ? end - base : 0u;
-  const uint32_t nv = cnt / 4;
-  const uint4* kv = (const uint4*)(keys + base);
-  uint4 q[MAX_ROUNDS / 4];
+  // the order inside the tile does not matter here: 16-byte loads from the aligned start
+  // below the tile, all issued up front; elements outside [base, end) are masked
+  const uint32_t a0 = base & ~3u;
+  const uint32_t nv = (end - a0 + 3) / 4;          // <= tile / 4 + 1 vectors
+  const uint4* kv = (const uint4*)(keys + a0);
+  constexpr int NV = MAX_ROUNDS / 4 + 1;
+  uint4 q[NV];
 #pragma unroll
-  for (int i = 0; i < MAX_ROUNDS / 4; ++i) {
+  for (int i = 0; i < NV; ++i) {
     const uint32_t v = threadIdx.x + i * SORT_THREADS;
+    // (the last vector of the array may reach past n by up to 3 elements: the buffers are
+    // allocated in multiples of 4)
     if (v < nv) q[i] = kv[v];
   }
 #pragma unroll
-  for (int i = 0; i < MAX_ROUNDS / 4; ++i) {
+  for (int i = 0; i < NV; ++i) {
     const uint32_t v = threadIdx.x + i * SORT_THREADS;
-    const bool valid = v < nv;
-    const uint32_t d0 = valid ? (q[i].x >> shift) & (RADIX - 1) : 0u;
-    const uint32_t d1 = valid ? (q[i].y >> shift) & (RADIX - 1) : 0u;
-    const uint32_t d2 = valid ? (q[i].z >> shift) & (RADIX - 1) : 0u;
-    const uint32_t d3 = valid ? (q[i].w >> shift) & (RADIX - 1) : 0u;
-    // in the later passes the input is sorted by the lower digits and whole waves share one
-    // digit: count those with a single LDS atomic instead of 256 colliding ones
-    const bool same4 = (d0 == d1) && (d1 == d2) && (d2 == d3);
-    const uint64_t vm = __ballot(valid);
+    const uint32_t j0 = a0 + 4 * v;
+    const bool any = v < nv;
+    const bool full = any && j0 >= base && j0 + 4 <= end;
+    const uint32_t d0 = ((q[i].x - rb) >> shift) & (RADIX - 1);
+    const uint32_t d1 = ((q[i].y - rb) >> shift) & (RADIX - 1);
+    const uint32_t d2 = ((q[i].z - rb) >> shift) & (RADIX - 1);
+    const uint32_t d3 = ((q[i].w - rb) >> shift) & (RADIX - 1);
+    // inside a long run of one hot row whole waves share one digit: count those with a single
+    // LDS atomic instead of 256 colliding ones
+    const bool same4 = full && (d0 == d1) && (d1 == d2) && (d2 == d3);
+    const uint64_t vm = __ballot(any);
     if (vm == 0) continue;
     const uint32_t lead = __builtin_amdgcn_readlane(d0, __builtin_ctzll(vm));
-    const bool uniform = __ballot(valid && !(same4 && d0 == lead)) == 0;
+    const bool uniform = __ballot(any && !(same4 && d0 == lead)) == 0;
     if (uniform) {
       if ((threadIdx.x & 63) == (uint32_t)__builtin_ctzll(vm)) atomicAdd(&hist[lead], 4u * (uint32_t)__popcll(vm));
-    } else if (valid) {
+    } else if (any) {
       if (same4) {
         atomicAdd(&hist[d0], 4u);
       } else {
-        atomicAdd(&hist[d0], 1u);
-        atomicAdd(&hist[d1], 1u);
-        atomicAdd(&hist[d2], 1u);
-        atomicAdd(&hist[d3], 1u);
+        if (j0 >= base && j0 < end) atomicAdd(&hist[d0], 1u);
+        if (j0 + 1 >= base && j0 + 1 < end) atomicAdd(&hist[d1], 1u);
+        if (j0 + 2 >= base && j0 + 2 < end) atomicAdd(&hist[d2], 1u);
+        if (j0 + 3 >= base && j0 + 3 < end) atomicAdd(&hist[d3], 1u);
       }
     }
   }
-  for (uint32_t j = base + nv * 4 + threadIdx.x; j < end; j += SORT_THREADS)
-    atomicAdd(&hist[(keys[j] >> shift) & (RADIX - 1)], 1u);
   __syncthreads();
-  block_hist[(size_t)threadIdx.x * nblocks + blockIdx.x] = hist[threadIdx.x];  // digit-major
+  block_hist[(size_t)threadIdx.x * pitch + blockIdx.x] = hist[threadIdx.x];  // digit-major
 }
 
-// One block per digit: exclusive scan of that digit's counts over the blocks (in place) and
-// the digit's total.
-__global__ __launch_bounds__(256) void radix_scan_kernel(uint32_t* __restrict__ block_hist,
-                                                         int nblocks,
-                                                         uint32_t* __restrict__ digit_tot) {
-  __shared__ uint32_t part[256];
-  uint32_t* row = block_hist + (size_t)blockIdx.x * nblocks;
-  const int tid = threadIdx.x;
-  const int per = (nblocks + 255) / 256;
-  const int lo = min(nblocks, tid * per), hi = min(nblocks, lo + per);
+// One wave per (digit, table): exclusive scan of that digit's counts over the table's tiles
+// (in place) and the digit's total inside the table.
+__global__ __launch_bounds__(64) void radix_scan_kernel(uint32_t* __restrict__ block_hist,
+                                                        int pitch, SegDev g, int pass,
+                                                        uint32_t* __restrict__ seg_tot) {
+  const int t = blockIdx.y, lane = threadIdx.x;
+  if ((int)g.passes[t] <= pass) return;
+  const uint32_t b0 = g.tile_base[t], nb = g.tile_base[t + 1] - b0;
+  uint32_t* row = block_hist + (size_t)blockIdx.x * pitch + b0;
+  const uint32_t per = (nb + 63) / 64;
+  const uint32_t lo = min(nb, lane * per), hi = min(nb, lo + per);
   uint32_t s = 0;
-  for (int i = lo; i < hi; ++i) s += row[i];
-  part[tid] = s;
-  __syncthreads();
-  for (int off = 1; off < 256; off <<= 1) {
-    uint32_t v = (tid >= off) ? part[tid - off] : 0;
-    __syncthreads();
-    part[tid] += v;
-    __syncthreads();
+  for (uint32_t i = lo; i < hi; ++i) s += row[i];
+  uint32_t incl = s;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t v = __shfl_up(incl, off);
+    if (lane >= off) incl += v;
   }
-  uint32_t run = part[tid] - s;
-  for (int i = lo; i < hi; ++i) {
-    uint32_t c = row[i];
+  uint32_t run = incl - s;
+  for (uint32_t i = lo; i < hi; ++i) {
+    const uint32_t c = row[i];
     row[i] = run;
     run += c;
   }
-  if (tid == 255) digit_tot[blockIdx.x] = part[255];
+  if (lane == 63) seg_tot[t * RADIX + blockIdx.x] = incl;
 }
 
 __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
-    const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in, uint32_t n,
-    int shift, int rounds, int nblocks, const uint32_t* __restrict__ block_hist,
-    const uint32_t* __restrict__ digit_tot, uint32_t* __restrict__ keys_out,
-    uint32_t* __restrict__ vals_out) {
+    const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in, SegDev g, int pass,
+    int rounds, int pitch, const uint32_t* __restrict__ block_hist,
+    const uint32_t* __restrict__ seg_tot, uint32_t* __restrict__ keys_mid,
+    uint32_t* __restrict__ vals_mid, uint32_t* __restrict__ keys_fin,
+    uint32_t* __restrict__ vals_fin) {
   // per-wave running digit counts; volatile: lanes of one wave hand values to each other
   // through it between rounds without a barrier
   __shared__ volatile uint32_t wrun[SORT_WAVES][RADIX];
@@ -128,7 +176,16 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
   __shared__ uint32_t skey[SORT_THREADS * MAX_ROUNDS], sval[SORT_THREADS * MAX_ROUNDS];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint32_t tile = (uint32_t)(SORT_THREADS * rounds);
-  const uint32_t wbase = blockIdx.x * tile + wave * (uint32_t)(SS_WAVE * rounds);
+  int t;
+  uint32_t base, n;   // n: end of this tile's elements
+  if (!seg_of_block(g, pass, tile, t, base, n)) return;
+  const uint32_t rb = g.meta.row_base[t];
+  const int shift = pass * RADIX_BITS;
+  // a table's last pass writes the common result buffers
+  const bool last = pass == (int)g.passes[t] - 1;
+  uint32_t* __restrict__ keys_out = last ? keys_fin : keys_mid;
+  uint32_t* __restrict__ vals_out = last ? vals_fin : vals_mid;
+  const uint32_t wbase = base + wave * (uint32_t)(SS_WAVE * rounds);
   // issue the loads first: this tile's keys and values, the digit totals, this block's offsets
   uint32_t key[MAX_ROUNDS], val[MAX_ROUNDS], rank[MAX_ROUNDS];
 #pragma unroll
@@ -139,8 +196,8 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
       val[r] = (j < n && vals_in) ? vals_in[j] : j;
     }
   }
-  const uint32_t dtot = digit_tot[tid];
-  const uint32_t boff = block_hist[(size_t)tid * nblocks + blockIdx.x];
+  const uint32_t dtot = seg_tot[t * RADIX + tid];
+  const uint32_t boff = block_hist[(size_t)tid * pitch + blockIdx.x] + g.seg_lo[t];
   for (int w = 0; w < SORT_WAVES; ++w) wrun[w][tid] = 0;
   __syncthreads();
 
@@ -149,7 +206,7 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
     if (r < rounds) {
       const uint32_t j = wbase + r * SS_WAVE + lane;
       const bool valid = j < n;
-      const uint32_t dg = (key[r] >> shift) & (RADIX - 1);
+      const uint32_t dg = ((key[r] - rb) >> shift) & (RADIX - 1);
       uint64_t m = __ballot(valid);
       // a wave inside a long run of one hot row (passes after the first: equal keys are
       // neighbours) holds a single digit: every valid lane matches every other
@@ -204,7 +261,7 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
     if (r < rounds) {
       const uint32_t j = wbase + r * SS_WAVE + lane;
       if (j < n) {
-        const uint32_t dg = (key[r] >> shift) & (RADIX - 1);
+        const uint32_t dg = ((key[r] - rb) >> shift) & (RADIX - 1);
         const uint32_t lp = lbase[dg] + wrun[wave][dg] + rank[r];
         skey[lp] = key[r];
         sval[lp] = val[r];
@@ -214,45 +271,55 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
   __syncthreads();
   // element i of the reordered tile goes to the i-th slot of its digit's run: neighbours in
   // the tile with the same digit are neighbours in the output
-  const uint32_t count = min(tile, n - min(n, blockIdx.x * tile));
+  const uint32_t count = n - base;
   for (uint32_t i = tid; i < count; i += SORT_THREADS) {
     const uint32_t k = skey[i], v = sval[i];
-    const uint32_t dg = (k >> shift) & (RADIX - 1);
+    const uint32_t dg = ((k - rb) >> shift) & (RADIX - 1);
     const uint32_t dst = gbase[dg] + (i - lbase[dg]);
     keys_out[dst] = k;
     vals_out[dst] = v;
   }
 }
 
-void launch_sort_pairs(const uint32_t* keys, const uint32_t* vals, uint32_t n, int key_bits,
-                       const SortScratch& sc, uint32_t** sorted_keys, uint32_t** sorted_vals,
-                       hipStream_t s) {
+void launch_sort_pairs(const uint32_t* keys, const uint32_t* vals, uint32_t n,
+                       const SortSegments& seg, const SortScratch& sc, uint32_t** sorted_keys,
+                       uint32_t** sorted_vals, hipStream_t s) {
+  *sorted_keys = sc.keys_f;
+  *sorted_vals = sc.vals_f;
+  if (n == 0) return;
+  int rounds = 1;
+  sort_num_blocks(n, &rounds);
+  const uint32_t tile = (uint32_t)(SORT_THREADS * rounds);
+  // upper bound of the tiles: every table's range may end in a partial one
+  const int nblocks = ceil_div(n, tile) + seg.T;
+  const int pitch = nblocks;
+  SegDev g;
+  g.seg_lo = sc.seg_lo; g.tile_base = sc.tile_base; g.T = seg.T; g.meta = *seg.meta;
+  int max_passes = 1;
+  for (int t = 0; t < seg.T; ++t) {
+    // bits of the largest local row of the table
+    const uint32_t rows = seg.meta->row_base[t + 1] - seg.meta->row_base[t];
+    int bits = 1;
+    while (bits < 32 && (1ull << bits) < rows) ++bits;
+    const int p = (bits + RADIX_BITS - 1) / RADIX_BITS;
+    g.passes[t] = p;
+    if (p > max_passes) max_passes = p;
+  }
   const uint32_t* kin = keys;
   const uint32_t* vin = vals;     // null: the value is the element's own position
-  uint32_t* kout = sc.keys_a;
-  uint32_t* kother = sc.keys_b;
-  uint32_t* vout = sc.vals;
-  uint32_t* vother = sc.vals_alt;
-  int passes = (key_bits + RADIX_BITS - 1) / RADIX_BITS;
-  if (passes < 1) passes = 1;
-  int rounds = 1;
-  const int nblocks = sort_num_blocks(n, &rounds);
-  *sorted_keys = sc.keys_a;
-  *sorted_vals = sc.vals;
-  if (n == 0) return;
-  for (int p = 0; p < passes; ++p) {
-    const int shift = p * RADIX_BITS;
-    hipLaunchKernelGGL(radix_hist_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, n, shift,
-                       rounds, nblocks, sc.block_hist);
-    hipLaunchKernelGGL(radix_scan_kernel, dim3(RADIX), dim3(256), 0, s, sc.block_hist, nblocks,
-                       sc.digit_tot);
-    hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, vin, n,
-                       shift, rounds, nblocks, sc.block_hist, sc.digit_tot, kout, vout);
-    *sorted_keys = kout;
-    *sorted_vals = vout;
-    kin = kout; vin = vout;
-    uint32_t* t = kout; kout = kother; kother = t;
-    t = vout; vout = vother; vother = t;
+  uint32_t* kmid = sc.keys_a; uint32_t* kother = sc.keys_b;
+  uint32_t* vmid = sc.vals; uint32_t* vother = sc.vals_alt;
+  for (int p = 0; p < max_passes; ++p) {
+    hipLaunchKernelGGL(radix_hist_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, g, p,
+                       rounds, pitch, sc.block_hist);
+    hipLaunchKernelGGL(radix_scan_kernel, dim3(RADIX, seg.T), dim3(64), 0, s, sc.block_hist, pitch,
+                       g, p, sc.seg_tot);
+    hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, vin, g,
+                       p, rounds, pitch, sc.block_hist, sc.seg_tot, kmid, vmid, sc.keys_f,
+                       sc.vals_f);
+    kin = kmid; vin = vmid;
+    uint32_t* x = kmid; kmid = kother; kother = x;
+    x = vmid; vmid = vother; vother = x;
   }
 }
 

@@ -28,10 +28,18 @@ void launch_fill_u32(uint32_t* p, uint64_t n, uint32_t v, hipStream_t s);
 // n_shards > 1: every table is split into n_shards equal row ranges, each range pools the rows
 // it owns into e_part[shard][b*T+t][d] and a second launch adds the partial results in shard
 // order into e (partial pooling).
+// Where the gather leaves the plan of the backward pass's sort (all null / zero: no plan):
+// seg_lo[t] = first position of table t (seg_lo[T] = number of ids), tile_base[t] = tiles of
+// `tile` elements before table t.
+struct SortPlanOut {
+  uint32_t* seg_lo;
+  uint32_t* tile_base;
+  uint32_t tile;
+};
 void launch_embedding_bag_fwd(const float* h, const int32_t* indices, const int32_t* offsets,
                               const TableMeta& meta, int B, int T, int d, float* e,
                               uint32_t* keys, int32_t* bag_of_pos, float* zero_scalar,
-                              float* inv_len, int n_shards, float* e_part, hipStream_t s);
+                              float* inv_len, int n_shards, float* e_part, const SortPlanOut& plan, hipStream_t s);
 
 struct SegScratch {
   uint32_t* block_counts;  // [seg_blocks]
@@ -67,21 +75,33 @@ void launch_row_update_finish(const uint32_t* sorted_keys, uint32_t n, const Row
 
 // ---------------------------------------------------------------------------- sort.hip
 struct SortScratch {
-  uint32_t* keys_a;     // [max_ids] ping-pong buffers of the passes
-  uint32_t* keys_b;     // [max_ids]
-  uint32_t* vals;       // [max_ids]
-  uint32_t* vals_alt;   // [max_ids]
+  uint32_t* keys_a;     // [max_ids + 4] ping-pong buffers of the passes
+  uint32_t* keys_b;     // [max_ids + 4]
+  uint32_t* keys_f;     // [max_ids + 4] result
+  uint32_t* vals;       // [max_ids + 4]
+  uint32_t* vals_alt;   // [max_ids + 4]
+  uint32_t* vals_f;     // [max_ids + 4] result
   uint32_t* block_hist; // [256 * max_sort_blocks]
-  uint32_t* digit_tot;  // [256]
+  uint32_t* seg_tot;    // [SS_MAX_TABLES * 256] digit totals per table
+  uint32_t* seg_lo;     // [SS_MAX_TABLES + 1] first position of every table (the plan, kept
+  uint32_t* tile_base;  // [SS_MAX_TABLES + 1]  between calls)
 };
 int sort_num_blocks(uint32_t n, int* rounds_out);
 int sort_max_blocks(uint32_t max_n);
-// Stable LSD radix sort of (key, value) pairs on key_bits bits; vals == nullptr sorts
-// (key, position).  The inputs are left as they are; the sorted arrays are returned through
-// the out pointers (one of the ping-pong buffers each).
-void launch_sort_pairs(const uint32_t* keys, const uint32_t* vals, uint32_t n, int key_bits,
-                       const SortScratch& sc, uint32_t** sorted_keys, uint32_t** sorted_vals,
-                       hipStream_t s);
+uint32_t sort_tile(uint32_t n);   // tile length the sort of n elements uses
+// The tables of the batch being sorted; their position ranges are read from the plan in the
+// scratch (seg_lo, tile_base: written by the gather of the same step, see SortPlanOut, for the
+// tile length sort_tile(n)).
+struct SortSegments {
+  int T;
+  const TableMeta* meta;
+};
+// Stable LSD radix sort of (key, value) pairs, every table's range on its own local rows;
+// vals == nullptr sorts (key, position).  The inputs (at least max_ids + 4 elements long) are
+// left as they are; the sorted arrays are returned through the out pointers.
+void launch_sort_pairs(const uint32_t* keys, const uint32_t* vals, uint32_t n,
+                       const SortSegments& seg, const SortScratch& sc, uint32_t** sorted_keys,
+                       uint32_t** sorted_vals, hipStream_t s);
 
 // ---------------------------------------------------------------------------- interaction.hip
 // f[b] = [z0[b], <V_r, V_c> for r>c], V = [z0[b]; e[b,0..T-1]].  Writes fp32 f (ldf floats per
