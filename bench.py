@@ -49,7 +49,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # may see a batch twice: fewer widths there)
 WIDTHS = {"large": (1, 2, 3, 4, 6), "mid": (1, 2, 4, 6, 8, 12, 16), "tiny": (1, 2, 4, 8),
           "hogwild": (1, 2, 4, 6, 8, 12, 16)}
-DEFAULT_WORKERS = {"large": "2", "mid": "6", "tiny": "2", "hogwild": "8,1,1,1"}
+DEFAULT_WORKERS = {"large": "1", "mid": "6", "tiny": "2", "hogwild": "8,1,1,1"}
 
 
 def parse():
@@ -89,9 +89,38 @@ def parse():
 
 # ------------------------------------------------------------------------------------------
 # inputs
-def _gen_one(args):
-    gen, s = args
-    return gen.batch(s)
+_GEN = None   # the generator the forked workers inherit (its Zipf tables are far too large to
+              # send with every task)
+
+
+_GEN_DIR = None   # hand-off directory (memory-backed where the system has one): a worker leaves
+                  # a batch's arrays there instead of pushing 28 MB through the result pipe
+
+
+def _gen_one(s):
+    import numpy as np
+    from paper_2003_03477_amd import synth
+    bt = _GEN.batch(s)
+    if _GEN_DIR is None:
+        return bt
+    paths = []
+    for k, a in enumerate(bt.as_tuple()):
+        path = os.path.join(_GEN_DIR, f"b{s}_{k}.npy")
+        np.save(path, a)
+        paths.append(path)
+    return paths
+
+
+def _collect(item):
+    import numpy as np
+    from paper_2003_03477_amd import synth
+    if not isinstance(item, list):
+        return item
+    arrays = []
+    for path in item:
+        arrays.append(np.load(path))
+        os.unlink(path)
+    return synth.Batch(*arrays)
 
 
 def progress(msg):
@@ -111,16 +140,23 @@ def make_batches(wl, n, fork=True):
     procs = min(16, n, max(1, (os.cpu_count() or 1)))
     # close + join: the workers leave through their normal exit (terminating them by signal
     # runs whatever handler a profiler preloaded into the process, which can block)
+    global _GEN, _GEN_DIR
+    import shutil
+    import tempfile
+    _GEN = gen
+    _GEN_DIR = tempfile.mkdtemp(prefix="ss_bench_", dir="/dev/shm" if os.path.isdir("/dev/shm") else None)
     pool = mp.get_context("fork").Pool(procs)
     try:
         out = []
-        for k, bt in enumerate(pool.imap(_gen_one, [(gen, s) for s in range(n)], chunksize=1)):
-            out.append(bt)
+        for k, item in enumerate(pool.imap(_gen_one, range(n), chunksize=1)):
+            out.append(_collect(item))
             if (k + 1) % 32 == 0:
                 progress(f"{k + 1} of {n} batches generated")
     finally:
         pool.close()
         pool.join()
+        shutil.rmtree(_GEN_DIR, ignore_errors=True)
+        _GEN_DIR = None
     return gen, out
 
 
@@ -170,10 +206,10 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
                  shadow_off=True, tag=""):
     """Build a context, run warm-up + timed sweeps (shadow on, then shadow off), return the
     measurements as a dict.  `workers` = worker streams per replica (list of K ints).
-    With more than one lock-free worker per replica the first two warm-up sweeps run stream
-    after stream: row-wise Adagrad starts from empty accumulators, where every update moves a
-    row by about lr whatever the gradient, and several stale workers doing that to the same hot
-    rows at once is the one moment a lock-free run can blow up (it did in the oracle's
+    The first two warm-up sweeps run stream after stream: row-wise Adagrad starts from empty
+    accumulators, where every update moves a row by about lr whatever the gradient, and several
+    stale workers (of one replica or of several: the tables are shared) doing that to the same
+    hot rows at once is the one moment a lock-free run can blow up (it did in the oracle's
     max-staleness schedule too).  A trainer spends a vanishing share of its life there; the
     remaining warm-up sweeps and everything timed run fully concurrent."""
     import numpy as np
@@ -298,13 +334,18 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
 
     # ---- warm-up: every stream, every kernel, the shadow loop
     shadow_loop(True)
-    region(warmup, serial=min(2, max(warmup - 1, 0)) if NS > K else 0)
+    region(warmup, serial=min(2, max(warmup - 1, 0)) if NS > 1 else 0)
     progress(f"{wl.name}{tag}: warm-up done")
     # ---- timed region, shadow on
+    # brackets cost a few per cent of a step when every launch carries one: every class gets
+    # about a hundred over the region (a step launches the gather once and GEMMs a dozen times)
     every = max(1, (steps * NS) // 96)
     if events:
         gpu.ss_profile_sample(every)
+        for kid in (binding.K_MLP_FWD, binding.K_MLP_DGRAD):
+            gpu.ss_profile_sample_class(kid, max(1, (steps * NS * (7 if wl.name == "large" else 2)) // 96))
         gpu.ss_profile_arm(*one.values())
+    per_step_guess = {"mlp_fwd": 7 if wl.name == "large" else 2, "mlp_dgrad": 6 if wl.name == "large" else 2}
     steps0, rounds0, _ = gpu.ss_get_counters()
     dt_on = region(steps)
     clock_on = state.get("clock_ns")
@@ -316,13 +357,19 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
             n, ms = gpu.ss_profile_read(kid)
             if n:
                 kernels[name] = {"brackets": n, "avg_us": ms / n * 1e3,
-                                 "where": f"timed region, 1 launch in {every} bracketed"}
+                                 "where": "timed region, about one launch in "
+                                          f"{max(1, round(steps * NS * per_step_guess.get(name, 1) / max(n, 1)))} bracketed"}
     shadow_loop(False)
     train_ne = gpu.ss_metrics_read(0)
     # ---- the same sweeps with the shadow stream off
     dt_off = None
     if shadow_off and not fg and shadow_mode != "off":
+        if events:   # the same brackets as in the shadow-on region, so that the ratio of the
+            gpu.ss_profile_arm(*one.values())   # two is the cost of the shadow loop alone
         dt_off = region(steps)
+        if events:
+            for kid in one.values():
+                gpu.ss_profile_read(kid)
     rounds = rounds1 - rounds0
     per_replica = (steps1 - steps0).astype(float)
 
@@ -581,11 +628,10 @@ def main():
     if args.shadow_period_us < 0:
         args.shadow_period_us = 1000 if wl.name == "large" else 0
     n_batches = max(args.batches, NS)
-    if wl.mean_ids < 1e6:
-        # small batches are cheap to generate: no stream sees a batch twice, so the loss and NE
-        # columns are progressive validation on fresh data (a Large batch is 50 MB and takes
-        # 14 s to generate: there the streams cycle their 64 / NS batches)
-        n_batches = max(n_batches, NS * (args.warmup + args.steps))
+    # no stream sees a batch twice in the warm-up and the timed region: the loss and NE columns
+    # are progressive validation on fresh data (the later regions -- shadow off, one stream
+    # alone -- run over the same batches again)
+    n_batches = max(n_batches, NS * (args.warmup + args.steps))
     if args.sweep != "none":
         # sweeps compare the loss reached, so no stream may see a batch twice: enough distinct
         # batches for the widest configuration (16 workers on each replica, or 8 replicas x 4)

@@ -338,6 +338,8 @@ typedef enum {
 } ss_kernel_id;
 int ss_profile_arm(ss_ctx* ctx, uint32_t kernel_mask);
 int ss_profile_sample(ss_ctx* ctx, int32_t every);
+/* the same for one class (a step launches some classes once and others a dozen times) */
+int ss_profile_sample_class(ss_ctx* ctx, int32_t kernel_id, int32_t every);
 int ss_profile_read(ss_ctx* ctx, int32_t kernel_id, int64_t* launches, double* total_ms);
 
 #ifdef __cplusplus

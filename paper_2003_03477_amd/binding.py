@@ -41,7 +41,7 @@ EXPORTS = [
     "ss_write_rows", "ss_write_adagrad", "ss_init_dense", "ss_num_params", "ss_train_step", "ss_eval_step",
     "ss_shadow_sync", "ss_easgd_exchange", "ss_sync_round", "ss_shadow_start", "ss_shadow_stop", "ss_read_dense",
     "ss_write_dense", "ss_read_rows", "ss_read_debug", "ss_get_counters", "ss_profile_arm",
-    "ss_profile_sample", "ss_profile_read", "ss_shadow_pace", "ss_metrics_read",
+    "ss_profile_sample", "ss_profile_sample_class", "ss_profile_read", "ss_shadow_pace", "ss_metrics_read",
     "ss_metrics_reset", "ss_eval_step_static", "ss_write_adam_state", "ss_read_adam_state",
     "ss_plan_placement",
 ]
@@ -119,6 +119,7 @@ def load() -> C.CDLL:
     lib.ss_get_counters.argtypes = [vp, vp, vp, vp]
     lib.ss_profile_arm.argtypes = [vp, C.c_uint32]
     lib.ss_profile_sample.argtypes = [vp, i32]
+    lib.ss_profile_sample_class.argtypes = [vp, i32, i32]
     lib.ss_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double)]
     for name in EXPORTS:
         fn = getattr(lib, name)
@@ -368,6 +369,11 @@ class ShadowSync:
     def ss_profile_sample(self, every: int):
         """Bracket only every `every`-th launch of each armed kernel class."""
         self._check(self.lib.ss_profile_sample(self.ctx, every), "ss_profile_sample")
+
+    def ss_profile_sample_class(self, kernel_id: int, every: int):
+        """The same for one kernel class."""
+        self._check(self.lib.ss_profile_sample_class(self.ctx, kernel_id, every),
+                    "ss_profile_sample_class")
 
     def ss_profile_read(self, kernel_id: int):
         n, ms = C.c_int64(0), C.c_double(0.0)

@@ -154,7 +154,7 @@ struct ss_ctx {
   // profiling
   std::mutex prof_mu;
   std::atomic<uint32_t> prof_mask{0};
-  std::atomic<uint32_t> prof_every{1};
+  std::atomic<uint32_t> prof_every[SS_K_COUNT];   // per class: bracket one launch in so many
   std::atomic<uint32_t> prof_seen[SS_K_COUNT];
   struct ProfPool {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
@@ -164,6 +164,7 @@ struct ss_ctx {
   explicit ss_ctx(int k) : steps(k) {
     for (auto& a : steps) a.store(0);
     for (auto& a : prof_seen) a.store(0);
+    for (auto& a : prof_every) a.store(1);
   }
 };
 
@@ -749,7 +750,7 @@ struct ProfScope {
   ss_ctx* x; hipStream_t s; hipEvent_t stop = nullptr;
   ProfScope(ss_ctx* ctx, int id, hipStream_t st) : x(ctx), s(st) {
     if (!(x->prof_mask.load(std::memory_order_relaxed) & (1u << id))) return;
-    const uint32_t every = x->prof_every.load(std::memory_order_relaxed);
+    const uint32_t every = x->prof_every[id].load(std::memory_order_relaxed);
     // launches are picked by a hash of their running number, not by its remainder: a step's
     // launches of one class cycle through the layers, and a fixed stride would always land on
     // the same ones
@@ -1487,7 +1488,15 @@ int ss_profile_arm(ss_ctx* ctx, uint32_t kernel_mask) {
 int ss_profile_sample(ss_ctx* ctx, int32_t every) {
   if (!ctx) return SS_EINVAL;
   if (every < 1) return fail(ctx, SS_EINVAL, "sampling interval must be >= 1");
-  ctx->prof_every = (uint32_t)every;
+  for (int id = 0; id < SS_K_COUNT; ++id) ctx->prof_every[id] = (uint32_t)every;
+  return SS_OK;
+}
+
+int ss_profile_sample_class(ss_ctx* ctx, int32_t kernel_id, int32_t every) {
+  if (!ctx) return SS_EINVAL;
+  if (kernel_id < 1 || kernel_id >= SS_K_COUNT) return fail(ctx, SS_EINVAL, "bad kernel id");
+  if (every < 1) return fail(ctx, SS_EINVAL, "sampling interval must be >= 1");
+  ctx->prof_every[kernel_id] = (uint32_t)every;
   return SS_OK;
 }
 
