@@ -106,7 +106,6 @@ struct ss_ctx {
   int n_bot_layers, n_top_layers;
   int64_t P, Pstride;
   int F, ldf, ldf16, maxw;
-  int key_bits;
   bool fused = false;              // small-network regime: fused per-sample-tile MLP kernels
   int ldT = 0;
   size_t lds_fwd_bot = 0, lds_fwd_top = 0, lds_bwd_bot = 0, lds_bwd_top = 0;
@@ -366,8 +365,6 @@ static ss_ctx* make_ctx(const ss_config* c) {
   for (int t = 0; t < x->T; ++t) { x->meta.row_base[t] = (uint32_t)base; base += (uint64_t)x->rows[t]; }
   x->meta.row_base[x->T] = (uint32_t)base;
   x->total_rows = base;
-  x->key_bits = 1;
-  while ((1ull << x->key_bits) < base) ++x->key_bits;
   int64_t off = 0;
   int maxw = 1;
   auto add = [&](const int32_t* dims, int n) {

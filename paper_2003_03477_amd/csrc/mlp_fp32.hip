@@ -1,7 +1,8 @@
 // fp32 MLP pieces (gfx950): a general strided LDS-tiled GEMM with fused bias / ReLU /
 // ReLU-gate epilogues, bias gradients, the log-loss, and the lock-free SGD step.  This path
-// serves models configured for fp32 arithmetic end to end; the bf16 MFMA path lives in
-// mlp_bf16.hip.  Bottom / top networks and their place in the step: Section 3.1 "Trainer".
+// serves models configured for fp32 arithmetic end to end; the bf16 MFMA paths live in
+// mlp_fused.hip and gemm_mfma.hip.  Bottom / top networks and their place in the step:
+// Section 3.1 "Trainer".
 #include "ss_internal.h"
 
 namespace ss {
