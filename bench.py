@@ -201,6 +201,21 @@ def measured_traffic(workload, kernel):
     return None
 
 
+def profiler_in_region_us(workload, kernel):
+    """A profiler's average duration of the class's launches inside the timed region of the same
+    command, from the committed rocprofv3 summary (a line `in_region_avg_us <class> <us>` in
+    profiles/<workload>_bench_kernel_stats.txt), or None."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_bench_kernel_stats.txt")
+    try:
+        for line in open(path):
+            m = re.match(r"\s*in_region_avg_us\s+(\S+)\s+([0-9.eE+]+)", line)
+            if m and m.group(1) == kernel:
+                return float(m.group(2))
+    except OSError:
+        pass
+    return None
+
+
 # ------------------------------------------------------------------------------------------
 def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, events=True,
                  shadow_off=True, tag=""):
@@ -411,6 +426,9 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
             kd["total_ms_in_timed_region"] = kd["avg_us"] * lps * train_steps * 1e-3
             n1, ms1 = alone.get(name, (0, 0.0))
             kd["alone_avg_us"] = (ms1 / n1 * 1e3) if n1 else None
+            # (from the committed profile of the same command, not measured in this run: an
+            # event pair under several streams also spans queueing, the profiler's does not)
+            kd["profiler_in_region_avg_us"] = profiler_in_region_us(wl.name, name)
             if name in flops:
                 work = flops[name] / lps
                 ach = work / (kd["avg_us"] * 1e-6) / 1e12
@@ -479,6 +497,7 @@ def pick_roofline(kernels, NS):
             "launches_per_step": kd["launches_per_step"],
             "work_per_launch": kd["algorithmic_flops_per_launch"] if mfma else kd["algorithmic_bytes_per_launch"],
             "alone_avg_launch_us": kd.get("alone_avg_us"),
+            "profiler_in_region_avg_launch_us": kd.get("profiler_in_region_avg_us"),
             "alone_achieved": kd.get("alone_TFLOPps") if mfma else kd.get("alone_GBps"),
             "alone_frac": kd.get("alone_frac_of_bf16_mfma_peak") if mfma else kd.get("alone_frac_of_hbm_peak"),
             "note": "largest summed time of all one-kernel classes over the timed region; HIP "

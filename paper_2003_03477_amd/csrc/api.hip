@@ -989,7 +989,7 @@ static void backward_wide(ss_ctx* x, Slot& s, float* w_rw, const float* loss, co
     const Layer& ly = x->layers[l];
     GemmXwArgs a{};
     a.A = s.dYr[l]; a.lda = x->pout[l]; a.Bf = s.wsw + x->wsw_r[l];
-    a.M = B; a.N = ly.in; a.K = x->kp_r[l];
+    a.M = B; a.N = ly.in; a.K = x->kp_r[l]; a.role = 1;
     if (l == nb) {
       a.C_f32 = s.df; a.ldc32 = x->ldf; a.epi = EPI_NONE;
     } else {

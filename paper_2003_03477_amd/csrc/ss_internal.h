@@ -177,6 +177,7 @@ struct GemmXwArgs {
   float* C_f32; int ldc32;
   int epi; const float* bias;
   const uint16_t* mask; int ldmask;
+  int role;   // 0: forward product, 1: data gradient (separate kernel names for profilers)
 };
 void launch_gemm_xw(const GemmXwArgs& a, hipStream_t s);
 // Weight gradients of all layers in one launch.  Layer l: part[z] (z = batch slice) receives

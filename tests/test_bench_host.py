@@ -69,6 +69,10 @@ def test_counter_summaries_are_parsed():
         for k in ("gather", "row_update_chunk", "interaction_bwd"):
             v = bench.measured_traffic(wl, k)
             assert v is not None and v > 1e6, (wl, k)
+        for k in ("gather", "row_update_chunk", "mlp_fwd", "mlp_dgrad", "mlp_wgrad"):
+            v = bench.profiler_in_region_us(wl, k)
+            assert v is not None and 1.0 < v < 1e4, (wl, k)
+    assert bench.profiler_in_region_us("large", "no_such_kernel") is None
     assert bench.measured_traffic("large", "no_such_kernel") is None
     assert bench.measured_traffic("no_such_workload", "gather") is None
 
