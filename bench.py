@@ -77,6 +77,8 @@ def parse():
     ap.add_argument("--sweep", default="none", choices=["none", "widths", "gap", "foreground"])
     ap.add_argument("--mlp-path", default="auto", choices=["auto", "layerwise"],
                     help="bf16 MLP kernels: auto = fused per-sample-tile kernels for widths <= 512")
+    ap.add_argument("--sort-digit-bits", type=int, default=0, choices=[0, 8, 9, 10],
+                    help="widest digit of a pass of the backward's radix sort (0: library default)")
     ap.add_argument("--no-shadow-off", action="store_true", help="skip the shadow-off region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sync-isolation", action="store_true")
@@ -236,7 +238,8 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
     NS = len(replica_of)
     assert len(host_batches) >= NS
     max_ids = max(int(b.offsets[-1]) for b in host_batches) + 4096
-    gpu = binding.from_workload(wl, num_worker_slots=NS, max_ids=max_ids, mlp_path=args.mlp_path)
+    gpu = binding.from_workload(wl, num_worker_slots=NS, max_ids=max_ids, mlp_path=args.mlp_path,
+                                sort_digit_bits=args.sort_digit_bits)
     gpu.ss_init_tables_hash()
     gpu.ss_init_dense(synth.dense_w0(wl))
     progress(f"{wl.name}{tag}: context ready, {NS} worker streams")

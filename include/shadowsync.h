@@ -111,6 +111,13 @@ typedef struct {
                                 every table is cut into S equal row ranges, the look-up pools
                                 per range and a second kernel adds the S partial vectors in
                                 range order                                              */
+  int32_t sort_digit_bits;   /* widest digit of a pass of the stable radix sort that orders the
+                                batch's (row, position) pairs for the table update: 8, 9 or 10;
+                                0 picks the default (8: wider digits take fewer passes, but
+                                each pass scatters into shorter runs and measured slower on
+                                both configured workloads).  A table whose local rows take b
+                                bits is sorted in ceil(b / this) passes of equal width; the
+                                sorted order does not depend on it                         */
 } ss_config;
 
 /* One mini-batch.  All pointers are DEVICE pointers owned by the caller and must stay

@@ -58,7 +58,7 @@ class ss_config(C.Structure):
                 ("adagrad_eps", C.c_float), ("seed", C.c_uint64), ("pooling", C.c_int32),
                 ("mlp_path", C.c_int32), ("emb_optimizer", C.c_int32),
                 ("adam_beta1", C.c_float), ("adam_beta2", C.c_float),
-                ("emb_row_shards", C.c_int32)]
+                ("emb_row_shards", C.c_int32), ("sort_digit_bits", C.c_int32)]
 
 
 class ss_shard(C.Structure):
@@ -179,7 +179,7 @@ class ShadowSync:
                  lr_emb: float = 0.01, adagrad_eps: float = 1e-8, seed: int = 0,
                  device: str = "cuda:0", pooling: str = "sum", mlp_path: str = "auto",
                  emb_optimizer: str = "rowwise_adagrad", adam_betas=(0.9, 0.999),
-                 emb_row_shards: int = 1):
+                 emb_row_shards: int = 1, sort_digit_bits: int = 0):
         import torch
         self.lib = load()
         self.torch = torch
@@ -192,7 +192,7 @@ class ShadowSync:
                              max_ids, num_worker_slots, SS_BF16 if bf16 else SS_FP32,
                              lr_dense, lr_emb, adagrad_eps, seed, POOLING[pooling],
                              MLP_PATHS[mlp_path], EMB_OPTIMIZERS[emb_optimizer],
-                             adam_betas[0], adam_betas[1], emb_row_shards)
+                             adam_betas[0], adam_betas[1], emb_row_shards, sort_digit_bits)
         self.rows, self.emb_dim, self.K = list(rows), emb_dim, num_replicas
         self.T = len(rows)
         self.ctx = C.c_void_p()
@@ -412,7 +412,7 @@ def ss_plan_placement(rows, cost, num_ps: int, max_rows_per_shard: int = 0):
 
 
 def from_workload(wl, rows=None, num_worker_slots: int = 1, max_ids: Optional[int] = None,
-                  device="cuda:0", mlp_path: str = "auto") -> ShadowSync:
+                  device="cuda:0", mlp_path: str = "auto", sort_digit_bits: int = 0) -> ShadowSync:
     """Context sized for a synth.Workload (rows may be overridden by a compacted problem)."""
     rows = list(rows if rows is not None else wl.rows)
     if max_ids is None:
@@ -422,4 +422,5 @@ def from_workload(wl, rows=None, num_worker_slots: int = 1, max_ids: Optional[in
                       max_ids, num_worker_slots, wl.bf16, wl.lr_dense, wl.lr_emb,
                       wl.adagrad_eps, wl.seed, device, wl.pooling, mlp_path,
                       getattr(wl, "emb_optimizer", "rowwise_adagrad"),
-                      getattr(wl, "adam_betas", (0.9, 0.999)), getattr(wl, "emb_row_shards", 1))
+                      getattr(wl, "adam_betas", (0.9, 0.999)), getattr(wl, "emb_row_shards", 1),
+                      sort_digit_bits)

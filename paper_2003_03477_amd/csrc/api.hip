@@ -100,6 +100,7 @@ struct ss_ctx {
   int T, d, num_dense, K, max_batch, num_slots, prec;
   bool pool_mean = false;          // mean instead of sum pooling
   int row_shards = 1;              // row shards per table (partial pooling); 1 = not split
+  int sort_digit_bits = 8;         // widest digit of a pass of the backward's radix sort
   int64_t max_ids;
   std::vector<int64_t> rows;
   std::vector<Layer> layers;
@@ -241,6 +242,8 @@ static int validate(const ss_config* c, std::string& why) {
   if (c->pooling != SS_POOL_SUM && c->pooling != SS_POOL_MEAN) BAD("bad pooling mode");
   if (c->mlp_path != SS_MLP_AUTO && c->mlp_path != SS_MLP_LAYERWISE) BAD("bad mlp_path");
   if (c->emb_row_shards < 0 || c->emb_row_shards > 64) BAD("emb_row_shards must be 0..64");
+  if (c->sort_digit_bits != 0 && (c->sort_digit_bits < 8 || c->sort_digit_bits > 10))
+    BAD("sort_digit_bits must be 0 (default), 8, 9 or 10");
   if (c->emb_optimizer != SS_OPT_ROWWISE_ADAGRAD && c->emb_optimizer != SS_OPT_ADAM)
     BAD("bad emb_optimizer");
   if (c->emb_optimizer == SS_OPT_ADAM &&
@@ -315,8 +318,8 @@ static void carve_slot(const ss_ctx* x, Carver& cv, Slot& s, int B, int64_t n, b
   s.sort.vals = cv.take<uint32_t>(n + 4);
   s.sort.vals_alt = cv.take<uint32_t>(n + 4);
   s.sort.vals_f = cv.take<uint32_t>(n + 4);
-  s.sort.block_hist = cv.take<uint32_t>((size_t)256 * sort_blocks);
-  s.sort.seg_tot = cv.take<uint32_t>((size_t)SS_MAX_TABLES * 256);
+  s.sort.block_hist = cv.take<uint32_t>((size_t)SORT_MAX_DIGITS * sort_blocks);
+  s.sort.seg_tot = cv.take<uint32_t>((size_t)SS_MAX_TABLES * SORT_MAX_DIGITS);
   s.sort.seg_lo = cv.take<uint32_t>(SS_MAX_TABLES + 1);
   s.sort.tile_base = cv.take<uint32_t>(SS_MAX_TABLES + 1);
   s.seg.block_counts = cv.take<uint32_t>(seg_blocks);
@@ -356,6 +359,7 @@ static ss_ctx* make_ctx(const ss_config* c) {
   x->num_slots = c->num_worker_slots; x->prec = c->mlp_prec;
   x->pool_mean = (c->pooling == SS_POOL_MEAN);
   x->row_shards = c->emb_row_shards < 1 ? 1 : c->emb_row_shards;
+  x->sort_digit_bits = c->sort_digit_bits == 0 ? 8 : c->sort_digit_bits;
   x->lr_dense = c->lr_dense; x->lr_emb = c->lr_emb; x->eps = c->adagrad_eps; x->seed = c->seed;
   x->adam = (c->emb_optimizer == SS_OPT_ADAM);
   x->beta1 = c->adam_beta1; x->beta2 = c->adam_beta2;
@@ -1157,7 +1161,7 @@ static int train_or_eval(ss_ctx* x, int replica, int slot, const ss_batch* bt, v
       ProfScope ps(x, SS_K_SORT, st);
       // the value carried through the passes is the pooled-vector id of the position: equal
       // rows keep the order of their positions (stable), and the update needs nothing else
-      const SortSegments seg{x->T, &x->meta};   // (the tables' ranges: planned by the gather)
+      const SortSegments seg{x->T, &x->meta, x->sort_digit_bits};   // (the tables' ranges: planned by the gather)
       launch_sort_pairs(s.keys, (const uint32_t*)s.bag_of_pos, n, seg, s.sort, &s.sorted_keys,
                         &s.sorted_bag, st);
       s.seg_valid = false;  // compacted segment starts are produced on demand (ss_read_debug)
@@ -1357,7 +1361,7 @@ int ss_read_debug(ss_ctx* ctx, int32_t worker_slot, int32_t item, void* host_out
     if (!host_out || bytes == 0 || ns == 0) return SS_OK;
     uint32_t *k = nullptr, *v = nullptr;
     // (the tables' position ranges are those the step's own sort left in its plan)
-    const SortSegments seg{ctx->T, &ctx->meta};
+    const SortSegments seg{ctx->T, &ctx->meta, ctx->sort_digit_bits};
     launch_sort_pairs(s.keys, nullptr, s.sort_n, seg, s.sort, &k, &v, nullptr);
     HIP_TRY(ctx, hipDeviceSynchronize());
     HIP_TRY(ctx, hipMemcpy(host_out, v, bytes < ns * 4 ? bytes : ns * 4, hipMemcpyDeviceToHost));

@@ -1,4 +1,4 @@
-// Stable LSD radix sort of (global row, value) pairs, 8 bits per pass (gfx950).
+// Stable LSD radix sort of (global row, value) pairs, up to 10 bits per pass (gfx950).
 // The embedding backward needs every distinct row's occurrences side by side and in
 // ascending flat position, so equal keys must keep their input order: each pass is
 // histogram -> per-digit scan over blocks -> stable scatter.
@@ -6,22 +6,25 @@
 // The input is table-major (all positions of table 0, then table 1, ...) and the key is
 // row_base[t] + row, so the tables' position ranges are already in key order: every table's
 // range is sorted on its own, on the digits of the LOCAL row, with as many passes as that
-// table's row count needs (a table of 60 000 rows takes two passes, one of 40 million four),
-// and a table's last pass writes into the common result buffers.  The ranges come from a
+// table's row count needs and digits of that table's own width: b bits of local row take
+// ceil(b / max_digit_bits) passes of ceil(b / passes) bits each (with the default of 8 a table
+// of 60 000 rows takes two passes of 8 bits, one of 40 million rows four of 7; with 10 a table
+// of a million rows takes two passes of 10 bits), and a table's last pass writes into the
+// common result buffers.  The ranges come from a
 // plan the step's gather kernel leaves in the scratch (first position and first tile of every
 // table); blocks map to (table, tile) through it.
 //
 // A block owns a contiguous tile of 256*rounds elements of one table; wave w of the block owns
 // the w-th quarter of the tile and walks it 64 elements at a time, so "earlier in the tile" is
-// (wave, round, lane) order.  Ranks among equal digits inside a wave come from 8 ballots
-// (one per digit bit); running per-wave digit counts live in LDS.  The scatter first reorders
+// (wave, round, lane) order.  Ranks among equal digits inside a wave come from one ballot per
+// digit bit; running per-wave digit counts live in LDS.  The scatter first reorders
 // its tile by digit inside LDS, so that elements with equal digits leave as contiguous runs.
 #include "ss_internal.h"
 
 namespace ss {
 
-constexpr int RADIX_BITS = 8;
-constexpr int RADIX = 1 << RADIX_BITS;
+constexpr int RADIX_BITS_MAX = 10;             // widest digit any pass may use
+constexpr int RADIX_MAX = 1 << RADIX_BITS_MAX;
 constexpr int SORT_THREADS = 256;
 constexpr int SORT_WAVES = SORT_THREADS / SS_WAVE;
 constexpr int MAX_ROUNDS = 16;
@@ -58,6 +61,7 @@ struct SegDev {
   // meta.row_base[t] from the byte address of passes[t] (base + t, plus 3 t), and a scalar load
   // ignores the two low bits of each of its address components
   int32_t passes[SS_MAX_TABLES];
+  int32_t width[SS_MAX_TABLES];   // digit bits of the table's passes (1..RADIX_BITS_MAX)
   TableMeta meta;
 };
 
@@ -77,14 +81,16 @@ __device__ __forceinline__ bool seg_of_block(const SegDev& g, int pass, uint32_t
 __global__ __launch_bounds__(SORT_THREADS) void radix_hist_kernel(
     const uint32_t* __restrict__ keys, SegDev g, int pass, int rounds, int pitch,
     uint32_t* __restrict__ block_hist) {
-  __shared__ uint32_t hist[RADIX];
+  __shared__ uint32_t hist[RADIX_MAX];
   const uint32_t tile = (uint32_t)(SORT_THREADS * rounds);
   int t;
   uint32_t base, end;
   if (!seg_of_block(g, pass, tile, t, base, end)) return;
   const uint32_t rb = g.meta.row_base[t];
-  const int shift = pass * RADIX_BITS;
-  hist[threadIdx.x] = 0;
+  const int width = g.width[t];
+  const int shift = pass * width;
+  const uint32_t dmask = (1u << width) - 1u;
+  for (int d = threadIdx.x; d < RADIX_MAX; d += SORT_THREADS) hist[d] = 0;
   __syncthreads();
   // the order inside the tile does not matter here: 16-byte loads from the aligned start
   // below the tile, all issued up front; elements outside [base, end) are masked
@@ -106,10 +112,10 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_hist_kernel(
     const uint32_t j0 = a0 + 4 * v;
     const bool any = v < nv;
     const bool full = any && j0 >= base && j0 + 4 <= end;
-    const uint32_t d0 = ((q[i].x - rb) >> shift) & (RADIX - 1);
-    const uint32_t d1 = ((q[i].y - rb) >> shift) & (RADIX - 1);
-    const uint32_t d2 = ((q[i].z - rb) >> shift) & (RADIX - 1);
-    const uint32_t d3 = ((q[i].w - rb) >> shift) & (RADIX - 1);
+    const uint32_t d0 = ((q[i].x - rb) >> shift) & dmask;
+    const uint32_t d1 = ((q[i].y - rb) >> shift) & dmask;
+    const uint32_t d2 = ((q[i].z - rb) >> shift) & dmask;
+    const uint32_t d3 = ((q[i].w - rb) >> shift) & dmask;
     // inside a long run of one hot row whole waves share one digit: count those with a single
     // LDS atomic instead of 256 colliding ones
     const bool same4 = full && (d0 == d1) && (d1 == d2) && (d2 == d3);
@@ -131,7 +137,8 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_hist_kernel(
     }
   }
   __syncthreads();
-  block_hist[(size_t)threadIdx.x * pitch + blockIdx.x] = hist[threadIdx.x];  // digit-major
+  for (uint32_t d = threadIdx.x; d <= dmask; d += SORT_THREADS)
+    block_hist[(size_t)d * pitch + blockIdx.x] = hist[d];  // digit-major
 }
 
 // One wave per (digit, table): exclusive scan of that digit's counts over the table's tiles
@@ -140,7 +147,7 @@ __global__ __launch_bounds__(64) void radix_scan_kernel(uint32_t* __restrict__ b
                                                         int pitch, SegDev g, int pass,
                                                         uint32_t* __restrict__ seg_tot) {
   const int t = blockIdx.y, lane = threadIdx.x;
-  if ((int)g.passes[t] <= pass) return;
+  if ((int)g.passes[t] <= pass || (int)blockIdx.x >= (1 << g.width[t])) return;
   const uint32_t b0 = g.tile_base[t], nb = g.tile_base[t + 1] - b0;
   uint32_t* row = block_hist + (size_t)blockIdx.x * pitch + b0;
   const uint32_t per = (nb + 63) / 64;
@@ -159,20 +166,27 @@ __global__ __launch_bounds__(64) void radix_scan_kernel(uint32_t* __restrict__ b
     row[i] = run;
     run += c;
   }
-  if (lane == 63) seg_tot[t * RADIX + blockIdx.x] = incl;
+  if (lane == 63) seg_tot[t * RADIX_MAX + blockIdx.x] = incl;
 }
 
+// RB: digit bits the kernel's LDS tables are sized for (the widest digit of any table of this
+// sort); a table with narrower digits uses the first 2^width entries.
+template <int RB>
 __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
     const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in, SegDev g, int pass,
     int rounds, int pitch, const uint32_t* __restrict__ block_hist,
     const uint32_t* __restrict__ seg_tot, uint32_t* __restrict__ keys_mid,
     uint32_t* __restrict__ vals_mid, uint32_t* __restrict__ keys_fin,
     uint32_t* __restrict__ vals_fin) {
+  constexpr int ND = 1 << RB;                   // digits the tables hold
+  constexpr int DPT = ND / SORT_THREADS;        // consecutive digits per thread (1, 2 or 4)
+  static_assert(DPT >= 1 && RB <= RADIX_BITS_MAX && RADIX_MAX == SORT_MAX_DIGITS, "digit tables are split over the block's threads");
   // per-wave running digit counts; volatile: lanes of one wave hand values to each other
   // through it between rounds without a barrier
-  __shared__ volatile uint32_t wrun[SORT_WAVES][RADIX];
-  __shared__ uint32_t gbase[RADIX];             // global start of this block's run of a digit
-  __shared__ uint32_t lbase[RADIX];             // start of the digit inside the block's tile
+  __shared__ volatile uint32_t wrun[SORT_WAVES][ND];
+  __shared__ uint32_t gbase[ND];                // global start of this block's run of a digit
+  __shared__ uint32_t lbase[ND];                // start of the digit inside the block's tile
+  __shared__ uint32_t gsum[SORT_THREADS], lsum[SORT_THREADS];
   __shared__ uint32_t skey[SORT_THREADS * MAX_ROUNDS], sval[SORT_THREADS * MAX_ROUNDS];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint32_t tile = (uint32_t)(SORT_THREADS * rounds);
@@ -180,7 +194,9 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
   uint32_t base, n;   // n: end of this tile's elements
   if (!seg_of_block(g, pass, tile, t, base, n)) return;
   const uint32_t rb = g.meta.row_base[t];
-  const int shift = pass * RADIX_BITS;
+  const int width = g.width[t];                 // <= RB
+  const int shift = pass * width;
+  const uint32_t dmask = (1u << width) - 1u;
   // a table's last pass writes the common result buffers
   const bool last = pass == (int)g.passes[t] - 1;
   uint32_t* __restrict__ keys_out = last ? keys_fin : keys_mid;
@@ -196,9 +212,20 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
       val[r] = (j < n && vals_in) ? vals_in[j] : j;
     }
   }
-  const uint32_t dtot = seg_tot[t * RADIX + tid];
-  const uint32_t boff = block_hist[(size_t)tid * pitch + blockIdx.x] + g.seg_lo[t];
-  for (int w = 0; w < SORT_WAVES; ++w) wrun[w][tid] = 0;
+  // this thread's digits: tid * DPT + i
+  uint32_t dtot[DPT], boff[DPT];
+  const uint32_t lo_t = g.seg_lo[t];
+#pragma unroll
+  for (int i = 0; i < DPT; ++i) {
+    const uint32_t d = (uint32_t)(tid * DPT + i);
+    const bool used = d <= dmask;
+    dtot[i] = used ? seg_tot[t * RADIX_MAX + d] : 0u;
+    boff[i] = used ? block_hist[(size_t)d * pitch + blockIdx.x] + lo_t : 0u;
+  }
+#pragma unroll
+  for (int w = 0; w < SORT_WAVES; ++w)
+#pragma unroll
+    for (int i = 0; i < DPT; ++i) wrun[w][tid + i * SORT_THREADS] = 0;
   __syncthreads();
 
 #pragma unroll
@@ -206,16 +233,18 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
     if (r < rounds) {
       const uint32_t j = wbase + r * SS_WAVE + lane;
       const bool valid = j < n;
-      const uint32_t dg = ((key[r] - rb) >> shift) & (RADIX - 1);
+      const uint32_t dg = ((key[r] - rb) >> shift) & dmask;
       uint64_t m = __ballot(valid);
       // a wave inside a long run of one hot row (passes after the first: equal keys are
       // neighbours) holds a single digit: every valid lane matches every other
       const uint32_t lead = __builtin_amdgcn_readfirstlane(dg);
       if (__ballot(valid && dg != lead) != 0) {
 #pragma unroll
-        for (int b = 0; b < RADIX_BITS; ++b) {
-          const uint64_t bal = __ballot((dg >> b) & 1u);
-          m &= ((dg >> b) & 1u) ? bal : ~bal;
+        for (int b = 0; b < RB; ++b) {
+          if (b < width) {   // wave-uniform
+            const uint64_t bal = __ballot((dg >> b) & 1u);
+            m &= ((dg >> b) & 1u) ? bal : ~bal;
+          }
         }
       }
       // m = valid lanes of this wave holding the same digit (includes this lane if valid)
@@ -231,29 +260,45 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
   __syncthreads();
   // per digit: exclusive prefix of the per-wave counts over the waves; the digit's count in
   // this tile feeds the scan over digits below
-  uint32_t cnt = 0;
-  for (int w = 0; w < SORT_WAVES; ++w) {
-    const uint32_t c = wrun[w][tid];
-    wrun[w][tid] = cnt;
-    cnt += c;
+  uint32_t cnt[DPT];
+  uint32_t gs = 0, ls = 0;
+#pragma unroll
+  for (int i = 0; i < DPT; ++i) {
+    const int d = tid * DPT + i;
+    uint32_t c0 = 0;
+#pragma unroll
+    for (int w = 0; w < SORT_WAVES; ++w) {
+      const uint32_t c = wrun[w][d];
+      wrun[w][d] = c0;
+      c0 += c;
+    }
+    cnt[i] = c0;
+    gs += dtot[i];
+    ls += c0;
   }
-  // two exclusive scans over the 256 digits at once: digit totals of the whole array (global
-  // digit starts) and digit counts of this tile (starts inside the tile)
-  gbase[tid] = dtot;
-  lbase[tid] = cnt;
+  // two exclusive scans over the digits at once: digit totals of the table's whole range
+  // (global digit starts) and digit counts of this tile (starts inside the tile); a thread's
+  // consecutive digits are scanned in registers, the threads' sums in LDS
+  gsum[tid] = gs;
+  lsum[tid] = ls;
   __syncthreads();
-  for (int off = 1; off < RADIX; off <<= 1) {
-    const uint32_t a = (tid >= off) ? gbase[tid - off] : 0;
-    const uint32_t b = (tid >= off) ? lbase[tid - off] : 0;
+  for (int off = 1; off < SORT_THREADS; off <<= 1) {
+    const uint32_t a = (tid >= off) ? gsum[tid - off] : 0;
+    const uint32_t b = (tid >= off) ? lsum[tid - off] : 0;
     __syncthreads();
-    gbase[tid] += a;
-    lbase[tid] += b;
+    gsum[tid] += a;
+    lsum[tid] += b;
     __syncthreads();
   }
-  const uint32_t gex = gbase[tid] - dtot, lex = lbase[tid] - cnt;
-  __syncthreads();
-  gbase[tid] = gex + boff;
-  lbase[tid] = lex;
+  uint32_t gex = gsum[tid] - gs, lex = lsum[tid] - ls;
+#pragma unroll
+  for (int i = 0; i < DPT; ++i) {
+    const int d = tid * DPT + i;
+    gbase[d] = gex + boff[i];
+    lbase[d] = lex;
+    gex += dtot[i];
+    lex += cnt[i];
+  }
   __syncthreads();
   // reorder the tile by digit inside LDS (stable: wave, round, lane order within a digit)
 #pragma unroll
@@ -261,7 +306,7 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
     if (r < rounds) {
       const uint32_t j = wbase + r * SS_WAVE + lane;
       if (j < n) {
-        const uint32_t dg = ((key[r] - rb) >> shift) & (RADIX - 1);
+        const uint32_t dg = ((key[r] - rb) >> shift) & dmask;
         const uint32_t lp = lbase[dg] + wrun[wave][dg] + rank[r];
         skey[lp] = key[r];
         sval[lp] = val[r];
@@ -274,7 +319,7 @@ __global__ __launch_bounds__(SORT_THREADS) void radix_scatter_kernel(
   const uint32_t count = n - base;
   for (uint32_t i = tid; i < count; i += SORT_THREADS) {
     const uint32_t k = skey[i], v = sval[i];
-    const uint32_t dg = ((k - rb) >> shift) & (RADIX - 1);
+    const uint32_t dg = ((k - rb) >> shift) & dmask;
     const uint32_t dst = gbase[dg] + (i - lbase[dg]);
     keys_out[dst] = k;
     vals_out[dst] = v;
@@ -293,18 +338,25 @@ void launch_sort_pairs(const uint32_t* keys, const uint32_t* vals, uint32_t n,
   // upper bound of the tiles: every table's range may end in a partial one
   const int nblocks = ceil_div(n, tile) + seg.T;
   const int pitch = nblocks;
+  int dmax = seg.max_digit_bits;
+  if (dmax < 8) dmax = 8;
+  if (dmax > RADIX_BITS_MAX) dmax = RADIX_BITS_MAX;
   SegDev g;
   g.seg_lo = sc.seg_lo; g.tile_base = sc.tile_base; g.T = seg.T; g.meta = *seg.meta;
-  int max_passes = 1;
+  int max_passes = 1, max_width = 1;
   for (int t = 0; t < seg.T; ++t) {
-    // bits of the largest local row of the table
+    // bits of the largest local row of the table, split evenly over the fewest passes
     const uint32_t rows = seg.meta->row_base[t + 1] - seg.meta->row_base[t];
     int bits = 1;
     while (bits < 32 && (1ull << bits) < rows) ++bits;
-    const int p = (bits + RADIX_BITS - 1) / RADIX_BITS;
+    const int p = (bits + dmax - 1) / dmax;
+    const int w = (bits + p - 1) / p;
     g.passes[t] = p;
+    g.width[t] = w;
     if (p > max_passes) max_passes = p;
+    if (w > max_width) max_width = w;
   }
+  for (int t = seg.T; t < SS_MAX_TABLES; ++t) { g.passes[t] = 0; g.width[t] = 1; }
   const uint32_t* kin = keys;
   const uint32_t* vin = vals;     // null: the value is the element's own position
   uint32_t* kmid = sc.keys_a; uint32_t* kother = sc.keys_b;
@@ -312,11 +364,20 @@ void launch_sort_pairs(const uint32_t* keys, const uint32_t* vals, uint32_t n,
   for (int p = 0; p < max_passes; ++p) {
     hipLaunchKernelGGL(radix_hist_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, g, p,
                        rounds, pitch, sc.block_hist);
-    hipLaunchKernelGGL(radix_scan_kernel, dim3(RADIX, seg.T), dim3(64), 0, s, sc.block_hist, pitch,
-                       g, p, sc.seg_tot);
-    hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, vin, g,
-                       p, rounds, pitch, sc.block_hist, sc.seg_tot, kmid, vmid, sc.keys_f,
-                       sc.vals_f);
+    hipLaunchKernelGGL(radix_scan_kernel, dim3(1 << max_width, seg.T), dim3(64), 0, s,
+                       sc.block_hist, pitch, g, p, sc.seg_tot);
+    if (max_width <= 8)
+      hipLaunchKernelGGL(radix_scatter_kernel<8>, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, vin,
+                         g, p, rounds, pitch, sc.block_hist, sc.seg_tot, kmid, vmid, sc.keys_f,
+                         sc.vals_f);
+    else if (max_width == 9)
+      hipLaunchKernelGGL(radix_scatter_kernel<9>, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin, vin,
+                         g, p, rounds, pitch, sc.block_hist, sc.seg_tot, kmid, vmid, sc.keys_f,
+                         sc.vals_f);
+    else
+      hipLaunchKernelGGL(radix_scatter_kernel<10>, dim3(nblocks), dim3(SORT_THREADS), 0, s, kin,
+                         vin, g, p, rounds, pitch, sc.block_hist, sc.seg_tot, kmid, vmid,
+                         sc.keys_f, sc.vals_f);
     kin = kmid; vin = vmid;
     uint32_t* x = kmid; kmid = kother; kother = x;
     x = vmid; vmid = vother; vother = x;

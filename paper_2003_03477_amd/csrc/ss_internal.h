@@ -81,11 +81,12 @@ struct SortScratch {
   uint32_t* vals;       // [max_ids + 4]
   uint32_t* vals_alt;   // [max_ids + 4]
   uint32_t* vals_f;     // [max_ids + 4] result
-  uint32_t* block_hist; // [256 * max_sort_blocks]
-  uint32_t* seg_tot;    // [SS_MAX_TABLES * 256] digit totals per table
+  uint32_t* block_hist; // [SORT_MAX_DIGITS * max_sort_blocks]
+  uint32_t* seg_tot;    // [SS_MAX_TABLES * SORT_MAX_DIGITS] digit totals per table
   uint32_t* seg_lo;     // [SS_MAX_TABLES + 1] first position of every table (the plan, kept
   uint32_t* tile_base;  // [SS_MAX_TABLES + 1]  between calls)
 };
+constexpr int SORT_MAX_DIGITS = 1024;   // values of the widest digit (10 bits) a pass may use
 int sort_num_blocks(uint32_t n, int* rounds_out);
 int sort_max_blocks(uint32_t max_n);
 uint32_t sort_tile(uint32_t n);   // tile length the sort of n elements uses
@@ -95,6 +96,7 @@ uint32_t sort_tile(uint32_t n);   // tile length the sort of n elements uses
 struct SortSegments {
   int T;
   const TableMeta* meta;
+  int max_digit_bits;   // 8..10: widest digit of a pass
 };
 // Stable LSD radix sort of (key, value) pairs, every table's range on its own local rows;
 // vals == nullptr sorts (key, position).  The inputs (at least max_ids + 4 elements long) are

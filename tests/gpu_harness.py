@@ -116,7 +116,8 @@ def oracle_step(gpu, orc, slot, replica, batch_tuple):
     return orc.train_step(replica, *batch_tuple, gate_flips=flips), n
 
 
-def make_pair(wl, batches, h0=None, rows=None, slots=1, dtype=np.float64, mlp_path="auto"):
+def make_pair(wl, batches, h0=None, rows=None, slots=1, dtype=np.float64, mlp_path="auto",
+              sort_digit_bits=0):
     """(gpu context, oracle trainer) holding the same initial state."""
     rows = tuple(rows if rows is not None else wl.rows)
     row_base = np.concatenate(([0], np.cumsum(rows)))
@@ -128,7 +129,8 @@ def make_pair(wl, batches, h0=None, rows=None, slots=1, dtype=np.float64, mlp_pa
                              max(b.dense.shape[0] for b in batches), max_ids, slots, wl.bf16,
                              wl.lr_dense, wl.lr_emb, wl.adagrad_eps, wl.seed, pooling=wl.pooling,
                              mlp_path=mlp_path, emb_optimizer=wl.emb_optimizer,
-                             adam_betas=wl.adam_betas, emb_row_shards=wl.emb_row_shards)
+                             adam_betas=wl.adam_betas, emb_row_shards=wl.emb_row_shards,
+                             sort_digit_bits=sort_digit_bits)
     for t in range(len(rows)):
         gpu.ss_write_rows(t, 0, h0[row_base[t]:row_base[t + 1]])
     gpu.ss_init_dense(w0)

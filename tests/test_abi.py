@@ -58,6 +58,11 @@ def test_workspace_size_and_validation_on_host():
         cfgb, keepb = _cfg(**bad)
         assert lib.ss_workspace_bytes(C.byref(cfgb)) == 0, bad
         assert lib.ss_last_error(None)
+    # widest digit of the backward's radix sort: 0 (default), 8, 9 or 10
+    for bits, ok in ((0, True), (8, True), (9, True), (10, True), (7, False), (11, False), (-1, False)):
+        cfgs, keeps = _cfg()
+        cfgs.sort_digit_bits = bits
+        assert (lib.ss_workspace_bytes(C.byref(cfgs)) == n) == ok, bits
     ctx = C.c_void_p()
     assert lib.ss_init(C.byref(cfg), None, n, C.byref(ctx)) == -1  # SS_EINVAL: null workspace
     # raw sync entry point rejects malformed arguments before touching the device

@@ -1,4 +1,6 @@
 """Parity of the HIP path (through the C ABI) against the CPU oracle on seeded inputs."""
+import functools
+
 import numpy as np
 import pytest
 
@@ -567,3 +569,37 @@ def test_many_small_tables():
     gpu, orc = H.make_pair(wl, batches)
     H.run_lockstep(gpu, orc, batches, 1, "ma", 1.0)
     H.compare_state(gpu, orc, H.FP32_RTOL, "33 tables", wl.row_base)
+
+
+_SORT_ROWS = (1, 2, 300, 70_000, 600_000, (1 << 20) + 1)
+
+
+@functools.lru_cache(maxsize=1)
+def _sort_width_problem():
+    rows = _SORT_ROWS
+    T = len(rows)
+    wl = synth.tiny().scaled(batch=512, rows=rows, emb_dim=16, bag_lambda=25.0,
+                             bot_dims=(13, 24, 16), top_dims=(16 + T * (T + 1) // 2, 32, 1),
+                             num_replicas=1, algo="ma", alpha=1.0)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(2)]
+    for b in batches:   # every table's last row (the top bit of its widest digit) is hit
+        for t in range(T):
+            lo, hi = int(b.offsets[t * wl.batch]), int(b.offsets[(t + 1) * wl.batch])
+            b.indices[lo + (hi - lo) // 3] = rows[t] - 1
+            b.indices[hi - 1] = rows[t] - 1
+    return wl, batches, synth.full_tables_h0(wl)
+
+
+@pytest.mark.parametrize("digit_bits", [8, 9, 10])
+def test_sort_digit_widths(digit_bits):
+    """The stable sort with every permitted digit width, on tables whose local rows need 1 to
+    21 bits (one to three passes each, widths 1 to 10), ~80k ids per step (tiles of 512
+    elements, several per table, ragged ends): sorted rows, positions, segment starts and the
+    updated rows against the oracle."""
+    wl, batches, h0 = _sort_width_problem()
+    assert min(int(b.offsets[-1]) for b in batches) > 65536
+    gpu, orc = H.make_pair(wl, batches, h0=h0.copy(), sort_digit_bits=digit_bits)
+    H.run_lockstep(gpu, orc, batches, 1, "ma", 1.0)
+    H.compare_state(gpu, orc, H.FP32_RTOL, f"sort digits of {digit_bits} bits", wl.row_base)
+    gpu.close()
