@@ -17,9 +17,10 @@ HBM before the clock starts.
 Prints ONE JSON line.  Besides the contract fields:
   no_shadow       the same K sweeps with the shadow stream off, and value / that (Section 3.2:
                   training is not stalled by the synchronisation)
-  roofline        the kernel with the largest summed time over the timed region (all classes,
-                  MLP kernels against the bf16 MFMA peak, memory-bound ones against HBM peak),
-                  HIP events on the launching streams inside the timed region
+  roofline        the kernel class a step spends most time in (all classes ranked, MLP kernels
+                  against the bf16 MFMA peak, memory-bound ones against HBM peak), timed with
+                  HIP events on the launching streams inside the timed region; the largest
+                  MFMA class is reported beside it
   kernels         event timing of every kernel class
   sync_isolation  the three shadow rules on K=8 x 50M-parameter replicas, GB/s vs HBM peak
   cpu_baseline    the numpy oracle on the host cores, on a bounded sample of the same workload
@@ -487,10 +488,28 @@ def pick_roofline(kernels, NS):
     cand = {k: v for k, v in kernels.items() if "total_ms_in_timed_region" in v}
     if not cand:
         return None
-    dom = max(cand, key=lambda k: cand[k]["total_ms_in_timed_region"])
+    # Ranked by the time a step spends in the class with one stream active (launches per step
+    # x duration alone, where an event pair and the profiler agree): with several streams an
+    # event pair also spans the launch's wait for free CUs, which inflates a class of many short
+    # launches far more than one long kernel (GEMM launches x2.4, the row update x1.25 against
+    # the profiler inside the same region) and would rank the classes differently from the
+    # profile of the same command.
+    def per_step_us(k):
+        v = cand[k]
+        return (v.get("alone_avg_us") or v["avg_us"]) * v["launches_per_step"]
+    dom = max(cand, key=per_step_us)
     kd = cand[dom]
     mfma = kd["bound"] == "mfma"
+    mf = {k: v for k, v in cand.items() if v["bound"] == "mfma"}
+    top_mfma = max(mf, key=per_step_us) if mf else None
     return {"bound": kd["bound"], "kernel": dom,
+            "ranking_us_per_step_one_stream": {k: per_step_us(k) for k in cand},
+            "largest_mfma_class": None if top_mfma is None else {
+                "kernel": top_mfma, "frac": mf[top_mfma]["frac_of_bf16_mfma_peak"],
+                "alone_frac": mf[top_mfma].get("alone_frac_of_bf16_mfma_peak"),
+                "avg_launch_us": mf[top_mfma]["avg_us"],
+                "alone_avg_launch_us": mf[top_mfma].get("alone_avg_us"),
+                "profiler_in_region_avg_launch_us": mf[top_mfma].get("profiler_in_region_avg_us")},
             "achieved": kd["TFLOPps"] if mfma else kd["GBps"],
             "peak": MFMA_BF16_PEAK_TFLOPS if mfma else HBM_PEAK_GBS,
             "unit": "TFLOP/s" if mfma else "GB/s",
@@ -503,7 +522,8 @@ def pick_roofline(kernels, NS):
             "profiler_in_region_avg_launch_us": kd.get("profiler_in_region_avg_us"),
             "alone_achieved": kd.get("alone_TFLOPps") if mfma else kd.get("alone_GBps"),
             "alone_frac": kd.get("alone_frac_of_bf16_mfma_peak") if mfma else kd.get("alone_frac_of_hbm_peak"),
-            "note": "largest summed time of all one-kernel classes over the timed region; HIP "
+            "note": "the one-kernel class a step spends most time in (all classes ranked by "
+                    "launches per step x duration with one stream active); achieved / frac: HIP "
                     f"events on the launching streams while {NS} worker streams (+ shadow) share "
                     "the GPU, so queueing and shared bandwidth are included; alone_*: the same "
                     "class with one stream active, measured after the timed regions; MFMA classes "

@@ -45,22 +45,30 @@ def test_mlp_flops_of_the_configs():
     assert 2.7e9 < mid_total < 2.9e9
 
 
-def test_dominant_kernel_is_the_largest_total_over_all_classes():
+def test_dominant_kernel_is_the_largest_per_step_time_over_all_classes():
+    """Classes are ranked by launches per step x duration with one stream active (the event
+    brackets under several streams inflate short launches); without that figure, by the
+    in-region brackets."""
     kernels = {
         "gather": {"total_ms_in_timed_region": 5.0, "bound": "hbm", "GBps": 4000.0, "frac_of_hbm_peak": 0.5,
-                   "avg_us": 100.0, "brackets": 50, "launches_per_step": 1,
+                   "avg_us": 100.0, "alone_avg_us": 90.0, "brackets": 50, "launches_per_step": 1,
                    "algorithmic_bytes_per_launch": 4e8, "counter_bytes_per_launch": 2e8},
         "mlp_fwd": {"total_ms_in_timed_region": 9.0, "bound": "mfma", "TFLOPps": 300.0,
-                    "frac_of_bf16_mfma_peak": 0.12, "avg_us": 20.0, "brackets": 350,
+                    "frac_of_bf16_mfma_peak": 0.12, "alone_frac_of_bf16_mfma_peak": 0.3,
+                    "avg_us": 50.0, "alone_avg_us": 20.0, "brackets": 350,
                     "launches_per_step": 7, "algorithmic_flops_per_launch": 6e9},
         "sort_all_passes": {"avg_us": 200.0, "brackets": 8},      # a group class: not a candidate
     }
-    r = bench.pick_roofline(kernels, 8)
+    r = bench.pick_roofline(kernels, 8)      # 7 x 20 us against 1 x 90 us
     assert r["kernel"] == "mlp_fwd" and r["bound"] == "mfma" and r["peak"] == 2500.0
     assert r["unit"] == "TFLOP/s" and r["frac"] == 0.12 and r["traffic"] is None
-    kernels["gather"]["total_ms_in_timed_region"] = 10.0
-    r = bench.pick_roofline(kernels, 8)
+    assert r["ranking_us_per_step_one_stream"] == {"gather": 90.0, "mlp_fwd": 140.0}
+    kernels["mlp_fwd"]["alone_avg_us"] = 10.0   # 70 us per step: the gather leads, although the
+    r = bench.pick_roofline(kernels, 8)         # in-region brackets sum to more for the MLP
     assert r["kernel"] == "gather" and r["peak"] == 8000.0 and r["traffic"] == 2e8
+    assert r["largest_mfma_class"]["kernel"] == "mlp_fwd" and r["largest_mfma_class"]["frac"] == 0.12
+    del kernels["mlp_fwd"]["alone_avg_us"]      # no one-stream figure: 7 x 50 us of brackets
+    assert bench.pick_roofline(kernels, 8)["kernel"] == "mlp_fwd"
     assert bench.pick_roofline({"sort_all_passes": {"avg_us": 1.0}}, 1) is None
 
 
