@@ -22,7 +22,9 @@ Prints ONE JSON line.  Besides the contract fields:
                   HIP events on the launching streams inside the timed region; the largest
                   MFMA class is reported beside it
   kernels         event timing of every kernel class
-  sync_isolation  the three shadow rules on K=8 x 50M-parameter replicas, GB/s vs HBM peak
+  sync_isolation  the three shadow rules on K=8 x 50M-parameter replicas, GB/s vs HBM peak, and
+                  the streaming ceiling of this GPU (a plain 800 MB device copy); every
+                  HBM-bound figure of the line is also given as a fraction of that ceiling
   cpu_baseline    the numpy oracle on the host cores, on a bounded sample of the same workload
   secondary       the Mid workload's throughput measured the same way (when the headline is Large)
 `--sweep widths|gap` adds the Hogwild width sweep (Section 4.4) / the sync gap against the
@@ -615,10 +617,49 @@ def sync_isolation(rounds=50):
         gbs = per_param[algo] * P / us / 1e3
         out[algo] = {"us_per_round": us, "algorithmic_bytes": per_param[algo] * P,
                      "GBps": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    # the streaming ceiling of this GPU, measured: a plain device-to-device copy of 800 MB
+    # (read + write counted), the figure the 8 TB/s datasheet peak is to be read against
+    half = K // 2 * P
+    with torch.cuda.stream(st):
+        for _ in range(3):
+            W[half:].copy_(W[:half])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(20):
+            W[half:].copy_(W[:half])
+        e1.record(st)
+    e1.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / 20
+    ceiling = 2 * 4 * half / us / 1e3
+    out["copy_ceiling"] = {"GBps": ceiling, "frac_of_hbm_peak": ceiling / HBM_PEAK_GBS,
+                           "what": f"torch device-to-device copy of {4 * half} bytes, read + write "
+                                   "counted, 20 copies back to back"}
+    for algo in ("easgd", "ma", "bmuf"):
+        out[algo]["frac_of_copy_ceiling"] = out[algo]["GBps"] / ceiling
     out["config"] = f"K={K} replicas x {P} fp32 parameters, {rounds} rounds per rule back to back"
     del W, ps, wg, v
     torch.cuda.empty_cache()
     return out
+
+
+def annotate_copy_ceiling(out, ceiling):
+    """Every HBM-bound figure of the line also as a fraction of the measured copy ceiling."""
+    def one(kd):
+        if kd and kd.get("bound") == "hbm":
+            g = kd.get("GBps", kd.get("achieved"))
+            if g is not None:
+                kd["frac_of_copy_ceiling"] = g / ceiling
+            a = kd.get("alone_GBps", kd.get("alone_achieved"))
+            if a is not None:
+                kd["alone_frac_of_copy_ceiling"] = a / ceiling
+    one(out.get("roofline"))
+    for kd in out.get("kernels", {}).values():
+        one(kd)
+    mid = out.get("secondary", {}).get("mid")
+    if mid:
+        one(mid.get("roofline"))
+        for kd in mid.get("kernels", {}).values():
+            one(kd)
 
 
 def parse_workers(text, K):
@@ -792,6 +833,7 @@ def main():
             "roofline": pick_roofline(r["kernels"], r["worker_streams"]), "kernels": r["kernels"]}}
     if not args.no_sync_isolation:
         out["sync_isolation"] = sync_isolation()
+        annotate_copy_ceiling(out, out["sync_isolation"]["copy_ceiling"]["GBps"])
         progress("sync isolation done")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

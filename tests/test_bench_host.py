@@ -88,3 +88,19 @@ def test_counter_summaries_are_parsed():
 def test_worker_lists():
     assert bench.parse_workers("2", 4) == [2, 2, 2, 2]
     assert bench.parse_workers("8,1,1,1", 4) == [8, 1, 1, 1]
+
+
+def test_fractions_of_the_measured_copy_ceiling():
+    out = {"roofline": {"bound": "hbm", "achieved": 2500.0, "alone_achieved": 4000.0},
+           "kernels": {"gather": {"bound": "hbm", "GBps": 3000.0, "alone_GBps": 4500.0},
+                       "mlp_fwd": {"bound": "mfma", "TFLOPps": 300.0},
+                       "sort_all_passes": {"avg_us": 1.0}},
+           "secondary": {"mid": {"roofline": {"bound": "mfma", "achieved": 30.0},
+                                 "kernels": {"row_update_chunk": {"bound": "hbm", "GBps": 1000.0}}}}}
+    bench.annotate_copy_ceiling(out, 5000.0)
+    assert out["roofline"]["frac_of_copy_ceiling"] == 0.5 and out["roofline"]["alone_frac_of_copy_ceiling"] == 0.8
+    assert out["kernels"]["gather"]["frac_of_copy_ceiling"] == 0.6
+    assert out["kernels"]["gather"]["alone_frac_of_copy_ceiling"] == 0.9
+    assert "frac_of_copy_ceiling" not in out["kernels"]["mlp_fwd"]
+    assert "frac_of_copy_ceiling" not in out["secondary"]["mid"]["roofline"]
+    assert out["secondary"]["mid"]["kernels"]["row_update_chunk"]["frac_of_copy_ceiling"] == 0.2
