@@ -145,22 +145,29 @@ __global__ __launch_bounds__(256) void row_update_chunk_kernel(
     tm_s[sl] = (uint32_t)(tb >> (gw * LPR)) & gmask;
     nv_s[sl] = __popc((uint32_t)(vb >> (gw * LPR)) & gmask);  // valid entries form a prefix
   }
+  // staging registers of a sub-block: gradient rows, and the table row, accumulator and row
+  // id of the entries that end a run.  Declared (and given a value) once: an entry's registers
+  // are only read under the condition they were loaded under, so nothing is cleared per
+  // sub-block.
+  float4 v[SUB], hv[SUB];
+  float Gv[SUB];
+  uint32_t rw[SUB];
+#pragma unroll
+  for (int i = 0; i < SUB; ++i) {
+    v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    hv[i] = v[i];
+    Gv[i] = 0.f;
+    rw[i] = 0;
+  }
 #pragma unroll
   for (int sl = 0; sl < CHUNK_SLICES; ++sl) {
     const uint32_t key = key_s[sl], hm = hm_s[sl], tm = tm_s[sl];
     const int bag = bag_s[sl], nv = nv_s[sl];
     for (int s0 = 0; s0 < nv; s0 += SUB) {
-      float4 v[SUB], hv[SUB];
-      float Gv[SUB];
-      uint32_t rw[SUB];
 #pragma unroll
       for (int i = 0; i < SUB; ++i) {
         const int p = s0 + i;
         const int bg = __shfl(bag, p, LPR);
-        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        hv[i] = v[i];
-        Gv[i] = 0.f;
-        rw[i] = 0;
         if (p < nv) {
           v[i] = *(const float4*)(de + (size_t)bg * D + c * 4);
           if (inv_len) {  // mean pooling: d(mean)/d(member) = 1 / bag length
