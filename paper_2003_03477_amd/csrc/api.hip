@@ -119,6 +119,7 @@ struct ss_ctx {
   std::vector<int64_t> wg_off, wg_stride;  // per layer: its batch slices inside Slot::wg_part
   int64_t wg_elems = 0;
   int wg_slices = 1, wg_slice_len = 0;     // batch slices of the grouped weight-gradient launch
+  int last_stride = 4;                     // floats per partial copy of the output unit's gradients
   std::vector<int4> wgrad_tiles;   // host copy of the tile table
   int4* wgrad_tiles_dev = nullptr;
   float lr_dense, lr_emb, eps;
@@ -288,7 +289,8 @@ static void carve_slot(const ss_ctx* x, Carver& cv, Slot& s, int B, int64_t n, b
   if (x->wide) s.xb = cv.take<uint16_t>((size_t)B * x->pin[0]);
   if (fwd_only) return;
   s.dlogit = cv.take<float>(B);
-  s.grads = cv.take<float>(x->Pstride);
+  // (followed by the partial copies of the output unit's gradients, cleared with it)
+  s.grads = cv.take<float>(x->Pstride + (size_t)LAST_GRAD_COPIES * x->last_stride);
   for (int i = 0; i < 2; ++i) {
     if (x->prec == SS_FP32) s.dbuf[i] = cv.take<float>((size_t)B * x->maxw);
   }
@@ -386,6 +388,7 @@ static ss_ctx* make_ctx(const ss_config* c) {
   x->n_bot_layers = c->n_bot - 1; x->n_top_layers = c->n_top - 1;
   x->P = off;
   x->Pstride = (off + 255) / 256 * 256;
+  x->last_stride = (x->layers.back().in + 1 + 3) / 4 * 4;
   x->F = c->top_dims[0];
   x->ldf = (x->F + 7) / 8 * 8;
   x->ldf16 = (x->F + 7) / 8 * 8;
@@ -918,7 +921,8 @@ static void launch_weight_snapshot(ss_ctx* x, Slot& s, const float* w, bool trai
     base += (end - x->wsw_f[l]) / 8;
   }
   pa.total_frags = base;
-  pa.zero = train ? s.grads : nullptr; pa.zero_n = x->P;
+  pa.zero = train ? s.grads : nullptr;
+  pa.zero_n = x->wide ? x->Pstride + (int64_t)LAST_GRAD_COPIES * x->last_stride : x->P;
   if (cast_dense) {   // layer-wise path: the dense input as bf16 rows of the first GEMM's pitch
     pa.cast_src = cast_dense->dense; pa.cast_dst = s.xb;
     pa.cast_rows = cast_dense->batch; pa.cast_cols = x->num_dense; pa.cast_ld = x->pin[0];
@@ -975,11 +979,11 @@ static void forward_wide(ss_ctx* x, Slot& s, const float* w, const ss_batch* bt,
       // gradient w.r.t. that output (no gate: f is no ReLU output)
       launch_last_layer_train(in, ld_in, w + last.w_off, w + last.b_off, bt->labels, B, last.in,
                               s.logits, s.dlogit, loss, nullptr, 0, s.df, x->ldf,
-                              s.grads + last.w_off, s.grads + last.b_off, st);
+                              s.grads + x->Pstride, x->last_stride, st);
     } else {
       launch_last_layer_train(in, ld_in, w + last.w_off, w + last.b_off, bt->labels, B, last.in,
                               s.logits, s.dlogit, loss, s.dYr[L - 2], x->pout[L - 2], nullptr, 0,
-                              s.grads + last.w_off, s.grads + last.b_off, st);
+                              s.grads + x->Pstride, x->last_stride, st);
     }
   }
 }
@@ -1038,12 +1042,12 @@ static void backward_wide(ss_ctx* x, Slot& s, float* w_rw, const float* loss, co
     g.tiles = x->wgrad_tiles_dev; g.n_tiles = (int)x->wgrad_tiles.size(); g.B = B;
     { ProfScope pk(x, SS_K_MLP_WGRAD, st); launch_gemm_wgrad(g, st); }
     // the reduction is also the step's SGD update of the replica ("update local param w^(i)":
-    // lock-free) and feeds the Train-NE accumulators; the output unit's gradients, complete
-    // since its own launch, ride along as a one-slice segment
+    // lock-free) and feeds the Train-NE accumulators; the output unit's gradients, left in
+    // partial copies by its own launch, ride along as one more segment
     const Layer& last = x->layers[L - 1];
     ReduceSegment& lg = red.seg[red.n_seg++];
-    lg.part = s.grads + last.w_off; lg.out = s.grads + last.w_off; lg.n = (int64_t)last.in + 1;
-    lg.stride = 0; lg.slices = 1; lg.block_base = red_blocks;
+    lg.part = s.grads + x->Pstride; lg.out = s.grads + last.w_off; lg.n = (int64_t)last.in + 1;
+    lg.stride = x->last_stride; lg.slices = LAST_GRAD_COPIES; lg.block_base = red_blocks;
     red_blocks += ceil_div(lg.n, 1024);
     for (int k = 0; k < red.n_seg; ++k) red.seg[k].w = w_rw + (red.seg[k].out - s.grads);
     red.lr = x->lr_dense; red.mean_loss = loss; red.y = bt->labels; red.B = B; red.acc = x->metrics;

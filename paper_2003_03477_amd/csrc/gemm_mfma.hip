@@ -512,14 +512,22 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(ReduceArgs a, int to
   if (vec) {
     const int64_t i = base + threadIdx.x * 4;
     if (i >= sg.n) return;
+    // the replica's element and up to eight slices' partial sums are requested together; the
+    // slices are added in ascending order all the same
+    float4 wv = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (sg.w) wv = *(const float4*)(sg.w + i);
     float4 acc = *(const float4*)(sg.part + i);
-    for (int z = 1; z < sg.slices; ++z) {
-      const float4 v = *(const float4*)(sg.part + (int64_t)z * sg.stride + i);
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    for (int z0 = 1; z0 < sg.slices; z0 += 8) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (z0 + u < sg.slices) v[u] = *(const float4*)(sg.part + (int64_t)(z0 + u) * sg.stride + i);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (z0 + u < sg.slices) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
     }
     *(float4*)(sg.out + i) = acc;
     if (sg.w) {
-      float4 wv = *(const float4*)(sg.w + i);
       wv.x -= a.lr * acc.x; wv.y -= a.lr * acc.y; wv.z -= a.lr * acc.z; wv.w -= a.lr * acc.w;
       *(float4*)(sg.w + i) = wv;
     }
@@ -529,7 +537,15 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(ReduceArgs a, int to
       const int64_t i = base + threadIdx.x + 256 * u;
       if (i < sg.n) {
         float acc = sg.part[i];
-        for (int z = 1; z < sg.slices; ++z) acc += sg.part[(int64_t)z * sg.stride + i];
+        for (int z0 = 1; z0 < sg.slices; z0 += 8) {
+          float v[8];
+#pragma unroll
+          for (int q = 0; q < 8; ++q)
+            if (z0 + q < sg.slices) v[q] = sg.part[(int64_t)(z0 + q) * sg.stride + i];
+#pragma unroll
+          for (int q = 0; q < 8; ++q)
+            if (z0 + q < sg.slices) acc += v[q];
+        }
         sg.out[i] = acc;
         if (sg.w) sg.w[i] -= a.lr * acc;
       }

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void last_layer_train_kernel(
     const float* __restrict__ bias, const float* __restrict__ y, int B, int in,
     float* __restrict__ logits, float* __restrict__ dlogit, float* __restrict__ loss,
     uint16_t* __restrict__ dX, int lddx, float* __restrict__ dX32, int lddx32,
-    float* __restrict__ gW, float* __restrict__ gb) {
+    float* __restrict__ gpart, int gstride) {
   static_assert(LAST_ROWS_PB * 8 == 256, "8 lanes per sample");
   __shared__ float dl[LAST_ROWS_PB], dlq[LAST_ROWS_PB], lossv[LAST_ROWS_PB];
   const int b0 = blockIdx.x * LAST_ROWS_PB;
@@ -135,22 +135,33 @@ __global__ __launch_bounds__(256) void last_layer_train_kernel(
     }
   }
   __syncthreads();
+  float* const gcopy = gpart + (size_t)(blockIdx.x % LAST_GRAD_COPIES) * gstride;
   for (int k = threadIdx.x; k < in; k += 256) {
     const float wq = bf16_to_f32(to_bf16(w[k]));
     float acc = 0.f;
-    for (int r = 0; r < nb; ++r) {
-      const uint16_t xb = X[(size_t)(b0 + r) * ldx + k];
-      const float d = dlq[r];
-      acc += d * bf16_to_f32(xb);
-      if (dX32) dX32[(size_t)(b0 + r) * lddx32 + k] = d * wq;
-      else dX[(size_t)(b0 + r) * lddx + k] = ((int16_t)xb > 0) ? to_bf16(d * wq) : (uint16_t)0;
+    // eight rows' loads in flight at a time (the rows are summed in ascending order all the same)
+    for (int r0 = 0; r0 < nb; r0 += 8) {
+      uint16_t xb[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        xb[i] = (r0 + i < nb) ? X[(size_t)(b0 + r0 + i) * ldx + k] : (uint16_t)0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int r = r0 + i;
+        if (r < nb) {
+          const float d = dlq[r];
+          acc += d * bf16_to_f32(xb[i]);
+          if (dX32) dX32[(size_t)(b0 + r) * lddx32 + k] = d * wq;
+          else dX[(size_t)(b0 + r) * lddx + k] = ((int16_t)xb[i] > 0) ? to_bf16(d * wq) : (uint16_t)0;
+        }
+      }
     }
-    atomicAdd(gW + k, acc);
+    atomicAdd(gcopy + k, acc);
   }
   if (threadIdx.x == 0) {
     float sb = 0.f, tot = 0.f;
     for (int r = 0; r < nb; ++r) { sb += dl[r]; tot += lossv[r]; }
-    atomicAdd(gb, sb);
+    atomicAdd(gcopy + in, sb);
     atomicAdd(loss, tot * (1.0f / (float)B));
   }
 }
@@ -158,9 +169,10 @@ __global__ __launch_bounds__(256) void last_layer_train_kernel(
 void launch_last_layer_train(const uint16_t* X, int ldx, const float* w, const float* bias,
                              const float* y, int B, int in, float* logits, float* dlogit,
                              float* loss, uint16_t* dX, int lddx, float* dX32, int lddx32,
-                             float* gW, float* gb, hipStream_t s) {
+                             float* gpart, int gstride, hipStream_t s) {
   hipLaunchKernelGGL(last_layer_train_kernel, dim3(ceil_div(B, LAST_ROWS_PB)), dim3(256), 0, s, X,
-                     ldx, w, bias, y, B, in, logits, dlogit, loss, dX, lddx, dX32, lddx32, gW, gb);
+                     ldx, w, bias, y, B, in, logits, dlogit, loss, dX, lddx, dX32, lddx32, gpart,
+                     gstride);
 }
 
 }  // namespace ss

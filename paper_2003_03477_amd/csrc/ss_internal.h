@@ -160,11 +160,16 @@ void launch_last_layer_fwd_loss(const uint16_t* X, int ldx, const float* w, cons
                                 const float* y, int B, int in, float* logits, float* dlogit,
                                 float* loss, hipStream_t s);
 // forward, loss and the layer's whole backward in one launch (training steps); the data
-// gradient goes either as bf16, gated by X > 0, to dX, or as fp32 without a gate to dX32
+// gradient goes either as bf16, gated by X > 0, to dX, or as fp32 without a gate to dX32.
+// The weight and bias gradients are added into LAST_GRAD_COPIES partial copies (copy c at
+// gpart + c * gstride: `in` weight sums, then the bias sum; zeroed by the caller), block b into
+// copy b % LAST_GRAD_COPIES: thousands of atomic adds onto the few cache lines of one copy
+// serialise in the L2.  The reduction that ends the backward adds the copies up.
+constexpr int LAST_GRAD_COPIES = 16;
 void launch_last_layer_train(const uint16_t* X, int ldx, const float* w, const float* bias,
                              const float* y, int B, int in, float* logits, float* dlogit,
                              float* loss, uint16_t* dX, int lddx, float* dX32, int lddx32,
-                             float* gW, float* gb, hipStream_t s);
+                             float* gpart, int gstride, hipStream_t s);
 // ---------------------------------------------------------------------------- gemm_mfma.hip
 #define SS_NT_MAX_LAYERS 16
 // C[M,N] = A[M,K] W^T (+ bias, ReLU, gate): A bf16 row-major with K (a multiple of 64) finite
