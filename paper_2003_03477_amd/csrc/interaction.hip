@@ -88,49 +88,68 @@ __global__ __launch_bounds__(256) void interaction_bwd_kernel(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ld = d + IPAD;
   const int n1 = T + 1;
-  float* Vs = smem + (size_t)wave * (n1 * ld + ((n1 * n1 + 3) & ~3));  // float4-aligned regions
+  const int n1p = (n1 + 3) & ~3;   // pitch of S: a lane reads four neighbouring entries at once
+  float* Vs = smem + (size_t)wave * (n1 * ld + n1 * n1p);  // float4-aligned regions
   float* Ss = Vs + n1 * ld;
   const int npairs = T * (T + 1) / 2;
   const int vec_per_row = d / 4;
+  const int row_blocks = n1p / 4;
   for (int b0 = blockIdx.x * 4; b0 < B; b0 += gridDim.x * 4) {
     const int b = b0 + wave;
     if (b < B) {
       stage_V(Vs, z0, e, b, T, d, lane);
-      for (int i = lane; i < n1; i += SS_WAVE) Ss[i * n1 + i] = 0.f;
+      // S is symmetric with a zero diagonal; the pitch padding (rows n1 .. n1p-1 of a column)
+      // only feeds output rows that do not exist
+      for (int i = lane; i < n1; i += SS_WAVE) Ss[i * n1p + i] = 0.f;
       for (int p = lane; p < npairs; p += SS_WAVE) {
         int r, c;
         pair_of(p, r, c);
         const float s = df[(size_t)b * lddf + d + p];
-        Ss[r * n1 + c] = s;
-        Ss[c * n1 + r] = s;
+        Ss[r * n1p + c] = s;
+        Ss[c * n1p + r] = s;
       }
     }
     __syncthreads();
     if (b < B) {
-      for (int i = lane; i < n1 * vec_per_row; i += SS_WAVE) {
-        const int r = i / vec_per_row, k4 = i - r * vec_per_row;
-        float4 acc = {0.f, 0.f, 0.f, 0.f};
+      // a lane owns four output rows r0..r0+3 and four columns 4 k4..4 k4+3: per source row c
+      // one 16-byte read of S[c][r0..r0+3] (= S[r0..r0+3][c]) and one of V[c] feed 16 FMAs
+      for (int i = lane; i < row_blocks * vec_per_row; i += SS_WAVE) {
+        const int rb = i / vec_per_row, k4 = i - rb * vec_per_row;
+        const int r0 = rb * 4;
+        float4 acc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int c = 0; c < n1; ++c) {
-          const float s = Ss[r * n1 + c];
+          const float4 s4 = *(const float4*)(Ss + c * n1p + r0);
           const float4 v = *(const float4*)(Vs + c * ld + 4 * k4);
-          acc.x += s * v.x; acc.y += s * v.y; acc.z += s * v.z; acc.w += s * v.w;
-        }
-        if (r == 0) {
-          const float4 pass = *(const float4*)(df + (size_t)b * lddf + 4 * k4);
-          const float4 z = *(const float4*)(Vs + 4 * k4);
-          float4 o;  // gradient w.r.t. the bottom MLP's last pre-activation: ReLU gate
-          o.x = z.x > 0.f ? acc.x + pass.x : 0.f;
-          o.y = z.y > 0.f ? acc.y + pass.y : 0.f;
-          o.z = z.z > 0.f ? acc.z + pass.z : 0.f;
-          o.w = z.w > 0.f ? acc.w + pass.w : 0.f;
-          *(float4*)(dz0 + (size_t)b * d + 4 * k4) = o;
-          if (dz0_bf16) {  // the same values as the bottom stack's bf16 GEMM operand
-            uint16_t* q = dz0_bf16 + (size_t)b * ld16 + 4 * k4;
-            *(uint2*)q = make_uint2((uint32_t)f32_to_bf16(o.x) | ((uint32_t)f32_to_bf16(o.y) << 16),
-                                    (uint32_t)f32_to_bf16(o.z) | ((uint32_t)f32_to_bf16(o.w) << 16));
+          const float sj[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            acc[j].x += sj[j] * v.x; acc[j].y += sj[j] * v.y;
+            acc[j].z += sj[j] * v.z; acc[j].w += sj[j] * v.w;
           }
-        } else {
-          *(float4*)(de + ((size_t)b * T + (r - 1)) * d + 4 * k4) = acc;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int r = r0 + j;
+          if (r >= n1) continue;
+          if (r == 0) {
+            const float4 pass = *(const float4*)(df + (size_t)b * lddf + 4 * k4);
+            const float4 z = *(const float4*)(Vs + 4 * k4);
+            float4 o;  // gradient w.r.t. the bottom MLP's last pre-activation: ReLU gate
+            o.x = z.x > 0.f ? acc[j].x + pass.x : 0.f;
+            o.y = z.y > 0.f ? acc[j].y + pass.y : 0.f;
+            o.z = z.z > 0.f ? acc[j].z + pass.z : 0.f;
+            o.w = z.w > 0.f ? acc[j].w + pass.w : 0.f;
+            *(float4*)(dz0 + (size_t)b * d + 4 * k4) = o;
+            if (dz0_bf16) {  // the same values as the bottom stack's bf16 GEMM operand
+              uint16_t* q = dz0_bf16 + (size_t)b * ld16 + 4 * k4;
+              *(uint2*)q = make_uint2((uint32_t)f32_to_bf16(o.x) | ((uint32_t)f32_to_bf16(o.y) << 16),
+                                      (uint32_t)f32_to_bf16(o.z) | ((uint32_t)f32_to_bf16(o.w) << 16));
+            }
+          } else {
+            *(float4*)(de + ((size_t)b * T + (r - 1)) * d + 4 * k4) = acc[j];
+          }
         }
       }
       if (dz0_bf16)   // zero padding of the operand row
@@ -155,7 +174,8 @@ void launch_interaction_bwd(const float* z0, const float* e, const float* df, in
                             hipStream_t s) {
   if (B == 0) return;
   const int n1 = T + 1;
-  const size_t shm = (size_t)4 * (n1 * (d + IPAD) + ((n1 * n1 + 3) & ~3)) * sizeof(float);
+  const int n1p = (n1 + 3) & ~3;
+  const size_t shm = (size_t)4 * (n1 * (d + IPAD) + n1 * n1p) * sizeof(float);
   int blocks = ceil_div(B, 4);
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(interaction_bwd_kernel, dim3(blocks), dim3(256), shm, s, z0, e, df, lddf, B,
