@@ -40,6 +40,28 @@ __device__ __forceinline__ void stage_V(float* Vs, const float* __restrict__ z0,
   }
 }
 
+// The same tile without row padding ([T+1][d], for readers whose lanes all read the same row),
+// loaded straight into LDS: every load instruction moves 64 x 16 bytes from per-lane global
+// addresses to 1 KB of consecutive LDS (lane l's 16 bytes at byte 16 l of the chunk), no
+// registers in between, so all of a sample's loads are in flight together.  The caller waits
+// for them (vector-memory counter) before the tile is read.
+__device__ __forceinline__ void stage_V_direct(float* Vs, const float* __restrict__ z0,
+                                               const float* __restrict__ e, int b, int T, int d,
+                                               int lane) {
+  const int vec_per_row = d / 4;
+  const int total = (T + 1) * vec_per_row;
+  for (int i0 = 0; i0 < total; i0 += SS_WAVE) {
+    const int i = i0 + lane;
+    if (i < total) {
+      const int r = i / vec_per_row, k4 = i - r * vec_per_row;
+      const float* src = (r == 0) ? (z0 + (size_t)b * d) : (e + ((size_t)b * T + (r - 1)) * d);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src + 4 * k4),
+          (__attribute__((address_space(3))) void*)(Vs + 4 * i0), 16, 0, 0);
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void interaction_fwd_kernel(
     const float* __restrict__ z0, const float* __restrict__ e, int B, int T, int d,
     float* __restrict__ f, int ldf, uint16_t* __restrict__ f_bf16, int ldf_bf16) {
@@ -86,7 +108,7 @@ __global__ __launch_bounds__(256) void interaction_bwd_kernel(
     uint16_t* __restrict__ dz0_bf16, int ld16) {
   extern __shared__ float smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int ld = d + IPAD;
+  const int ld = d;                // no row padding: all lanes of a wave read the same row of V
   const int n1 = T + 1;
   const int n1p = (n1 + 3) & ~3;   // pitch of S: a lane reads four neighbouring entries at once
   float* Vs = smem + (size_t)wave * (n1 * ld + n1 * n1p);  // float4-aligned regions
@@ -97,7 +119,7 @@ __global__ __launch_bounds__(256) void interaction_bwd_kernel(
   for (int b0 = blockIdx.x * 4; b0 < B; b0 += gridDim.x * 4) {
     const int b = b0 + wave;
     if (b < B) {
-      stage_V(Vs, z0, e, b, T, d, lane);
+      stage_V_direct(Vs, z0, e, b, T, d, lane);
       // S is symmetric with a zero diagonal; the pitch padding (rows n1 .. n1p-1 of a column)
       // only feeds output rows that do not exist
       for (int i = lane; i < n1; i += SS_WAVE) Ss[i * n1p + i] = 0.f;
@@ -109,6 +131,7 @@ __global__ __launch_bounds__(256) void interaction_bwd_kernel(
         Ss[c * n1p + r] = s;
       }
     }
+    __builtin_amdgcn_s_waitcnt(0);   // the direct loads into Vs have landed
     __syncthreads();
     if (b < B) {
       // a lane owns four output rows r0..r0+3 and four columns 4 k4..4 k4+3: per source row c
@@ -175,7 +198,7 @@ void launch_interaction_bwd(const float* z0, const float* e, const float* df, in
   if (B == 0) return;
   const int n1 = T + 1;
   const int n1p = (n1 + 3) & ~3;
-  const size_t shm = (size_t)4 * (n1 * (d + IPAD) + n1 * n1p) * sizeof(float);
+  const size_t shm = (size_t)4 * (n1 * d + n1 * n1p) * sizeof(float);
   int blocks = ceil_div(B, 4);
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(interaction_bwd_kernel, dim3(blocks), dim3(256), shm, s, z0, e, df, lddf, B,
