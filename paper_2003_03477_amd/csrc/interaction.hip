@@ -10,8 +10,6 @@
 
 namespace ss {
 
-constexpr int IPAD = 4;  // LDS row padding in floats (keeps float4 alignment)
-
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   uint32_t u = __float_as_uint(f);
   u += 0x7FFFu + ((u >> 16) & 1u);
@@ -27,33 +25,24 @@ __device__ __forceinline__ void pair_of(int p, int& r, int& c) {
   c = p - rr * (rr - 1) / 2;
 }
 
-__device__ __forceinline__ void stage_V(float* Vs, const float* __restrict__ z0,
-                                        const float* __restrict__ e, int b, int T, int d,
-                                        int lane) {
-  const int ld = d + IPAD;
-  const int vec_per_row = d / 4;
-  const int total = (T + 1) * vec_per_row;
-  for (int i = lane; i < total; i += SS_WAVE) {
-    const int r = i / vec_per_row, k4 = i - r * vec_per_row;
-    const float* src = (r == 0) ? (z0 + (size_t)b * d) : (e + ((size_t)b * T + (r - 1)) * d);
-    *(float4*)(Vs + r * ld + 4 * k4) = *(const float4*)(src + 4 * k4);
-  }
-}
-
-// The same tile without row padding ([T+1][d], for readers whose lanes all read the same row),
-// loaded straight into LDS: every load instruction moves 64 x 16 bytes from per-lane global
-// addresses to 1 KB of consecutive LDS (lane l's 16 bytes at byte 16 l of the chunk), no
-// registers in between, so all of a sample's loads are in flight together.  The caller waits
-// for them (vector-memory counter) before the tile is read.
+// The sample's tile [T+1][d] (no row padding), loaded straight into LDS: every load
+// instruction moves 64 x 16 bytes from per-lane global addresses to 1 KB of consecutive LDS
+// (lane l's 16 bytes at byte 16 l of the chunk), no registers in between, so all of a sample's
+// loads are in flight together.  The caller waits for them (vector-memory counter) before the
+// tile is read.  SWZ: the 16-byte piece k of row r sits in slot k ^ (r mod d/4) of its row, for
+// readers whose lanes read the same piece of different rows at once (rows are a multiple of
+// the bank width apart); without it piece k is slot k (readers whose lanes share the row).
+template <bool SWZ>
 __device__ __forceinline__ void stage_V_direct(float* Vs, const float* __restrict__ z0,
                                                const float* __restrict__ e, int b, int T, int d,
                                                int lane) {
-  const int vec_per_row = d / 4;
+  const int vec_per_row = d / 4;   // a power of two
   const int total = (T + 1) * vec_per_row;
   for (int i0 = 0; i0 < total; i0 += SS_WAVE) {
     const int i = i0 + lane;
     if (i < total) {
-      const int r = i / vec_per_row, k4 = i - r * vec_per_row;
+      const int r = i / vec_per_row, slot = i - r * vec_per_row;
+      const int k4 = SWZ ? (slot ^ (r & (vec_per_row - 1))) : slot;
       const float* src = (r == 0) ? (z0 + (size_t)b * d) : (e + ((size_t)b * T + (r - 1)) * d);
       __builtin_amdgcn_global_load_lds(
           (const __attribute__((address_space(1))) void*)(src + 4 * k4),
@@ -67,28 +56,31 @@ __global__ __launch_bounds__(256) void interaction_fwd_kernel(
     float* __restrict__ f, int ldf, uint16_t* __restrict__ f_bf16, int ldf_bf16) {
   extern __shared__ float smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int ld = d + IPAD;
-  float* Vs = smem + (size_t)wave * (T + 1) * ld;
+  const int vmask = d / 4 - 1;
+  float* Vs = smem + (size_t)wave * (T + 1) * d;   // swizzled rows, see stage_V_direct
   const int npairs = T * (T + 1) / 2;
   const int F = d + npairs;
   for (int b0 = blockIdx.x * 4; b0 < B; b0 += gridDim.x * 4) {
     const int b = b0 + wave;
-    if (b < B) stage_V(Vs, z0, e, b, T, d, lane);
+    if (b < B) stage_V_direct<true>(Vs, z0, e, b, T, d, lane);
+    __builtin_amdgcn_s_waitcnt(0);   // the direct loads have landed
     __syncthreads();
     if (b < B) {
       for (int k = lane; k < d; k += SS_WAVE) {
-        const float v = Vs[k];
+        const float v = Vs[k];       // row 0 is not permuted
         if (f) f[(size_t)b * ldf + k] = v;
         if (f_bf16) f_bf16[(size_t)b * ldf_bf16 + k] = f32_to_bf16(v);
       }
       for (int p = lane; p < npairs; p += SS_WAVE) {
         int r, c;
         pair_of(p, r, c);
-        const float4* vr = (const float4*)(Vs + r * ld);
-        const float4* vc = (const float4*)(Vs + c * ld);
+        const float* vr = Vs + r * d;
+        const float* vc = Vs + c * d;
+        const int xr = r & vmask, xc = c & vmask;
         float4 acc = {0.f, 0.f, 0.f, 0.f};
         for (int k4 = 0; k4 < d / 4; ++k4) {
-          const float4 x = vr[k4], y = vc[k4];
+          const float4 x = *(const float4*)(vr + ((k4 ^ xr) << 2));
+          const float4 y = *(const float4*)(vc + ((k4 ^ xc) << 2));
           acc.x += x.x * y.x; acc.y += x.y * y.y; acc.z += x.z * y.z; acc.w += x.w * y.w;
         }
         const float dot = (acc.x + acc.y) + (acc.z + acc.w);
@@ -119,7 +111,7 @@ __global__ __launch_bounds__(256) void interaction_bwd_kernel(
   for (int b0 = blockIdx.x * 4; b0 < B; b0 += gridDim.x * 4) {
     const int b = b0 + wave;
     if (b < B) {
-      stage_V_direct(Vs, z0, e, b, T, d, lane);
+      stage_V_direct<false>(Vs, z0, e, b, T, d, lane);
       // S is symmetric with a zero diagonal; the pitch padding (rows n1 .. n1p-1 of a column)
       // only feeds output rows that do not exist
       for (int i = lane; i < n1; i += SS_WAVE) Ss[i * n1p + i] = 0.f;
@@ -185,7 +177,7 @@ __global__ __launch_bounds__(256) void interaction_bwd_kernel(
 void launch_interaction_fwd(const float* z0, const float* e, int B, int T, int d, float* f,
                             int ldf, uint16_t* f_bf16, int ldf_bf16, hipStream_t s) {
   if (B == 0) return;
-  const size_t shm = (size_t)4 * (T + 1) * (d + IPAD) * sizeof(float);
+  const size_t shm = (size_t)4 * (T + 1) * d * sizeof(float);
   int blocks = ceil_div(B, 4);
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(interaction_fwd_kernel, dim3(blocks), dim3(256), shm, s, z0, e, B, T, d, f,
