@@ -250,8 +250,13 @@ static int validate(const ss_config* c, std::string& why) {
   if (c->emb_optimizer == SS_OPT_ADAM &&
       !(c->adam_beta1 >= 0.f && c->adam_beta1 < 1.f && c->adam_beta2 >= 0.f && c->adam_beta2 < 1.f))
     BAD("Adam betas must lie in [0, 1)");
-  const size_t shm = (size_t)4 * ((T + 1) * (c->emb_dim + 4) + (T + 1) * ((T + 1 + 3) & ~3)) * 4;
-  if (shm > 64 * 1024) BAD("interaction tile (T+1) x d does not fit the LDS budget");
+  {  // LDS of the interaction kernels, four samples per workgroup (see interaction.hip)
+    const int n1 = T + 1, n1p = (n1 + 3) & ~3, np4 = (T * (T + 1) / 2 + 3) & ~3;
+    const size_t fwd = (size_t)4 * (n1p * c->emb_dim + np4) * 4;
+    const size_t bwd = (size_t)4 * (n1 * c->emb_dim + n1 * n1p) * 4;
+    if (fwd > 64 * 1024 || bwd > 64 * 1024)
+      BAD("interaction tile (T+1) x d does not fit the LDS budget");
+  }
 #undef BAD
   return SS_OK;
 }

@@ -51,15 +51,27 @@ __device__ __forceinline__ void stage_V_direct(float* Vs, const float* __restric
   }
 }
 
+// Forward.  The Gram matrix V V^T of a sample is computed in 4x4 register blocks of its lower
+// triangle: a task (rb, cb <= rb) reads rows 4 rb .. 4 rb + 3 and 4 cb .. 4 cb + 3 piece by
+// piece (8 LDS reads of 16 bytes feed 64 FMAs) and is shared by KS neighbouring lanes, each
+// summing a 1/KS share of the d columns; the lanes' sums are added with lane exchanges.  The
+// entries below the diagonal go to an LDS copy of the output row, which the wave then writes
+// out in consecutive order.
 __global__ __launch_bounds__(256) void interaction_fwd_kernel(
-    const float* __restrict__ z0, const float* __restrict__ e, int B, int T, int d,
+    const float* __restrict__ z0, const float* __restrict__ e, int B, int T, int d, int KS,
     float* __restrict__ f, int ldf, uint16_t* __restrict__ f_bf16, int ldf_bf16) {
   extern __shared__ float smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int vmask = d / 4 - 1;
-  float* Vs = smem + (size_t)wave * (T + 1) * d;   // swizzled rows, see stage_V_direct
+  const int vec_per_row = d / 4, vmask = vec_per_row - 1;
+  const int n1 = T + 1, n1p = (n1 + 3) & ~3;
   const int npairs = T * (T + 1) / 2;
   const int F = d + npairs;
+  const int row_blocks = n1p / 4, ntasks = row_blocks * (row_blocks + 1) / 2;
+  // per wave: the tile (rows n1 .. n1p-1 are never written: they only feed entries that are
+  // dropped), then the pair values
+  float* Vs = smem + (size_t)wave * (n1p * d + ((npairs + 3) & ~3));   // swizzled rows
+  float* Fs = Vs + n1p * d;
+  const int kshare = vec_per_row / KS;
   for (int b0 = blockIdx.x * 4; b0 < B; b0 += gridDim.x * 4) {
     const int b = b0 + wave;
     if (b < B) stage_V_direct<true>(Vs, z0, e, b, T, d, lane);
@@ -71,19 +83,55 @@ __global__ __launch_bounds__(256) void interaction_fwd_kernel(
         if (f) f[(size_t)b * ldf + k] = v;
         if (f_bf16) f_bf16[(size_t)b * ldf_bf16 + k] = f32_to_bf16(v);
       }
-      for (int p = lane; p < npairs; p += SS_WAVE) {
-        int r, c;
-        pair_of(p, r, c);
-        const float* vr = Vs + r * d;
-        const float* vc = Vs + c * d;
-        const int xr = r & vmask, xc = c & vmask;
-        float4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int k4 = 0; k4 < d / 4; ++k4) {
-          const float4 x = *(const float4*)(vr + ((k4 ^ xr) << 2));
-          const float4 y = *(const float4*)(vc + ((k4 ^ xc) << 2));
-          acc.x += x.x * y.x; acc.y += x.y * y.y; acc.z += x.z * y.z; acc.w += x.w * y.w;
+      // (ntasks * KS <= 64, or KS == 1: the KS lanes of a task are neighbours in one round)
+      for (int u0 = 0; u0 < ntasks * KS; u0 += SS_WAVE) {
+        const int u = u0 + lane;
+        const bool on = u < ntasks * KS;
+        const int t = on ? u / KS : 0, ks = u % KS;
+        int rb1, cb;
+        pair_of(t, rb1, cb);         // t = rb (rb + 1) / 2 + cb with rb = rb1 - 1 >= cb
+        const int r0 = (rb1 - 1) * 4, c0 = cb * 4;
+        float acc[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+        if (on) {
+          for (int k4 = ks * kshare; k4 < (ks + 1) * kshare; ++k4) {
+            float4 x[4], y[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              x[i] = *(const float4*)(Vs + (r0 + i) * d + ((k4 ^ ((r0 + i) & vmask)) << 2));
+              y[i] = *(const float4*)(Vs + (c0 + i) * d + ((k4 ^ ((c0 + i) & vmask)) << 2));
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                acc[i][j] += (x[i].x * y[j].x + x[i].y * y[j].y) + (x[i].z * y[j].z + x[i].w * y[j].w);
+          }
         }
-        const float dot = (acc.x + acc.y) + (acc.z + acc.w);
+        for (int m = 1; m < KS; m <<= 1) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] += __shfl_xor(acc[i][j], m);
+        }
+        if (on && ks == 0) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const int r = r0 + i, c = c0 + j;
+              if (r < n1 && c < r) Fs[r * (r - 1) / 2 + c] = acc[i][j];
+            }
+        }
+      }
+    }
+    __syncthreads();   // (a wave reads what its own lanes wrote; the barrier is for the compiler)
+    if (b < B) {
+      for (int p = lane; p < npairs; p += SS_WAVE) {
+        const float dot = Fs[p];
         if (f) f[(size_t)b * ldf + d + p] = dot;
         if (f_bf16) f_bf16[(size_t)b * ldf_bf16 + d + p] = f32_to_bf16(dot);
       }
@@ -177,11 +225,16 @@ __global__ __launch_bounds__(256) void interaction_bwd_kernel(
 void launch_interaction_fwd(const float* z0, const float* e, int B, int T, int d, float* f,
                             int ldf, uint16_t* f_bf16, int ldf_bf16, hipStream_t s) {
   if (B == 0) return;
-  const size_t shm = (size_t)4 * (T + 1) * d * sizeof(float);
+  const int n1p = (T + 1 + 3) & ~3, npairs = T * (T + 1) / 2;
+  const size_t shm = (size_t)4 * (n1p * d + ((npairs + 3) & ~3)) * sizeof(float);
+  // lanes that share a block of the Gram matrix: as many as keep all tasks in one round
+  const int rbk = n1p / 4, ntasks = rbk * (rbk + 1) / 2;
+  int KS = 1;
+  while (ntasks * KS * 2 <= SS_WAVE && KS * 2 <= d / 4) KS *= 2;
   int blocks = ceil_div(B, 4);
   if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(interaction_fwd_kernel, dim3(blocks), dim3(256), shm, s, z0, e, B, T, d, f,
-                     ldf, f_bf16, ldf_bf16);
+  hipLaunchKernelGGL(interaction_fwd_kernel, dim3(blocks), dim3(256), shm, s, z0, e, B, T, d, KS,
+                     f, ldf, f_bf16, ldf_bf16);
 }
 
 void launch_interaction_bwd(const float* z0, const float* e, const float* df, int lddf, int B,
