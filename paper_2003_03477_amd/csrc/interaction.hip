@@ -56,7 +56,7 @@ __device__ __forceinline__ void stage_V_direct(float* Vs, const float* __restric
 // piece (8 LDS reads of 16 bytes feed 64 FMAs) and is shared by KS neighbouring lanes, each
 // summing a 1/KS share of the d columns; the lanes' sums are added with lane exchanges.  The
 // entries below the diagonal go to an LDS copy of the output row, which the wave then writes
-// out in consecutive order.
+// out in consecutive order.  With at most 64 pairs (KS == 0) a lane computes one pair instead.
 __global__ __launch_bounds__(256) void interaction_fwd_kernel(
     const float* __restrict__ z0, const float* __restrict__ e, int B, int T, int d, int KS,
     float* __restrict__ f, int ldf, uint16_t* __restrict__ f_bf16, int ldf_bf16) {
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void interaction_fwd_kernel(
   // dropped), then the pair values
   float* Vs = smem + (size_t)wave * (n1p * d + ((npairs + 3) & ~3));   // swizzled rows
   float* Fs = Vs + n1p * d;
-  const int kshare = vec_per_row / KS;
+  const int kshare = KS ? vec_per_row / KS : 0;
   for (int b0 = blockIdx.x * 4; b0 < B; b0 += gridDim.x * 4) {
     const int b = b0 + wave;
     if (b < B) stage_V_direct<true>(Vs, z0, e, b, T, d, lane);
@@ -82,6 +82,24 @@ __global__ __launch_bounds__(256) void interaction_fwd_kernel(
         const float v = Vs[k];       // row 0 is not permuted
         if (f) f[(size_t)b * ldf + k] = v;
         if (f_bf16) f_bf16[(size_t)b * ldf_bf16 + k] = f32_to_bf16(v);
+      }
+      if (KS == 0) {
+        // few pairs (at most one per lane): a lane takes a whole pair and writes it itself
+        const int p = lane;
+        if (p < npairs) {
+          int r, c;
+          pair_of(p, r, c);
+          const float* vr = Vs + r * d;
+          const float* vc = Vs + c * d;
+          const int xr = r & vmask, xc = c & vmask;
+          float4 acc = {0.f, 0.f, 0.f, 0.f};
+          for (int k4 = 0; k4 < vec_per_row; ++k4) {
+            const float4 x = *(const float4*)(vr + ((k4 ^ xr) << 2));
+            const float4 y = *(const float4*)(vc + ((k4 ^ xc) << 2));
+            acc.x += x.x * y.x; acc.y += x.y * y.y; acc.z += x.z * y.z; acc.w += x.w * y.w;
+          }
+          Fs[p] = (acc.x + acc.y) + (acc.z + acc.w);
+        }
       }
       // (ntasks * KS <= 64, or KS == 1: the KS lanes of a task are neighbours in one round)
       for (int u0 = 0; u0 < ntasks * KS; u0 += SS_WAVE) {
@@ -231,6 +249,7 @@ void launch_interaction_fwd(const float* z0, const float* e, int B, int T, int d
   const int rbk = n1p / 4, ntasks = rbk * (rbk + 1) / 2;
   int KS = 1;
   while (ntasks * KS * 2 <= SS_WAVE && KS * 2 <= d / 4) KS *= 2;
+  if (npairs <= SS_WAVE) KS = 0;   // one pair per lane is cheaper than sharing blocks
   int blocks = ceil_div(B, 4);
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(interaction_fwd_kernel, dim3(blocks), dim3(256), shm, s, z0, e, B, T, d, KS,
