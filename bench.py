@@ -82,6 +82,8 @@ def parse():
                     help="bf16 MLP kernels: auto = fused per-sample-tile kernels for widths <= 512")
     ap.add_argument("--sort-digit-bits", type=int, default=0, choices=[0, 8, 9, 10],
                     help="widest digit of a pass of the backward's radix sort (0: library default)")
+    ap.add_argument("--serial-warmup", type=int, default=2,
+                    help="warm-up sweeps run one stream at a time (at most warmup - 1)")
     ap.add_argument("--no-shadow-off", action="store_true", help="skip the shadow-off region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sync-isolation", action="store_true")
@@ -355,7 +357,7 @@ def run_workload(args, wl, workers, shadow_mode, steps, warmup, host_batches, ev
 
     # ---- warm-up: every stream, every kernel, the shadow loop
     shadow_loop(True)
-    region(warmup, serial=min(2, max(warmup - 1, 0)) if NS > 1 else 0)
+    region(warmup, serial=min(args.serial_warmup, max(warmup - 1, 0)) if NS > 1 else 0)
     progress(f"{wl.name}{tag}: warm-up done")
     # ---- timed region, shadow on
     # brackets cost a few per cent of a step when every launch carries one: every class gets
