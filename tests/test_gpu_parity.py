@@ -603,3 +603,19 @@ def test_sort_digit_widths(digit_bits):
     H.run_lockstep(gpu, orc, batches, 1, "ma", 1.0)
     H.compare_state(gpu, orc, H.FP32_RTOL, f"sort digits of {digit_bits} bits", wl.row_base)
     gpu.close()
+
+
+@pytest.mark.parametrize("T,d", [(13, 32), (40, 16), (1, 16)])
+def test_interaction_shapes(T, d):
+    """Shapes that drive the interaction kernels' other branches: 91 pairs in 4x4 blocks shared
+    by four lanes (T=13, d=32), 66 blocks in two rounds of the wave (T=40), a single pair
+    (T=1); fp32 lockstep against the oracle."""
+    wl = synth.tiny().scaled(batch=24, rows=(50,) * T, emb_dim=d, bag_lambda=2.0,
+                             bot_dims=(13, 24, d), top_dims=(d + T * (T + 1) // 2, 32, 1),
+                             num_replicas=1, algo="ma", alpha=1.0)
+    gen = synth.BatchGenerator(wl)
+    batches = [gen.batch(s) for s in range(3)]
+    gpu, orc = H.make_pair(wl, batches)
+    H.run_lockstep(gpu, orc, batches, 1, "ma", 1.0)
+    H.compare_state(gpu, orc, H.FP32_RTOL, f"T={T} d={d}", wl.row_base)
+    gpu.close()
